@@ -1,0 +1,314 @@
+// CPU oracle for single-stream SRU / QRNN inference (arXiv 1803.11389).
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+// GPU library is checked against.  It shares no code with the GPU path, is not
+// linked into it, and must never be called from it.
+//
+// What it computes
+//   * SRU layer, paper Eq. (2):   xh = W x,  f = sigma(W_f x + b_f),
+//     r = sigma(W_r x + b_r),  c_t = f*c_{t-1} + (1-f)*xh,
+//     h_t = r*tanh(c_t) + (1-r)*x_t.
+//   * QRNN layer, paper Eq. (3), written for a causal window of k inputs
+//     (the paper prints k = 2):  u_g = sum_{j<k} W_g^j x_{t-j},
+//     xh = tanh(u_0), f = sigma(u_1), o = sigma(u_2),
+//     c_t = f*c_{t-1} + (1-f)*xh,  h_t = o*tanh(c_t).
+//   * Multi-time-step blocking, paper Section 3 and Eq. (4): the gate
+//     pre-activations of T consecutive steps are produced together as one
+//     matrix-matrix product, one weight row being fetched once and applied to
+//     all T columns, and only then does the element-wise recurrence ripple
+//     over the T steps.
+//   * A stack feeds layer l's h_t to layer l+1 as x_t.
+//
+// Arithmetic: every sum, gate and state is IEEE double; weights are given in
+// their storage type (fp32, or bf16 bit patterns) and widened exactly.  Each dot product adds its terms in ascending column
+// order whatever T is, so the result is bit-identical for every block size.
+// Nothing is rounded between layers.
+//
+// Pins (tests/test_oracle_*.py): hand-worked d=2 examples for both cells,
+// step-by-step brute force (oracle_*_step below, written separately),
+// closed forms (f==0, f==1/2, f==1, r==0, W==0), the non-iterative solution of
+// the linear recurrence, an independent library matrix product for the weight
+// layout, block-size invariance, chunk chaining and boundedness.
+//
+// Storage conventions
+//   SRU  W  : row-major [3d x d],   rows [0,d) = W, [d,2d) = W_f, [2d,3d) = W_r
+//   SRU  b  : [2d] = b_f | b_r  (no bias on xh, Eq. 2);  NULL means zero
+//   QRNN W  : row-major [3d x k*d], column block j multiplies x_{t-j};
+//             rows [0,d) = xh, [d,2d) = f, [2d,3d) = o
+//   QRNN b  : [3d] or NULL (Eq. 3 has none)
+//   x, h    : time-major [L x d]
+//   xhist   : [n_layers x (k-1) x d]; entry (l, j) is layer l's input at lag
+//             j+1 before the first step of the call (zeros when NULL)
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+enum { WDT_F32 = 0, WDT_BF16 = 1 };
+
+inline double widen_bf16(uint16_t bits) {
+  uint32_t u = static_cast<uint32_t>(bits) << 16;
+  float f;
+  std::memcpy(&f, &u, sizeof f);
+  return static_cast<double>(f);
+}
+
+inline double weight_at(const void* W, int wdt, size_t idx) {
+  if (wdt == WDT_BF16) return widen_bf16(static_cast<const uint16_t*>(W)[idx]);
+  return static_cast<double>(static_cast<const float*>(W)[idx]);
+}
+
+inline double sigma(double z) { return 1.0 / (1.0 + std::exp(-z)); }
+
+// U[g][i][t] = sum_col W[g*d+i][col] * X[col][t]   (Eq. 4 for all three gates)
+// X is the [ncol x nt] block, column t contiguous in t for a fixed col.
+// One weight is read once and applied to all nt columns (Section 3).
+void gate_block(const void* W, int wdt, int d, int ncol, const double* X,
+                int nt, double* U /* [3][d][nt] */) {
+#pragma omp parallel for schedule(static)
+  for (int row = 0; row < 3 * d; ++row) {
+    double* acc = U + static_cast<size_t>(row) * nt;
+    for (int t = 0; t < nt; ++t) acc[t] = 0.0;
+    const size_t base = static_cast<size_t>(row) * ncol;
+    for (int col = 0; col < ncol; ++col) {
+      const double w = weight_at(W, wdt, base + col);
+      const double* xc = X + static_cast<size_t>(col) * nt;
+      for (int t = 0; t < nt; ++t) acc[t] += w * xc[t];
+    }
+  }
+}
+
+// One SRU layer over the whole sequence, T steps per block.
+// xin/hout: double [L x d]; c: double [d] in/out.
+void sru_layer(const void* W, int wdt, const float* bias, const double* xin,
+               double* hout, double* c, int d, long L, int T) {
+  std::vector<double> X(static_cast<size_t>(d) * T);
+  std::vector<double> U(static_cast<size_t>(3) * d * T);
+  for (long t0 = 0; t0 < L; t0 += T) {
+    const int nt = static_cast<int>(L - t0 < T ? L - t0 : T);
+    // X = [x_{t0} ... x_{t0+nt-1}] as columns
+    for (int j = 0; j < d; ++j)
+      for (int t = 0; t < nt; ++t)
+        X[static_cast<size_t>(j) * nt + t] = xin[(t0 + t) * d + j];
+    gate_block(W, wdt, d, d, X.data(), nt, U.data());
+    const double* Ux = U.data();
+    const double* Uf = U.data() + static_cast<size_t>(d) * nt;
+    const double* Ur = U.data() + static_cast<size_t>(2) * d * nt;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < d; ++i) {
+      const double bf = bias ? static_cast<double>(bias[i]) : 0.0;
+      const double br = bias ? static_cast<double>(bias[d + i]) : 0.0;
+      double ci = c[i];
+      for (int t = 0; t < nt; ++t) {
+        const double xh = Ux[static_cast<size_t>(i) * nt + t];
+        const double f = sigma(Uf[static_cast<size_t>(i) * nt + t] + bf);
+        const double r = sigma(Ur[static_cast<size_t>(i) * nt + t] + br);
+        ci = f * ci + (1.0 - f) * xh;
+        const double xt = xin[(t0 + t) * d + i];
+        hout[(t0 + t) * d + i] = r * std::tanh(ci) + (1.0 - r) * xt;
+      }
+      c[i] = ci;
+    }
+  }
+}
+
+// One QRNN layer.  hist: double [(k-1) x d] in/out (lag j+1 at row j).
+void qrnn_layer(const void* W, int wdt, const float* bias, const double* xin,
+                double* hout, double* c, double* hist, int d, long L, int T,
+                int k) {
+  const int ncol = k * d;
+  std::vector<double> X(static_cast<size_t>(ncol) * T);
+  std::vector<double> U(static_cast<size_t>(3) * d * T);
+  // input at absolute time s (s may be negative: taken from hist)
+  auto x_at = [&](long s, int m) -> double {
+    if (s >= 0) return xin[s * d + m];
+    return hist[static_cast<size_t>(-s - 1) * d + m];
+  };
+  for (long t0 = 0; t0 < L; t0 += T) {
+    const int nt = static_cast<int>(L - t0 < T ? L - t0 : T);
+    // column t of X is [x_t ; x_{t-1} ; ... ; x_{t-k+1}]
+    for (int j = 0; j < k; ++j)
+      for (int m = 0; m < d; ++m)
+        for (int t = 0; t < nt; ++t)
+          X[(static_cast<size_t>(j) * d + m) * nt + t] = x_at(t0 + t - j, m);
+    gate_block(W, wdt, d, ncol, X.data(), nt, U.data());
+    const double* Uz = U.data();
+    const double* Uf = U.data() + static_cast<size_t>(d) * nt;
+    const double* Uo = U.data() + static_cast<size_t>(2) * d * nt;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < d; ++i) {
+      const double bz = bias ? static_cast<double>(bias[i]) : 0.0;
+      const double bf = bias ? static_cast<double>(bias[d + i]) : 0.0;
+      const double bo = bias ? static_cast<double>(bias[2 * d + i]) : 0.0;
+      double ci = c[i];
+      for (int t = 0; t < nt; ++t) {
+        const double z = std::tanh(Uz[static_cast<size_t>(i) * nt + t] + bz);
+        const double f = sigma(Uf[static_cast<size_t>(i) * nt + t] + bf);
+        const double o = sigma(Uo[static_cast<size_t>(i) * nt + t] + bo);
+        ci = f * ci + (1.0 - f) * z;
+        hout[(t0 + t) * d + i] = o * std::tanh(ci);
+      }
+      c[i] = ci;
+    }
+  }
+  // new history: the last k-1 inputs seen, most recent first
+  if (k > 1) {
+    std::vector<double> nh(static_cast<size_t>(k - 1) * d);
+    for (int j = 0; j < k - 1; ++j)
+      for (int m = 0; m < d; ++m) nh[static_cast<size_t>(j) * d + m] = x_at(L - 1 - j, m);
+    std::memcpy(hist, nh.data(), nh.size() * sizeof(double));
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
+// Stacked SRU forward (Eq. 2 per layer, Section 3 blocking with block size T).
+// W[l]: fp32 or bf16-bit [3d x d]; bias: NULL, or array whose entries may be
+// NULL; x: double [L x d] (fp32 inputs are widened exactly by the caller);
+// c_init: double [n_layers x d] or NULL; outputs double:
+// h [L x d] (top layer), c_final [n_layers x d], h_all optional
+// [n_layers x L x d] (every layer's output).  Returns 0, or 1 on bad arguments.
+int oracle_sru_forward(const void* const* W, const float* const* bias,
+                       const double* x, const double* c_init, double* h,
+                       double* c_final, double* h_all, int n_layers, int d,
+                       long L, int T, int wdt) {
+  if (!W || !c_final || n_layers < 1 || d < 1 || L < 0 || T < 1) return 1;
+  if (L > 0 && (!x || !h)) return 1;
+  if (wdt != WDT_F32 && wdt != WDT_BF16) return 1;
+  const size_t n = static_cast<size_t>(L) * d;
+  std::vector<double> cur(n), nxt(n);
+  for (size_t i = 0; i < n; ++i) cur[i] = x[i];
+  for (int l = 0; l < n_layers; ++l) {
+    std::vector<double> c(d);
+    for (int i = 0; i < d; ++i)
+      c[i] = c_init ? c_init[static_cast<size_t>(l) * d + i] : 0.0;
+    sru_layer(W[l], wdt, bias ? bias[l] : nullptr, cur.data(), nxt.data(),
+              c.data(), d, L, T);
+    std::memcpy(c_final + static_cast<size_t>(l) * d, c.data(), d * sizeof(double));
+    if (h_all && n) std::memcpy(h_all + static_cast<size_t>(l) * n, nxt.data(), n * sizeof(double));
+    cur.swap(nxt);
+  }
+  if (n) std::memcpy(h, cur.data(), n * sizeof(double));
+  return 0;
+}
+
+// Stacked QRNN forward (Eq. 3 per layer, window k, fo-pooling, blocked by T).
+// xhist_init: double [n_layers x (k-1) x d] or NULL (zeros: causal padding);
+// xhist_final: double, same shape, or NULL.
+int oracle_qrnn_forward(const void* const* W, const float* const* bias,
+                        const double* x, const double* c_init,
+                        const double* xhist_init, double* h, double* c_final,
+                        double* xhist_final, double* h_all, int n_layers,
+                        int d, long L, int T, int k, int wdt) {
+  if (!W || !c_final || n_layers < 1 || d < 1 || L < 0 || T < 1 || k < 1) return 1;
+  if (L > 0 && (!x || !h)) return 1;
+  if (wdt != WDT_F32 && wdt != WDT_BF16) return 1;
+  const size_t n = static_cast<size_t>(L) * d;
+  const size_t nh = static_cast<size_t>(k - 1) * d;
+  std::vector<double> cur(n), nxt(n);
+  for (size_t i = 0; i < n; ++i) cur[i] = x[i];
+  for (int l = 0; l < n_layers; ++l) {
+    std::vector<double> c(d), hist(nh ? nh : 1, 0.0);
+    for (int i = 0; i < d; ++i)
+      c[i] = c_init ? c_init[static_cast<size_t>(l) * d + i] : 0.0;
+    if (xhist_init)
+      for (size_t i = 0; i < nh; ++i) hist[i] = xhist_init[l * nh + i];
+    qrnn_layer(W[l], wdt, bias ? bias[l] : nullptr, cur.data(), nxt.data(),
+               c.data(), hist.data(), d, L, T, k);
+    std::memcpy(c_final + static_cast<size_t>(l) * d, c.data(), d * sizeof(double));
+    if (xhist_final && nh) std::memcpy(xhist_final + l * nh, hist.data(), nh * sizeof(double));
+    if (h_all && n) std::memcpy(h_all + static_cast<size_t>(l) * n, nxt.data(), n * sizeof(double));
+    cur.swap(nxt);
+  }
+  if (n) std::memcpy(h, cur.data(), n * sizeof(double));
+  return 0;
+}
+
+// ---- brute force: one layer, one time step, no blocking -------------------
+// Written on its own (a matrix-vector product per gate, then Eq. 2 / Eq. 3
+// once) so that the blocked functions above can be checked against it.
+
+// x_t, c (in/out), h_t are double [d].
+int oracle_sru_step(const void* W, const float* bias, const double* x_t,
+                    double* c, double* h_t, int d, int wdt) {
+  if (!W || !x_t || !c || !h_t || d < 1) return 1;
+  for (int i = 0; i < d; ++i) {
+    double ux = 0.0, uf = 0.0, ur = 0.0;
+    for (int j = 0; j < d; ++j) ux += weight_at(W, wdt, static_cast<size_t>(i) * d + j) * x_t[j];
+    for (int j = 0; j < d; ++j) uf += weight_at(W, wdt, static_cast<size_t>(d + i) * d + j) * x_t[j];
+    for (int j = 0; j < d; ++j) ur += weight_at(W, wdt, static_cast<size_t>(2 * d + i) * d + j) * x_t[j];
+    if (bias) { uf += bias[i]; ur += bias[d + i]; }
+    const double f = 1.0 / (1.0 + std::exp(-uf));
+    const double r = 1.0 / (1.0 + std::exp(-ur));
+    c[i] = f * c[i] + (1.0 - f) * ux;
+    h_t[i] = r * std::tanh(c[i]) + (1.0 - r) * x_t[i];
+  }
+  return 0;
+}
+
+// xwin: double [k x d], row j = x_{t-j} (row 0 is the current input).
+int oracle_qrnn_step(const void* W, const float* bias, const double* xwin,
+                     double* c, double* h_t, int d, int k, int wdt) {
+  if (!W || !xwin || !c || !h_t || d < 1 || k < 1) return 1;
+  const size_t ld = static_cast<size_t>(k) * d;
+  for (int i = 0; i < d; ++i) {
+    double u[3] = {0.0, 0.0, 0.0};
+    for (int g = 0; g < 3; ++g)
+      for (int j = 0; j < k; ++j)
+        for (int m = 0; m < d; ++m)
+          u[g] += weight_at(W, wdt, (static_cast<size_t>(g) * d + i) * ld + static_cast<size_t>(j) * d + m) *
+                  xwin[static_cast<size_t>(j) * d + m];
+    if (bias) { u[0] += bias[i]; u[1] += bias[d + i]; u[2] += bias[2 * d + i]; }
+    const double z = std::tanh(u[0]);
+    const double f = 1.0 / (1.0 + std::exp(-u[1]));
+    const double o = 1.0 / (1.0 + std::exp(-u[2]));
+    c[i] = f * c[i] + (1.0 - f) * z;
+    h_t[i] = o * std::tanh(c[i]);
+  }
+  return 0;
+}
+
+// y[L x d_out] = feat[L x d_in] * P^T, P row-major [d_out x d_in], no bias, no
+// activation: the input projection of the ASR-shaped workload (not part of the
+// paper's method; a plain matrix product).
+int oracle_linear_forward(const float* P, const float* feat, double* y,
+                          int d_out, int d_in, long L) {
+  if (!P || !feat || !y || d_out < 1 || d_in < 1 || L < 0) return 1;
+#pragma omp parallel for schedule(static)
+  for (long t = 0; t < L; ++t)
+    for (int i = 0; i < d_out; ++i) {
+      double acc = 0.0;
+      for (int j = 0; j < d_in; ++j)
+        acc += static_cast<double>(P[static_cast<size_t>(i) * d_in + j]) *
+               static_cast<double>(feat[t * d_in + j]);
+      y[t * d_out + i] = acc;
+    }
+  return 0;
+}
+
+}  // extern "C"

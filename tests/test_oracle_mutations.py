@@ -1,0 +1,91 @@
+"""The pins must be able to fail: each case plants one plausible mistake in a
+copy of the oracle's source (on the CPU, never in the GPU library), builds the
+copy, points the pin tests at it and expects at least one of them to fail.
+"""
+import os
+
+import pytest
+
+import oracle
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "ssrnn_oracle.cpp")
+
+# (label, text in the source, replacement)
+MUTATIONS = [
+    ("sru: candidate weight uses f instead of 1-f", "ci = f * ci + (1.0 - f) * xh;", "ci = f * ci + f * xh;"),
+    ("sru: forget gate not applied to old state", "ci = f * ci + (1.0 - f) * xh;", "ci = ci + (1.0 - f) * xh;"),
+    ("sru: highway term dropped", "r * std::tanh(ci) + (1.0 - r) * xt;", "r * std::tanh(ci);"),
+    ("sru: highway term uses r", "r * std::tanh(ci) + (1.0 - r) * xt;", "r * std::tanh(ci) + r * xt;"),
+    ("sru: no tanh on the cell", "r * std::tanh(ci) + (1.0 - r) * xt;", "r * ci + (1.0 - r) * xt;"),
+    ("sru: f and r row blocks swapped",
+     "const double* Uf = U.data() + static_cast<size_t>(d) * nt;\n    const double* Ur = U.data() + static_cast<size_t>(2) * d * nt;",
+     "const double* Ur = U.data() + static_cast<size_t>(d) * nt;\n    const double* Uf = U.data() + static_cast<size_t>(2) * d * nt;"),
+    ("sru: biases swapped", "const double bf = bias ? static_cast<double>(bias[i]) : 0.0;\n      const double br = bias ? static_cast<double>(bias[d + i]) : 0.0;\n      double ci = c[i];\n      for (int t = 0; t < nt; ++t) {\n        const double xh",
+     "const double br = bias ? static_cast<double>(bias[i]) : 0.0;\n      const double bf = bias ? static_cast<double>(bias[d + i]) : 0.0;\n      double ci = c[i];\n      for (int t = 0; t < nt; ++t) {\n        const double xh"),
+    ("sigmoid sign", "return 1.0 / (1.0 + std::exp(-z));", "return 1.0 / (1.0 + std::exp(z));"),
+    ("weights read transposed (square case)", "const size_t base = static_cast<size_t>(row) * ncol;\n    for (int col = 0; col < ncol; ++col) {\n      const double w = weight_at(W, wdt, base + col);",
+     "const size_t base = static_cast<size_t>(row) * ncol;\n    for (int col = 0; col < ncol; ++col) {\n      const double w = weight_at(W, wdt, ncol == d ? (static_cast<size_t>(row / d) * d + col) * ncol + row % d : base + col);"),
+    ("qrnn: lag blocks reversed", "X[(static_cast<size_t>(j) * d + m) * nt + t] = x_at(t0 + t - j, m);",
+     "X[(static_cast<size_t>(k - 1 - j) * d + m) * nt + t] = x_at(t0 + t - j, m);"),
+    ("qrnn: looks ahead instead of back", "= x_at(t0 + t - j, m);", "= x_at(t0 + t + j < L ? t0 + t + j : L - 1, m);"),
+    ("qrnn: candidate not squashed", "const double z = std::tanh(Uz[static_cast<size_t>(i) * nt + t] + bz);",
+     "const double z = Uz[static_cast<size_t>(i) * nt + t] + bz;"),
+    ("qrnn: output without tanh", "hout[(t0 + t) * d + i] = o * std::tanh(ci);", "hout[(t0 + t) * d + i] = o * ci;"),
+    ("qrnn: history order reversed", "nh[static_cast<size_t>(j) * d + m] = x_at(L - 1 - j, m);",
+     "nh[static_cast<size_t>(k - 2 - j) * d + m] = x_at(L - 1 - j, m);"),
+    ("state not carried across blocks", "      c[i] = ci;\n    }\n  }\n}\n\n// One QRNN layer.", "    }\n  }\n}\n\n// One QRNN layer."),
+    ("initial state ignored (sru)", "c[i] = c_init ? c_init[static_cast<size_t>(l) * d + i] : 0.0;\n    sru_layer", "c[i] = 0.0;\n    sru_layer"),
+    ("bf16 widened with the wrong shift", "static_cast<uint32_t>(bits) << 16;", "static_cast<uint32_t>(bits) << 15;"),
+    ("stack: every layer reads the external input", "    cur.swap(nxt);\n  }\n  if (n) std::memcpy(h, cur.data(), n * sizeof(double));\n  return 0;\n}\n\n// Stacked QRNN",
+     "    if (l == n_layers - 1) cur.swap(nxt);\n  }\n  if (n) std::memcpy(h, cur.data(), n * sizeof(double));\n  return 0;\n}\n\n// Stacked QRNN"),
+    ("step function: bias dropped", "if (bias) { uf += bias[i]; ur += bias[d + i]; }", ""),
+    ("projection transposed", "static_cast<double>(P[static_cast<size_t>(i) * d_in + j])", "static_cast<double>(P[(static_cast<size_t>(j) * d_out + i) % (static_cast<size_t>(d_in) * d_out)])"),
+]
+
+BATTERY = [
+    lambda: [pins.test_sru_hand_example(n, T) for n in ("sru_d2_example_a.txt", "sru_d2_example_b.txt") for T in (1, 2, 4)],
+    lambda: [pins.test_qrnn_hand_example(T) for T in (1, 2, 4)],
+    pins.test_step_functions_hand_examples,
+    lambda: pins.test_sru_blocked_equals_bruteforce_bitwise(2, 2, 5, 11, 4, False),
+    lambda: pins.test_sru_blocked_equals_bruteforce_bitwise(5, 2, 6, 13, 5, True),
+    lambda: pins.test_qrnn_blocked_equals_bruteforce_bitwise(13, 3, 4, 20, 16, 3, False),
+    pins.test_sru_forget_zero_gives_candidate,
+    pins.test_sru_forget_half_is_exponential_average,
+    pins.test_sru_reset_zero_is_identity_through_a_stack,
+    lambda: pins.test_sru_layer_against_library_product_and_solved_recurrence(41),
+    lambda: pins.test_qrnn_layer_against_library_product_and_solved_recurrence(44, 3),
+    pins.test_stack_feeds_h_to_next_layer,
+    pins.test_chunk_chaining_equals_one_call,
+    pins.test_bf16_weights_are_widened_exactly,
+    pins.test_linear_projection_against_numpy,
+    pins.test_future_inputs_do_not_change_past_outputs,
+]
+
+
+def _battery_fails() -> bool:
+    for check in BATTERY:
+        try:
+            check()
+        except AssertionError:
+            return True
+    return False
+
+
+def test_unmodified_oracle_passes_the_battery():
+    oracle.use_library(None)
+    assert not _battery_fails()
+
+
+@pytest.mark.parametrize("label,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(tmp_path, label, old, new):
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"mutation '{label}' no longer matches the source"
+    mutated = tmp_path / "mutant.cpp"
+    mutated.write_text(text.replace(old, new, 1))
+    lib = oracle.load_library(oracle.compile_source(str(mutated), str(tmp_path / "libmutant.so")))
+    oracle.use_library(lib)
+    try:
+        assert _battery_fails(), f"no pin noticed: {label}"
+    finally:
+        oracle.use_library(None)

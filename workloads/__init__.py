@@ -1,0 +1,164 @@
+"""Seeded synthetic inputs for the five benchmark configurations.
+
+This module holds NO arithmetic of the method (no gates, no recurrence, no
+matrix products): only a counter-based random generator, fp32 -> bf16
+rounding of stored weights, and the table of workload shapes.  It serves both
+the CPU oracle's tests and the GPU tests / bench, so both sides read the same
+tensors; numpy only.
+
+Generator: value(seed, tensor_id, index) = splitmix64 finaliser of a 64-bit
+counter, top 32 bits -> u in (0,1).  Uniform(+-b) = (2u-1)*b; normal = Box-
+Muller on the pair of counters (2*index, 2*index+1).  Everything is computed
+in float64 and rounded once to float32.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+BASE_SEED = 180311389
+
+_GAMMA = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+_CHUNK = 1 << 22
+
+
+def _mix(z: np.ndarray) -> np.ndarray:
+    z = (z ^ (z >> np.uint64(30))) * _M1
+    z = (z ^ (z >> np.uint64(27))) * _M2
+    return z ^ (z >> np.uint64(31))
+
+
+def _stream_key(seed: int, tensor_id: int) -> np.uint64:
+    with np.errstate(over="ignore"):
+        k = _mix(np.array([np.uint64(seed) * _GAMMA + np.uint64(tensor_id)], np.uint64))
+        k = _mix(k + _GAMMA)
+    return k[0]
+
+
+def _unit(key: np.uint64, counters: np.ndarray) -> np.ndarray:
+    """u in (0,1) as float64, from 64-bit counters."""
+    with np.errstate(over="ignore"):
+        bits = _mix(key + counters * _GAMMA)
+    return ((bits >> np.uint64(32)).astype(np.float64) + 0.5) * (1.0 / 4294967296.0)
+
+
+def uniform(seed: int, tensor_id: int, shape, bound: float) -> np.ndarray:
+    """float32 array, entries (2u-1)*bound."""
+    n = int(np.prod(shape))
+    out = np.empty(n, np.float32)
+    key = _stream_key(seed, tensor_id)
+    for s in range(0, n, _CHUNK):
+        e = min(n, s + _CHUNK)
+        u = _unit(key, np.arange(s, e, dtype=np.uint64))
+        out[s:e] = ((2.0 * u - 1.0) * bound).astype(np.float32)
+    return out.reshape(shape)
+
+
+def normal(seed: int, tensor_id: int, shape) -> np.ndarray:
+    """float32 array of N(0,1) draws."""
+    n = int(np.prod(shape))
+    out = np.empty(n, np.float32)
+    key = _stream_key(seed, tensor_id)
+    for s in range(0, n, _CHUNK):
+        e = min(n, s + _CHUNK)
+        i = np.arange(s, e, dtype=np.uint64)
+        u1 = _unit(key, i * np.uint64(2))
+        u2 = _unit(key, i * np.uint64(2) + np.uint64(1))
+        out[s:e] = (np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * math.pi * u2)).astype(np.float32)
+    return out.reshape(shape)
+
+
+def to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# tensor ids within one configuration's seed
+TID_X, TID_FEAT, TID_PROJ, TID_W0 = 1, 2, 3, 100
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    cell: str                 # "sru" | "qrnn"
+    n_layers: int
+    d: int
+    L: int
+    Ts: Tuple[int, ...]
+    k: int = 1                # causal window (QRNN); 1 for SRU
+    wdtype: str = "f32"       # "f32" | "bf16" storage type of the weights
+    d_feat: int = 0           # >0: inputs are d_feat-dim features projected to d
+    index: int = 0            # position in the benchmark's config list
+
+    @property
+    def seed(self) -> int:
+        return BASE_SEED + self.index
+
+    @property
+    def ncol(self) -> int:
+        return self.k * self.d
+
+    def weight_bytes_per_layer(self) -> int:
+        return 3 * self.d * self.ncol * (2 if self.wdtype == "bf16" else 4)
+
+    def algorithmic_bytes_per_step(self, T: int) -> float:
+        """Bytes the method must move per time step for the whole stack: every
+        layer's weights once per T steps, plus each layer's input read and
+        output written (fp32)."""
+        return self.n_layers * (self.weight_bytes_per_layer() / T + 2 * self.d * 4)
+
+    def flops_per_step(self) -> float:
+        return self.n_layers * 2.0 * 3 * self.d * self.ncol
+
+
+CONFIGS: Tuple[Workload, ...] = (
+    Workload("C1_sru1_d128", "sru", 1, 128, 64, (4,), index=0),
+    Workload("C2_sru4_d1024_asr", "sru", 4, 1024, 1000, (1, 4, 16, 64), d_feat=40, index=1),
+    Workload("C3_qrnn4_d1024_k2", "qrnn", 4, 1024, 1000, (1, 4, 16, 64), k=2, index=2),
+    Workload("C4_sru8_d4096", "sru", 8, 4096, 2048, (1, 2, 4, 8, 16, 32, 64, 128), index=3),
+    Workload("C5_qrnn8_d4096_k2_bf16", "qrnn", 8, 4096, 4096, (16, 64, 256), k=2, wdtype="bf16", index=4),
+)
+
+
+def by_name(prefix: str) -> Workload:
+    for c in CONFIGS:
+        if c.name.startswith(prefix):
+            return c
+    raise KeyError(prefix)
+
+
+def layer_weight(wl: Workload, layer: int) -> np.ndarray:
+    """[3d, k*d] weights of one layer, U(+-1/sqrt(k*d)); uint16 bf16 bits if the
+    workload stores bf16."""
+    w = uniform(wl.seed, TID_W0 + layer, (3 * wl.d, wl.ncol), 1.0 / math.sqrt(wl.ncol))
+    return to_bf16_bits(w) if wl.wdtype == "bf16" else w
+
+
+def make_inputs(wl: Workload, L: Optional[int] = None, n_layers: Optional[int] = None):
+    """Returns a dict: W (list), x [L, d] float32 or feat/P for projected
+    inputs.  Biases are zero and c_init is zero in every configuration, so
+    they are not generated.  L / n_layers may be cut down for prefix tests;
+    the draws of a prefix equal the leading draws of the full tensors."""
+    L_full = wl.L
+    L = L_full if L is None else L
+    n_layers = wl.n_layers if n_layers is None else n_layers
+    out = {"W": [layer_weight(wl, l) for l in range(n_layers)]}
+    if wl.d_feat:
+        out["feat"] = normal(wl.seed, TID_FEAT, (L_full, wl.d_feat))[:L].copy()
+        out["P"] = uniform(wl.seed, TID_PROJ, (wl.d, wl.d_feat), 1.0 / math.sqrt(wl.d_feat))
+    else:
+        # time-major, so a prefix in time is a prefix of the counter stream
+        n = L * wl.d
+        out["x"] = normal(wl.seed, TID_X, (n,)).reshape(L, wl.d)
+    return out
