@@ -1,0 +1,124 @@
+/* ssrnn -- single-stream, multi-time-step inference of stacked SRU and QRNN
+ * layers on one MI355X (gfx950).  C ABI of libssrnn.so.
+ *
+ * Method: arXiv 1803.11389.  A block of T consecutive time steps is processed
+ * per pass over a layer's weights (Section 3, Eq. 4): the gate pre-activations
+ * of the T steps are one skinny matrix product U = W * X, X = [x_0 ... x_{T-1}],
+ * so that each weight fetched from memory is used T times; the element-wise
+ * recurrence of Eq. 2 (SRU) / Eq. 3 (QRNN) then ripples over the T steps.
+ * Blocks are taken in streaming order: block b goes through every layer before
+ * block b+1 starts, so the whole stack's weights are re-read once per block.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless it says "host".  W[] and bias[]
+ *     are HOST arrays (n_layers entries) of device pointers.
+ *   - The caller owns every buffer.  *_forward never allocates or frees device
+ *     memory and never synchronises with the host: all work is queued on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     Buffers must stay valid until that work has finished.
+ *   - x, h: time-major [L x d] fp32, row t = time step t.  State c: fp32.
+ *   - Weights: row-major, fp32 (SSRNN_F32) or bfloat16 bit patterns
+ *     (SSRNN_BF16; products accumulate in fp32, state stays fp32).
+ *   - Return value: an ssrnn_status.  On failure nothing (EINVAL, EUNSUPPORTED,
+ *     EWORKSPACE) or an unspecified part (EDEVICE) of the work was queued, and
+ *     ssrnn_last_error() describes the cause.  No exception crosses the ABI.
+ *   - L == 0 is valid: c_final (and xhist_final) receive the initial state.
+ *     T > L is valid (one short block); L need not be a multiple of T.
+ *   - Results do not depend on T, nor on `flags`, beyond fp32 re-association.
+ */
+#ifndef SSRNN_H
+#define SSRNN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SSRNN_OK = 0,
+  SSRNN_EINVAL = 1,       /* NULL required pointer, size out of range              */
+  SSRNN_EUNSUPPORTED = 2, /* shape or option no kernel here can take               */
+  SSRNN_EWORKSPACE = 3,   /* workspace NULL, misaligned or too small               */
+  SSRNN_EDEVICE = 4       /* a HIP call failed, or a kernel reported a failed wait */
+} ssrnn_status;
+
+typedef enum { SSRNN_F32 = 0, SSRNN_BF16 = 1 } ssrnn_wdtype;
+
+/* `flags` of *_forward: 0 picks the schedule and kernel by shape.  The other
+ * values force one (tests and measurements use them); a forced choice that the
+ * shape does not allow returns SSRNN_EUNSUPPORTED. */
+enum {
+  SSRNN_SCHED_AUTO = 0,
+  SSRNN_SCHED_STAGES = 1,     /* one kernel launch per (block, layer) stage                  */
+  SSRNN_SCHED_PERSISTENT = 2, /* one cooperative launch; stages separated by a grid barrier  */
+  SSRNN_SCHED_MASK = 3,
+  SSRNN_KERNEL_AUTO = 0,
+  SSRNN_KERNEL_GENERIC = 1 << 4, /* any d, k, T: one wavefront per output feature            */
+  SSRNN_KERNEL_VALU = 2 << 4,    /* bandwidth kernel, FMA on the vector ALU                  */
+  SSRNN_KERNEL_MFMA = 3 << 4,    /* matrix-core kernel                                       */
+  SSRNN_KERNEL_MASK = 7 << 4
+};
+
+/* Library version, major*10000 + minor*100 + patch.  Host; never fails. */
+int ssrnn_version(void);
+
+/* Description of the last failure on the calling thread (host, static storage,
+ * valid until the next failing call on that thread); "" if none. */
+const char* ssrnn_last_error(void);
+
+/* Bytes of device scratch *_forward needs for this shape (inter-layer
+ * activations for one block, per-layer running state, barrier words).  Host.
+ * Returns 0 for arguments *_forward would reject.  The workspace must be
+ * 256-byte aligned; its contents need not be initialised and are not preserved. */
+size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype);
+
+/* Stacked SRU forward, Eq. 2 per layer, T steps per weight pass (Section 3).
+ *   xh = W x_t;  f = sigma(W_f x_t + b_f);  r = sigma(W_r x_t + b_r);
+ *   c_t = f*c_{t-1} + (1-f)*xh;  h_t = r*tanh(c_t) + (1-r)*x_t.
+ * W[l]     [3d x d] rows [0,d) = W, [d,2d) = W_f, [2d,3d) = W_r.
+ * bias     NULL (all zero), or host array whose entry l is NULL or [2d] = b_f | b_r.
+ * x        [L x d] input of layer 0.
+ * c_init   [n_layers x d], or NULL for zeros.
+ * h        out [L x d]: the top layer's output.
+ * c_final  out [n_layers x d]: state after the last step; may alias c_init.
+ * d >= 1, n_layers >= 1, L >= 0, T >= 1. */
+int sru_forward(const void* const* W, const float* const* bias, const float* x,
+                const float* c_init, float* h, float* c_final, int n_layers,
+                int d, long L, int T, int wdtype, int flags, void* workspace,
+                size_t workspace_bytes, void* stream);
+
+/* Stacked QRNN forward with fo-pooling, Eq. 3 per layer generalised from the
+ * printed window of 2 to a causal window of k inputs:
+ *   u_g = sum_{j<k} W_g^j x_{t-j} (+ b_g);  xh = tanh(u_0); f = sigma(u_1); o = sigma(u_2);
+ *   c_t = f*c_{t-1} + (1-f)*xh;  h_t = o*tanh(c_t).
+ * W[l]        [3d x k*d]; columns [j*d,(j+1)*d) multiply x_{t-j}; rows xh | f | o.
+ * bias        NULL, or host array whose entry l is NULL or [3d] (Eq. 3 has none).
+ * xhist_init  [n_layers x (k-1) x d]: entry (l, j) is layer l's input at lag
+ *             j+1 before step 0; NULL for zeros (causal zero padding).
+ * xhist_final out, same shape, or NULL: the last k-1 inputs of every layer.
+ *             May alias xhist_init.  Ignored when k == 1.
+ * Other arguments as for sru_forward.  k >= 1. */
+int qrnn_forward(const void* const* W, const float* const* bias, const float* x,
+                 const float* c_init, const float* xhist_init, float* h,
+                 float* c_final, float* xhist_final, int n_layers, int d,
+                 long L, int T, int k, int wdtype, int flags, void* workspace,
+                 size_t workspace_bytes, void* stream);
+
+/* y[L x d_out] = feat[L x d_in] * P^T, P row-major [d_out x d_in]; no bias, no
+ * activation.  The input projection of the ASR-shaped benchmark workload
+ * (40-dim features -> d); not part of the paper's method. */
+int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
+                         int d_in, long L, void* stream);
+
+/* Measurement aid: override one launch-geometry choice of the kernels for the
+ * calls that follow, process-wide (not thread-safe; 0 restores the default).
+ * Keys: "valu_F" (features per workgroup), "valu_nw" (wavefronts per
+ * workgroup), "valu_nv" (column chunks per lane).  A value the shape does not
+ * allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
+int ssrnn_tune(const char* key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSRNN_H */

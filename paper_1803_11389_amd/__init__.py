@@ -1,0 +1,220 @@
+"""Python binding of libssrnn (include/ssrnn.h): single-stream, multi-time-step
+inference of stacked SRU / QRNN layers (arXiv 1803.11389) on one MI355X.
+
+This module only marshals arguments: torch supplies device memory and the
+current stream, every step of the computation runs in the HIP kernels of
+libssrnn.so.  There is no CPU or PyTorch fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libssrnn.so")
+
+F32, BF16 = 0, 1
+SCHED_AUTO, SCHED_STAGES, SCHED_PERSISTENT = 0, 1, 2
+KERNEL_AUTO, KERNEL_GENERIC, KERNEL_VALU, KERNEL_MFMA = 0, 1 << 4, 2 << 4, 3 << 4
+
+# every symbol include/ssrnn.h declares
+EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",
+           "qrnn_forward", "ssrnn_linear_forward", "ssrnn_tune")
+
+_lib = None
+
+
+class SsrnnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ssrnn status {status}: {message}")
+        self.status = status
+
+
+def load_library():
+    """dlopen libssrnn.so (built by paper_1803_11389_amd.build) and declare its
+    signatures.  Raises if the library has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_1803_11389_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ip, lp, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_size_t
+    lib.ssrnn_version.restype = ip
+    lib.ssrnn_last_error.restype = ctypes.c_char_p
+    lib.ssrnn_workspace_bytes.restype = sz
+    lib.ssrnn_workspace_bytes.argtypes = [ip] * 5
+    lib.sru_forward.restype = ip
+    lib.sru_forward.argtypes = [vp] * 6 + [ip, ip, lp, ip, ip, ip, vp, sz, vp]
+    lib.qrnn_forward.restype = ip
+    lib.qrnn_forward.argtypes = [vp] * 8 + [ip, ip, lp, ip, ip, ip, ip, vp, sz, vp]
+    lib.ssrnn_linear_forward.restype = ip
+    lib.ssrnn_linear_forward.argtypes = [vp] * 3 + [ip, ip, lp, vp]
+    lib.ssrnn_tune.restype = ip
+    lib.ssrnn_tune.argtypes = [ctypes.c_char_p, ip]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SsrnnError(rc, load_library().ssrnn_last_error().decode())
+
+
+def version() -> int:
+    return load_library().ssrnn_version()
+
+
+def tune(key: str, value: int) -> None:
+    _check(load_library().ssrnn_tune(key.encode(), int(value)))
+
+
+def workspace_bytes(n_layers: int, d: int, k: int, T: int, wdtype: int) -> int:
+    return load_library().ssrnn_workspace_bytes(n_layers, d, k, T, wdtype)
+
+
+def _wdtype(w) -> int:
+    import torch
+    if w.dtype == torch.float32:
+        return F32
+    if w.dtype in (torch.bfloat16, torch.uint16, torch.int16):
+        return BF16
+    raise TypeError(f"weights must be float32 or bfloat16 (or their 16-bit patterns), got {w.dtype}")
+
+
+def _ptr_table(tensors: Optional[Sequence]):
+    """Host array of device pointers (entries may be None)."""
+    if tensors is None:
+        return None
+    t = (ctypes.c_void_p * len(tensors))()
+    for i, a in enumerate(tensors):
+        t[i] = None if a is None else a.data_ptr()
+    return t
+
+
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def _req(t, name, shape=None, dtype=None):
+    import torch
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+class Workspace:
+    """Device scratch for *_forward, reusable across calls of the same or a
+    smaller shape."""
+
+    def __init__(self, nbytes: int, device="cuda"):
+        import torch
+        self.nbytes = int(nbytes)
+        self.buf = torch.empty(max(self.nbytes, 256), dtype=torch.uint8, device=device)
+        assert self.buf.data_ptr() % 256 == 0
+
+    @classmethod
+    def for_shape(cls, n_layers, d, k, T, wdtype, device="cuda"):
+        return cls(workspace_bytes(n_layers, d, k, T, wdtype), device)
+
+
+def _stream_handle(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def sru_forward(W: List, bias: Optional[List], x, c_init=None, *, T: int, flags: int = 0,
+                h=None, c_final=None, workspace: Optional[Workspace] = None, stream=None):
+    """sru_forward of include/ssrnn.h.  W: list of [3d, d] device tensors; bias:
+    None or list of None / [2d]; x: [L, d] fp32.  Returns (h, c_final)."""
+    import torch
+    lib = load_library()
+    n_layers = len(W)
+    d = W[0].shape[1]
+    wdt = _wdtype(W[0])
+    for w in W:
+        _req(w, "W[l]", (3 * d, d))
+    _req(x, "x", None, torch.float32)
+    L = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != d:
+        raise ValueError("x must be [L, d]")
+    _req(c_init, "c_init", (n_layers, d), torch.float32)
+    if bias is not None:
+        for b in bias:
+            _req(b, "bias[l]", (2 * d,), torch.float32)
+    if h is None:
+        h = torch.empty((L, d), dtype=torch.float32, device=x.device)
+    if c_final is None:
+        c_final = torch.empty((n_layers, d), dtype=torch.float32, device=x.device)
+    _req(h, "h", (L, d), torch.float32)
+    _req(c_final, "c_final", (n_layers, d), torch.float32)
+    if workspace is None:
+        workspace = Workspace.for_shape(n_layers, d, 1, T, wdt, x.device)
+    wt, bt = _ptr_table(W), _ptr_table(bias)
+    rc = lib.sru_forward(wt, bt, _p(x), _p(c_init), _p(h), _p(c_final), n_layers, d, L, int(T), wdt,
+                         int(flags), workspace.buf.data_ptr(), workspace.nbytes, _stream_handle(stream))
+    _check(rc)
+    return h, c_final
+
+
+def qrnn_forward(W: List, bias: Optional[List], x, c_init=None, xhist_init=None, *, T: int, k: int = 2,
+                 flags: int = 0, h=None, c_final=None, xhist_final=None,
+                 workspace: Optional[Workspace] = None, stream=None):
+    """qrnn_forward of include/ssrnn.h.  W: list of [3d, k*d]; x: [L, d] fp32.
+    Returns (h, c_final, xhist_final)."""
+    import torch
+    lib = load_library()
+    n_layers = len(W)
+    d = W[0].shape[0] // 3
+    wdt = _wdtype(W[0])
+    for w in W:
+        _req(w, "W[l]", (3 * d, k * d))
+    _req(x, "x", None, torch.float32)
+    L = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != d:
+        raise ValueError("x must be [L, d]")
+    _req(c_init, "c_init", (n_layers, d), torch.float32)
+    _req(xhist_init, "xhist_init", (n_layers, k - 1, d), torch.float32)
+    if bias is not None:
+        for b in bias:
+            _req(b, "bias[l]", (3 * d,), torch.float32)
+    if h is None:
+        h = torch.empty((L, d), dtype=torch.float32, device=x.device)
+    if c_final is None:
+        c_final = torch.empty((n_layers, d), dtype=torch.float32, device=x.device)
+    if xhist_final is None:
+        xhist_final = torch.empty((n_layers, k - 1, d), dtype=torch.float32, device=x.device)
+    _req(h, "h", (L, d), torch.float32)
+    _req(c_final, "c_final", (n_layers, d), torch.float32)
+    _req(xhist_final, "xhist_final", (n_layers, k - 1, d), torch.float32)
+    if workspace is None:
+        workspace = Workspace.for_shape(n_layers, d, k, T, wdt, x.device)
+    wt, bt = _ptr_table(W), _ptr_table(bias)
+    rc = lib.qrnn_forward(wt, bt, _p(x), _p(c_init), _p(xhist_init), _p(h), _p(c_final),
+                          _p(xhist_final) if k > 1 else None, n_layers, d, L, int(T), int(k), wdt,
+                          int(flags), workspace.buf.data_ptr(), workspace.nbytes, _stream_handle(stream))
+    _check(rc)
+    return h, c_final, xhist_final
+
+
+def linear_forward(P, feat, y=None, stream=None):
+    """ssrnn_linear_forward: feat [L, d_in] times P[d_out, d_in]^T -> [L, d_out]."""
+    import torch
+    lib = load_library()
+    _req(P, "P", None, torch.float32)
+    _req(feat, "feat", None, torch.float32)
+    d_out, d_in = P.shape
+    L = feat.shape[0]
+    if y is None:
+        y = torch.empty((L, d_out), dtype=torch.float32, device=feat.device)
+    _req(y, "y", (L, d_out), torch.float32)
+    _check(lib.ssrnn_linear_forward(_p(P), _p(feat), _p(y), d_out, d_in, L, _stream_handle(stream)))
+    return y

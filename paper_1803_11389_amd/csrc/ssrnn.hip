@@ -1,0 +1,346 @@
+// libssrnn host side: argument checking, workspace layout, the (block, layer)
+// stage schedule and kernel selection behind the C ABI of include/ssrnn.h.
+//
+// Schedule (arXiv 1803.11389, Section 3): the sequence is cut into blocks of T
+// steps; block b passes through all layers before block b+1 starts (streaming
+// order), each (block, layer) pair being one "stage" that reads the layer's
+// weights once.  Layer l's output block is handed to layer l+1 through a
+// [(k-1)+T] x d buffer in the workspace whose first k-1 rows keep the tail of
+// the previous block (the QRNN's causal window, Eq. 3).
+#include "../../include/ssrnn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+
+#include "common.hip.h"
+#include "kernel_generic.hip.h"
+#include "kernel_valu.hip.h"
+
+using namespace ssrnn;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                   \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) return fail(SSRNN_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr size_t WS_ALIGN = 256;
+constexpr size_t WS_CONTROL_BYTES = 256;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WorkspaceLayout {
+  size_t act_stride;   // bytes of one inter-layer buffer [(k-1)+T] x d fp32
+  size_t act_offset;   // offset of buffer 0
+  size_t total;
+};
+
+WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T) {
+  WorkspaceLayout w;
+  w.act_stride = align_up(static_cast<size_t>(k - 1 + T) * d * sizeof(float), WS_ALIGN);
+  w.act_offset = WS_CONTROL_BYTES;
+  w.total = w.act_offset + static_cast<size_t>(n_layers > 1 ? n_layers - 1 : 0) * w.act_stride;
+  return w;
+}
+
+bool shape_ok(int n_layers, int d, int k, int T, int wdt) {
+  if (n_layers < 1 || d < 1 || k < 1 || T < 1) return false;
+  if (wdt != SSRNN_F32 && wdt != SSRNN_BF16) return false;
+  if (static_cast<long long>(k) * d > (1LL << 24)) return false;          // 3d * k*d must index in size_t comfortably
+  if (static_cast<long long>(k - 1 + T) * d > (1LL << 40)) return false;
+  return true;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ------------------------------------------------------------ small kernels
+
+__global__ void init_state_kernel(const float* c_init, float* c, long n) {
+  const long i = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
+  if (i < n) c[i] = c_init ? c_init[i] : 0.0f;
+}
+
+// xhist_final[l][j][m] = layer l's input at time L-1-j.  Layer 0 reads x (and
+// xhist_init for times before 0); layer l > 0 reads the hand-off buffer behind
+// layer l-1, whose rows end with the last block.  One thread per (l, m), lags
+// in descending order so that an aliased xhist_init is read before it is
+// overwritten.
+__global__ void gather_history_kernel(const float* x, const float* xhist_init, float* xhist_final,
+                                      const char* act0, size_t act_stride, int n_layers, int d,
+                                      int k, long L, int nt_last) {
+  const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
+  if (id >= static_cast<long>(n_layers) * d) return;
+  const int l = static_cast<int>(id / d);
+  const int m = static_cast<int>(id - static_cast<long>(l) * d);
+  float* out = xhist_final + static_cast<long>(l) * (k - 1) * d;
+  for (int j = k - 2; j >= 0; --j) {
+    float v;
+    if (l == 0) {
+      const long s = L - 1 - j;
+      if (s >= 0) v = x[s * d + m];
+      else v = xhist_init ? xhist_init[(-s - 1) * d + m] : 0.0f;
+    } else {
+      const float* a = reinterpret_cast<const float*>(act0 + static_cast<size_t>(l - 1) * act_stride);
+      v = a[static_cast<long>(k - 1 + nt_last - 1 - j) * d + m];
+    }
+    out[static_cast<long>(j) * d + m] = v;
+  }
+}
+
+__global__ void copy_history_kernel(const float* src, float* dst, long n) {
+  const long i = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
+  if (i < n) dst[i] = src ? src[i] : 0.0f;
+}
+
+// y[t][i] = sum_j P[i][j] * feat[t][j]; one thread per output, d_in is small.
+__global__ void linear_kernel(const float* __restrict__ P, const float* __restrict__ feat,
+                              float* __restrict__ y, int d_out, int d_in, long L) {
+  const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
+  if (id >= L * d_out) return;
+  const long t = id / d_out;
+  const int i = static_cast<int>(id - t * d_out);
+  const float* p = P + static_cast<long>(i) * d_in;
+  const float* f = feat + t * d_in;
+  float acc = 0.0f;
+  for (int j = 0; j < d_in; ++j) acc = fmaf(p[j], f[j], acc);
+  y[id] = acc;
+}
+
+// --------------------------------------------------------------- the plan
+
+enum KernelKind { K_GENERIC = 1, K_VALU = 2, K_MFMA = 3 };
+
+struct Plan {
+  int cell, n_layers, d, k, T, wdt;
+  long L;
+  KernelKind kind;
+  // VALU kernel geometry
+  int tt, nv, nw, npass, F, grid;
+};
+
+int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
+
+bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
+  if (p.wdt != SSRNN_F32 || p.T > 8 || p.d % 256 != 0) return false;
+  if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
+  for (int l = 0; l < p.n_layers; ++l)
+    if (!aligned16(W[l])) return false;
+  p.tt = p.T <= 1 ? 1 : p.T <= 2 ? 2 : p.T <= 4 ? 4 : 8;
+  const int fg = p.tt >= 8 ? 2 : 4;
+  const int q = p.k * p.d / 256;
+  p.nv = (q % 2 == 0 && q >= 16) ? 2 : 1;
+  if (g_tune_valu_nv == 1 || (g_tune_valu_nv == 2 && q % 2 == 0)) p.nv = g_tune_valu_nv;
+  const int qq = q / p.nv;
+  p.nw = 1;
+  for (int w = 1; w <= VALU_MAX_WAVES; ++w)
+    if (qq % w == 0) p.nw = w;
+  if (g_tune_valu_nw >= 1 && g_tune_valu_nw <= VALU_MAX_WAVES && qq % g_tune_valu_nw == 0) p.nw = g_tune_valu_nw;
+  p.npass = qq / p.nw;
+  int F = 0;
+  for (int f = fg; f <= 64; f += fg)
+    if (p.d % f == 0 && f * 256 >= p.d) { F = f; break; }
+  if (F == 0) F = fg;
+  if (g_tune_valu_F > 0 && g_tune_valu_F % fg == 0 && g_tune_valu_F <= 64 && p.d % g_tune_valu_F == 0) F = g_tune_valu_F;
+  if (p.d % F != 0) return false;
+  p.F = F;
+  p.grid = p.d / F;
+  return true;
+}
+
+template <int CELL>
+int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
+  const dim3 grid(p.grid), block(p.nw * 64);
+  const size_t lds = static_cast<size_t>(p.nw) * 3 * p.F * p.tt * sizeof(float);
+#define SSRNN_VALU_CASE(TT_, NV_)                                                          \
+  if (p.tt == TT_ && p.nv == NV_) {                                                        \
+    hipLaunchKernelGGL((stage_valu_kernel<CELL, TT_, NV_>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
+    return SSRNN_OK;                                                                       \
+  }
+  SSRNN_VALU_CASE(1, 1) SSRNN_VALU_CASE(2, 1) SSRNN_VALU_CASE(4, 1) SSRNN_VALU_CASE(8, 1)
+  SSRNN_VALU_CASE(1, 2) SSRNN_VALU_CASE(2, 2) SSRNN_VALU_CASE(4, 2) SSRNN_VALU_CASE(8, 2)
+#undef SSRNN_VALU_CASE
+  return fail(SSRNN_EUNSUPPORTED, "no vector-ALU kernel for T tile %d, NV %d", p.tt, p.nv);
+}
+
+template <int CELL>
+int launch_generic(const Plan& p, const Stage& s, hipStream_t st) {
+  const int grid = (p.d + GENERIC_WAVES - 1) / GENERIC_WAVES;
+  const dim3 g(grid < 4096 ? grid : 4096), b(GENERIC_WAVES * 64);
+  if (p.wdt == SSRNN_BF16)
+    hipLaunchKernelGGL((stage_generic_kernel<CELL, W_BF16>), g, b, 0, st, s, p.d, p.k);
+  else
+    hipLaunchKernelGGL((stage_generic_kernel<CELL, W_F32>), g, b, 0, st, s, p.d, p.k);
+  return SSRNN_OK;
+}
+
+template <int CELL>
+int launch_stage(const Plan& p, const Stage& s, hipStream_t st) {
+  switch (p.kind) {
+    case K_VALU: return launch_valu<CELL>(p, s, st);
+    default: return launch_generic<CELL>(p, s, st);
+  }
+}
+
+int forward(int cell, const void* const* W, const float* const* bias, const float* x,
+            const float* c_init, const float* xhist_init, float* h, float* c_final,
+            float* xhist_final, int n_layers, int d, long L, int T, int k, int wdt, int flags,
+            void* workspace, size_t workspace_bytes, void* stream) {
+  const char* name = cell == CELL_SRU ? "sru_forward" : "qrnn_forward";
+  if (!W) return fail(SSRNN_EINVAL, "%s: W is NULL", name);
+  if (!c_final) return fail(SSRNN_EINVAL, "%s: c_final is NULL", name);
+  if (n_layers < 1 || d < 1 || L < 0 || T < 1 || k < 1)
+    return fail(SSRNN_EINVAL, "%s: need n_layers >= 1, d >= 1, L >= 0, T >= 1, k >= 1 (got %d, %d, %ld, %d, %d)",
+                name, n_layers, d, L, T, k);
+  if (wdt != SSRNN_F32 && wdt != SSRNN_BF16) return fail(SSRNN_EINVAL, "%s: unknown weight type %d", name, wdt);
+  if (!shape_ok(n_layers, d, k, T, wdt)) return fail(SSRNN_EUNSUPPORTED, "%s: shape too large", name);
+  if (L > 0 && (!x || !h)) return fail(SSRNN_EINVAL, "%s: x and h are required when L > 0", name);
+  for (int l = 0; l < n_layers; ++l)
+    if (!W[l]) return fail(SSRNN_EINVAL, "%s: W[%d] is NULL", name, l);
+  const int sched = flags & SSRNN_SCHED_MASK;
+  const int kforce = flags & SSRNN_KERNEL_MASK;
+  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK)) != 0 || sched == 3)
+    return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
+  if (T > L && L > 0) T = static_cast<int>(L);   // one short block; buffers sized by the caller's T still suffice
+  const WorkspaceLayout wl = workspace_layout(n_layers, d, k, T);
+  if (L > 0) {
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % WS_ALIGN) != 0)
+      return fail(SSRNN_EWORKSPACE, "%s: workspace is NULL or not %zu-byte aligned", name, WS_ALIGN);
+    if (workspace_bytes < wl.total)
+      return fail(SSRNN_EWORKSPACE, "%s: workspace has %zu bytes, %zu needed", name, workspace_bytes, wl.total);
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const long nstate = static_cast<long>(n_layers) * d;
+
+  // running state lives in c_final
+  hipLaunchKernelGGL(init_state_kernel, dim3((nstate + 255) / 256), dim3(256), 0, st, c_init, c_final, nstate);
+  if (L == 0) {
+    if (xhist_final && k > 1) {
+      const long n = nstate * (k - 1);
+      if (xhist_final != xhist_init)
+        hipLaunchKernelGGL(copy_history_kernel, dim3((n + 255) / 256), dim3(256), 0, st, xhist_init, xhist_final, n);
+    }
+    HIP_TRY(hipGetLastError());
+    return SSRNN_OK;
+  }
+
+  Plan p{};
+  p.cell = cell; p.n_layers = n_layers; p.d = d; p.k = k; p.T = T; p.wdt = wdt; p.L = L;
+  p.kind = K_GENERIC;
+  if (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU) {
+    if (plan_valu(p, W, x, xhist_init, workspace)) p.kind = K_VALU;
+    else if (kforce == SSRNN_KERNEL_VALU)
+      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 8, d %% 256 == 0 and 16-byte aligned buffers", name);
+  }
+  if (kforce == SSRNN_KERNEL_MFMA) return fail(SSRNN_EUNSUPPORTED, "%s: matrix-core kernel not available for this shape", name);
+  if (sched == SSRNN_SCHED_PERSISTENT) return fail(SSRNN_EUNSUPPORTED, "%s: persistent schedule not available for this shape", name);
+
+  char* act0 = static_cast<char*>(workspace) + wl.act_offset;
+  const long nblocks = (L + T - 1) / T;
+  int nt_last = T;
+  for (long b = 0; b < nblocks; ++b) {
+    const long t0 = b * T;
+    const int nt = static_cast<int>(L - t0 < T ? L - t0 : T);
+    nt_last = nt;
+    for (int l = 0; l < n_layers; ++l) {
+      Stage s{};
+      s.W = W[l];
+      s.bias = (bias && bias[l]) ? bias[l] : nullptr;
+      if (l == 0) {
+        s.xcur = x + t0 * d;
+        s.n_before = static_cast<int>(t0 < k - 1 ? t0 : k - 1);
+        s.older = xhist_init;
+      } else {
+        s.xcur = reinterpret_cast<const float*>(act0 + static_cast<size_t>(l - 1) * wl.act_stride) + static_cast<long>(k - 1) * d;
+        s.n_before = k - 1;
+        s.older = nullptr;
+      }
+      if (l == n_layers - 1) {
+        s.hout = h + t0 * d;
+        s.hist_mode = 0;
+      } else {
+        s.hout = reinterpret_cast<float*>(act0 + static_cast<size_t>(l) * wl.act_stride) + static_cast<long>(k - 1) * d;
+        s.hist_mode = (k > 1) ? (b == 0 ? 2 : 1) : 0;
+        s.hist_shift = T;
+        s.hist_init = xhist_init ? xhist_init + static_cast<long>(l + 1) * (k - 1) * d : nullptr;
+      }
+      s.c = c_final + static_cast<long>(l) * d;
+      s.nt = nt;
+      const int rc = (cell == CELL_SRU) ? launch_stage<CELL_SRU>(p, s, st) : launch_stage<CELL_QRNN>(p, s, st);
+      if (rc != SSRNN_OK) return rc;
+    }
+  }
+  if (xhist_final && k > 1)
+    hipLaunchKernelGGL(gather_history_kernel, dim3((nstate + 255) / 256), dim3(256), 0, st, x, xhist_init, xhist_final,
+                       act0, wl.act_stride, n_layers, d, k, L, nt_last);
+  HIP_TRY(hipGetLastError());
+  return SSRNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ssrnn_version(void) { return 100; }
+
+const char* ssrnn_last_error(void) { return g_last_error.c_str(); }
+
+size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype) {
+  if (!shape_ok(n_layers, d, k, T, wdtype)) return 0;
+  return workspace_layout(n_layers, d, k, T).total;
+}
+
+int sru_forward(const void* const* W, const float* const* bias, const float* x, const float* c_init,
+                float* h, float* c_final, int n_layers, int d, long L, int T, int wdtype, int flags,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  return forward(CELL_SRU, W, bias, x, c_init, nullptr, h, c_final, nullptr, n_layers, d, L, T, 1, wdtype,
+                 flags, workspace, workspace_bytes, stream);
+}
+
+int qrnn_forward(const void* const* W, const float* const* bias, const float* x, const float* c_init,
+                 const float* xhist_init, float* h, float* c_final, float* xhist_final, int n_layers,
+                 int d, long L, int T, int k, int wdtype, int flags, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+  return forward(CELL_QRNN, W, bias, x, c_init, xhist_init, h, c_final, xhist_final, n_layers, d, L, T, k,
+                 wdtype, flags, workspace, workspace_bytes, stream);
+}
+
+int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out, int d_in, long L,
+                         void* stream) {
+  if (!P || !feat || !y) return fail(SSRNN_EINVAL, "ssrnn_linear_forward: NULL pointer");
+  if (d_out < 1 || d_in < 1 || L < 0) return fail(SSRNN_EINVAL, "ssrnn_linear_forward: bad sizes");
+  if (L == 0) return SSRNN_OK;
+  const long n = L * d_out;
+  hipLaunchKernelGGL(linear_kernel, dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream), P, feat, y,
+                     d_out, d_in, L);
+  HIP_TRY(hipGetLastError());
+  return SSRNN_OK;
+}
+
+int ssrnn_tune(const char* key, int value) {
+  if (!key) return fail(SSRNN_EINVAL, "ssrnn_tune: key is NULL");
+  if (!strcmp(key, "valu_F")) g_tune_valu_F = value;
+  else if (!strcmp(key, "valu_nw")) g_tune_valu_nw = value;
+  else if (!strcmp(key, "valu_nv")) g_tune_valu_nv = value;
+  else return fail(SSRNN_EINVAL, "ssrnn_tune: unknown key %s", key);
+  return SSRNN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,41 @@
+"""Helpers for the GPU parity tests: move numpy inputs to the device, call the
+library through its Python binding (a thin ctypes layer over the C ABI), bring
+results back."""
+import numpy as np
+
+
+def to_dev(a):
+    import torch
+    if a is None:
+        return None
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_sru(W, bias, x, c_init=None, T=1, flags=0):
+    import torch
+    import paper_1803_11389_amd as ss
+    Wd = [to_dev(w) for w in W]
+    bd = None if bias is None else [to_dev(b) for b in bias]
+    h, c = ss.sru_forward(Wd, bd, to_dev(np.asarray(x, np.float32)), to_dev(None if c_init is None else np.asarray(c_init, np.float32)),
+                          T=T, flags=flags)
+    torch.cuda.synchronize()
+    return h.cpu().numpy(), c.cpu().numpy()
+
+
+def gpu_qrnn(W, bias, x, c_init=None, xhist_init=None, T=1, k=2, flags=0):
+    import torch
+    import paper_1803_11389_amd as ss
+    Wd = [to_dev(w) for w in W]
+    bd = None if bias is None else [to_dev(b) for b in bias]
+    h, c, xh = ss.qrnn_forward(Wd, bd, to_dev(np.asarray(x, np.float32)),
+                               to_dev(None if c_init is None else np.asarray(c_init, np.float32)),
+                               to_dev(None if xhist_init is None else np.asarray(xhist_init, np.float32)),
+                               T=T, k=k, flags=flags)
+    torch.cuda.synchronize()
+    return h.cpu().numpy(), c.cpu().numpy(), xh.cpu().numpy()
+
+
+def max_abs(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    return float(np.max(np.abs(a - b))) if a.size else 0.0

@@ -1,0 +1,81 @@
+"""The C ABI without a GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before any device work."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1803_11389_amd as ss
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ss.LIB_PATH):
+        from paper_1803_11389_amd.build import build
+        build()
+    return ss.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ssrnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"}
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert names == set(ss.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_workspace_query(lib):
+    assert lib.ssrnn_version() >= 100
+    assert ss.workspace_bytes(1, 128, 1, 4, ss.F32) >= 256
+    one = ss.workspace_bytes(2, 1024, 2, 16, ss.F32)
+    assert one >= 256 + (16 + 1) * 1024 * 4
+    assert ss.workspace_bytes(0, 128, 1, 4, ss.F32) == 0
+    assert ss.workspace_bytes(1, 128, 1, 0, ss.F32) == 0
+    assert ss.workspace_bytes(1, 128, 1, 4, 7) == 0
+
+
+def test_bad_arguments_fail_on_the_host(lib):
+    fake = ctypes.c_void_p(0x1000)     # never dereferenced: every call below fails validation first
+    tab = (ctypes.c_void_p * 1)(0x1000)
+    args = dict(W=tab, bias=None, x=fake, c_init=None, h=fake, c_final=fake, n_layers=1, d=128, L=8, T=4,
+                wdt=0, flags=0, ws=fake, ws_bytes=1 << 20, stream=None)
+
+    def call(**kw):
+        a = dict(args, **kw)
+        return lib.sru_forward(a["W"], a["bias"], a["x"], a["c_init"], a["h"], a["c_final"], a["n_layers"],
+                               a["d"], a["L"], a["T"], a["wdt"], a["flags"], a["ws"], a["ws_bytes"], a["stream"])
+
+    assert call(W=None) == 1 and b"W is NULL" in lib.ssrnn_last_error()
+    assert call(c_final=None) == 1
+    assert call(x=None) == 1
+    assert call(h=None) == 1
+    assert call(n_layers=0) == 1
+    assert call(d=0) == 1
+    assert call(L=-1) == 1
+    assert call(T=0) == 1
+    assert call(wdt=5) == 1
+    assert call(flags=1 << 20) == 1
+    assert call(W=(ctypes.c_void_p * 1)(None)) == 1
+    assert call(ws=None) == 3
+    assert call(ws=ctypes.c_void_p(0x1010)) == 3                 # misaligned
+    assert call(n_layers=2, W=(ctypes.c_void_p * 2)(0x1000, 0x1000), ws_bytes=512) == 3 and b"needed" in lib.ssrnn_last_error()
+    q = lib.qrnn_forward(tab, None, fake, None, None, fake, fake, None, 1, 128, 8, 4, 0, 0, 0, fake, 1 << 20, None)
+    assert q == 1                                               # k = 0
+    assert lib.ssrnn_linear_forward(None, fake, fake, 4, 4, 4, None) == 1
+    assert lib.ssrnn_tune(b"no_such_key", 1) == 1
+    assert lib.ssrnn_tune(None, 1) == 1
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch):
+    monkeypatch.setattr(ss, "_lib", None)
+    monkeypatch.setattr(ss, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libssrnn.so"))
+    with pytest.raises(ImportError):
+        ss.load_library()

@@ -1,0 +1,200 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on the same seeded inputs.
+
+Tolerance (fp32 weights): max |delta| <= 1e-4 on every output and on the final
+state.  bf16 weights: max |delta| / max |reference| <= 2e-2 over the tensor.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from golden_io import load_example
+from gpu_util import gpu_qrnn, gpu_sru, max_abs
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+GENERIC, VALU, MFMA = 1 << 4, 2 << 4, 3 << 4
+STAGES, PERSISTENT = 1, 2
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _sru_inputs(seed, n_layers, d, L, with_bias=True, with_c0=True, scale=1.0, bf16=False):
+    rng = _rng(seed)
+    W = [(rng.uniform(-1, 1, (3 * d, d)) * scale / math.sqrt(d)).astype(np.float32) for _ in range(n_layers)]
+    if bf16:
+        W = [wl.to_bf16_bits(w) for w in W]
+    b = [rng.uniform(-1, 1, 2 * d).astype(np.float32) for _ in range(n_layers)] if with_bias else None
+    x = rng.standard_normal((L, d)).astype(np.float32)
+    c0 = rng.standard_normal((n_layers, d)).astype(np.float32) if with_c0 else None
+    return W, b, x, c0
+
+
+def _qrnn_inputs(seed, n_layers, d, L, k, with_bias=True, with_state=True, scale=1.0, bf16=False):
+    rng = _rng(seed)
+    W = [(rng.uniform(-1, 1, (3 * d, k * d)) * scale / math.sqrt(k * d)).astype(np.float32) for _ in range(n_layers)]
+    if bf16:
+        W = [wl.to_bf16_bits(w) for w in W]
+    b = [rng.uniform(-1, 1, 3 * d).astype(np.float32) for _ in range(n_layers)] if with_bias else None
+    x = rng.standard_normal((L, d)).astype(np.float32)
+    c0 = rng.standard_normal((n_layers, d)).astype(np.float32) if with_state else None
+    xh0 = rng.standard_normal((n_layers, k - 1, d)).astype(np.float32) if with_state else None
+    return W, b, x, c0, xh0
+
+
+def _check_sru(W, b, x, c0, T, flags, tol=TOL):
+    print(f"sru d={W[0].shape[1]} layers={len(W)} L={len(x)} T={T} flags={flags:#x}", flush=True)
+    h_ref, c_ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
+    h, c = gpu_sru(W, b, x, c0, T=T, flags=flags)
+    assert np.all(np.isfinite(h)) and np.all(np.isfinite(c))
+    assert max_abs(h, h_ref) <= tol, f"h: {max_abs(h, h_ref)}"
+    assert max_abs(c, c_ref) <= tol, f"c: {max_abs(c, c_ref)}"
+
+
+def _check_qrnn(W, b, x, c0, xh0, T, k, flags, tol=TOL):
+    print(f"qrnn d={W[0].shape[0] // 3} layers={len(W)} L={len(x)} T={T} k={k} flags={flags:#x}", flush=True)
+    h_ref, c_ref, xh_ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
+    h, c, xh = gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, flags=flags)
+    assert np.all(np.isfinite(h)) and np.all(np.isfinite(c))
+    assert max_abs(h, h_ref) <= tol, f"h: {max_abs(h, h_ref)}"
+    assert max_abs(c, c_ref) <= tol, f"c: {max_abs(c, c_ref)}"
+    if k > 1:
+        # the window of the top layers holds computed activations, layer 0's holds inputs (exact)
+        np.testing.assert_array_equal(xh[0], xh_ref[0].astype(np.float32))
+        assert max_abs(xh, xh_ref) <= tol
+
+
+# ----------------------------------------------------- hand-worked examples
+
+@pytest.mark.parametrize("T", [1, 2, 3, 8])
+def test_hand_examples_on_gpu(T):
+    for name in ("sru_d2_example_a.txt", "sru_d2_example_b.txt"):
+        ex = load_example(name)
+        bias = None if ex["bias"] is None else [ex["bias"]]
+        h, c = gpu_sru([ex["W"]], bias, ex["x"], ex["c_init"][None, :], T=T)
+        assert max_abs(h, ex["h"]) <= 2e-6 and max_abs(c[0], ex["c"][-1]) <= 2e-6
+    ex = load_example("qrnn_d2_k2_example.txt")
+    h, c, xh = gpu_qrnn([ex["W"]], None, ex["x"], ex["c_init"][None, :], None, T=T, k=2)
+    assert max_abs(h, ex["h"]) <= 2e-6 and max_abs(c[0], ex["c"][-1]) <= 2e-6
+    np.testing.assert_array_equal(xh[0, 0], ex["x"][-1])
+
+
+# -------------------------------------------------- generic kernel, any shape
+
+@pytest.mark.parametrize("d,n_layers,L,T", [
+    (2, 1, 5, 1), (5, 2, 11, 4), (64, 3, 33, 16), (128, 2, 19, 64), (70, 2, 21, 7), (130, 1, 9, 9),
+])
+def test_sru_generic_small_shapes(d, n_layers, L, T):
+    W, b, x, c0 = _sru_inputs(100 + d, n_layers, d, L, scale=2.0)
+    _check_sru(W, b, x, c0, T, GENERIC)
+
+
+@pytest.mark.parametrize("d,n_layers,L,T,k", [
+    (2, 1, 5, 1, 2), (5, 2, 11, 4, 2), (64, 3, 33, 16, 3), (128, 2, 19, 64, 2), (70, 2, 21, 7, 1),
+    (6, 2, 2, 1, 4), (6, 3, 9, 2, 4), (33, 2, 40, 1, 3),
+])
+def test_qrnn_generic_small_shapes(d, n_layers, L, T, k):
+    W, b, x, c0, xh0 = _qrnn_inputs(200 + d + k, n_layers, d, L, k, scale=2.0)
+    _check_qrnn(W, b, x, c0, xh0, T, k, GENERIC)
+
+
+def test_generic_bf16_weights_match_exactly_widened_weights():
+    W, b, x, c0 = _sru_inputs(301, 2, 96, 20, bf16=True)
+    _check_sru(W, b, x, c0, 4, GENERIC)      # fp32 activations: the fp32 tolerance holds
+    Wq, bq, xq, cq, xhq = _qrnn_inputs(302, 2, 96, 20, 2, bf16=True)
+    _check_qrnn(Wq, bq, xq, cq, xhq, 5, 2, GENERIC)
+
+
+def test_defaults_zero_state_and_no_bias():
+    W, _, x, _ = _sru_inputs(303, 2, 64, 17, with_bias=False, with_c0=False)
+    _check_sru(W, None, x, None, 4, 0)
+    Wq, _, xq, _, _ = _qrnn_inputs(304, 2, 64, 17, 2, with_bias=False, with_state=False)
+    _check_qrnn(Wq, None, xq, None, None, 4, 2, 0)
+
+
+# ------------------------------------------- bandwidth (vector ALU) kernel
+
+@pytest.mark.parametrize("d,n_layers,L,T", [
+    (256, 2, 13, 1), (256, 1, 10, 2), (512, 3, 21, 4), (768, 2, 19, 3), (1024, 2, 37, 8),
+    (1024, 2, 20, 5), (2048, 2, 9, 4), (4096, 2, 9, 4), (4096, 2, 5, 8), (4096, 1, 3, 1), (1280, 2, 7, 2),
+])
+def test_sru_valu_kernel(d, n_layers, L, T):
+    W, b, x, c0 = _sru_inputs(400 + d + T, n_layers, d, L, scale=2.0)
+    _check_sru(W, b, x, c0, T, VALU | STAGES)
+
+
+@pytest.mark.parametrize("d,n_layers,L,T,k", [
+    (256, 2, 13, 1, 2), (512, 3, 21, 4, 2), (1024, 2, 37, 8, 2), (1024, 2, 11, 2, 3), (256, 2, 6, 1, 4),
+    (2048, 2, 9, 4, 2), (4096, 1, 6, 4, 2), (768, 2, 10, 3, 1),
+])
+def test_qrnn_valu_kernel(d, n_layers, L, T, k):
+    W, b, x, c0, xh0 = _qrnn_inputs(500 + d + T + k, n_layers, d, L, k, scale=2.0)
+    _check_qrnn(W, b, x, c0, xh0, T, k, VALU | STAGES)
+
+
+def test_valu_kernel_refuses_what_it_cannot_take():
+    import paper_1803_11389_amd as ss
+    W, b, x, c0 = _sru_inputs(601, 1, 100, 4)
+    with pytest.raises(ss.SsrnnError) as e:
+        gpu_sru(W, b, x, c0, T=4, flags=VALU)
+    assert e.value.status == 2
+
+
+# ------------------------------------------------------- properties on the GPU
+
+def test_block_size_invariance_on_gpu():
+    W, b, x, c0 = _sru_inputs(701, 3, 512, 50, scale=2.0)
+    ref = gpu_sru(W, b, x, c0, T=1)
+    for T in (2, 3, 4, 7, 8, 16, 49, 50, 64):
+        out = gpu_sru(W, b, x, c0, T=T)
+        assert max_abs(out[0], ref[0]) <= TOL and max_abs(out[1], ref[1]) <= TOL
+
+
+def test_chunk_chaining_on_gpu():
+    W, b, x, c0, xh0 = _qrnn_inputs(702, 3, 256, 30, 3, scale=2.0)
+    h, c, xh = gpu_qrnn(W, b, x, c0, xh0, T=4, k=3)
+    for m in (1, 2, 13):
+        h1, c1, xh1 = gpu_qrnn(W, b, x[:m], c0, xh0, T=4, k=3)
+        h2, c2, xh2 = gpu_qrnn(W, b, x[m:], c1, xh1, T=4, k=3)
+        assert max_abs(np.concatenate([h1, h2]), h) <= 1e-5
+        assert max_abs(c2, c) <= 1e-5 and max_abs(xh2, xh) <= 1e-5
+
+
+def test_empty_sequence_returns_initial_state():
+    W, b, x, c0, xh0 = _qrnn_inputs(703, 2, 64, 0, 3)
+    h, c, xh = gpu_qrnn(W, b, x, c0, xh0, T=4, k=3)
+    assert h.shape == (0, 64)
+    np.testing.assert_array_equal(c, c0)
+    np.testing.assert_array_equal(xh, xh0)
+    Ws, bs, xs, cs = _sru_inputs(704, 2, 64, 0, with_c0=False)
+    _, c = gpu_sru(Ws, bs, xs, None, T=4)
+    np.testing.assert_array_equal(c, np.zeros((2, 64), np.float32))
+
+
+def test_saturated_gates_stay_finite():
+    """Large pre-activations: sigma and tanh saturate to 0 / 1 / -1 without NaN."""
+    d, L = 64, 12
+    rng = _rng(705)
+    W = [(rng.uniform(-1, 1, (3 * d, d)) * 40.0).astype(np.float32)]
+    x = (rng.standard_normal((L, d)) * 10).astype(np.float32)
+    h_ref, c_ref = oracle.sru_forward(W, None, x, T=4)
+    h, c = gpu_sru(W, None, x, None, T=4)
+    assert np.all(np.isfinite(h)) and np.all(np.isfinite(c))
+    scale = max(1.0, float(np.abs(c_ref).max()))
+    assert max_abs(h, h_ref) <= 1e-4 * max(1.0, float(np.abs(h_ref).max()))
+    assert max_abs(c, c_ref) <= 1e-5 * scale * 10
+
+
+# ---------------------------------------------------------------- config C1
+
+def test_config1_sru_d128():
+    c1 = wl.CONFIGS[0]
+    inp = wl.make_inputs(c1)
+    for flags in (0, GENERIC):
+        _check_sru(inp["W"], None, inp["x"], None, c1.Ts[0], flags)
