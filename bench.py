@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: single-stream time steps per second versus block
+size T, and achieved HBM bandwidth against the 8 TB/s peak.
+
+A "step" of this benchmark (--steps K) is one pass of the whole hot path over
+one batch of synthetic input: the full L-step sequence through the whole layer
+stack, in streaming order (block b goes through all layers before block b+1),
+with one block size T.  The headline workload is the benchmark's HBM-roofline
+configuration (8-layer SRU, d = 4096, fp32 weights, 1.6 GB, L = 2048) at T = 4.
+Inputs and weights are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = time steps per second of the headline (T given
+by --T); `sweep` lists the other block sizes of the same workload; `roofline`
+prices the dominant kernel against the HBM peak; `cpu_baseline` is the CPU
+oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
+FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 (vector / matrix) peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C4", help="workload name prefix (C1..C5)")
+    ap.add_argument("--T", type=int, default=4, help="block size of the headline number")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the other block sizes")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--flags", type=int, default=0, help="ssrnn flags (schedule / kernel override)")
+    ap.add_argument("--cpu-sample-steps", type=int, default=0, help="time steps of the CPU sample (0 = auto)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path is a single-stream, single-GPU kernel; run with --gpus 1 "
+              "(sharding across GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1803_11389_amd as ss
+    import workloads as wl
+
+    cfg = wl.by_name(args.config)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    ss.load_library()
+
+    t_gen = time.perf_counter()
+    inp = wl.make_inputs(cfg)
+    W_host = inp["W"]
+    W = [torch.from_numpy(w).to(dev) for w in W_host]
+    if cfg.d_feat:
+        feat = torch.from_numpy(inp["feat"]).to(dev)
+        P = torch.from_numpy(inp["P"]).to(dev)
+        x = ss.linear_forward(P, feat)
+    else:
+        x = torch.from_numpy(inp["x"]).to(dev)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    wdt = ss.BF16 if cfg.wdtype == "bf16" else ss.F32
+    h = torch.empty((cfg.L, cfg.d), dtype=torch.float32, device=dev)
+    c_final = torch.empty((cfg.n_layers, cfg.d), dtype=torch.float32, device=dev)
+    Tmax = max(max(cfg.Ts), args.T)
+    ws = ss.Workspace.for_shape(cfg.n_layers, cfg.d, cfg.k, Tmax, wdt, dev)
+
+    def one_pass(T):
+        if cfg.cell == "sru":
+            ss.sru_forward(W, None, x, None, T=T, flags=args.flags, h=h, c_final=c_final, workspace=ws)
+        else:
+            ss.qrnn_forward(W, None, x, None, None, T=T, k=cfg.k, flags=args.flags, h=h, c_final=c_final, workspace=ws)
+
+    def measure(T, steps, warmup):
+        """Returns (seconds per pass by the host clock, ms per pass by HIP events
+        recorded on the stream the kernels are launched on)."""
+        for _ in range(warmup):
+            one_pass(T)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            one_pass(T)
+        e1.record()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        return dt / steps, e0.elapsed_time(e1) / steps
+
+    def row(T, sec, ev_ms):
+        nstage = cfg.n_layers * ((cfg.L + T - 1) // T)
+        steps_s = cfg.L / sec
+        gbs = cfg.algorithmic_bytes_per_step(T) * steps_s / 1e9
+        tf = cfg.flops_per_step() * steps_s / 1e12
+        return {"T": T, "steps_per_s": round(steps_s, 1), "ms_per_pass": round(sec * 1e3, 3),
+                "us_per_stage": round(ev_ms * 1e3 / nstage, 2), "algorithmic_GBps": round(gbs, 1),
+                "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "TFLOPps": round(tf, 2)}
+
+    sec, ev_ms = measure(args.T, args.steps, args.warmup)
+    head = row(args.T, sec, ev_ms)
+    h_head = h[: min(cfg.L, 512)].clone()
+
+    sweep = []
+    if not args.no_sweep:
+        for T in cfg.Ts:
+            if T == args.T:
+                sweep.append(head)
+                continue
+            s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
+            sweep.append(row(T, s_, e_))
+
+    # dominant kernel: the (block, layer) stage kernel.  Algorithmic bytes of one
+    # stage = the layer's weights once + the input block read + the output block
+    # written (fp32).  Duration = event time of the timed region / stages in it.
+    T = args.T
+    nstage = cfg.n_layers * ((cfg.L + T - 1) // T)
+    stage_bytes = cfg.weight_bytes_per_layer() + 2 * cfg.d * 4 * T
+    stage_s = ev_ms * 1e-3 / nstage
+    achieved = stage_bytes / stage_s / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "stage kernel (one per block and layer)", "launches_per_pass": nstage,
+                "avg_launch_us": round(stage_s * 1e6, 2), "algorithmic_bytes_per_launch": stage_bytes,
+                "weights_vs_infinity_cache": round(cfg.n_layers * cfg.weight_bytes_per_layer() / 256e6, 2)}
+
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        cores = oracle.num_threads()
+        n = args.cpu_sample_steps or (256 if cfg.d >= 4096 else 1000)
+        n = min(n, cfg.L)
+        xs = x[:n].cpu().numpy()
+        t0 = time.perf_counter()
+        if cfg.cell == "sru":
+            h_ref, _ = oracle.sru_forward(W_host, None, xs, T=args.T)
+        else:
+            h_ref, _, _ = oracle.qrnn_forward(W_host, None, xs, T=args.T, k=cfg.k)
+        dt = time.perf_counter() - t0
+        m = min(n, h_head.shape[0])
+        err = float(np.abs(h_head[:m].cpu().numpy().astype(np.float64) - h_ref[:m]).max())
+        cpu = {"value": round(n / dt, 2), "unit": "time steps/s", "cores": cores, "kind": "oracle",
+               "sample": f"first {n} of {cfg.L} time steps, all {cfg.n_layers} layers, T={args.T}, "
+                         f"{dt:.1f} s of CPU time",
+               "gpu_vs_oracle_max_abs_err_on_sample": err}
+
+    out = {
+        "metric": "single-stream time steps/sec vs block T; achieved HBM GB/s (% of peak)",
+        "value": head["steps_per_s"], "unit": "time steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_pass"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if cfg.wdtype == "f32" else "bf16 weights, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_layers}-layer {cfg.cell.upper()}, d={cfg.d}, k={cfg.k}, "
+                               f"L={cfg.L}, batch 1, {cfg.wdtype} weights "
+                               f"({cfg.n_layers * cfg.weight_bytes_per_layer() / 1e9:.2f} GB), block T={args.T}",
+                   "T": args.T, "schedule": "streaming (block-major)", "flags": args.flags},
+        "achieved_hbm_GBps": head["algorithmic_GBps"], "frac_hbm_peak": head["frac_hbm_peak"],
+        "sweep": sweep, "roofline": roofline, "cpu_baseline": cpu,
+        "setup_s": round(t_gen, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
