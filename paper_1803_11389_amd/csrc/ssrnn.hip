@@ -19,6 +19,7 @@
 #include "common.hip.h"
 #include "kernel_generic.hip.h"
 #include "kernel_valu.hip.h"
+#include "kernel_mfma.hip.h"
 
 using namespace ssrnn;
 
@@ -134,6 +135,8 @@ struct Plan {
   KernelKind kind;
   // VALU kernel geometry
   int tt, nv, nw, npass, F, grid;
+  // MFMA kernel geometry
+  int nt_tiles;
 };
 
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
@@ -180,6 +183,38 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
   return fail(SSRNN_EUNSUPPORTED, "no vector-ALU kernel for T tile %d, NV %d", p.tt, p.nv);
 }
 
+bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
+  if (p.d % MFMA_F != 0 || p.T > MFMA_MAX_T) return false;
+  if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
+  for (int l = 0; l < p.n_layers; ++l)
+    if (!aligned16(W[l])) return false;
+  const int tiles = (p.T + 15) / 16;
+  p.nt_tiles = tiles <= 1 ? 1 : tiles <= 2 ? 2 : tiles <= 4 ? 4 : tiles <= 8 ? 8 : 16;
+  const int nw = p.nt_tiles >= 8 ? 4 : 8;
+  const int kstep = p.wdt == SSRNN_BF16 ? 32 : 16;
+  const long ncol = static_cast<long>(p.k) * p.d;
+  if (ncol % (nw * kstep) != 0) return false;
+  if (p.d % (kstep / 4) != 0) return false;
+  return true;
+}
+
+template <int CELL>
+int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
+  const dim3 grid(p.d / MFMA_F);
+#define SSRNN_MFMA_CASE(NT_)                                                                          \
+  if (p.nt_tiles == NT_) {                                                                            \
+    const dim3 block(MfmaCfg<NT_>::NW * 64);                                                          \
+    if (p.wdt == SSRNN_BF16)                                                                          \
+      hipLaunchKernelGGL((stage_mfma_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k);    \
+    else                                                                                              \
+      hipLaunchKernelGGL((stage_mfma_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
+    return SSRNN_OK;                                                                                  \
+  }
+  SSRNN_MFMA_CASE(1) SSRNN_MFMA_CASE(2) SSRNN_MFMA_CASE(4) SSRNN_MFMA_CASE(8) SSRNN_MFMA_CASE(16)
+#undef SSRNN_MFMA_CASE
+  return fail(SSRNN_EUNSUPPORTED, "no matrix-core kernel for %d time tiles", p.nt_tiles);
+}
+
 template <int CELL>
 int launch_generic(const Plan& p, const Stage& s, hipStream_t st) {
   const int grid = (p.d + GENERIC_WAVES - 1) / GENERIC_WAVES;
@@ -195,6 +230,7 @@ template <int CELL>
 int launch_stage(const Plan& p, const Stage& s, hipStream_t st) {
   switch (p.kind) {
     case K_VALU: return launch_valu<CELL>(p, s, st);
+    case K_MFMA: return launch_mfma<CELL>(p, s, st);
     default: return launch_generic<CELL>(p, s, st);
   }
 }
@@ -219,6 +255,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK)) != 0 || sched == 3)
     return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
   if (T > L && L > 0) T = static_cast<int>(L);   // one short block; buffers sized by the caller's T still suffice
+  const int T_asked = T;
   const WorkspaceLayout wl = workspace_layout(n_layers, d, k, T);
   if (L > 0) {
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % WS_ALIGN) != 0)
@@ -249,7 +286,17 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     else if (kforce == SSRNN_KERNEL_VALU)
       return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 8, d %% 256 == 0 and 16-byte aligned buffers", name);
   }
-  if (kforce == SSRNN_KERNEL_MFMA) return fail(SSRNN_EUNSUPPORTED, "%s: matrix-core kernel not available for this shape", name);
+  if (p.kind == K_GENERIC && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_MFMA)) {
+    // the matrix-core kernel accumulates at most MFMA_MAX_T steps per weight pass: longer blocks are cut
+    p.T = T < MFMA_MAX_T ? T : MFMA_MAX_T;
+    if (plan_mfma(p, W, x, xhist_init, workspace)) { p.kind = K_MFMA; T = p.T; }
+    else {
+      p.T = T;
+      if (kforce == SSRNN_KERNEL_MFMA)
+        return fail(SSRNN_EUNSUPPORTED, "%s: matrix-core kernel needs d %% 16 == 0, k*d %% 256 == 0 and 16-byte aligned buffers", name);
+    }
+  }
+  (void)T_asked;
   if (sched == SSRNN_SCHED_PERSISTENT) return fail(SSRNN_EUNSUPPORTED, "%s: persistent schedule not available for this shape", name);
 
   char* act0 = static_cast<char*>(workspace) + wl.act_offset;

@@ -198,3 +198,60 @@ def test_config1_sru_d128():
     inp = wl.make_inputs(c1)
     for flags in (0, GENERIC):
         _check_sru(inp["W"], None, inp["x"], None, c1.Ts[0], flags)
+
+
+# ------------------------------------------------------ matrix-core kernel
+
+BF16_TOL = 2e-2
+
+
+def _rel_err(a, ref):
+    return max_abs(a, ref) / max(float(np.abs(ref).max()), 1e-6)
+
+
+@pytest.mark.parametrize("d,n_layers,L,T", [
+    (256, 2, 40, 16), (256, 2, 23, 9), (512, 2, 70, 32), (1024, 2, 100, 64), (1024, 1, 150, 128),
+    (512, 2, 300, 256), (256, 2, 600, 400), (4096, 1, 20, 16), (128, 2, 33, 12), (2048, 2, 64, 64),
+])
+def test_sru_mfma_kernel_fp32(d, n_layers, L, T):
+    W, b, x, c0 = _sru_inputs(800 + d + T, n_layers, d, L, scale=2.0)
+    _check_sru(W, b, x, c0, T, MFMA | STAGES)
+
+
+@pytest.mark.parametrize("d,n_layers,L,T,k", [
+    (256, 2, 40, 16, 2), (512, 2, 70, 32, 2), (1024, 2, 100, 64, 2), (256, 2, 50, 20, 3),
+    (512, 1, 200, 128, 2), (256, 2, 300, 256, 2), (128, 2, 30, 4, 2), (256, 2, 10, 1, 2),
+])
+def test_qrnn_mfma_kernel_fp32(d, n_layers, L, T, k):
+    W, b, x, c0, xh0 = _qrnn_inputs(900 + d + T + k, n_layers, d, L, k, scale=2.0)
+    _check_qrnn(W, b, x, c0, xh0, T, k, MFMA | STAGES)
+
+
+@pytest.mark.parametrize("cell,d,n_layers,L,T,k", [
+    ("qrnn", 256, 2, 40, 16, 2), ("qrnn", 1024, 3, 100, 64, 2), ("qrnn", 512, 2, 300, 256, 2),
+    ("sru", 512, 2, 70, 32, 1), ("qrnn", 256, 2, 30, 4, 2), ("sru", 1024, 2, 150, 128, 1),
+])
+def test_mfma_kernel_bf16_weights(cell, d, n_layers, L, T, k):
+    """bf16 weights, inputs rounded to bf16 inside the kernel, fp32 accumulation
+    and state: tensor-level relative error against the oracle (which reads the
+    same bf16 weights but keeps activations exact)."""
+    print(f"bf16 {cell} d={d} layers={n_layers} L={L} T={T} k={k}", flush=True)
+    if cell == "sru":
+        W, b, x, c0 = _sru_inputs(1000 + d + T, n_layers, d, L, bf16=True)
+        h_ref, c_ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
+        h, c = gpu_sru(W, b, x, c0, T=T, flags=MFMA)
+    else:
+        W, b, x, c0, xh0 = _qrnn_inputs(1000 + d + T + k, n_layers, d, L, k, bf16=True)
+        h_ref, c_ref, _ = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
+        h, c, _ = gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, flags=MFMA)
+    assert np.all(np.isfinite(h))
+    assert _rel_err(h, h_ref) <= BF16_TOL, _rel_err(h, h_ref)
+    assert _rel_err(c, c_ref) <= BF16_TOL, _rel_err(c, c_ref)
+
+
+def test_kernels_agree_with_each_other():
+    """Same inputs through the generic, vector-ALU and matrix-core kernels."""
+    W, b, x, c0 = _sru_inputs(1101, 2, 512, 24, scale=2.0)
+    outs = [gpu_sru(W, b, x, c0, T=8, flags=f) for f in (GENERIC, VALU, MFMA)]
+    for o in outs[1:]:
+        assert max_abs(o[0], outs[0][0]) <= 2e-5 and max_abs(o[1], outs[0][1]) <= 2e-5
