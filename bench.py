@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--flags", type=int, default=0, help="ssrnn flags (schedule / kernel override)")
     ap.add_argument("--cpu-sample-steps", type=int, default=0, help="time steps of the CPU sample (0 = auto)")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="only run a plain device copy of this many MiB three times and exit: the reference "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     return ap.parse_args()
 
 
@@ -60,6 +63,15 @@ def main():
     cfg = wl.by_name(args.config)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.copy_probe:
+        n = args.copy_probe * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_MiB": args.copy_probe, "bytes_read_per_copy": n * 4, "bytes_written_per_copy": n * 4}))
+        return
     ss.load_library()
 
     t_gen = time.perf_counter()

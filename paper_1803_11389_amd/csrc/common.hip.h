@@ -14,17 +14,18 @@ enum WType : int { W_F32 = 0, W_BF16 = 1 };
 // One (block, layer) stage: nt consecutive time steps of one layer.
 //
 // Input rows are addressed relative to the block's first step: row r >= 0 is
-// step r of the block, row r < 0 is |r| steps before it.  Rows down to
-// -n_before are read from xcur (which therefore must be preceded in memory by
-// that many valid rows); older rows come from `older` (row -n_before-1-m is
-// older[m]) or are zero when `older` is null.
+// step r of the block, row r < 0 is |r| steps before it.  xcur points at row 0
+// of a buffer that holds the k-1 rows before it as well (the causal window of
+// Eq. 3), so every row r >= -(k-1) is a plain load.  xcur16, when not null, is
+// a bf16 copy of the same rows (operand of the bf16 matrix-core kernel).
 struct Stage {
-  const void* W;       // [3d x k*d] row-major
-  const float* bias;   // SRU [2d], QRNN [3d], or null
-  const float* xcur;   // row r at xcur + r*d
-  const float* older;  // [.. x d] or null
-  float* hout;         // [nt x d] rows of the layer's output
-  float* c;            // [d] running cell state, read and written
+  const void* W;           // [3d x k*d] row-major
+  const float* bias;       // SRU [2d], QRNN [3d], or null
+  const float* xcur;       // row r at xcur + r*d, r in [-(k-1), nt)
+  const uint16_t* xcur16;  // same rows as bf16 bit patterns, or null
+  float* hout;             // [nt x d] rows of the layer's output
+  uint16_t* hout16;        // bf16 copy of the output rows for the next layer, or null
+  float* c;                // [d] running cell state, read and written
   // QRNN only: before the stage's outputs are written, the k-1 rows in front
   // of hout (the next layer's view of "earlier inputs") are refreshed by the
   // owner of each column.  hist_mode 0: nothing; 1: rows move down by
@@ -33,7 +34,6 @@ struct Stage {
   const float* hist_init;
   int hist_mode;
   int hist_shift;
-  int n_before;
   int nt;
 };
 
@@ -47,17 +47,18 @@ __device__ __forceinline__ float load_w(const void* W, size_t idx) {
   else return static_cast<const float*>(W)[idx];
 }
 
-// Input element: block-relative row r (may be negative), column m.
+// Input element: block-relative row r >= -(k-1), column m.
 __device__ __forceinline__ float x_at(const Stage& s, int d, int r, int m) {
-  if (r >= -s.n_before) return s.xcur[static_cast<long>(r) * d + m];
-  if (s.older) return s.older[static_cast<long>(-r - 1 - s.n_before) * d + m];
-  return 0.0f;
+  return s.xcur[static_cast<long>(r) * d + m];
 }
 
 __device__ __forceinline__ float4 x_at4(const Stage& s, int d, int r, int m) {
-  if (r >= -s.n_before) return *reinterpret_cast<const float4*>(s.xcur + static_cast<long>(r) * d + m);
-  if (s.older) return *reinterpret_cast<const float4*>(s.older + static_cast<long>(-r - 1 - s.n_before) * d + m);
-  return make_float4(0.f, 0.f, 0.f, 0.f);
+  return *reinterpret_cast<const float4*>(s.xcur + static_cast<long>(r) * d + m);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return static_cast<uint16_t>((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);   // finite inputs only
 }
 
 // Logistic function and tanh from the hardware exp2; absolute error a few
@@ -87,15 +88,18 @@ __device__ __forceinline__ float cell_step(float u0, float u1, float u2, float x
   }
 }
 
-// Refresh the k-1 history rows in front of hout for column i (see Stage).
+// Refresh the k-1 history rows in front of hout for column i (see Stage), in
+// the fp32 buffer and, when present, in its bf16 copy.
 __device__ __forceinline__ void refresh_history(const Stage& s, int d, int k, int i) {
   if (s.hist_mode == 0 || k <= 1) return;
   float* hist = s.hout - static_cast<long>(k - 1) * d;   // rows 0..k-2, ascending time
-  if (s.hist_mode == 1) {
-    for (int r = 0; r < k - 1; ++r) hist[static_cast<long>(r) * d + i] = hist[static_cast<long>(r + s.hist_shift) * d + i];
-  } else {
-    for (int j = 0; j < k - 1; ++j)
-      hist[static_cast<long>(k - 2 - j) * d + i] = s.hist_init ? s.hist_init[static_cast<long>(j) * d + i] : 0.0f;
+  uint16_t* hist16 = s.hout16 ? s.hout16 - static_cast<long>(k - 1) * d : nullptr;
+  for (int r = 0; r < k - 1; ++r) {
+    float v;
+    if (s.hist_mode == 1) v = hist[static_cast<long>(r + s.hist_shift) * d + i];
+    else v = s.hist_init ? s.hist_init[static_cast<long>(k - 2 - r) * d + i] : 0.0f;
+    hist[static_cast<long>(r) * d + i] = v;
+    if (hist16) hist16[static_cast<long>(r) * d + i] = f32_to_bf16_rne(v);
   }
 }
 

@@ -57,6 +57,8 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
   constexpr int CW = KSTEP / 4;                      // columns per lane per step (16 bytes of W)
   constexpr int ESIZE = (WT == W_BF16) ? 2 : 4;
   constexpr int CHUNK = NTC * 256;                   // (time, feature) pairs per epilogue chunk
+  constexpr int NB = (WT == W_BF16 && NT > 8) ? 8 : NT;   // N tiles whose B fragments are fetched together
+  constexpr int NBI = NT / NB;                       // B fetches per k-step
 
   __shared__ float part[NW * 3 * CHUNK];
   __shared__ float g_a[CHUNK], g_b[CHUNK], g_o[CHUNK], g_c[CHUNK];
@@ -85,72 +87,96 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
 #pragma unroll
     for (int n = 0; n < NT; ++n) acc[g][n] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
+  // Row of X a lane reads for N tile n: time n*16 + li.  Rows past the end of a
+  // short block repeat its last row; the columns they produce are never read out.
+  int trow[NT];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) trow[n] = min(n * 16 + li, s.nt - 1);
+
   auto load_a = [&](int ks, float4 (&dst)[3]) {
 #pragma unroll
     for (int g = 0; g < 3; ++g)
       dst[g] = *reinterpret_cast<const float4*>(arow[g] + static_cast<size_t>(ks) * KSTEP * ESIZE);
   };
-  constexpr int NB = (WT == W_BF16 && NT > 4) ? 4 : NT;   // N tiles whose B fragments are live together
+  // B fragments of k-step ks for tiles nb0 .. nb0+NB-1.  Column col0 + ks*KSTEP
+  // lies in lag block j = col / d (lag blocks are multiples of KSTEP wide).
   auto load_b = [&](int ks, int nb0, BFrag<WT> (&b)[NB]) {
     const int col = col0 + ks * KSTEP;
     const int j = col / d;
     const int m = col - j * d;
 #pragma unroll
     for (int n = 0; n < NB; ++n) {
-      const int t = (nb0 + n) * 16 + li;
+      const long off = static_cast<long>(trow[nb0 + n] - j) * d + m;
+      if constexpr (WT == W_BF16) b[n].v = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
+      else b[n].v = *reinterpret_cast<const float4*>(s.xcur + off);
+    }
+  };
+  auto mma = [&](const float4 (&a)[3], const BFrag<WT> (&b)[NB], int nb0) {
+#pragma unroll
+    for (int g = 0; g < 3; ++g) {
       if constexpr (WT == W_BF16) {
-        float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
-        if (t < s.nt) { lo = x_at4(s, d, t - j, m); hi = x_at4(s, d, t - j, m + 4); }
-        bf16x8_t v;
-        v[0] = static_cast<__bf16>(lo.x); v[1] = static_cast<__bf16>(lo.y);
-        v[2] = static_cast<__bf16>(lo.z); v[3] = static_cast<__bf16>(lo.w);
-        v[4] = static_cast<__bf16>(hi.x); v[5] = static_cast<__bf16>(hi.y);
-        v[6] = static_cast<__bf16>(hi.z); v[7] = static_cast<__bf16>(hi.w);
-        b[n].v = v;
+        bf16x8_t av;
+        __builtin_memcpy(&av, &a[g], sizeof av);
+#pragma unroll
+        for (int n = 0; n < NB; ++n)
+          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[n].v, acc[g][nb0 + n], 0, 0, 0);
       } else {
-        b[n].v = (t < s.nt) ? x_at4(s, d, t - j, m) : make_float4(0.f, 0.f, 0.f, 0.f);
+        // The empty asm makes the whole 16-byte fragment one value, so the
+        // compiler keeps its load a single dwordx4 instead of four dword loads.
+        floatx4_t av = floatx4_t{a[g].x, a[g].y, a[g].z, a[g].w};
+        asm volatile("" : "+v"(av));
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[0], b[n].v.x, acc[g][nb0 + n], 0, 0, 0);
+          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[1], b[n].v.y, acc[g][nb0 + n], 0, 0, 0);
+          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[2], b[n].v.z, acc[g][nb0 + n], 0, 0, 0);
+          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[3], b[n].v.w, acc[g][nb0 + n], 0, 0, 0);
+        }
       }
     }
   };
 
-  float4 aring[PF][3];
-#pragma unroll
-  for (int p = 0; p < PF; ++p)
-    if (p < nks) load_a(p, aring[p]);
-
-  for (int ks0 = 0; ks0 < nks; ks0 += PF) {
+  // Main loop over groups of PF k-steps.  A fragments are fetched PF k-steps
+  // ahead and B fragments PFB fetches ahead, each into the register slot its
+  // consumer has just freed, so loads issue in the order they are consumed and
+  // a wait for one step leaves the later steps' loads in flight.  Indices past
+  // the end are clamped to the last step: a few redundant, in-bounds loads
+  // instead of branches in the loop.
+  constexpr int PFB = (NBI == 1) ? PF : 2;
+  static_assert(PFB % NBI == 0 && (PF * NBI) % PFB == 0, "B ring slots must repeat with the unrolled body");
+  const int nmain = (nks / PF) * PF;
+  if (nmain > 0) {
+    float4 aring[PF][3];
+    BFrag<WT> bring[PFB][NB];
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
-      const int ks = ks0 + p;
-      if (ks < nks) {
-        float4 a[3];
+      load_a(p, aring[p]);
 #pragma unroll
-        for (int g = 0; g < 3; ++g) a[g] = aring[p][g];
-        if (ks + PF < nks) load_a(ks + PF, aring[p]);
+      for (int bi = 0; bi < NBI; ++bi)
+        if (p * NBI + bi < PFB) load_b(p, bi * NB, bring[p * NBI + bi]);
+    }
+    for (int ks0 = 0; ks0 < nmain; ks0 += PF) {
 #pragma unroll
-        for (int nb0 = 0; nb0 < NT; nb0 += NB) {
-          BFrag<WT> b[NB];
-          load_b(ks, nb0, b);
+      for (int p = 0; p < PF; ++p) {
+        const int ks = ks0 + p;
 #pragma unroll
-          for (int g = 0; g < 3; ++g) {
-            if constexpr (WT == W_BF16) {
-              bf16x8_t av;
-              __builtin_memcpy(&av, &a[g], sizeof av);
-#pragma unroll
-              for (int n = 0; n < NB; ++n)
-                acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[n].v, acc[g][nb0 + n], 0, 0, 0);
-            } else {
-#pragma unroll
-              for (int n = 0; n < NB; ++n) {
-                acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[g].x, b[n].v.x, acc[g][nb0 + n], 0, 0, 0);
-                acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[g].y, b[n].v.y, acc[g][nb0 + n], 0, 0, 0);
-                acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[g].z, b[n].v.z, acc[g][nb0 + n], 0, 0, 0);
-                acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[g].w, b[n].v.w, acc[g][nb0 + n], 0, 0, 0);
-              }
-            }
-          }
+        for (int bi = 0; bi < NBI; ++bi) {
+          const int slot = (p * NBI + bi) % PFB;
+          mma(aring[p], bring[slot], bi * NB);
+          load_b(min(ks + PFB / NBI, nmain - 1), bi * NB, bring[slot]);
         }
+        load_a(min(ks + PF, nmain - 1), aring[p]);
       }
+    }
+  }
+  for (int ks = nmain; ks < nks; ++ks) {     // remainder (fewer than PF steps): no prefetch
+    float4 a[3];
+    load_a(ks, a);
+#pragma unroll
+    for (int bi = 0; bi < NBI; ++bi) {
+      BFrag<WT> b[NB];
+      load_b(ks, bi * NB, b);
+      mma(a, b, bi * NB);
     }
   }
 
@@ -211,6 +237,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
           float hv = o * tanhf_fast(g_c[e]);
           if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * d + i];
           s.hout[static_cast<long>(t) * d + i] = hv;
+          if (s.hout16) s.hout16[static_cast<long>(t) * d + i] = f32_to_bf16_rne(hv);
         }
       }
       __syncthreads();

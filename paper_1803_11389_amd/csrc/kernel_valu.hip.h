@@ -12,11 +12,15 @@
 //     reads 1 KiB of one row contiguously (global_load_dwordx4);
 //   - the wave's slice of the input block X (4*NV columns x TT steps per lane)
 //     stays in registers for the whole stage when one pass covers all columns;
-//   - per group of FG features a lane accumulates 3*FG*TT partial dot products,
-//     which a transposing butterfly over the 64 lanes (each exchange halves
-//     the number of live values) reduces to one value per lane; the per-wave
-//     sums meet in LDS, and one thread per feature finishes the split-K sum,
-//     applies the gates and runs the T-step recurrence with c in a register.
+//   - weights are double-buffered in registers: the loads of the next group of
+//     FG features are in flight while the current group is multiplied, so the
+//     memory pipe does not drain while the ALU works;
+//   - per group a lane accumulates 3*FG*TT partial dot products, which a
+//     transposing butterfly over the 64 lanes (each exchange halves the number
+//     of live values; lane-permute and DPP instructions, no LDS traffic)
+//     reduces to one value per lane; the per-wave sums meet in LDS, and one
+//     thread per feature finishes the split-K sum, applies the gates and runs
+//     the T-step recurrence with c in a register.
 #pragma once
 
 #include "common.hip.h"
@@ -24,12 +28,7 @@
 namespace ssrnn {
 
 constexpr int VALU_MAX_WAVES = 8;
-
-template <int TT>
-struct ValuCfg {
-  static constexpr int FG = (TT >= 8) ? 2 : 4;   // features per accumulation group
-  static constexpr int VB = FG * TT;             // values per gate entering the butterfly
-};
+constexpr int VALU_FG = 2;        // features per accumulation group
 
 __device__ __forceinline__ float dot4(const float4& w, const float4& x, float acc) {
   acc = fmaf(w.x, x.x, acc);
@@ -39,27 +38,71 @@ __device__ __forceinline__ float dot4(const float4& w, const float4& x, float ac
   return acc;
 }
 
+// ---- wave-wide sums without LDS ---------------------------------------------
+// Step s pairs each lane with a partner that differs in lane bit 5-s:
+//   s = 0: lane ^ 32 (v_permlane32_swap)      s = 1: lane ^ 16 (v_permlane16_swap)
+//   s = 2: lane ^ 15 (DPP row_mirror)         s = 3: lane ^ 7  (DPP row_half_mirror)
+//   s = 4: lane ^ 2  (DPP quad_perm)          s = 5: lane ^ 1  (DPP quad_perm)
+// halve_step(a, b): the lane whose bit 5-s is clear returns a summed over the
+// pair, the other lane returns b summed over the pair.
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float v) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), CTRL, 0xf, 0xf, false));
+}
+
+template <int S>
+__device__ __forceinline__ float partner_value(float v) {
+  static_assert(S >= 2 && S <= 5, "DPP steps only");
+  if constexpr (S == 2) return dpp_get<0x140>(v);       // row_mirror
+  else if constexpr (S == 3) return dpp_get<0x141>(v);  // row_half_mirror
+  else if constexpr (S == 4) return dpp_get<0x4E>(v);   // quad_perm [2,3,0,1]
+  else return dpp_get<0xB1>(v);                         // quad_perm [1,0,3,2]
+}
+
+template <int S>
+__device__ __forceinline__ float halve_step(float a, float b, int lane) {
+  if constexpr (S == 0) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  } else if constexpr (S == 1) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  } else {
+    const bool upper = ((lane >> (5 - S)) & 1) != 0;
+    const float send = upper ? a : b;
+    const float keep = upper ? b : a;
+    return keep + partner_value<S>(send);
+  }
+}
+
+template <int S>
+__device__ __forceinline__ float allreduce_step(float v) {
+  if constexpr (S <= 1) return halve_step<S>(v, v, 0);
+  else return v + partner_value<S>(v);
+}
+
+template <int N, int S>
+__device__ __forceinline__ void butterfly_from(float (&v)[N], int lane) {
+  if constexpr (S < 6) {
+    constexpr int live = (N >> S) > 0 ? (N >> S) : 1;     // values still held before step S
+    if constexpr (live > 1) {
+#pragma unroll
+      for (int q = 0; q < live / 2; ++q) v[q] = halve_step<S>(v[2 * q], v[2 * q + 1], lane);
+    } else {
+      v[0] = allreduce_step<S>(v[0]);
+    }
+    butterfly_from<N, S + 1>(v, lane);
+  }
+}
+
 // Sum N per-lane values over the 64 lanes of the wave.  On return v[0] of lane
 // l holds the complete sum of the value with index butterfly_index<N>(l);
 // lanes that share the top log2(N) lane bits hold the same result.
 template <int N>
 __device__ __forceinline__ void butterfly_sum(float (&v)[N], int lane) {
   static_assert(N >= 1 && N <= 64 && (N & (N - 1)) == 0, "N must be a power of two");
-  int mask = 32;
-#pragma unroll
-  for (int n = N; n > 1; n >>= 1) {
-    const bool upper = (lane & mask) != 0;
-#pragma unroll
-    for (int q = 0; q < n / 2; ++q) {
-      const float a = v[2 * q], b = v[2 * q + 1];
-      const float send = upper ? a : b;
-      const float keep = upper ? b : a;
-      v[q] = keep + __shfl_xor(send, mask, 64);
-    }
-    mask >>= 1;
-  }
-#pragma unroll
-  for (; mask >= 1; mask >>= 1) v[0] += __shfl_xor(v[0], mask, 64);
+  butterfly_from<N, 0>(v, lane);
 }
 
 template <int N>
@@ -70,10 +113,15 @@ __device__ __forceinline__ int butterfly_index(int lane) {
   return idx;
 }
 
-template <int CELL, int TT, int NV>
-__global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s, int d, int k, int F, int npass) {
-  constexpr int FG = ValuCfg<TT>::FG;
-  constexpr int VB = ValuCfg<TT>::VB;
+// ---- the stage kernel ---------------------------------------------------------
+
+// MP = false: one pass covers all k*d columns (npass == 1), X stays in registers.
+// MP = true: several passes; X is re-read (from cache) per feature group and pass.
+template <int CELL, int TT, int NV, bool MP>
+__global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s, int d, int k, int F, int npass_arg) {
+  const int npass = MP ? npass_arg : 1;
+  constexpr int FG = VALU_FG;
+  constexpr int VB = FG * TT;                // values per gate entering the butterfly
   extern __shared__ float part[];            // [NW][3][F][TT]
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -96,44 +144,69 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
         xr[v][t] = (t < s.nt) ? x_at4(s, d, t - j, m) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
-  if (npass == 1) load_x(0);
 
-  for (int g = 0; g < F; g += FG) {
-    float acc[3][VB];
+  // work item it = (feature group, pass): FG features x one pass of columns
+  const int nitems = (F / FG) * npass;
+  auto load_w = [&](float4 (&w)[3][FG][NV], int it) {
+    const int g = (it / npass) * FG;
+    const int p = it - (it / npass) * npass;
 #pragma unroll
     for (int gate = 0; gate < 3; ++gate)
 #pragma unroll
-      for (int q = 0; q < VB; ++q) acc[gate][q] = 0.0f;
+      for (int f = 0; f < FG; ++f) {
+        const float* row = Wf + static_cast<size_t>(gate * d + f0 + g + f) * ncol + p * passw + lanecol;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) w[gate][f][v] = *reinterpret_cast<const float4*>(row + v * 256);
+      }
+  };
 
-    for (int p = 0; p < npass; ++p) {
-      if (npass > 1) load_x(p);
-      float4 w[3][FG][NV];
+  float acc[3][VB];
+  const int idx = butterfly_index<VB>(lane);
+  const bool writer = (lane & (64 / VB - 1)) == 0;
+  auto process = [&](const float4 (&w)[3][FG][NV], int it) {
+    const int gi = it / npass;
+    const int p = it - gi * npass;
+    if (MP) load_x(p);
+    if (!MP || p == 0) {
 #pragma unroll
       for (int gate = 0; gate < 3; ++gate)
 #pragma unroll
-        for (int f = 0; f < FG; ++f) {
-          const float* row = Wf + static_cast<size_t>(gate * d + f0 + g + f) * ncol + p * passw + lanecol;
-#pragma unroll
-          for (int v = 0; v < NV; ++v) w[gate][f][v] = *reinterpret_cast<const float4*>(row + v * 256);
-        }
-#pragma unroll
-      for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-        for (int f = 0; f < FG; ++f)
-#pragma unroll
-          for (int v = 0; v < NV; ++v)
-#pragma unroll
-            for (int t = 0; t < TT; ++t)
-              acc[gate][f * TT + t] = dot4(w[gate][f][v], xr[v][t], acc[gate][f * TT + t]);
+        for (int q = 0; q < VB; ++q) acc[gate][q] = 0.0f;
     }
+#pragma unroll
+    for (int gate = 0; gate < 3; ++gate)
+#pragma unroll
+      for (int f = 0; f < FG; ++f)
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+          for (int t = 0; t < TT; ++t)
+            acc[gate][f * TT + t] = dot4(w[gate][f][v], xr[v][t], acc[gate][f * TT + t]);
+    if (!MP || p == npass - 1) {
+#pragma unroll
+      for (int gate = 0; gate < 3; ++gate) {
+        butterfly_sum<VB>(acc[gate], lane);
+        if (writer) part[((wave * 3 + gate) * F + gi * FG + idx / TT) * TT + idx % TT] = acc[gate][0];
+      }
+    }
+  };
 
-    const int idx = butterfly_index<VB>(lane);
-    const bool writer = (lane & (64 / VB - 1)) == 0;
-#pragma unroll
-    for (int gate = 0; gate < 3; ++gate) {
-      butterfly_sum<VB>(acc[gate], lane);
-      if (writer) part[((wave * 3 + gate) * F + g + idx / TT) * TT + idx % TT] = acc[gate][0];
-    }
+  float4 wa[3][FG][NV], wb[3][FG][NV];
+  load_w(wa, 0);
+  if (!MP) load_x(0);
+  int it = 0;
+  for (; it + 2 < nitems; it += 2) {     // steady state: the other buffer's loads are always in flight
+    load_w(wb, it + 1);
+    process(wa, it);
+    load_w(wa, it + 2);
+    process(wb, it + 1);
+  }
+  if (it + 1 < nitems) {
+    load_w(wb, it + 1);
+    process(wa, it);
+    process(wb, it + 1);
+  } else {
+    process(wa, it);
   }
   __syncthreads();
 

@@ -49,16 +49,25 @@ constexpr size_t WS_CONTROL_BYTES = 256;
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-  size_t act_stride;   // bytes of one inter-layer buffer [(k-1)+T] x d fp32
-  size_t act_offset;   // offset of buffer 0
+  size_t act_stride;    // bytes of one fp32 hand-off buffer [(k-1)+T] x d
+  size_t act_offset;    // buffer 0 = staged input of layer 0, buffer l = output of layer l-1
+  size_t act16_stride;  // bytes of one bf16 copy (0 when the weight type does not use them)
+  size_t act16_offset;
   size_t total;
 };
 
-WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T) {
+// Buffer b (0 <= b < n_layers) holds the input rows of layer b for the current
+// block, preceded by the k-1 rows before it.  Buffer 0 is filled from x by a
+// staging kernel (only when k > 1 or a bf16 copy is needed; otherwise layer 0
+// reads x in place).
+WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
   WorkspaceLayout w;
-  w.act_stride = align_up(static_cast<size_t>(k - 1 + T) * d * sizeof(float), WS_ALIGN);
+  const size_t rows = static_cast<size_t>(k - 1 + T);
+  w.act_stride = align_up(rows * d * sizeof(float), WS_ALIGN);
   w.act_offset = WS_CONTROL_BYTES;
-  w.total = w.act_offset + static_cast<size_t>(n_layers > 1 ? n_layers - 1 : 0) * w.act_stride;
+  w.act16_stride = (wdt == SSRNN_BF16) ? align_up(rows * d * sizeof(uint16_t), WS_ALIGN) : 0;
+  w.act16_offset = w.act_offset + static_cast<size_t>(n_layers) * w.act_stride;
+  w.total = w.act16_offset + static_cast<size_t>(n_layers) * w.act16_stride;
   return w;
 }
 
@@ -99,11 +108,29 @@ __global__ void gather_history_kernel(const float* x, const float* xhist_init, f
       if (s >= 0) v = x[s * d + m];
       else v = xhist_init ? xhist_init[(-s - 1) * d + m] : 0.0f;
     } else {
-      const float* a = reinterpret_cast<const float*>(act0 + static_cast<size_t>(l - 1) * act_stride);
+      const float* a = reinterpret_cast<const float*>(act0 + static_cast<size_t>(l) * act_stride);
       v = a[static_cast<long>(k - 1 + nt_last - 1 - j) * d + m];
     }
     out[static_cast<long>(j) * d + m] = v;
   }
+}
+
+// Rows -(k-1) .. nt-1 of layer 0's input for the block that starts at time t0,
+// gathered from x (times >= 0) and xhist_init / zeros (times < 0), as fp32 and
+// optionally as bf16.  dst / dst16 point at row 0 of their buffers.
+__global__ void stage_input_kernel(const float* x, const float* xhist_init, float* dst, uint16_t* dst16,
+                                   int d, int k, long t0, int nt) {
+  const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
+  const long n = static_cast<long>(k - 1 + nt) * d;
+  if (id >= n) return;
+  const long r = id / d - (k - 1);
+  const int m = static_cast<int>(id % d);
+  const long sabs = t0 + r;
+  float v;
+  if (sabs >= 0) v = x[sabs * d + m];
+  else v = xhist_init ? xhist_init[(-sabs - 1) * d + m] : 0.0f;
+  dst[r * d + m] = v;
+  if (dst16) dst16[r * d + m] = f32_to_bf16_rne(v);
 }
 
 __global__ void copy_history_kernel(const float* src, float* dst, long n) {
@@ -147,7 +174,7 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
   for (int l = 0; l < p.n_layers; ++l)
     if (!aligned16(W[l])) return false;
   p.tt = p.T <= 1 ? 1 : p.T <= 2 ? 2 : p.T <= 4 ? 4 : 8;
-  const int fg = p.tt >= 8 ? 2 : 4;
+  const int fg = VALU_FG;
   const int q = p.k * p.d / 256;
   p.nv = (q % 2 == 0 && q >= 16) ? 2 : 1;
   if (g_tune_valu_nv == 1 || (g_tune_valu_nv == 2 && q % 2 == 0)) p.nv = g_tune_valu_nv;
@@ -174,7 +201,10 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
   const size_t lds = static_cast<size_t>(p.nw) * 3 * p.F * p.tt * sizeof(float);
 #define SSRNN_VALU_CASE(TT_, NV_)                                                          \
   if (p.tt == TT_ && p.nv == NV_) {                                                        \
-    hipLaunchKernelGGL((stage_valu_kernel<CELL, TT_, NV_>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
+    if (p.npass == 1)                                                                      \
+      hipLaunchKernelGGL((stage_valu_kernel<CELL, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
+    else                                                                                   \
+      hipLaunchKernelGGL((stage_valu_kernel<CELL, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
     return SSRNN_OK;                                                                       \
   }
   SSRNN_VALU_CASE(1, 1) SSRNN_VALU_CASE(2, 1) SSRNN_VALU_CASE(4, 1) SSRNN_VALU_CASE(8, 1)
@@ -194,7 +224,7 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   const int kstep = p.wdt == SSRNN_BF16 ? 32 : 16;
   const long ncol = static_cast<long>(p.k) * p.d;
   if (ncol % (nw * kstep) != 0) return false;
-  if (p.d % (kstep / 4) != 0) return false;
+  if (p.d % kstep != 0) return false;   // a k-step never straddles two lag blocks
   return true;
 }
 
@@ -256,7 +286,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
   if (T > L && L > 0) T = static_cast<int>(L);   // one short block; buffers sized by the caller's T still suffice
   const int T_asked = T;
-  const WorkspaceLayout wl = workspace_layout(n_layers, d, k, T);
+  const WorkspaceLayout wl = workspace_layout(n_layers, d, k, T, wdt);
   if (L > 0) {
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % WS_ALIGN) != 0)
       return fail(SSRNN_EWORKSPACE, "%s: workspace is NULL or not %zu-byte aligned", name, WS_ALIGN);
@@ -300,30 +330,40 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   if (sched == SSRNN_SCHED_PERSISTENT) return fail(SSRNN_EUNSUPPORTED, "%s: persistent schedule not available for this shape", name);
 
   char* act0 = static_cast<char*>(workspace) + wl.act_offset;
+  char* act16_0 = static_cast<char*>(workspace) + wl.act16_offset;
+  const bool use16 = (p.kind == K_MFMA && wdt == SSRNN_BF16);
+  const bool stage_in = (k > 1) || use16;
+  auto act = [&](int b) { return reinterpret_cast<float*>(act0 + static_cast<size_t>(b) * wl.act_stride) + static_cast<long>(k - 1) * d; };
+  auto act16 = [&](int b) { return reinterpret_cast<uint16_t*>(act16_0 + static_cast<size_t>(b) * wl.act16_stride) + static_cast<long>(k - 1) * d; };
   const long nblocks = (L + T - 1) / T;
   int nt_last = T;
   for (long b = 0; b < nblocks; ++b) {
     const long t0 = b * T;
     const int nt = static_cast<int>(L - t0 < T ? L - t0 : T);
     nt_last = nt;
+    if (stage_in) {
+      const long n = static_cast<long>(k - 1 + nt) * d;
+      hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0),
+                         use16 ? act16(0) : nullptr, d, k, t0, nt);
+    }
     for (int l = 0; l < n_layers; ++l) {
       Stage s{};
       s.W = W[l];
       s.bias = (bias && bias[l]) ? bias[l] : nullptr;
-      if (l == 0) {
+      if (l == 0 && !stage_in) {
         s.xcur = x + t0 * d;
-        s.n_before = static_cast<int>(t0 < k - 1 ? t0 : k - 1);
-        s.older = xhist_init;
+        s.xcur16 = nullptr;
       } else {
-        s.xcur = reinterpret_cast<const float*>(act0 + static_cast<size_t>(l - 1) * wl.act_stride) + static_cast<long>(k - 1) * d;
-        s.n_before = k - 1;
-        s.older = nullptr;
+        s.xcur = act(l);
+        s.xcur16 = use16 ? act16(l) : nullptr;
       }
       if (l == n_layers - 1) {
         s.hout = h + t0 * d;
+        s.hout16 = nullptr;
         s.hist_mode = 0;
       } else {
-        s.hout = reinterpret_cast<float*>(act0 + static_cast<size_t>(l) * wl.act_stride) + static_cast<long>(k - 1) * d;
+        s.hout = act(l + 1);
+        s.hout16 = use16 ? act16(l + 1) : nullptr;
         s.hist_mode = (k > 1) ? (b == 0 ? 2 : 1) : 0;
         s.hist_shift = T;
         s.hist_init = xhist_init ? xhist_init + static_cast<long>(l + 1) * (k - 1) * d : nullptr;
@@ -351,7 +391,7 @@ const char* ssrnn_last_error(void) { return g_last_error.c_str(); }
 
 size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype) {
   if (!shape_ok(n_layers, d, k, T, wdtype)) return 0;
-  return workspace_layout(n_layers, d, k, T).total;
+  return workspace_layout(n_layers, d, k, T, wdtype).total;
 }
 
 int sru_forward(const void* const* W, const float* const* bias, const float* x, const float* c_init,
