@@ -11,13 +11,14 @@
 //   - the N dimension is time: NT tiles of 16 steps, all accumulated at once
 //     so that W is read once per block (acc = 3*NT tiles of 4 registers);
 //   - the NW wavefronts split the k*d columns; a wave walks its slice in
-//     steps of KSTEP columns (16 for fp32, 32 for bf16).  In one step lane
-//     (i = lane%16, g = lane/16) loads 16 bytes of row i at column offset
-//     g*16B for A, and 16 bytes (or 32, converted to 8 bf16) of time row i at
-//     the same columns for B.  A and B use the same lane -> column map, so any
-//     such map gives the right contraction; this one makes every load a
-//     dwordx4 and every row segment 64 contiguous bytes, straight from the
-//     row-major matrices.  A fragments are prefetched PF steps ahead.
+//     steps of KSTEP columns = 128 bytes of a row (32 fp32 / 64 bf16).  In one
+//     step lane (i = lane%16, g = lane/16) loads the 32 bytes of weight row i
+//     at byte offset g*32 for A, and the same columns of time row i for B
+//     (from the fp32 hand-off buffer, or its bf16 copy).  A and B use the same
+//     lane -> column map, so any such map gives the right contraction; this
+//     one makes every load a dwordx4 and the four lanes of a row cover one
+//     full 128-byte line, straight from the row-major matrices.  A and B
+//     fragments are prefetched PF steps ahead.
 //   - epilogue, 32 steps of time at a time: per-wave partial tiles go to LDS,
 //     all threads finish the split-K sum and apply the gate non-linearities,
 //     one thread per feature runs c_t = f_t*c_{t-1} + b_t serially, all
@@ -38,26 +39,26 @@ template <int NT>
 struct MfmaCfg {
   static constexpr int NW = (NT >= 8) ? 4 : 8;      // waves: 512 registers each when NT is large
   static constexpr int NTC = (NT < 2) ? NT : 2;     // N tiles per epilogue chunk
-  static constexpr int PF = (NT >= 8) ? 2 : 4;      // A prefetch depth (k-steps)
+  static constexpr int PF = (NT <= 2) ? 4 : 2;      // prefetch depth (k-steps of 128 B per row)
 };
 
 template <int WT>
 struct BFrag;
 template <>
-struct BFrag<W_F32> { float4 v; };
+struct BFrag<W_F32> { float4 v[2]; };
 template <>
-struct BFrag<W_BF16> { bf16x8_t v; };
+struct BFrag<W_BF16> { bf16x8_t v[2]; };
 
 template <int CELL, int WT, int NT>
 __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage s, int d, int k) {
   constexpr int NW = MfmaCfg<NT>::NW;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int PF = MfmaCfg<NT>::PF;
-  constexpr int KSTEP = (WT == W_BF16) ? 32 : 16;
-  constexpr int CW = KSTEP / 4;                      // columns per lane per step (16 bytes of W)
+  constexpr int KSTEP = (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
+  constexpr int CW = KSTEP / 4;                      // columns per lane per step (32 bytes of W)
   constexpr int ESIZE = (WT == W_BF16) ? 2 : 4;
   constexpr int CHUNK = NTC * 256;                   // (time, feature) pairs per epilogue chunk
-  constexpr int NB = (WT == W_BF16 && NT > 8) ? 8 : NT;   // N tiles whose B fragments are fetched together
+  constexpr int NB = (NT > 8) ? 4 : NT;              // N tiles whose B fragments are fetched together
   constexpr int NBI = NT / NB;                       // B fetches per k-step
 
   __shared__ float part[NW * 3 * CHUNK];
@@ -93,10 +94,13 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
 #pragma unroll
   for (int n = 0; n < NT; ++n) trow[n] = min(n * 16 + li, s.nt - 1);
 
-  auto load_a = [&](int ks, float4 (&dst)[3]) {
+  auto load_a = [&](int ks, float4 (&dst)[3][2]) {
 #pragma unroll
-    for (int g = 0; g < 3; ++g)
-      dst[g] = *reinterpret_cast<const float4*>(arow[g] + static_cast<size_t>(ks) * KSTEP * ESIZE);
+    for (int g = 0; g < 3; ++g) {
+      const float4* src = reinterpret_cast<const float4*>(arow[g] + static_cast<size_t>(ks) * KSTEP * ESIZE);
+      dst[g][0] = src[0];
+      dst[g][1] = src[1];
+    }
   };
   // B fragments of k-step ks for tiles nb0 .. nb0+NB-1.  Column col0 + ks*KSTEP
   // lies in lag block j = col / d (lag blocks are multiples of KSTEP wide).
@@ -107,31 +111,49 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
 #pragma unroll
     for (int n = 0; n < NB; ++n) {
       const long off = static_cast<long>(trow[nb0 + n] - j) * d + m;
-      if constexpr (WT == W_BF16) b[n].v = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
-      else b[n].v = *reinterpret_cast<const float4*>(s.xcur + off);
+      if constexpr (WT == W_BF16) {
+        b[n].v[0] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
+        b[n].v[1] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off + 8);
+      } else {
+        b[n].v[0] = *reinterpret_cast<const float4*>(s.xcur + off);
+        b[n].v[1] = *reinterpret_cast<const float4*>(s.xcur + off + 4);
+      }
     }
   };
-  auto mma = [&](const float4 (&a)[3], const BFrag<WT> (&b)[NB], int nb0) {
+  // Issue order: consecutive MFMAs write different accumulators (gate, tile
+  // innermost), so an instruction never waits on the one just before it.
+  auto mma = [&](const float4 (&a)[3][2], const BFrag<WT> (&b)[NB], int nb0) {
+    floatx4_t av[3][2];
 #pragma unroll
-    for (int g = 0; g < 3; ++g) {
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        // The empty asm makes the 16-byte fragment one value, so the compiler
+        // keeps its load a single dwordx4 instead of narrower loads.
+        av[g][h] = floatx4_t{a[g][h].x, a[g][h].y, a[g][h].z, a[g][h].w};
+        asm volatile("" : "+v"(av[g][h]));
+      }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
       if constexpr (WT == W_BF16) {
-        bf16x8_t av;
-        __builtin_memcpy(&av, &a[g], sizeof av);
 #pragma unroll
-        for (int n = 0; n < NB; ++n)
-          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[n].v, acc[g][nb0 + n], 0, 0, 0);
-      } else {
-        // The empty asm makes the whole 16-byte fragment one value, so the
-        // compiler keeps its load a single dwordx4 instead of four dword loads.
-        floatx4_t av = floatx4_t{a[g].x, a[g].y, a[g].z, a[g].w};
-        asm volatile("" : "+v"(av));
+        for (int g = 0; g < 3; ++g) {
+          bf16x8_t ab;
+          __builtin_memcpy(&ab, &av[g][h], sizeof ab);
 #pragma unroll
-        for (int n = 0; n < NB; ++n) {
-          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[0], b[n].v.x, acc[g][nb0 + n], 0, 0, 0);
-          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[1], b[n].v.y, acc[g][nb0 + n], 0, 0, 0);
-          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[2], b[n].v.z, acc[g][nb0 + n], 0, 0, 0);
-          acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[3], b[n].v.w, acc[g][nb0 + n], 0, 0, 0);
+          for (int n = 0; n < NB; ++n)
+            acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, b[n].v[h], acc[g][nb0 + n], 0, 0, 0);
         }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int g = 0; g < 3; ++g)
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+              const float bq = q == 0 ? b[n].v[h].x : q == 1 ? b[n].v[h].y : q == 2 ? b[n].v[h].z : b[n].v[h].w;
+              acc[g][nb0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[g][h][q], bq, acc[g][nb0 + n], 0, 0, 0);
+            }
       }
     }
   };
@@ -143,17 +165,17 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
   // the end are clamped to the last step: a few redundant, in-bounds loads
   // instead of branches in the loop.
   constexpr int PFB = (NBI == 1) ? PF : 2;
-  static_assert(PFB % NBI == 0 && (PF * NBI) % PFB == 0, "B ring slots must repeat with the unrolled body");
+  static_assert((PF * NBI) % PFB == 0, "B ring slots must repeat with the unrolled body");
   const int nmain = (nks / PF) * PF;
   if (nmain > 0) {
-    float4 aring[PF][3];
+    float4 aring[PF][3][2];
     BFrag<WT> bring[PFB][NB];
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
       load_a(p, aring[p]);
 #pragma unroll
       for (int bi = 0; bi < NBI; ++bi)
-        if (p * NBI + bi < PFB) load_b(p, bi * NB, bring[p * NBI + bi]);
+        if (p * NBI + bi < PFB) load_b(min(p, nmain - 1), bi * NB, bring[p * NBI + bi]);
     }
     for (int ks0 = 0; ks0 < nmain; ks0 += PF) {
 #pragma unroll
@@ -162,15 +184,16 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
 #pragma unroll
         for (int bi = 0; bi < NBI; ++bi) {
           const int slot = (p * NBI + bi) % PFB;
+          const int nxt = p * NBI + bi + PFB;          // the fetch that reuses this slot
           mma(aring[p], bring[slot], bi * NB);
-          load_b(min(ks + PFB / NBI, nmain - 1), bi * NB, bring[slot]);
+          load_b(min(ks0 + nxt / NBI, nmain - 1), (nxt % NBI) * NB, bring[slot]);
         }
         load_a(min(ks + PF, nmain - 1), aring[p]);
       }
     }
   }
   for (int ks = nmain; ks < nks; ++ks) {     // remainder (fewer than PF steps): no prefetch
-    float4 a[3];
+    float4 a[3][2];
     load_a(ks, a);
 #pragma unroll
     for (int bi = 0; bi < NBI; ++bi) {

@@ -221,7 +221,7 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   const int tiles = (p.T + 15) / 16;
   p.nt_tiles = tiles <= 1 ? 1 : tiles <= 2 ? 2 : tiles <= 4 ? 4 : tiles <= 8 ? 8 : 16;
   const int nw = p.nt_tiles >= 8 ? 4 : 8;
-  const int kstep = p.wdt == SSRNN_BF16 ? 32 : 16;
+  const int kstep = p.wdt == SSRNN_BF16 ? 64 : 32;
   const long ncol = static_cast<long>(p.k) * p.d;
   if (ncol % (nw * kstep) != 0) return false;
   if (p.d % kstep != 0) return false;   // a k-step never straddles two lag blocks

@@ -211,7 +211,7 @@ def _rel_err(a, ref):
 
 @pytest.mark.parametrize("d,n_layers,L,T", [
     (256, 2, 40, 16), (256, 2, 23, 9), (512, 2, 70, 32), (1024, 2, 100, 64), (1024, 1, 150, 128),
-    (512, 2, 300, 256), (256, 2, 600, 400), (4096, 1, 20, 16), (128, 2, 33, 12), (2048, 2, 64, 64),
+    (512, 2, 300, 256), (256, 2, 600, 400), (4096, 1, 20, 16), (256, 2, 33, 12), (2048, 2, 64, 64),
 ])
 def test_sru_mfma_kernel_fp32(d, n_layers, L, T):
     W, b, x, c0 = _sru_inputs(800 + d + T, n_layers, d, L, scale=2.0)
