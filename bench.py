@@ -29,6 +29,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
 FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 (vector / matrix) peak
 
+# HBM bytes per stage launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+# scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same workloads).
+MEASURED_TRAFFIC_BYTES = {
+    ("C4", 4): 202_290_000,     # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
+    ("C4", 64): 216_900_000,    # profiles/stage_mfma_kernel_f32_C4_sru8_d4096_T64.txt
+    ("C5", 64): 211_500_000,    # profiles/stage_mfma_kernel_bf16_C5_qrnn8_d4096_T64.txt
+    ("C5", 256): 224_800_000,   # profiles/stage_mfma_kernel_bf16_C5_qrnn8_d4096_T256.txt
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -144,13 +153,23 @@ def main():
     T = args.T
     nstage = cfg.n_layers * ((cfg.L + T - 1) // T)
     stage_bytes = cfg.weight_bytes_per_layer() + 2 * cfg.d * 4 * T
+    stage_flops = 2.0 * 3 * cfg.d * cfg.ncol * T
     stage_s = ev_ms * 1e-3 / nstage
-    achieved = stage_bytes / stage_s / 1e9
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": "stage kernel (one per block and layer)", "launches_per_pass": nstage,
-                "avg_launch_us": round(stage_s * 1e6, 2), "algorithmic_bytes_per_launch": stage_bytes,
-                "weights_vs_infinity_cache": round(cfg.n_layers * cfg.weight_bytes_per_layer() / 256e6, 2)}
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name[:2], T)) if args.flags == 0 else None
+    common = {"traffic": traffic, "kernel": "stage kernel (one per block and layer)", "launches_per_pass": nstage,
+              "avg_launch_us": round(stage_s * 1e6, 2), "algorithmic_bytes_per_launch": stage_bytes,
+              "flops_per_launch": stage_flops,
+              "weights_vs_infinity_cache": round(cfg.n_layers * cfg.weight_bytes_per_layer() / 256e6, 2)}
+    # fp32 weights cross the ridge (157.3 TFLOP/s against 8 TB/s) near T = 39; bf16 weights stay
+    # HBM-bound up to T = 256 (ridge near T = 310 against 2.5 PFLOP/s)
+    if cfg.wdtype == "f32" and T >= 64:
+        achieved = stage_flops / stage_s / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / FP32_PEAK_TFLOPS, 4), **common}
+    else:
+        achieved = stage_bytes / stage_s / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), **common}
 
     cpu = None
     if not args.no_cpu:
