@@ -21,7 +21,7 @@ enum WType : int { W_F32 = 0, W_BF16 = 1 };
 struct Stage {
   const void* W;           // [3d x k*d] row-major
   const float* bias;       // SRU [2d], QRNN [3d], or null
-  const float* xcur;       // row r at xcur + r*d, r in [-(k-1), nt)
+  const float* xcur;       // row r at xcur + r*ldx, r in [-(k-1), nt)
   const uint16_t* xcur16;  // same rows as bf16 bit patterns, or null
   float* hout;             // [nt x d] rows of the layer's output
   uint16_t* hout16;        // bf16 copy of the output rows for the next layer, or null
@@ -35,6 +35,8 @@ struct Stage {
   int hist_mode;
   int hist_shift;
   int nt;
+  int ldx;                 // row stride (elements) of xcur and xcur16
+  int ldh;                 // row stride (elements) of hout and hout16
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
@@ -49,11 +51,11 @@ __device__ __forceinline__ float load_w(const void* W, size_t idx) {
 
 // Input element: block-relative row r >= -(k-1), column m.
 __device__ __forceinline__ float x_at(const Stage& s, int d, int r, int m) {
-  return s.xcur[static_cast<long>(r) * d + m];
+  return s.xcur[static_cast<long>(r) * s.ldx + m];
 }
 
 __device__ __forceinline__ float4 x_at4(const Stage& s, int d, int r, int m) {
-  return *reinterpret_cast<const float4*>(s.xcur + static_cast<long>(r) * d + m);
+  return *reinterpret_cast<const float4*>(s.xcur + static_cast<long>(r) * s.ldx + m);
 }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -92,14 +94,14 @@ __device__ __forceinline__ float cell_step(float u0, float u1, float u2, float x
 // the fp32 buffer and, when present, in its bf16 copy.
 __device__ __forceinline__ void refresh_history(const Stage& s, int d, int k, int i) {
   if (s.hist_mode == 0 || k <= 1) return;
-  float* hist = s.hout - static_cast<long>(k - 1) * d;   // rows 0..k-2, ascending time
-  uint16_t* hist16 = s.hout16 ? s.hout16 - static_cast<long>(k - 1) * d : nullptr;
+  float* hist = s.hout - static_cast<long>(k - 1) * s.ldh;   // rows 0..k-2, ascending time
+  uint16_t* hist16 = s.hout16 ? s.hout16 - static_cast<long>(k - 1) * s.ldh : nullptr;
   for (int r = 0; r < k - 1; ++r) {
     float v;
-    if (s.hist_mode == 1) v = hist[static_cast<long>(r + s.hist_shift) * d + i];
+    if (s.hist_mode == 1) v = hist[static_cast<long>(r + s.hist_shift) * s.ldh + i];
     else v = s.hist_init ? s.hist_init[static_cast<long>(k - 2 - r) * d + i] : 0.0f;
-    hist[static_cast<long>(r) * d + i] = v;
-    if (hist16) hist16[static_cast<long>(r) * d + i] = f32_to_bf16_rne(v);
+    hist[static_cast<long>(r) * s.ldh + i] = v;
+    if (hist16) hist16[static_cast<long>(r) * s.ldh + i] = f32_to_bf16_rne(v);
   }
 }
 

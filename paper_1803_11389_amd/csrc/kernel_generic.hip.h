@@ -67,8 +67,8 @@ __global__ __launch_bounds__(GENERIC_WAVES * 64) void stage_generic_kernel(Stage
 #pragma unroll
         for (int t = 0; t < GENERIC_TSUB; ++t) {
           if (t < tn) {
-            const float xt = (CELL == CELL_SRU) ? s.xcur[static_cast<long>(ts + t) * d + i] : 0.0f;
-            s.hout[static_cast<long>(ts + t) * d + i] = cell_step<CELL>(a0[t] + b0, a1[t] + b1, a2[t] + b2, xt, c);
+            const float xt = (CELL == CELL_SRU) ? s.xcur[static_cast<long>(ts + t) * s.ldx + i] : 0.0f;
+            s.hout[static_cast<long>(ts + t) * s.ldh + i] = cell_step<CELL>(a0[t] + b0, a1[t] + b1, a2[t] + b2, xt, c);
           }
         }
       }

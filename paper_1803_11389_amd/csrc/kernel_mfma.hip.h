@@ -39,7 +39,8 @@ template <int NT>
 struct MfmaCfg {
   static constexpr int NW = (NT >= 8) ? 4 : 8;      // waves: 512 registers each when NT is large
   static constexpr int NTC = (NT < 2) ? NT : 2;     // N tiles per epilogue chunk
-  static constexpr int PF = (NT <= 2) ? 4 : 2;      // prefetch depth (k-steps of 128 B per row)
+  static constexpr int PF = (NT <= 2) ? 4 : 2;      // prefetch depth (k-steps of 128 B per row), NT = 16 only
+  static constexpr int SLOTS = (NT <= 2) ? 4 : 2;   // fragment ring slots of the interleaved main loop
 };
 
 template <int WT>
@@ -105,12 +106,19 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
   // B fragments of k-step ks for tiles nb0 .. nb0+NB-1.  Column col0 + ks*KSTEP
   // lies in lag block j = col / d (lag blocks are multiples of KSTEP wide).
   auto load_b = [&](int ks, int nb0, BFrag<WT> (&b)[NB]) {
+#ifdef SSRNN_EXP_B0
+    const int col = col0 + (ks & 1) * KSTEP;
+#else
     const int col = col0 + ks * KSTEP;
+#endif
     const int j = col / d;
     const int m = col - j * d;
 #pragma unroll
     for (int n = 0; n < NB; ++n) {
-      const long off = static_cast<long>(trow[nb0 + n] - j) * d + m;
+#ifdef SSRNN_EXP_BCONST
+      if constexpr (WT == W_F32) { b[n].v[0] = make_float4(lane * 1e-3f, 1.f, 2.f, n); b[n].v[1] = b[n].v[0]; continue; }
+#endif
+      const long off = static_cast<long>(trow[nb0 + n] - j) * s.ldx + m;
       if constexpr (WT == W_BF16) {
         b[n].v[0] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
         b[n].v[1] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off + 8);
@@ -158,51 +166,147 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
     }
   };
 
-  // Main loop over groups of PF k-steps.  A fragments are fetched PF k-steps
-  // ahead and B fragments PFB fetches ahead, each into the register slot its
-  // consumer has just freed, so loads issue in the order they are consumed and
-  // a wait for one step leaves the later steps' loads in flight.  Indices past
-  // the end are clamped to the last step: a few redundant, in-bounds loads
-  // instead of branches in the loop.
-  constexpr int PFB = (NBI == 1) ? PF : 2;
-  static_assert((PF * NBI) % PFB == 0, "B ring slots must repeat with the unrolled body");
-  const int nmain = (nks / PF) * PF;
-  if (nmain > 0) {
-    float4 aring[PF][3][2];
-    BFrag<WT> bring[PFB][NB];
+  if constexpr (NBI == 1) {
+    // ---- interleaved main loop (NT <= 8) ---------------------------------
+    // A ring of S slots holds the A and B fragments of S-1 future k-steps.
+    // While step ks is multiplied out of slot ks % S, the loads of step
+    // ks+S-1 go into the slot step ks-1 has just left, one or two at a time
+    // between groups of MFMAs: a wave never queues a burst of loads ahead of
+    // its matrix work, and the loads of later steps stay in flight across the
+    // wait for the current one.  The load cursor stops at the last step
+    // (redundant in-bounds loads instead of branches).
+    constexpr int S = MfmaCfg<NT>::SLOTS;
+    constexpr int NLD = 6 + 2 * NT;                      // 16-byte loads per k-step
+    constexpr int NGRP = (WT == W_BF16) ? 6 : 8;         // MFMA groups per k-step
+    const int nmain = (nks / S) * S;
+    floatx4_t aring[S][3][2];
+    BFrag<WT> bring[S][NT];
+    // load cursor: step number, its lag block j and column m within the block (lane's first column)
+    int lks = 0;
+    int lj = (wave * KS) / d;
+    int lm = wave * KS - lj * d + kg * CW;
+    auto advance_cursor = [&]() {
+      if (lks < nmain - 1) {
+        ++lks;
+        lm += KSTEP;
+        if (lm >= d) { lm -= d; ++lj; }
+      }
+    };
+    auto issue_load = [&](int slot, int i) {
+      if (i < 6) {
+        const int g = i >> 1, h = i & 1;
+        aring[slot][g][h] = *reinterpret_cast<const floatx4_t*>(arow[g] + static_cast<size_t>(lks) * KSTEP * ESIZE + h * 16);
+      } else {
+        const int n = (i - 6) >> 1, h = (i - 6) & 1;
+        const long off = static_cast<long>(trow[n] - lj) * s.ldx + lm + h * (CW / 2);
+        if constexpr (WT == W_BF16) bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
+        else bring[slot][n].v[h] = *reinterpret_cast<const float4*>(s.xcur + off);
+      }
+    };
+    auto mfma_group = [&](int slot, int grp) {
+      if constexpr (WT == W_BF16) {
+        const int h = grp / 3, g = grp - 3 * (grp / 3);
+        floatx4_t av = aring[slot][g][h];
+        asm volatile("" : "+v"(av));       // keeps the fragment's load one dwordx4
+        bf16x8_t ab;
+        __builtin_memcpy(&ab, &av, sizeof ab);
 #pragma unroll
-    for (int p = 0; p < PF; ++p) {
-      load_a(p, aring[p]);
+        for (int n = 0; n < NT; ++n)
+          acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[slot][n].v[h], acc[g][n], 0, 0, 0);
+      } else {
+        const int h = grp >> 2, q = grp & 3;
 #pragma unroll
-      for (int bi = 0; bi < NBI; ++bi)
-        if (p * NBI + bi < PFB) load_b(min(p, nmain - 1), bi * NB, bring[p * NBI + bi]);
+        for (int g = 0; g < 3; ++g) {
+          floatx4_t av = aring[slot][g][h];
+          asm volatile("" : "+v"(av));     // keeps the fragment's load one dwordx4
+#pragma unroll
+          for (int n = 0; n < NT; ++n) {
+            const float4 bv = bring[slot][n].v[h];
+            const float bq = q == 0 ? bv.x : q == 1 ? bv.y : q == 2 ? bv.z : bv.w;
+            acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q], bq, acc[g][n], 0, 0, 0);
+          }
+        }
+      }
+    };
+    if (nmain > 0) {
+#pragma unroll
+      for (int p = 0; p < S - 1; ++p) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) issue_load(p, i);
+        advance_cursor();
+      }
+      for (int ks0 = 0; ks0 < nmain; ks0 += S) {
+#pragma unroll
+        for (int p = 0; p < S; ++p) {
+          const int tslot = (p + S - 1) % S;
+#pragma unroll
+          for (int grp = 0; grp < NGRP; ++grp) {
+            mfma_group(p, grp);
+#pragma unroll
+            for (int i = (grp * NLD) / NGRP; i < ((grp + 1) * NLD) / NGRP; ++i) issue_load(tslot, i);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          advance_cursor();
+        }
+      }
     }
-    for (int ks0 = 0; ks0 < nmain; ks0 += PF) {
+    for (int ks = nmain; ks < nks; ++ks) {     // remainder (fewer than S steps): no prefetch
+      float4 a[3][2];
+      load_a(ks, a);
+      BFrag<WT> b[NB];
+      load_b(ks, 0, b);
+      mma(a, b, 0);
+    }
+  } else {
+  // Main loop over groups of PF k-steps.  A fragments are fetched PF k-steps
+    // ahead and B fragments PFB fetches ahead, each into the register slot its
+    // consumer has just freed, so loads issue in the order they are consumed and
+    // a wait for one step leaves the later steps' loads in flight.  Indices past
+    // the end are clamped to the last step: a few redundant, in-bounds loads
+    // instead of branches in the loop.
+    constexpr int PFB = (NBI == 1) ? PF : 2;
+    static_assert((PF * NBI) % PFB == 0, "B ring slots must repeat with the unrolled body");
+    const int nmain = (nks / PF) * PF;
+    if (nmain > 0) {
+      float4 aring[PF][3][2];
+      BFrag<WT> bring[PFB][NB];
 #pragma unroll
       for (int p = 0; p < PF; ++p) {
-        const int ks = ks0 + p;
+        load_a(p, aring[p]);
 #pragma unroll
-        for (int bi = 0; bi < NBI; ++bi) {
-          const int slot = (p * NBI + bi) % PFB;
-          const int nxt = p * NBI + bi + PFB;          // the fetch that reuses this slot
-          mma(aring[p], bring[slot], bi * NB);
-          load_b(min(ks0 + nxt / NBI, nmain - 1), (nxt % NBI) * NB, bring[slot]);
+        for (int bi = 0; bi < NBI; ++bi)
+          if (p * NBI + bi < PFB) load_b(min(p, nmain - 1), bi * NB, bring[p * NBI + bi]);
+      }
+      for (int ks0 = 0; ks0 < nmain; ks0 += PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+          const int ks = ks0 + p;
+#pragma unroll
+          for (int bi = 0; bi < NBI; ++bi) {
+            const int slot = (p * NBI + bi) % PFB;
+            const int nxt = p * NBI + bi + PFB;          // the fetch that reuses this slot
+            mma(aring[p], bring[slot], bi * NB);
+            load_b(min(ks0 + nxt / NBI, nmain - 1), (nxt % NBI) * NB, bring[slot]);
+          }
+          load_a(min(ks + PF, nmain - 1), aring[p]);
         }
-        load_a(min(ks + PF, nmain - 1), aring[p]);
+      }
+    }
+    for (int ks = nmain; ks < nks; ++ks) {     // remainder (fewer than PF steps): no prefetch
+      float4 a[3][2];
+      load_a(ks, a);
+#pragma unroll
+      for (int bi = 0; bi < NBI; ++bi) {
+        BFrag<WT> b[NB];
+        load_b(ks, bi * NB, b);
+        mma(a, b, bi * NB);
       }
     }
   }
-  for (int ks = nmain; ks < nks; ++ks) {     // remainder (fewer than PF steps): no prefetch
-    float4 a[3][2];
-    load_a(ks, a);
-#pragma unroll
-    for (int bi = 0; bi < NBI; ++bi) {
-      BFrag<WT> b[NB];
-      load_b(ks, bi * NB, b);
-      mma(a, b, bi * NB);
-    }
-  }
 
+#ifdef SSRNN_EXP_NOEPI
+  if (s.nt > 0) { if (acc[0][0][0] == 123.456f) s.hout[0] = acc[1][0][1] + acc[2][NT - 1][2]; return; }
+#endif
   // ---- epilogue: NTC tiles of 16 steps at a time -------------------------
   float b0 = 0.f, b1 = 0.f, b2 = 0.f;          // biases of the feature this thread handles in phase B
   const int fe = tid & 15;                     // feature index of the (time, feature) pairs this thread handles
@@ -258,9 +362,9 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
           const int i = f0 + (e & 15);
           const float o = g_o[e];
           float hv = o * tanhf_fast(g_c[e]);
-          if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * d + i];
-          s.hout[static_cast<long>(t) * d + i] = hv;
-          if (s.hout16) s.hout16[static_cast<long>(t) * d + i] = f32_to_bf16_rne(hv);
+          if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * s.ldx + i];
+          s.hout[static_cast<long>(t) * s.ldh + i] = hv;
+          if (s.hout16) s.hout16[static_cast<long>(t) * s.ldh + i] = f32_to_bf16_rne(hv);
         }
       }
       __syncthreads();

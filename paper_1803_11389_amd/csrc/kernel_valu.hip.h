@@ -19,8 +19,8 @@
 //     transposing butterfly over the 64 lanes (each exchange halves the number
 //     of live values; lane-permute and DPP instructions, no LDS traffic)
 //     reduces to one value per lane; the per-wave sums meet in LDS, and one
-//     thread per feature finishes the split-K sum, applies the gates and runs
-//     the T-step recurrence with c in a register.
+//     thread per (feature, step) finishes the split-K sum and applies the
+//     gates; the T-step recurrence is a prefix scan over T adjacent lanes.
 #pragma once
 
 #include "common.hip.h"
@@ -210,34 +210,44 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
   }
   __syncthreads();
 
-  const int e = threadIdx.x;
-  if (e < F) {
+  // Epilogue: one thread per (feature, step).  Each finishes the split-K sum of
+  // its three pre-activations and applies the gate non-linearities; the
+  // recurrence c_t = f_t c_{t-1} + (1 - f_t) cand_t over the TT steps of a
+  // feature is a prefix scan of affine maps over TT adjacent lanes.
+  for (int id = threadIdx.x; id < F * TT; id += blockDim.x) {
+    const int e = id / TT;
+    const int t = id - e * TT;
     const int i = f0 + e;
-    float u[3][TT];
-#pragma unroll
-    for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-      for (int t = 0; t < TT; ++t) u[gate][t] = 0.0f;
-    for (int w = 0; w < NW; ++w)
-#pragma unroll
-      for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-        for (int t = 0; t < TT; ++t) u[gate][t] += part[((w * 3 + gate) * F + e) * TT + t];
-    float b0 = 0.f, b1 = 0.f, b2 = 0.f;
+    float u0 = 0.f, u1 = 0.f, u2 = 0.f;
+    for (int w = 0; w < NW; ++w) {
+      u0 += part[((w * 3 + 0) * F + e) * TT + t];
+      u1 += part[((w * 3 + 1) * F + e) * TT + t];
+      u2 += part[((w * 3 + 2) * F + e) * TT + t];
+    }
     if (s.bias) {
-      if (CELL == CELL_SRU) { b1 = s.bias[i]; b2 = s.bias[d + i]; }
-      else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
+      if (CELL == CELL_SRU) { u1 += s.bias[i]; u2 += s.bias[d + i]; }
+      else { u0 += s.bias[i]; u1 += s.bias[d + i]; u2 += s.bias[2 * d + i]; }
     }
-    if (CELL == CELL_QRNN) refresh_history(s, d, k, i);
-    float c = s.c[i];
+    if (CELL == CELL_QRNN && t == 0) refresh_history(s, d, k, i);
+    const float f = sigmoidf_fast(u1);
+    const float o = sigmoidf_fast(u2);
+    const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
+    float a = f, b = (1.0f - f) * cand;      // c_t = a * c_{t-1} + b
 #pragma unroll
-    for (int t = 0; t < TT; ++t) {
-      if (t < s.nt) {
-        const float xt = (CELL == CELL_SRU) ? s.xcur[static_cast<long>(t) * d + i] : 0.0f;
-        s.hout[static_cast<long>(t) * d + i] = cell_step<CELL>(u[0][t] + b0, u[1][t] + b1, u[2][t] + b2, xt, c);
-      }
+    for (int off = 1; off < TT; off <<= 1) {
+      const float ap = __shfl_up(a, off, TT);
+      const float bp = __shfl_up(b, off, TT);
+      if (t >= off) { b = fmaf(a, bp, b); a *= ap; }
     }
-    s.c[i] = c;
+    const float c = fmaf(a, s.c[i], b);      // state after step t
+    if (t < s.nt) {
+      float hv = o * tanhf_fast(c);
+      if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * s.ldx + i];
+      s.hout[static_cast<long>(t) * s.ldh + i] = hv;
+    }
+    // every lane of the feature has read the old state (the shuffles above are
+    // wave-synchronous points after that read) before the last step overwrites it
+    if (t == s.nt - 1) s.c[i] = c;
   }
 }
 

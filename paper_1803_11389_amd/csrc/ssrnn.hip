@@ -48,8 +48,11 @@ constexpr size_t WS_CONTROL_BYTES = 256;
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+constexpr int ACT_PAD = 64;   // extra elements per row of a hand-off buffer (256 B fp32, 128 B bf16)
+
 struct WorkspaceLayout {
-  size_t act_stride;    // bytes of one fp32 hand-off buffer [(k-1)+T] x d
+  int ld;               // row stride (elements) of the hand-off buffers: d + ACT_PAD
+  size_t act_stride;    // bytes of one fp32 hand-off buffer [(k-1)+T] x ld
   size_t act_offset;    // buffer 0 = staged input of layer 0, buffer l = output of layer l-1
   size_t act16_stride;  // bytes of one bf16 copy (0 when the weight type does not use them)
   size_t act16_offset;
@@ -63,9 +66,10 @@ struct WorkspaceLayout {
 WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
   WorkspaceLayout w;
   const size_t rows = static_cast<size_t>(k - 1 + T);
-  w.act_stride = align_up(rows * d * sizeof(float), WS_ALIGN);
+  w.ld = d + ACT_PAD;
+  w.act_stride = align_up(rows * w.ld * sizeof(float), WS_ALIGN);
   w.act_offset = WS_CONTROL_BYTES;
-  w.act16_stride = (wdt == SSRNN_BF16) ? align_up(rows * d * sizeof(uint16_t), WS_ALIGN) : 0;
+  w.act16_stride = (wdt == SSRNN_BF16) ? align_up(rows * w.ld * sizeof(uint16_t), WS_ALIGN) : 0;
   w.act16_offset = w.act_offset + static_cast<size_t>(n_layers) * w.act_stride;
   w.total = w.act16_offset + static_cast<size_t>(n_layers) * w.act16_stride;
   return w;
@@ -94,7 +98,7 @@ __global__ void init_state_kernel(const float* c_init, float* c, long n) {
 // in descending order so that an aliased xhist_init is read before it is
 // overwritten.
 __global__ void gather_history_kernel(const float* x, const float* xhist_init, float* xhist_final,
-                                      const char* act0, size_t act_stride, int n_layers, int d,
+                                      const char* act0, size_t act_stride, int ld, int n_layers, int d,
                                       int k, long L, int nt_last) {
   const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
   if (id >= static_cast<long>(n_layers) * d) return;
@@ -109,7 +113,7 @@ __global__ void gather_history_kernel(const float* x, const float* xhist_init, f
       else v = xhist_init ? xhist_init[(-s - 1) * d + m] : 0.0f;
     } else {
       const float* a = reinterpret_cast<const float*>(act0 + static_cast<size_t>(l) * act_stride);
-      v = a[static_cast<long>(k - 1 + nt_last - 1 - j) * d + m];
+      v = a[static_cast<long>(k - 1 + nt_last - 1 - j) * ld + m];
     }
     out[static_cast<long>(j) * d + m] = v;
   }
@@ -119,7 +123,7 @@ __global__ void gather_history_kernel(const float* x, const float* xhist_init, f
 // gathered from x (times >= 0) and xhist_init / zeros (times < 0), as fp32 and
 // optionally as bf16.  dst / dst16 point at row 0 of their buffers.
 __global__ void stage_input_kernel(const float* x, const float* xhist_init, float* dst, uint16_t* dst16,
-                                   int d, int k, long t0, int nt) {
+                                   int ld, int d, int k, long t0, int nt) {
   const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
   const long n = static_cast<long>(k - 1 + nt) * d;
   if (id >= n) return;
@@ -129,8 +133,8 @@ __global__ void stage_input_kernel(const float* x, const float* xhist_init, floa
   float v;
   if (sabs >= 0) v = x[sabs * d + m];
   else v = xhist_init ? xhist_init[(-sabs - 1) * d + m] : 0.0f;
-  dst[r * d + m] = v;
-  if (dst16) dst16[r * d + m] = f32_to_bf16_rne(v);
+  dst[r * ld + m] = v;
+  if (dst16) dst16[r * ld + m] = f32_to_bf16_rne(v);
 }
 
 __global__ void copy_history_kernel(const float* src, float* dst, long n) {
@@ -332,9 +336,9 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   char* act0 = static_cast<char*>(workspace) + wl.act_offset;
   char* act16_0 = static_cast<char*>(workspace) + wl.act16_offset;
   const bool use16 = (p.kind == K_MFMA && wdt == SSRNN_BF16);
-  const bool stage_in = (k > 1) || use16;
-  auto act = [&](int b) { return reinterpret_cast<float*>(act0 + static_cast<size_t>(b) * wl.act_stride) + static_cast<long>(k - 1) * d; };
-  auto act16 = [&](int b) { return reinterpret_cast<uint16_t*>(act16_0 + static_cast<size_t>(b) * wl.act16_stride) + static_cast<long>(k - 1) * d; };
+  const bool stage_in = (k > 1) || p.kind == K_MFMA;   // the matrix-core kernel wants padded rows
+  auto act = [&](int b) { return reinterpret_cast<float*>(act0 + static_cast<size_t>(b) * wl.act_stride) + static_cast<long>(k - 1) * wl.ld; };
+  auto act16 = [&](int b) { return reinterpret_cast<uint16_t*>(act16_0 + static_cast<size_t>(b) * wl.act16_stride) + static_cast<long>(k - 1) * wl.ld; };
   const long nblocks = (L + T - 1) / T;
   int nt_last = T;
   for (long b = 0; b < nblocks; ++b) {
@@ -344,7 +348,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     if (stage_in) {
       const long n = static_cast<long>(k - 1 + nt) * d;
       hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0),
-                         use16 ? act16(0) : nullptr, d, k, t0, nt);
+                         use16 ? act16(0) : nullptr, wl.ld, d, k, t0, nt);
     }
     for (int l = 0; l < n_layers; ++l) {
       Stage s{};
@@ -353,17 +357,21 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       if (l == 0 && !stage_in) {
         s.xcur = x + t0 * d;
         s.xcur16 = nullptr;
+        s.ldx = d;
       } else {
         s.xcur = act(l);
         s.xcur16 = use16 ? act16(l) : nullptr;
+        s.ldx = wl.ld;
       }
       if (l == n_layers - 1) {
         s.hout = h + t0 * d;
         s.hout16 = nullptr;
+        s.ldh = d;
         s.hist_mode = 0;
       } else {
         s.hout = act(l + 1);
         s.hout16 = use16 ? act16(l + 1) : nullptr;
+        s.ldh = wl.ld;
         s.hist_mode = (k > 1) ? (b == 0 ? 2 : 1) : 0;
         s.hist_shift = T;
         s.hist_init = xhist_init ? xhist_init + static_cast<long>(l + 1) * (k - 1) * d : nullptr;
@@ -376,7 +384,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   }
   if (xhist_final && k > 1)
     hipLaunchKernelGGL(gather_history_kernel, dim3((nstate + 255) / 256), dim3(256), 0, st, x, xhist_init, xhist_final,
-                       act0, wl.act_stride, n_layers, d, k, L, nt_last);
+                       act0, wl.act_stride, wl.ld, n_layers, d, k, L, nt_last);
   HIP_TRY(hipGetLastError());
   return SSRNN_OK;
 }
