@@ -58,6 +58,14 @@ __device__ __forceinline__ float4 x_at4(const Stage& s, int d, int r, int m) {
   return *reinterpret_cast<const float4*>(s.xcur + static_cast<long>(r) * s.ldx + m);
 }
 
+// 16-byte weight load with the non-temporal hint: weights are used once per
+// pass, and streaming them past the caches instead of allocating lines there
+// measurably raises the HBM rate of the stage kernels.
+typedef float ssrnn_f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ ssrnn_f32x4 load_stream16(const void* p) {
+  return __builtin_nontemporal_load(static_cast<const ssrnn_f32x4*>(p));
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   const uint32_t u = __float_as_uint(f);
   return static_cast<uint16_t>((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);   // finite inputs only

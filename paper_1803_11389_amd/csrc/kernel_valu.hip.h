@@ -132,6 +132,22 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
   const int lanecol = wave * NV * 256 + lane * 4;
   const float* __restrict__ Wf = static_cast<const float*>(s.W);
 
+  // Global operands of the epilogue (old state, bias, the SRU's own input) are
+  // fetched now, so their latency hides behind the weight stream instead of
+  // sitting in the kernel's tail.
+  float ep_c = 0.f, ep_x = 0.f, ep_b0 = 0.f, ep_b1 = 0.f, ep_b2 = 0.f;
+  if (static_cast<int>(threadIdx.x) < F * TT) {
+    const int e = threadIdx.x / TT;
+    const int t = threadIdx.x - e * TT;
+    const int i = f0 + e;
+    ep_c = s.c[i];
+    if (s.bias) {
+      if (CELL == CELL_SRU) { ep_b1 = s.bias[i]; ep_b2 = s.bias[d + i]; }
+      else { ep_b0 = s.bias[i]; ep_b1 = s.bias[d + i]; ep_b2 = s.bias[2 * d + i]; }
+    }
+    if (CELL == CELL_SRU && t < s.nt) ep_x = s.xcur[static_cast<long>(t) * s.ldx + i];
+  }
+
   float4 xr[NV][TT];
   auto load_x = [&](int p) {
 #pragma unroll
@@ -156,7 +172,10 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
       for (int f = 0; f < FG; ++f) {
         const float* row = Wf + static_cast<size_t>(gate * d + f0 + g + f) * ncol + p * passw + lanecol;
 #pragma unroll
-        for (int v = 0; v < NV; ++v) w[gate][f][v] = *reinterpret_cast<const float4*>(row + v * 256);
+        for (int v = 0; v < NV; ++v) {
+          const ssrnn_f32x4 t4 = load_stream16(row + v * 256);
+          w[gate][f][v] = make_float4(t4[0], t4[1], t4[2], t4[3]);
+        }
       }
   };
 
@@ -224,7 +243,9 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
       u1 += part[((w * 3 + 1) * F + e) * TT + t];
       u2 += part[((w * 3 + 2) * F + e) * TT + t];
     }
-    if (s.bias) {
+    const bool first = id == static_cast<int>(threadIdx.x);     // operands fetched at kernel start
+    if (first) { u0 += ep_b0; u1 += ep_b1; u2 += ep_b2; }
+    else if (s.bias) {
       if (CELL == CELL_SRU) { u1 += s.bias[i]; u2 += s.bias[d + i]; }
       else { u0 += s.bias[i]; u1 += s.bias[d + i]; u2 += s.bias[2 * d + i]; }
     }
@@ -239,10 +260,10 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
       const float bp = __shfl_up(b, off, TT);
       if (t >= off) { b = fmaf(a, bp, b); a *= ap; }
     }
-    const float c = fmaf(a, s.c[i], b);      // state after step t
+    const float c = fmaf(a, first ? ep_c : s.c[i], b);      // state after step t
     if (t < s.nt) {
       float hv = o * tanhf_fast(c);
-      if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * s.ldx + i];
+      if (CELL == CELL_SRU) hv += (1.0f - o) * (first ? ep_x : s.xcur[static_cast<long>(t) * s.ldx + i]);
       s.hout[static_cast<long>(t) * s.ldh + i] = hv;
     }
     // every lane of the feature has read the old state (the shuffles above are
