@@ -196,6 +196,10 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
       if (i < 6) {
         const int g = i >> 1, h = i & 1;
         // plain (cached) load: the two halves of a 128-byte line are fetched by two instructions
+#ifdef SSRNN_EXP_NT2
+        if (h == 1) aring[slot][g][h] = load_stream16(arow[g] + static_cast<size_t>(lks) * KSTEP * ESIZE + h * 16);
+        else
+#endif
         aring[slot][g][h] = *reinterpret_cast<const floatx4_t*>(arow[g] + static_cast<size_t>(lks) * KSTEP * ESIZE + h * 16);
       } else {
         const int n = (i - 6) >> 1, h = (i - 6) & 1;

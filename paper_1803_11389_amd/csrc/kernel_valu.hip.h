@@ -1,4 +1,4 @@
-// Bandwidth kernel for short blocks (T <= 8, fp32 weights): the skinny product
+// Bandwidth kernel for short blocks (T <= 16, fp32 weights): the skinny product
 // U = W * X of Eq. 4 (arXiv 1803.11389) on the vector ALU, with the gates and
 // the recurrence of Eq. 2 / Eq. 3 fused behind it.
 //
@@ -28,7 +28,9 @@
 namespace ssrnn {
 
 constexpr int VALU_MAX_WAVES = 8;
-constexpr int VALU_FG = 2;        // features per accumulation group
+constexpr int VALU_MAX_T = 16;    // longest block this kernel takes
+// features per accumulation group: two, or one when 16 steps fill the registers
+constexpr int valu_fg(int tt) { return tt >= 16 ? 1 : 2; }
 
 __device__ __forceinline__ float dot4(const float4& w, const float4& x, float acc) {
   acc = fmaf(w.x, x.x, acc);
@@ -120,7 +122,7 @@ __device__ __forceinline__ int butterfly_index(int lane) {
 template <int CELL, int TT, int NV, bool MP>
 __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s, int d, int k, int F, int npass_arg) {
   const int npass = MP ? npass_arg : 1;
-  constexpr int FG = VALU_FG;
+  constexpr int FG = valu_fg(TT);
   constexpr int VB = FG * TT;                // values per gate entering the butterfly
   extern __shared__ float part[];            // [NW][3][F][TT]
   const int lane = threadIdx.x & 63;

@@ -173,12 +173,12 @@ struct Plan {
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
-  if (p.wdt != SSRNN_F32 || p.T > 8 || p.d % 256 != 0) return false;
+  if (p.wdt != SSRNN_F32 || p.T > VALU_MAX_T || p.d % 256 != 0) return false;
   if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
   for (int l = 0; l < p.n_layers; ++l)
     if (!aligned16(W[l])) return false;
-  p.tt = p.T <= 1 ? 1 : p.T <= 2 ? 2 : p.T <= 4 ? 4 : 8;
-  const int fg = VALU_FG;
+  p.tt = p.T <= 1 ? 1 : p.T <= 2 ? 2 : p.T <= 4 ? 4 : p.T <= 8 ? 8 : 16;
+  const int fg = 2;   // F is kept even for every T so that one workgroup shape serves all block sizes
   const int q = p.k * p.d / 256;
   p.nv = (q % 2 == 0 && q >= 16) ? 2 : 1;
   if (g_tune_valu_nv == 1 || (g_tune_valu_nv == 2 && q % 2 == 0)) p.nv = g_tune_valu_nv;
@@ -211,8 +211,8 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
       hipLaunchKernelGGL((stage_valu_kernel<CELL, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
     return SSRNN_OK;                                                                       \
   }
-  SSRNN_VALU_CASE(1, 1) SSRNN_VALU_CASE(2, 1) SSRNN_VALU_CASE(4, 1) SSRNN_VALU_CASE(8, 1)
-  SSRNN_VALU_CASE(1, 2) SSRNN_VALU_CASE(2, 2) SSRNN_VALU_CASE(4, 2) SSRNN_VALU_CASE(8, 2)
+  SSRNN_VALU_CASE(1, 1) SSRNN_VALU_CASE(2, 1) SSRNN_VALU_CASE(4, 1) SSRNN_VALU_CASE(8, 1) SSRNN_VALU_CASE(16, 1)
+  SSRNN_VALU_CASE(1, 2) SSRNN_VALU_CASE(2, 2) SSRNN_VALU_CASE(4, 2) SSRNN_VALU_CASE(8, 2) SSRNN_VALU_CASE(16, 2)
 #undef SSRNN_VALU_CASE
   return fail(SSRNN_EUNSUPPORTED, "no vector-ALU kernel for T tile %d, NV %d", p.tt, p.nv);
 }
@@ -318,7 +318,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   if (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU) {
     if (plan_valu(p, W, x, xhist_init, workspace)) p.kind = K_VALU;
     else if (kforce == SSRNN_KERNEL_VALU)
-      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 8, d %% 256 == 0 and 16-byte aligned buffers", name);
+      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 16, d %% 256 == 0 and 16-byte aligned buffers", name);
   }
   if (p.kind == K_GENERIC && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_MFMA)) {
     // the matrix-core kernel accumulates at most MFMA_MAX_T steps per weight pass: longer blocks are cut

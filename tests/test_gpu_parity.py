@@ -123,6 +123,7 @@ def test_defaults_zero_state_and_no_bias():
 @pytest.mark.parametrize("d,n_layers,L,T", [
     (256, 2, 13, 1), (256, 1, 10, 2), (512, 3, 21, 4), (768, 2, 19, 3), (1024, 2, 37, 8),
     (1024, 2, 20, 5), (2048, 2, 9, 4), (4096, 2, 9, 4), (4096, 2, 5, 8), (4096, 1, 3, 1), (1280, 2, 7, 2),
+    (1024, 2, 50, 16), (512, 2, 30, 12), (4096, 2, 20, 16), (256, 3, 40, 9),
 ])
 def test_sru_valu_kernel(d, n_layers, L, T):
     W, b, x, c0 = _sru_inputs(400 + d + T, n_layers, d, L, scale=2.0)
@@ -131,7 +132,7 @@ def test_sru_valu_kernel(d, n_layers, L, T):
 
 @pytest.mark.parametrize("d,n_layers,L,T,k", [
     (256, 2, 13, 1, 2), (512, 3, 21, 4, 2), (1024, 2, 37, 8, 2), (1024, 2, 11, 2, 3), (256, 2, 6, 1, 4),
-    (2048, 2, 9, 4, 2), (4096, 1, 6, 4, 2), (768, 2, 10, 3, 1),
+    (2048, 2, 9, 4, 2), (4096, 1, 6, 4, 2), (768, 2, 10, 3, 1), (1024, 2, 40, 16, 2), (512, 2, 35, 11, 3),
 ])
 def test_qrnn_valu_kernel(d, n_layers, L, T, k):
     W, b, x, c0, xh0 = _qrnn_inputs(500 + d + T + k, n_layers, d, L, k, scale=2.0)
