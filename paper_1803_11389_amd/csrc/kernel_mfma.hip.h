@@ -21,8 +21,8 @@
 //     fragments are prefetched PF steps ahead.
 //   - epilogue, 32 steps of time at a time: per-wave partial tiles go to LDS,
 //     all threads finish the split-K sum and apply the gate non-linearities,
-//     one thread per feature runs c_t = f_t*c_{t-1} + b_t serially, all
-//     threads form h_t.
+//     then the recurrence c_t = f_t*c_{t-1} + b_t runs as a prefix scan over
+//     32 adjacent lanes per feature, and the same lanes form h_t.
 #pragma once
 
 #include "common.hip.h"
@@ -63,7 +63,8 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
   constexpr int NBI = NT / NB;                       // B fetches per k-step
 
   __shared__ float part[NW * 3 * CHUNK];
-  __shared__ float g_a[CHUNK], g_b[CHUNK], g_o[CHUNK], g_c[CHUNK];
+  __shared__ float g_a[MFMA_F * (NTC * 16 + 1)], g_b[MFMA_F * (NTC * 16 + 1)], g_o[MFMA_F * (NTC * 16 + 1)];
+  __shared__ float c_carry[MFMA_F];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -312,30 +313,37 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
 #ifdef SSRNN_EXP_NOEPI
   if (s.nt > 0) { if (acc[0][0][0] == 123.456f) s.hout[0] = acc[1][0][1] + acc[2][NT - 1][2]; return; }
 #endif
-  // ---- epilogue: NTC tiles of 16 steps at a time -------------------------
+  // ---- epilogue: NTC tiles (CT = 16*NTC steps) at a time ------------------
+  // A: per-wave partial tiles -> LDS.  B: every thread finishes the split-K sum
+  // of one (step, feature) pair and applies the gate non-linearities, leaving
+  // f_t, (1-f_t)*cand_t and the output gate in LDS transposed to
+  // [feature][step].  C: one thread per (feature, step), steps on adjacent
+  // lanes: the recurrence c_t = f_t c_{t-1} + b_t is a prefix scan of affine
+  // maps over CT lanes, then h_t.  The state crosses chunks through c_carry.
+  constexpr int CT = NTC * 16;
+  constexpr int TS = CT + 1;                   // padded row of the transposed arrays
   float b0 = 0.f, b1 = 0.f, b2 = 0.f;          // biases of the feature this thread handles in phase B
-  const int fe = tid & 15;                     // feature index of the (time, feature) pairs this thread handles
+  const int fe = tid & 15;
   if (s.bias) {
     const int i = f0 + fe;
     if (CELL == CELL_SRU) { b1 = s.bias[i]; b2 = s.bias[d + i]; }
     else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
   }
-  float c = (tid < MFMA_F) ? s.c[f0 + tid] : 0.0f;
+  if (tid < MFMA_F) c_carry[tid] = s.c[f0 + tid];
 
 #pragma unroll
   for (int n0 = 0; n0 < NT; n0 += NTC) {
     if (n0 * 16 < s.nt) {   // uniform over the workgroup
-      // A: per-wave partial tiles -> LDS as [tile][time n][feature], a lane's 4 registers are 4 consecutive features
 #pragma unroll
       for (int g = 0; g < 3; ++g)
 #pragma unroll
         for (int q = 0; q < NTC; ++q) {
+          // [tile][time n][feature]: a lane's 4 registers are 4 consecutive features
           float* dst = part + ((wave * 3 + g) * NTC + q) * 256 + li * 16 + kg * 4;
           *reinterpret_cast<float4*>(dst) = make_float4(acc[g][n0 + q][0], acc[g][n0 + q][1], acc[g][n0 + q][2], acc[g][n0 + q][3]);
         }
       __syncthreads();
-      // B: finish the split-K sum, apply the gates.  e = local time * 16 + feature.
-      for (int e = tid; e < CHUNK; e += NW * 64) {
+      for (int e = tid; e < CHUNK; e += NW * 64) {      // e = local time * 16 + feature
         float u0 = b0, u1 = b1, u2 = b2;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
@@ -346,36 +354,41 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
         }
         const float f = sigmoidf_fast(u1);
         const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
-        g_a[e] = f;
-        g_b[e] = (1.0f - f) * cand;
-        g_o[e] = sigmoidf_fast(u2);
+        const int at = (e & 15) * TS + (e >> 4);
+        g_a[at] = f;
+        g_b[at] = (1.0f - f) * cand;
+        g_o[at] = sigmoidf_fast(u2);
       }
       __syncthreads();
-      // C: the recurrence c_t = f_t c_{t-1} + (1 - f_t) cand_t, serial in t, one thread per feature
-      if (tid < MFMA_F) {
-        const int tmax = min(NTC * 16, s.nt - n0 * 16);
-        for (int tl = 0; tl < tmax; ++tl) {
-          c = fmaf(g_a[tl * 16 + tid], c, g_b[tl * 16 + tid]);
-          g_c[tl * 16 + tid] = c;
+      const int tlast = min(CT, s.nt - n0 * 16) - 1;      // last valid step of this chunk
+      for (int id = tid; id < MFMA_F * CT; id += NW * 64) {
+        const int fi = id / CT;
+        const int tl = id - fi * CT;
+        float a = g_a[fi * TS + tl], b = g_b[fi * TS + tl];
+        const float o = g_o[fi * TS + tl];
+        const float cin = c_carry[fi];
+#pragma unroll
+        for (int off = 1; off < CT; off <<= 1) {
+          const float ap = __shfl_up(a, off, CT);
+          const float bp = __shfl_up(b, off, CT);
+          if (tl >= off) { b = fmaf(a, bp, b); a *= ap; }
         }
-      }
-      __syncthreads();
-      // D: outputs
-      for (int e = tid; e < CHUNK; e += NW * 64) {
-        const int t = n0 * 16 + (e >> 4);
-        if (t < s.nt) {
-          const int i = f0 + (e & 15);
-          const float o = g_o[e];
-          float hv = o * tanhf_fast(g_c[e]);
+        const float c = fmaf(a, cin, b);                   // state after step tl of the chunk
+        const int t = n0 * 16 + tl;
+        const int i = f0 + fi;
+        if (tl <= tlast) {
+          float hv = o * tanhf_fast(c);
           if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * s.ldx + i];
           s.hout[static_cast<long>(t) * s.ldh + i] = hv;
           if (s.hout16) s.hout16[static_cast<long>(t) * s.ldh + i] = f32_to_bf16_rne(hv);
         }
+        // the CT lanes of a feature sit in one wave and have read c_carry above
+        if (tl == tlast) { c_carry[fi] = c; s.c[i] = c; }
       }
-      __syncthreads();
+      // the next chunk's phase A only writes `part`, which every wave has finished
+      // reading; its first barrier orders this phase's reads before the next phase B
     }
   }
-  if (tid < MFMA_F) s.c[f0 + tid] = c;
 }
 
 }  // namespace ssrnn

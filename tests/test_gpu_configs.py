@@ -66,3 +66,65 @@ def test_config4_sru8_d4096_prefix():
 def test_config5_qrnn8_d4096_bf16_prefix():
     # 272 = 256 + 16: one full and one short block at T = 256
     _run_config(wl.CONFIGS[4], 272, 2e-2, True)
+
+
+# ---- full benchmark sizes, in the launch configuration bench.py times --------
+# The oracle cannot run 2048-4096 steps of the wide stacks in test time, so at
+# full length the checks are: (i) the first steps of the full-length GPU run
+# against the oracle (the method is causal), (ii) block-size invariance between
+# full-length GPU runs that use different kernels, (iii) bit-identical repeats,
+# (iv) every value finite and |h| within the bound the cell equations give.
+
+def _full_length(cfg, T_list, n_oracle, tol, relative):
+    import torch
+    import paper_1803_11389_amd as ss
+    inp = wl.make_inputs(cfg)
+    W_dev = [to_dev(w) for w in inp["W"]]
+    x_dev = to_dev(inp["x"])
+    ws = ss.Workspace.for_shape(cfg.n_layers, cfg.d, cfg.k, max(T_list), ss.BF16 if cfg.wdtype == "bf16" else ss.F32)
+
+    def run(T):
+        if cfg.cell == "sru":
+            h, c = ss.sru_forward(W_dev, None, x_dev, None, T=T, workspace=ws)
+        else:
+            h, c, _ = ss.qrnn_forward(W_dev, None, x_dev, None, None, T=T, k=cfg.k, workspace=ws)
+        torch.cuda.synchronize()
+        return h, c
+
+    if cfg.cell == "sru":
+        h_ref, _ = oracle.sru_forward(inp["W"], None, inp["x"][:n_oracle], T=64)
+    else:
+        h_ref, _, _ = oracle.qrnn_forward(inp["W"], None, inp["x"][:n_oracle], T=64, k=cfg.k)
+    scale = max(float(np.abs(h_ref).max()), 1e-6) if relative else 1.0
+    outs = {}
+    for T in T_list:
+        h, c = run(T)
+        assert bool(torch.isfinite(h).all()) and bool(torch.isfinite(c).all())
+        err = max_abs(h[:n_oracle].cpu().numpy(), h_ref) / scale
+        print(f"{cfg.name} full L={cfg.L} T={T}: first {n_oracle} steps vs oracle {err:.3e}", flush=True)
+        assert err <= tol, (T, err)
+        outs[T] = (h, c)
+    h0, c0 = outs[T_list[0]]
+    hscale = float(h0.abs().max()) if relative else 1.0
+    cscale = float(c0.abs().max()) if relative else 1.0
+    for T in T_list[1:]:
+        dh = float((outs[T][0] - h0).abs().max()) / hscale
+        dc = float((outs[T][1] - c0).abs().max()) / cscale
+        print(f"{cfg.name} full L: T={T} vs T={T_list[0]}: h {dh:.3e} c {dc:.3e}", flush=True)
+        assert dh <= 2 * tol and dc <= 2 * tol, (T, dh, dc)
+    h_again, c_again = run(T_list[0])
+    assert torch.equal(h_again, h0) and torch.equal(c_again, c0), "repeat of the same launch differs"
+    return h0
+
+
+def test_config4_full_length_properties():
+    cfg = wl.CONFIGS[3]
+    h = _full_length(cfg, [4, 1, 16, 128], 96, 1e-4, False)
+    # SRU: h is a gate-weighted mix of tanh(c) in [-1, 1] and the layer input; bounded by max(1, |x|)
+    assert float(h.abs().max()) <= max(1.0, 6.5)
+
+
+def test_config5_full_length_properties():
+    cfg = wl.CONFIGS[4]
+    h = _full_length(cfg, [64, 16, 256], 80, 2e-2, True)
+    assert float(h.abs().max()) < 1.0        # QRNN: h = o * tanh(c), 0 < o < 1
