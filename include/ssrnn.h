@@ -114,8 +114,9 @@ int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
 /* Measurement aid: override one launch-geometry choice of the kernels for the
  * calls that follow, process-wide (not thread-safe; 0 restores the default).
  * Keys: "valu_F" (features per workgroup), "valu_nw" (wavefronts per
- * workgroup), "valu_nv" (column chunks per lane).  A value the shape does not
- * allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
+ * workgroup), "valu_nv" (column chunks per lane), "mfma_lds" (1: matrix-core
+ * kernel loads weight fragments straight from memory instead of staging whole
+ * lines through LDS).  A value the shape does not allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
 int ssrnn_tune(const char* key, int value);
 
 #ifdef __cplusplus

@@ -50,6 +50,97 @@ struct BFrag<W_F32> { float4 v[2]; };
 template <>
 struct BFrag<W_BF16> { bf16x8_t v[2]; };
 
+// Epilogue shared by the matrix-core kernels.  acc[g][n]: this wave's partial
+// 16x16 tiles (gate g, time tile n) in the MFMA result layout (lane = time
+// n%16 + 16*(feature/4), register = feature%4).
+template <int CELL, int NT, int NW>
+__device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, floatx4_t (&acc)[3][NT], float* part,
+                                              float* g_a, float* g_b, float* g_o, float* c_carry) {
+  constexpr int NTC = MfmaCfg<NT>::NTC;
+  constexpr int CHUNK = NTC * 256;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int li = lane & 15;
+  const int kg = lane >> 4;
+  // ---- epilogue: NTC tiles (CT = 16*NTC steps) at a time ------------------
+  // A: per-wave partial tiles -> LDS.  B: every thread finishes the split-K sum
+  // of one (step, feature) pair and applies the gate non-linearities, leaving
+  // f_t, (1-f_t)*cand_t and the output gate in LDS transposed to
+  // [feature][step].  C: one thread per (feature, step), steps on adjacent
+  // lanes: the recurrence c_t = f_t c_{t-1} + b_t is a prefix scan of affine
+  // maps over CT lanes, then h_t.  The state crosses chunks through c_carry.
+  constexpr int CT = NTC * 16;
+  constexpr int TS = CT + 1;                   // padded row of the transposed arrays
+  float b0 = 0.f, b1 = 0.f, b2 = 0.f;          // biases of the feature this thread handles in phase B
+  const int fe = tid & 15;
+  if (s.bias) {
+    const int i = f0 + fe;
+    if (CELL == CELL_SRU) { b1 = s.bias[i]; b2 = s.bias[d + i]; }
+    else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
+  }
+  if (tid < MFMA_F) c_carry[tid] = s.c[f0 + tid];
+
+#pragma unroll
+  for (int n0 = 0; n0 < NT; n0 += NTC) {
+    if (n0 * 16 < s.nt) {   // uniform over the workgroup
+#pragma unroll
+      for (int g = 0; g < 3; ++g)
+#pragma unroll
+        for (int q = 0; q < NTC; ++q) {
+          // [tile][time n][feature]: a lane's 4 registers are 4 consecutive features
+          float* dst = part + ((wave * 3 + g) * NTC + q) * 256 + li * 16 + kg * 4;
+          *reinterpret_cast<float4*>(dst) = make_float4(acc[g][n0 + q][0], acc[g][n0 + q][1], acc[g][n0 + q][2], acc[g][n0 + q][3]);
+        }
+      __syncthreads();
+      for (int e = tid; e < CHUNK; e += NW * 64) {      // e = local time * 16 + feature
+        float u0 = b0, u1 = b1, u2 = b2;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          const int q = e >> 8, r = e & 255;
+          u0 += part[((w * 3 + 0) * NTC + q) * 256 + r];
+          u1 += part[((w * 3 + 1) * NTC + q) * 256 + r];
+          u2 += part[((w * 3 + 2) * NTC + q) * 256 + r];
+        }
+        const float f = sigmoidf_fast(u1);
+        const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
+        const int at = (e & 15) * TS + (e >> 4);
+        g_a[at] = f;
+        g_b[at] = (1.0f - f) * cand;
+        g_o[at] = sigmoidf_fast(u2);
+      }
+      __syncthreads();
+      const int tlast = min(CT, s.nt - n0 * 16) - 1;      // last valid step of this chunk
+      for (int id = tid; id < MFMA_F * CT; id += NW * 64) {
+        const int fi = id / CT;
+        const int tl = id - fi * CT;
+        float a = g_a[fi * TS + tl], b = g_b[fi * TS + tl];
+        const float o = g_o[fi * TS + tl];
+        const float cin = c_carry[fi];
+#pragma unroll
+        for (int off = 1; off < CT; off <<= 1) {
+          const float ap = __shfl_up(a, off, CT);
+          const float bp = __shfl_up(b, off, CT);
+          if (tl >= off) { b = fmaf(a, bp, b); a *= ap; }
+        }
+        const float c = fmaf(a, cin, b);                   // state after step tl of the chunk
+        const int t = n0 * 16 + tl;
+        const int i = f0 + fi;
+        if (tl <= tlast) {
+          float hv = o * tanhf_fast(c);
+          if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * s.ldx + i];
+          s.hout[static_cast<long>(t) * s.ldh + i] = hv;
+          if (s.hout16) s.hout16[static_cast<long>(t) * s.ldh + i] = f32_to_bf16_rne(hv);
+        }
+        // the CT lanes of a feature sit in one wave and have read c_carry above
+        if (tl == tlast) { c_carry[fi] = c; s.c[i] = c; }
+      }
+      // the next chunk's phase A only writes `part`, which every wave has finished
+      // reading; its first barrier orders this phase's reads before the next phase B
+    }
+  }
+}
+
 template <int CELL, int WT, int NT>
 __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage s, int d, int k) {
   constexpr int NW = MfmaCfg<NT>::NW;
@@ -313,82 +404,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
 #ifdef SSRNN_EXP_NOEPI
   if (s.nt > 0) { if (acc[0][0][0] == 123.456f) s.hout[0] = acc[1][0][1] + acc[2][NT - 1][2]; return; }
 #endif
-  // ---- epilogue: NTC tiles (CT = 16*NTC steps) at a time ------------------
-  // A: per-wave partial tiles -> LDS.  B: every thread finishes the split-K sum
-  // of one (step, feature) pair and applies the gate non-linearities, leaving
-  // f_t, (1-f_t)*cand_t and the output gate in LDS transposed to
-  // [feature][step].  C: one thread per (feature, step), steps on adjacent
-  // lanes: the recurrence c_t = f_t c_{t-1} + b_t is a prefix scan of affine
-  // maps over CT lanes, then h_t.  The state crosses chunks through c_carry.
-  constexpr int CT = NTC * 16;
-  constexpr int TS = CT + 1;                   // padded row of the transposed arrays
-  float b0 = 0.f, b1 = 0.f, b2 = 0.f;          // biases of the feature this thread handles in phase B
-  const int fe = tid & 15;
-  if (s.bias) {
-    const int i = f0 + fe;
-    if (CELL == CELL_SRU) { b1 = s.bias[i]; b2 = s.bias[d + i]; }
-    else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
-  }
-  if (tid < MFMA_F) c_carry[tid] = s.c[f0 + tid];
-
-#pragma unroll
-  for (int n0 = 0; n0 < NT; n0 += NTC) {
-    if (n0 * 16 < s.nt) {   // uniform over the workgroup
-#pragma unroll
-      for (int g = 0; g < 3; ++g)
-#pragma unroll
-        for (int q = 0; q < NTC; ++q) {
-          // [tile][time n][feature]: a lane's 4 registers are 4 consecutive features
-          float* dst = part + ((wave * 3 + g) * NTC + q) * 256 + li * 16 + kg * 4;
-          *reinterpret_cast<float4*>(dst) = make_float4(acc[g][n0 + q][0], acc[g][n0 + q][1], acc[g][n0 + q][2], acc[g][n0 + q][3]);
-        }
-      __syncthreads();
-      for (int e = tid; e < CHUNK; e += NW * 64) {      // e = local time * 16 + feature
-        float u0 = b0, u1 = b1, u2 = b2;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-          const int q = e >> 8, r = e & 255;
-          u0 += part[((w * 3 + 0) * NTC + q) * 256 + r];
-          u1 += part[((w * 3 + 1) * NTC + q) * 256 + r];
-          u2 += part[((w * 3 + 2) * NTC + q) * 256 + r];
-        }
-        const float f = sigmoidf_fast(u1);
-        const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
-        const int at = (e & 15) * TS + (e >> 4);
-        g_a[at] = f;
-        g_b[at] = (1.0f - f) * cand;
-        g_o[at] = sigmoidf_fast(u2);
-      }
-      __syncthreads();
-      const int tlast = min(CT, s.nt - n0 * 16) - 1;      // last valid step of this chunk
-      for (int id = tid; id < MFMA_F * CT; id += NW * 64) {
-        const int fi = id / CT;
-        const int tl = id - fi * CT;
-        float a = g_a[fi * TS + tl], b = g_b[fi * TS + tl];
-        const float o = g_o[fi * TS + tl];
-        const float cin = c_carry[fi];
-#pragma unroll
-        for (int off = 1; off < CT; off <<= 1) {
-          const float ap = __shfl_up(a, off, CT);
-          const float bp = __shfl_up(b, off, CT);
-          if (tl >= off) { b = fmaf(a, bp, b); a *= ap; }
-        }
-        const float c = fmaf(a, cin, b);                   // state after step tl of the chunk
-        const int t = n0 * 16 + tl;
-        const int i = f0 + fi;
-        if (tl <= tlast) {
-          float hv = o * tanhf_fast(c);
-          if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * s.ldx + i];
-          s.hout[static_cast<long>(t) * s.ldh + i] = hv;
-          if (s.hout16) s.hout16[static_cast<long>(t) * s.ldh + i] = f32_to_bf16_rne(hv);
-        }
-        // the CT lanes of a feature sit in one wave and have read c_carry above
-        if (tl == tlast) { c_carry[fi] = c; s.c[i] = c; }
-      }
-      // the next chunk's phase A only writes `part`, which every wave has finished
-      // reading; its first barrier orders this phase's reads before the next phase B
-    }
-  }
+  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
 }
 
 }  // namespace ssrnn

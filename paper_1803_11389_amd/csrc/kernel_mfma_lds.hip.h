@@ -1,0 +1,220 @@
+// Matrix-core kernel, weights staged through LDS (NT <= 8 time tiles).
+//
+// Same decomposition and epilogue as stage_mfma_kernel; what differs is how
+// the weight fragments reach the matrix cores.  A 16x16 MFMA wants 16 rows on
+// 16 lanes, so loading fragments straight from the row-major matrix splits
+// every 128-byte line of a row over two load instructions, which doubles the
+// cache's outstanding-request entries per byte and rules out streaming
+// (non-temporal) loads.  Here each load instruction reads 8 rows x 128 B,
+// i.e. eight whole lines, with the non-temporal hint; the wave writes them to
+// its private LDS tile (48 rows of one k-step, rows 144 B apart so that both
+// the writes and the fragment reads are bank-conflict free) and reads them
+// back in the MFMA layout.  Global loads run G k-steps ahead of their LDS
+// write; LDS reads run one k-step ahead of the MFMAs that use them; loads,
+// LDS traffic and MFMAs of one step are interleaved in issue order.  No
+// workgroup barrier is needed in the main loop: a wave only touches its own
+// tile and LDS operations of one wave execute in order.
+#pragma once
+
+#include "kernel_mfma.hip.h"
+
+namespace ssrnn {
+
+constexpr int MFMA_LDS_ROW = 144;                       // bytes between rows of a wave's tile
+constexpr int MFMA_LDS_TILE = 48 * MFMA_LDS_ROW;        // 48 weight rows of one k-step
+
+template <int NT>
+struct MfmaLdsCfg {
+  static constexpr int G = (NT <= 2 || NT >= 8) ? 4 : 2;  // k-steps of weight loads in flight
+  static constexpr int S = (NT <= 2) ? 4 : 2;             // B fragment ring slots
+};
+
+template <int CELL, int WT, int NT>
+__global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(Stage s, int d, int k) {
+  static_assert(NT <= 8, "the LDS-staged kernel holds all B tiles of a step at once");
+  constexpr int NW = MfmaCfg<NT>::NW;
+  constexpr int NTC = MfmaCfg<NT>::NTC;
+  constexpr int KSTEP = (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
+  constexpr int CW = KSTEP / 4;                      // columns per lane per step in the MFMA layout (32 bytes)
+  constexpr int ESIZE = (WT == W_BF16) ? 2 : 4;
+  constexpr int CHUNK = NTC * 256;
+  constexpr int G = MfmaLdsCfg<NT>::G;
+  constexpr int S = MfmaLdsCfg<NT>::S;
+  constexpr int U = (G > S) ? G : S;                 // unroll: both rings and the fragment double buffer repeat
+  static_assert(U % G == 0 && U % S == 0 && U % 2 == 0, "ring sizes must divide the unroll factor");
+
+  constexpr int EPI_FLOATS = NW * 3 * CHUNK + 3 * MFMA_F * (NTC * 16 + 1) + MFMA_F;
+  constexpr int SMEM_BYTES = (NW * MFMA_LDS_TILE > EPI_FLOATS * 4) ? NW * MFMA_LDS_TILE : EPI_FLOATS * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+  float* part = reinterpret_cast<float*>(smem);
+  float* g_a = part + NW * 3 * CHUNK;
+  float* g_b = g_a + MFMA_F * (NTC * 16 + 1);
+  float* g_o = g_b + MFMA_F * (NTC * 16 + 1);
+  float* c_carry = g_o + MFMA_F * (NTC * 16 + 1);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int li = lane & 15;
+  const int kg = lane >> 4;
+  const int ncol = k * d;
+  const int f0 = blockIdx.x * MFMA_F;
+  const int KS = ncol / NW;
+  const int nks = KS / KSTEP;
+
+  if (CELL == CELL_QRNN && tid < MFMA_F) refresh_history(s, d, k, f0 + tid);
+
+  // global side: instruction q reads tile rows 8q .. 8q+7 (row r = gate r/16, feature r%16), 16 B per lane
+  const int lrow = lane >> 3;
+  const int lchunk = (lane & 7) * 16;
+  const char* gptr[6];
+#pragma unroll
+  for (int q = 0; q < 6; ++q) {
+    const int r = 8 * q + lrow;
+    gptr[q] = static_cast<const char*>(s.W) +
+              (static_cast<size_t>((r >> 4) * d + f0 + (r & 15)) * ncol + static_cast<size_t>(wave) * KS) * ESIZE + lchunk;
+  }
+  unsigned char* tile = smem + wave * MFMA_LDS_TILE;
+  unsigned char* wr_at = tile + lrow * MFMA_LDS_ROW + lchunk;              // + q * 8 rows
+  const unsigned char* rd_at = tile + li * MFMA_LDS_ROW + kg * 32;         // + gate * 16 rows + half * 16
+
+  floatx4_t acc[3][NT];
+#pragma unroll
+  for (int g = 0; g < 3; ++g)
+#pragma unroll
+    for (int n = 0; n < NT; ++n) acc[g][n] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  int trow[NT];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) trow[n] = min(n * 16 + li, s.nt - 1);
+
+  floatx4_t greg[G][6];          // weight lines in flight from memory
+  floatx4_t afr[2][3][2];        // fragments of the current and the next k-step
+  BFrag<WT> bring[S][NT];
+
+  // cursors stop at the last k-step: redundant in-bounds loads instead of branches
+  int a_ks = 0;                                   // next k-step whose weight lines are requested
+  int b_ks = 0, b_j = (wave * KS) / d, b_m = wave * KS - ((wave * KS) / d) * d + kg * CW;
+  auto load_a_line = [&](int slot, int q) {
+    greg[slot][q] = load_stream16(gptr[q] + static_cast<size_t>(a_ks) * KSTEP * ESIZE);
+  };
+  auto advance_a = [&]() { if (a_ks < nks - 1) ++a_ks; };
+  auto load_b_piece = [&](int slot, int i) {      // i = tile * 2 + half
+    const int n = i >> 1, h = i & 1;
+#ifdef SSRNN_EXP_BCONST
+    if constexpr (WT == W_F32) { bring[slot][n].v[h] = make_float4(lane * 1e-3f, 1.f, 2.f, n); return; }
+#endif
+    const long off = static_cast<long>(trow[n] - b_j) * s.ldx + b_m + h * (CW / 2);
+    if constexpr (WT == W_BF16) bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
+    else bring[slot][n].v[h] = *reinterpret_cast<const float4*>(s.xcur + off);
+  };
+  auto advance_b = [&]() {
+    if (b_ks < nks - 1) {
+      ++b_ks;
+      b_m += KSTEP;
+      if (b_m >= d) { b_m -= d; ++b_j; }
+    }
+  };
+  auto lds_write = [&](int slot, int q) {
+    *reinterpret_cast<floatx4_t*>(wr_at + q * 8 * MFMA_LDS_ROW) = greg[slot][q];
+  };
+  auto lds_read = [&](int buf, int i) {           // i = gate * 2 + half
+    const int g = i >> 1, h = i & 1;
+    afr[buf][g][h] = *reinterpret_cast<const floatx4_t*>(rd_at + g * 16 * MFMA_LDS_ROW + h * 16);
+  };
+  auto mfma_group = [&](int buf, int bslot, int grp) {
+    if constexpr (WT == W_BF16) {
+      const int h = grp / 3, g = grp - 3 * (grp / 3);
+      bf16x8_t ab;
+      __builtin_memcpy(&ab, &afr[buf][g][h], sizeof ab);
+#pragma unroll
+      for (int n = 0; n < NT; ++n)
+        acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[h], acc[g][n], 0, 0, 0);
+    } else {
+      const int h = grp >> 2, q = grp & 3;
+#pragma unroll
+      for (int g = 0; g < 3; ++g)
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+          const float4 bv = bring[bslot][n].v[h];
+          const float bq = q == 0 ? bv.x : q == 1 ? bv.y : q == 2 ? bv.z : bv.w;
+          acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(afr[buf][g][h][q], bq, acc[g][n], 0, 0, 0);
+        }
+    }
+  };
+
+  // ---- prologue: weight lines of steps 0..G-1, B of steps 0..S-2, fragments of step 0
+#pragma unroll
+  for (int p = 0; p < G; ++p) {
+#pragma unroll
+    for (int q = 0; q < 6; ++q) load_a_line(p, q);
+    advance_a();
+  }
+#pragma unroll
+  for (int p = 0; p < S - 1; ++p) {
+#pragma unroll
+    for (int i = 0; i < 2 * NT; ++i) load_b_piece(p, i);
+    advance_b();
+  }
+#pragma unroll
+  for (int q = 0; q < 6; ++q) lds_write(0, q);
+#pragma unroll
+  for (int q = 0; q < 6; ++q) load_a_line(0, q);        // step G into the slot just written out
+  advance_a();
+#pragma unroll
+  for (int i = 0; i < 6; ++i) lds_read(0, i);
+
+  // ---- main loop.  Step ks multiplies fragments afr[ks&1] with bring[ks%S]; meanwhile, in this order,
+  //   the lines of step ks+1 go from greg[(ks+1)%G] to LDS, that slot is refilled with step ks+1+G,
+  //   the B pieces of step ks+S-1 are requested, and the fragments of step ks+1 are read back.
+  constexpr int NGRP = (WT == W_BF16) ? 6 : 8;
+  constexpr int NITEM = 6 + 6 + 2 * NT + 6;             // LDS writes, line loads, B pieces, LDS reads
+  const int nmain = (nks / U) * U;
+  for (int ks0 = 0; ks0 < nmain; ks0 += U) {
+#pragma unroll
+    for (int p = 0; p < U; ++p) {
+      const int gslot = (p + 1) % G;
+      const int bslot = p % S;
+      const int bnext = (p + S - 1) % S;
+#pragma unroll
+      for (int grp = 0; grp < NGRP; ++grp) {
+        mfma_group(p & 1, bslot, grp);
+#pragma unroll
+        for (int it = (grp * NITEM) / NGRP; it < ((grp + 1) * NITEM) / NGRP; ++it) {
+          if (it < 6) lds_write(gslot, it);
+          else if (it < 12) load_a_line(gslot, it - 6);
+          else if (it < 12 + 2 * NT) load_b_piece(bnext, it - 12);
+          else lds_read((p + 1) & 1, it - 12 - 2 * NT);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      advance_a();
+      advance_b();
+    }
+  }
+  // ---- remainder steps (nks not a multiple of U): same data path, no overlap
+  for (int ks = nmain; ks < nks; ++ks) {
+    a_ks = ks;
+#pragma unroll
+    for (int q = 0; q < 6; ++q) load_a_line(0, q);
+    b_ks = ks;
+    {
+      const int col = wave * KS + ks * KSTEP;
+      b_j = col / d;
+      b_m = col - b_j * d + kg * CW;
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * NT; ++i) load_b_piece(0, i);
+#pragma unroll
+    for (int q = 0; q < 6; ++q) lds_write(0, q);
+#pragma unroll
+    for (int i = 0; i < 6; ++i) lds_read(0, i);
+#pragma unroll
+    for (int grp = 0; grp < NGRP; ++grp) mfma_group(0, 0, grp);
+  }
+
+  __syncthreads();      // the epilogue's LDS arrays overlay the waves' tiles
+  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
+}
+
+}  // namespace ssrnn

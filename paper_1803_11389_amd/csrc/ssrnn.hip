@@ -20,6 +20,7 @@
 #include "kernel_generic.hip.h"
 #include "kernel_valu.hip.h"
 #include "kernel_mfma.hip.h"
+#include "kernel_mfma_lds.hip.h"
 
 using namespace ssrnn;
 
@@ -171,6 +172,7 @@ struct Plan {
 };
 
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
+int g_tune_mfma_lds = 0;   // 0 = default (LDS-staged weights when the shape allows), 1 = off, 2 = on
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
   if (p.wdt != SSRNN_F32 || p.T > VALU_MAX_T || p.d % 256 != 0) return false;
@@ -243,6 +245,21 @@ int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
     else                                                                                              \
       hipLaunchKernelGGL((stage_mfma_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
     return SSRNN_OK;                                                                                  \
+  }
+  // Weights staged through LDS (whole-line streaming loads) measure faster except for fp32 at 64 steps.
+  const bool lds_default = !(p.wdt == SSRNN_F32 && p.nt_tiles == 4);
+  if (g_tune_mfma_lds == 2 || (g_tune_mfma_lds == 0 && lds_default)) {
+#define SSRNN_MFMA_LDS_CASE(NT_)                                                                          \
+  if (p.nt_tiles == NT_) {                                                                                \
+    const dim3 block(MfmaCfg<NT_>::NW * 64);                                                              \
+    if (p.wdt == SSRNN_BF16)                                                                              \
+      hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k);    \
+    else                                                                                                  \
+      hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
+    return SSRNN_OK;                                                                                      \
+  }
+    SSRNN_MFMA_LDS_CASE(1) SSRNN_MFMA_LDS_CASE(2) SSRNN_MFMA_LDS_CASE(4) SSRNN_MFMA_LDS_CASE(8)
+#undef SSRNN_MFMA_LDS_CASE
   }
   SSRNN_MFMA_CASE(1) SSRNN_MFMA_CASE(2) SSRNN_MFMA_CASE(4) SSRNN_MFMA_CASE(8) SSRNN_MFMA_CASE(16)
 #undef SSRNN_MFMA_CASE
@@ -434,6 +451,7 @@ int ssrnn_tune(const char* key, int value) {
   if (!strcmp(key, "valu_F")) g_tune_valu_F = value;
   else if (!strcmp(key, "valu_nw")) g_tune_valu_nw = value;
   else if (!strcmp(key, "valu_nv")) g_tune_valu_nv = value;
+  else if (!strcmp(key, "mfma_lds")) g_tune_mfma_lds = value;
   else return fail(SSRNN_EINVAL, "ssrnn_tune: unknown key %s", key);
   return SSRNN_OK;
 }
