@@ -32,9 +32,10 @@ FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 (vector / matrix) peak
 # HBM bytes per stage launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
 # scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same workloads).
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", 4): 202_290_000,     # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
-    ("C4", 64): 216_900_000,    # profiles/stage_mfma_kernel_f32_C4_sru8_d4096_T64.txt
-    ("C5", 64): 211_500_000,    # profiles/stage_mfma_kernel_bf16_C5_qrnn8_d4096_T64.txt
+    ("C4", 1): 201_630_000,     # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
+    ("C4", 4): 202_140_000,     # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
+    ("C4", 64): 213_220_000,    # profiles/stage_mfma_kernel_f32_C4_sru8_d4096_T64.txt
+    ("C5", 64): 237_390_000,    # profiles/stage_mfma_lds_kernel_bf16_C5_qrnn8_d4096_T64.txt
     ("C5", 256): 224_800_000,   # profiles/stage_mfma_kernel_bf16_C5_qrnn8_d4096_T256.txt
 }
 
