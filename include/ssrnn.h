@@ -116,7 +116,9 @@ int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
  * Keys: "valu_F" (features per workgroup), "valu_nw" (wavefronts per
  * workgroup), "valu_nv" (column chunks per lane), "mfma_lds" (1: matrix-core
  * kernel loads weight fragments straight from memory instead of staging whole
- * lines through LDS).  A value the shape does not allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
+ * lines through LDS), "ksplit" (1: never split a narrow layer's columns over
+ * several workgroups; 2, 4, 8: at most that many parts).  A value the shape
+ * does not allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
 int ssrnn_tune(const char* key, int value);
 
 #ifdef __cplusplus

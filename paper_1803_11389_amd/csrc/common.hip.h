@@ -37,6 +37,12 @@ struct Stage {
   int nt;
   int ldx;                 // row stride (elements) of xcur and xcur16
   int ldh;                 // row stride (elements) of hout and hout16
+  // Narrow layers only: the k*d columns are split over ksplit workgroups per
+  // feature tile; each writes its partial pre-activations to
+  // upart[((part*3 + gate)*d + feature)*tp + t] and a second kernel finishes.
+  float* upart;
+  int ksplit;              // 1: no split (upart unused)
+  int tp;                  // steps per feature row of upart
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {

@@ -53,9 +53,10 @@ struct BFrag<W_BF16> { bf16x8_t v[2]; };
 // Epilogue shared by the matrix-core kernels.  acc[g][n]: this wave's partial
 // 16x16 tiles (gate g, time tile n) in the MFMA result layout (lane = time
 // n%16 + 16*(feature/4), register = feature%4).
-template <int CELL, int NT, int NW>
+template <int CELL, int NT>
 __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, floatx4_t (&acc)[3][NT], float* part,
                                               float* g_a, float* g_b, float* g_o, float* c_carry) {
+  const int NW = blockDim.x >> 6;               // waves that split the columns
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int CHUNK = NTC * 256;
   const int tid = threadIdx.x;
@@ -95,7 +96,6 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
       __syncthreads();
       for (int e = tid; e < CHUNK; e += NW * 64) {      // e = local time * 16 + feature
         float u0 = b0, u1 = b1, u2 = b2;
-#pragma unroll
         for (int w = 0; w < NW; ++w) {
           const int q = e >> 8, r = e & 255;
           u0 += part[((w * 3 + 0) * NTC + q) * 256 + r];
@@ -139,6 +139,105 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
       // reading; its first barrier orders this phase's reads before the next phase B
     }
   }
+}
+
+// Split-K over workgroups (narrow layers): instead of the epilogue, a workgroup
+// sums its waves' partial tiles through LDS and stores the result as one plane
+// of s.upart; split_epilogue_kernel adds the planes and finishes the stage.
+template <int NT>
+__device__ __forceinline__ void mfma_store_partials(const Stage& s, int d, int f0, int ksp, floatx4_t (&acc)[3][NT],
+                                                    float* part) {
+  const int NW = blockDim.x >> 6;
+  constexpr int NTC = MfmaCfg<NT>::NTC;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int li = lane & 15;
+  const int kg = lane >> 4;
+#pragma unroll
+  for (int n0 = 0; n0 < NT; n0 += NTC) {
+    if (n0 * 16 < s.nt) {
+#pragma unroll
+      for (int g = 0; g < 3; ++g)
+#pragma unroll
+        for (int q = 0; q < NTC; ++q) {
+          float* dst = part + ((wave * 3 + g) * NTC + q) * 256 + li * 16 + kg * 4;
+          *reinterpret_cast<float4*>(dst) = make_float4(acc[g][n0 + q][0], acc[g][n0 + q][1], acc[g][n0 + q][2], acc[g][n0 + q][3]);
+        }
+      __syncthreads();
+      // one thread per (feature, step), steps on adjacent lanes, so that the planes
+      // [part][gate][feature][step] are written (and later read) along their fastest index
+      constexpr int CT = NTC * 16;
+      for (int id = tid; id < MFMA_F * CT; id += NW * 64) {
+        const int fi = id / CT;
+        const int tl = id - fi * CT;
+        const int q = tl >> 4, r = (tl & 15) * 16 + fi;
+        float u0 = 0.f, u1 = 0.f, u2 = 0.f;
+        for (int w = 0; w < NW; ++w) {
+          u0 += part[((w * 3 + 0) * NTC + q) * 256 + r];
+          u1 += part[((w * 3 + 1) * NTC + q) * 256 + r];
+          u2 += part[((w * 3 + 2) * NTC + q) * 256 + r];
+        }
+        const long plane = static_cast<long>(d) * s.tp;
+        const long at = static_cast<long>(f0 + fi) * s.tp + n0 * 16 + tl;
+        s.upart[(ksp * 3 + 0) * plane + at] = u0;
+        s.upart[(ksp * 3 + 1) * plane + at] = u1;
+        s.upart[(ksp * 3 + 2) * plane + at] = u2;
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// Second kernel of a split stage: one workgroup of 512 threads per 16 features,
+// thread = (feature, step within a chunk of 32): adds the ksplit planes and the
+// bias, applies the gates, scans the recurrence over 32 adjacent lanes and
+// writes h (and its bf16 copy).
+template <int CELL>
+__global__ __launch_bounds__(512) void split_epilogue_kernel(Stage s, int d, int k) {
+  const int tid = threadIdx.x;
+  const int fi = tid >> 5;
+  const int tl = tid & 31;
+  const int i = blockIdx.x * MFMA_F + fi;
+  if (CELL == CELL_QRNN && tl == 0) refresh_history(s, d, k, i);
+  float b0 = 0.f, b1 = 0.f, b2 = 0.f;
+  if (s.bias) {
+    if (CELL == CELL_SRU) { b1 = s.bias[i]; b2 = s.bias[d + i]; }
+    else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
+  }
+  float cin = s.c[i];
+  const long plane = static_cast<long>(s.tp) * d;
+  for (int t0 = 0; t0 < s.nt; t0 += 32) {
+    const int t = t0 + tl;
+    const int tr = min(t, s.nt - 1);                     // rows past the end repeat the last one and are not written
+    float u0 = b0, u1 = b1, u2 = b2;
+    for (int p = 0; p < s.ksplit; ++p) {
+      const long at = static_cast<long>(i) * s.tp + tr;
+      u0 += s.upart[(p * 3 + 0) * plane + at];
+      u1 += s.upart[(p * 3 + 1) * plane + at];
+      u2 += s.upart[(p * 3 + 2) * plane + at];
+    }
+    const float f = sigmoidf_fast(u1);
+    const float o = sigmoidf_fast(u2);
+    const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
+    float a = f, b = (1.0f - f) * cand;
+#pragma unroll
+    for (int off = 1; off < 32; off <<= 1) {
+      const float ap = __shfl_up(a, off, 32);
+      const float bp = __shfl_up(b, off, 32);
+      if (tl >= off) { b = fmaf(a, bp, b); a *= ap; }
+    }
+    const float c = fmaf(a, cin, b);
+    if (t < s.nt) {
+      float hv = o * tanhf_fast(c);
+      if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * s.ldx + i];
+      s.hout[static_cast<long>(t) * s.ldh + i] = hv;
+      if (s.hout16) s.hout16[static_cast<long>(t) * s.ldh + i] = f32_to_bf16_rne(hv);
+    }
+    const int tlast = min(32, s.nt - t0) - 1;
+    cin = __shfl(c, tlast, 32);                          // state after the chunk's last valid step
+  }
+  if (tl == 0) s.c[i] = cin;
 }
 
 template <int CELL, int WT, int NT>
@@ -404,7 +503,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
 #ifdef SSRNN_EXP_NOEPI
   if (s.nt > 0) { if (acc[0][0][0] == 123.456f) s.hout[0] = acc[1][0][1] + acc[2][NT - 1][2]; return; }
 #endif
-  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
+  mfma_epilogue<CELL, NT>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
 }
 
 }  // namespace ssrnn

@@ -16,6 +16,8 @@
 // tile and LDS operations of one wave execute in order.
 #pragma once
 
+#include <type_traits>
+
 #include "kernel_mfma.hip.h"
 
 namespace ssrnn {
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
   constexpr int G = MfmaLdsCfg<NT>::G;
   constexpr int S = MfmaLdsCfg<NT>::S;
   constexpr int U = (G > S) ? G : S;                 // unroll: both rings and the fragment double buffer repeat
-  static_assert(U % G == 0 && U % S == 0 && U % 2 == 0, "ring sizes must divide the unroll factor");
+  static_assert(U % G == 0 && U % S == 0 && U % 2 == 0 && G <= U && S <= U, "ring sizes must divide the unroll factor");
 
   constexpr int EPI_FLOATS = NW * 3 * CHUNK + 3 * MFMA_F * (NTC * 16 + 1) + MFMA_F;
   constexpr int SMEM_BYTES = (NW * MFMA_LDS_TILE > EPI_FLOATS * 4) ? NW * MFMA_LDS_TILE : EPI_FLOATS * 4;
@@ -58,11 +60,15 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
   const int li = lane & 15;
   const int kg = lane >> 4;
   const int ncol = k * d;
-  const int f0 = blockIdx.x * MFMA_F;
-  const int KS = ncol / NW;
+  const int ntile = d / MFMA_F;
+  const int ksp = blockIdx.x / ntile;                // which part of the columns (0 unless the stage is split)
+  const int f0 = (blockIdx.x - ksp * ntile) * MFMA_F;
+  const int nw = blockDim.x >> 6;                    // waves launched (<= NW; fewer when a part has few columns)
+  const int KS = ncol / (nw * s.ksplit);             // columns per wave
   const int nks = KS / KSTEP;
+  const int wcol = (ksp * nw + wave) * KS;           // this wave's first column
 
-  if (CELL == CELL_QRNN && tid < MFMA_F) refresh_history(s, d, k, f0 + tid);
+  if (CELL == CELL_QRNN && s.ksplit == 1 && tid < MFMA_F) refresh_history(s, d, k, f0 + tid);
 
   // global side: instruction q reads tile rows 8q .. 8q+7 (row r = gate r/16, feature r%16), 16 B per lane
   const int lrow = lane >> 3;
@@ -72,7 +78,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
   for (int q = 0; q < 6; ++q) {
     const int r = 8 * q + lrow;
     gptr[q] = static_cast<const char*>(s.W) +
-              (static_cast<size_t>((r >> 4) * d + f0 + (r & 15)) * ncol + static_cast<size_t>(wave) * KS) * ESIZE + lchunk;
+              (static_cast<size_t>((r >> 4) * d + f0 + (r & 15)) * ncol + static_cast<size_t>(wcol)) * ESIZE + lchunk;
   }
   unsigned char* tile = smem + wave * MFMA_LDS_TILE;
   unsigned char* wr_at = tile + lrow * MFMA_LDS_ROW + lchunk;              // + q * 8 rows
@@ -92,13 +98,12 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
   floatx4_t afr[2][3][2];        // fragments of the current and the next k-step
   BFrag<WT> bring[S][NT];
 
-  // cursors stop at the last k-step: redundant in-bounds loads instead of branches
+  // cursors of the two prefetch streams; the pipeline's last iteration issues no load past the last k-step
   int a_ks = 0;                                   // next k-step whose weight lines are requested
-  int b_ks = 0, b_j = (wave * KS) / d, b_m = wave * KS - ((wave * KS) / d) * d + kg * CW;
+  int b_j = wcol / d, b_m = wcol - (wcol / d) * d + kg * CW;
   auto load_a_line = [&](int slot, int q) {
     greg[slot][q] = load_stream16(gptr[q] + static_cast<size_t>(a_ks) * KSTEP * ESIZE);
   };
-  auto advance_a = [&]() { if (a_ks < nks - 1) ++a_ks; };
   auto load_b_piece = [&](int slot, int i) {      // i = tile * 2 + half
     const int n = i >> 1, h = i & 1;
 #ifdef SSRNN_EXP_BCONST
@@ -109,11 +114,8 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
     else bring[slot][n].v[h] = *reinterpret_cast<const float4*>(s.xcur + off);
   };
   auto advance_b = [&]() {
-    if (b_ks < nks - 1) {
-      ++b_ks;
-      b_m += KSTEP;
-      if (b_m >= d) { b_m -= d; ++b_j; }
-    }
+    b_m += KSTEP;
+    if (b_m >= d) { b_m -= d; ++b_j; }
   };
   auto lds_write = [&](int slot, int q) {
     *reinterpret_cast<floatx4_t*>(wr_at + q * 8 * MFMA_LDS_ROW) = greg[slot][q];
@@ -143,63 +145,79 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
     }
   };
 
-  // ---- prologue: weight lines of steps 0..G-1, B of steps 0..S-2, fragments of step 0
-#pragma unroll
-  for (int p = 0; p < G; ++p) {
-#pragma unroll
-    for (int q = 0; q < 6; ++q) load_a_line(p, q);
-    advance_a();
-  }
-#pragma unroll
-  for (int p = 0; p < S - 1; ++p) {
-#pragma unroll
-    for (int i = 0; i < 2 * NT; ++i) load_b_piece(p, i);
-    advance_b();
-  }
-#pragma unroll
-  for (int q = 0; q < 6; ++q) lds_write(0, q);
-#pragma unroll
-  for (int q = 0; q < 6; ++q) load_a_line(0, q);        // step G into the slot just written out
-  advance_a();
-#pragma unroll
-  for (int i = 0; i < 6; ++i) lds_read(0, i);
-
-  // ---- main loop.  Step ks multiplies fragments afr[ks&1] with bring[ks%S]; meanwhile, in this order,
-  //   the lines of step ks+1 go from greg[(ks+1)%G] to LDS, that slot is refilled with step ks+1+G,
-  //   the B pieces of step ks+S-1 are requested, and the fragments of step ks+1 are read back.
   constexpr int NGRP = (WT == W_BF16) ? 6 : 8;
   constexpr int NITEM = 6 + 6 + 2 * NT + 6;             // LDS writes, line loads, B pieces, LDS reads
-  const int nmain = (nks / U) * U;
-  for (int ks0 = 0; ks0 < nmain; ks0 += U) {
+  // One k-step of the pipeline at ring position p.  Step ks multiplies fragments afr[ks&1] with
+  // bring[ks%S]; meanwhile, in this order, the lines of step ks+1 go from greg[(ks+1)%G] to LDS, slot
+  // ks%G (written out one step earlier) is refilled with step ks+G, the B pieces of step ks+S-1 are
+  // requested, and the fragments of step ks+1 are read back.  Every prefetch reaches at most G <= U
+  // steps ahead, so only the last iteration (LAST) can run past the end; there the work
+  // for steps that do not exist is left out at compile time.  No load is issued twice or out of range.
+  auto pipeline_step = [&](auto last_tag, auto p_tag) {
+    constexpr bool LAST = decltype(last_tag)::value;
+    constexpr int p = decltype(p_tag)::value;
+    constexpr bool stage_next = !LAST || (p + 1 < U);           // a step ks+1 exists
+    constexpr bool fetch_a = !LAST || (p + G < U);              // a step ks+G exists
+    constexpr bool fetch_b = !LAST || (p + S - 1 < U);          // a step ks+S-1 exists
+    constexpr int wslot = (p + 1) % G;                          // lines of step ks+1, fetched G-1 steps ago
+    constexpr int aslot = p % G;                                // lines of step ks went to LDS one step ago: refill
+    constexpr int bslot = p % S;
+    constexpr int bnext = (p + S - 1) % S;
 #pragma unroll
-    for (int p = 0; p < U; ++p) {
-      const int gslot = (p + 1) % G;
-      const int bslot = p % S;
-      const int bnext = (p + S - 1) % S;
+    for (int grp = 0; grp < NGRP; ++grp) {
+      mfma_group(p & 1, bslot, grp);
 #pragma unroll
-      for (int grp = 0; grp < NGRP; ++grp) {
-        mfma_group(p & 1, bslot, grp);
-#pragma unroll
-        for (int it = (grp * NITEM) / NGRP; it < ((grp + 1) * NITEM) / NGRP; ++it) {
-          if (it < 6) lds_write(gslot, it);
-          else if (it < 12) load_a_line(gslot, it - 6);
-          else if (it < 12 + 2 * NT) load_b_piece(bnext, it - 12);
-          else lds_read((p + 1) & 1, it - 12 - 2 * NT);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+      for (int it = (grp * NITEM) / NGRP; it < ((grp + 1) * NITEM) / NGRP; ++it) {
+        if (it < 6) { if constexpr (stage_next) lds_write(wslot, it); }
+        else if (it < 12) { if constexpr (fetch_a) load_a_line(aslot, it - 6); }
+        else if (it < 12 + 2 * NT) { if constexpr (fetch_b) load_b_piece(bnext, it - 12); }
+        else { if constexpr (stage_next) lds_read((p + 1) & 1, it - 12 - 2 * NT); }
       }
-      advance_a();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (fetch_a) ++a_ks;
+    if constexpr (fetch_b) advance_b();
+  };
+  auto pipeline_iteration = [&](auto last_tag) {
+    static_assert(U == 2 || U == 4, "ring positions are spelled out below");
+    pipeline_step(last_tag, std::integral_constant<int, 0>{});
+    pipeline_step(last_tag, std::integral_constant<int, 1>{});
+    if constexpr (U > 2) {
+      pipeline_step(last_tag, std::integral_constant<int, 2>{});
+      pipeline_step(last_tag, std::integral_constant<int, 3>{});
+    }
+  };
+
+  int ks_done = 0;
+  if (nks >= U && nks % U == 0) {
+    // ---- prologue: weight lines of steps 0..G-1, B of steps 0..S-2, fragments of step 0
+#pragma unroll
+    for (int p = 0; p < G; ++p) {
+#pragma unroll
+      for (int q = 0; q < 6; ++q) load_a_line(p, q);
+      ++a_ks;
+    }
+#pragma unroll
+    for (int p = 0; p < S - 1; ++p) {
+#pragma unroll
+      for (int i = 0; i < 2 * NT; ++i) load_b_piece(p, i);
       advance_b();
     }
+#pragma unroll
+    for (int q = 0; q < 6; ++q) lds_write(0, q);
+#pragma unroll
+    for (int i = 0; i < 6; ++i) lds_read(0, i);
+    for (int ks0 = 0; ks0 < nks - U; ks0 += U) pipeline_iteration(std::false_type{});
+    pipeline_iteration(std::true_type{});
+    ks_done = nks;
   }
-  // ---- remainder steps (nks not a multiple of U): same data path, no overlap
-  for (int ks = nmain; ks < nks; ++ks) {
+  // ---- k-step counts the pipeline does not take (not a multiple of its depth): same data path, no overlap
+  for (int ks = ks_done; ks < nks; ++ks) {
     a_ks = ks;
 #pragma unroll
     for (int q = 0; q < 6; ++q) load_a_line(0, q);
-    b_ks = ks;
     {
-      const int col = wave * KS + ks * KSTEP;
+      const int col = wcol + ks * KSTEP;
       b_j = col / d;
       b_m = col - b_j * d + kg * CW;
     }
@@ -214,7 +232,11 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
   }
 
   __syncthreads();      // the epilogue's LDS arrays overlay the waves' tiles
-  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
+  if (s.ksplit > 1) {
+    mfma_store_partials<NT>(s, d, f0, ksp, acc, part);
+    return;
+  }
+  mfma_epilogue<CELL, NT>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
 }
 
 }  // namespace ssrnn

@@ -57,8 +57,13 @@ struct WorkspaceLayout {
   size_t act_offset;    // buffer 0 = staged input of layer 0, buffer l = output of layer l-1
   size_t act16_stride;  // bytes of one bf16 copy (0 when the weight type does not use them)
   size_t act16_offset;
+  size_t upart_offset;  // partial pre-activations of split stages (narrow layers only)
+  size_t upart_bytes;
+  int upart_rows;       // rows per (part, gate) plane
   size_t total;
 };
+
+constexpr int KSPLIT_MAX = 8;
 
 // Buffer b (0 <= b < n_layers) holds the input rows of layer b for the current
 // block, preceded by the k-1 rows before it.  Buffer 0 is filled from x by a
@@ -72,7 +77,12 @@ WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
   w.act_offset = WS_CONTROL_BYTES;
   w.act16_stride = (wdt == SSRNN_BF16) ? align_up(rows * w.ld * sizeof(uint16_t), WS_ALIGN) : 0;
   w.act16_offset = w.act_offset + static_cast<size_t>(n_layers) * w.act_stride;
-  w.total = w.act16_offset + static_cast<size_t>(n_layers) * w.act16_stride;
+  w.upart_offset = w.act16_offset + static_cast<size_t>(n_layers) * w.act16_stride;
+  const int tcap = T < MFMA_MAX_T ? T : MFMA_MAX_T;
+  w.upart_rows = (tcap + 15) / 16 * 16;
+  w.upart_bytes = (d % MFMA_F == 0 && d / MFMA_F < 128)
+                      ? align_up(static_cast<size_t>(KSPLIT_MAX) * 3 * w.upart_rows * d * sizeof(float), WS_ALIGN) : 0;
+  w.total = w.upart_offset + w.upart_bytes;
   return w;
 }
 
@@ -169,9 +179,12 @@ struct Plan {
   int tt, nv, nw, npass, F, grid;
   // MFMA kernel geometry
   int nt_tiles;
+  int ksplit;          // workgroups per feature tile (columns split), 1 unless the layer is narrow
+  int mfma_nw;         // waves per workgroup of the matrix-core kernel
 };
 
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
+int g_tune_ksplit = 0;     // 0 = default, 1 = never split, 2/4/8 = at most that many parts
 int g_tune_mfma_lds = 0;   // 0 = default (LDS-staged weights when the shape allows), 1 = off, 2 = on
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
@@ -231,12 +244,26 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   const long ncol = static_cast<long>(p.k) * p.d;
   if (ncol % (nw * kstep) != 0) return false;
   if (p.d % kstep != 0) return false;   // a k-step never straddles two lag blocks
+  // Narrow layers: d/16 feature tiles do not fill 256 CUs, so the columns are split over
+  // up to KSPLIT_MAX workgroups per tile (LDS-staged kernel only) and a second kernel finishes.
+  p.ksplit = 1;
+  const int ntile = p.d / MFMA_F;
+  if (ntile < 128 && p.nt_tiles <= 8 && g_tune_mfma_lds != 1 && g_tune_ksplit != 1) {
+    int ks = 1;
+    while (ks < KSPLIT_MAX && ntile * ks * 2 <= 256 && ncol % (static_cast<long>(nw) * kstep * ks * 2) == 0) ks *= 2;
+    if (g_tune_ksplit > 1 && g_tune_ksplit <= ks) ks = g_tune_ksplit;
+    p.ksplit = ks;
+  }
+  // waves per workgroup: the kernel's maximum, halved (not below one per SIMD) while a wave would get a single k-step
+  p.mfma_nw = nw;
+  if (p.ksplit > 1)
+    while (p.mfma_nw > 4 && ncol / (static_cast<long>(p.mfma_nw) * p.ksplit * kstep) < 2) p.mfma_nw /= 2;
   return true;
 }
 
 template <int CELL>
 int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
-  const dim3 grid(p.d / MFMA_F);
+  const dim3 grid(p.d / MFMA_F * p.ksplit);
 #define SSRNN_MFMA_CASE(NT_)                                                                          \
   if (p.nt_tiles == NT_) {                                                                            \
     const dim3 block(MfmaCfg<NT_>::NW * 64);                                                          \
@@ -248,14 +275,16 @@ int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
   }
   // Weights staged through LDS (whole-line streaming loads) measure faster except for fp32 at 64 steps.
   const bool lds_default = !(p.wdt == SSRNN_F32 && p.nt_tiles == 4);
-  if (g_tune_mfma_lds == 2 || (g_tune_mfma_lds == 0 && lds_default)) {
+  if (p.ksplit > 1 || g_tune_mfma_lds == 2 || (g_tune_mfma_lds == 0 && lds_default)) {
 #define SSRNN_MFMA_LDS_CASE(NT_)                                                                          \
   if (p.nt_tiles == NT_) {                                                                                \
-    const dim3 block(MfmaCfg<NT_>::NW * 64);                                                              \
+    const dim3 block(p.mfma_nw * 64);                                                                     \
     if (p.wdt == SSRNN_BF16)                                                                              \
       hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k);    \
     else                                                                                                  \
       hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
+    if (p.ksplit > 1)                                                                                     \
+      hipLaunchKernelGGL((split_epilogue_kernel<CELL>), dim3(p.d / MFMA_F), dim3(512), 0, st, s, p.d, p.k); \
     return SSRNN_OK;                                                                                      \
   }
     SSRNN_MFMA_LDS_CASE(1) SSRNN_MFMA_LDS_CASE(2) SSRNN_MFMA_LDS_CASE(4) SSRNN_MFMA_LDS_CASE(8)
@@ -395,6 +424,9 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       }
       s.c = c_final + static_cast<long>(l) * d;
       s.nt = nt;
+      s.ksplit = (p.kind == K_MFMA) ? p.ksplit : 1;
+      s.upart = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.upart_offset);
+      s.tp = wl.upart_rows;
       const int rc = (cell == CELL_SRU) ? launch_stage<CELL_SRU>(p, s, st) : launch_stage<CELL_QRNN>(p, s, st);
       if (rc != SSRNN_OK) return rc;
     }
@@ -452,6 +484,7 @@ int ssrnn_tune(const char* key, int value) {
   else if (!strcmp(key, "valu_nw")) g_tune_valu_nw = value;
   else if (!strcmp(key, "valu_nv")) g_tune_valu_nv = value;
   else if (!strcmp(key, "mfma_lds")) g_tune_mfma_lds = value;
+  else if (!strcmp(key, "ksplit")) g_tune_ksplit = value;
   else return fail(SSRNN_EINVAL, "ssrnn_tune: unknown key %s", key);
   return SSRNN_OK;
 }
