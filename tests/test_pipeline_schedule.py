@@ -1,0 +1,96 @@
+"""CPU model of the software pipeline in csrc/kernel_mfma_lds.hip.h.
+
+The kernel keeps three rings per wavefront -- G register slots of weight lines
+in flight from memory, S slots of B fragments, two fragment buffers fed from
+the wave's LDS tile -- and unrolls U k-steps per loop iteration, leaving out in
+the last iteration the prefetches that would run past the last k-step.  This
+model replays that schedule (same slot arithmetic, same compile-time
+predicates) and checks that every load index is in range, that every k-step is
+loaded exactly once, and that each multiply consumes the fragments of its own
+step.  An out-of-range prefetch is a GPU memory fault, so the schedule is
+checked here, on the CPU, for every ring configuration the kernel instantiates.
+"""
+import pytest
+
+
+def replay(G, S, U, nks):
+    assert nks >= U and nks % U == 0
+    greg = [None] * G
+    bring = [None] * S
+    afr = [None, None]
+    a_ks = 0
+    b_ks = 0
+    loaded_a, loaded_b = [], []
+
+    def load_a(slot):
+        assert 0 <= a_ks < nks, ("weight prefetch out of range", a_ks, nks)
+        greg[slot] = a_ks
+        loaded_a.append(a_ks)
+
+    def load_b(slot):
+        assert 0 <= b_ks < nks, ("B prefetch out of range", b_ks, nks)
+        bring[slot] = b_ks
+        loaded_b.append(b_ks)
+
+    # prologue
+    for p in range(G):
+        load_a(p)
+        a_ks += 1
+    for p in range(S - 1):
+        load_b(p)
+        b_ks += 1
+    lds = greg[0]
+    afr[0] = lds
+    ks = 0
+    niter = nks // U
+    for it in range(niter):
+        last = it == niter - 1
+        for p in range(U):
+            stage_next = (not last) or (p + 1 < U)
+            fetch_a = (not last) or (p + G < U)
+            fetch_b = (not last) or (p + S - 1 < U)
+            assert afr[p & 1] == ks, ("fragments of the wrong step", afr[p & 1], ks)
+            assert bring[p % S] == ks, ("B fragments of the wrong step", bring[p % S], ks)
+            if stage_next:
+                assert greg[(p + 1) % G] == ks + 1, ("lines of the wrong step go to LDS", greg, ks)
+                lds = greg[(p + 1) % G]
+            if fetch_a:
+                load_a(p % G)
+                a_ks += 1
+            if fetch_b:
+                load_b((p + S - 1) % S)
+                b_ks += 1
+            if stage_next:
+                afr[(p + 1) & 1] = lds
+            ks += 1
+    assert ks == nks
+    assert sorted(loaded_a) == list(range(nks)), "each k-step's weight lines are loaded exactly once"
+    assert sorted(loaded_b) == list(range(nks)), "each k-step's B fragments are loaded exactly once"
+
+
+# (G, S) per number of time tiles as in MfmaLdsCfg: NT <= 2 -> (4, 4); NT = 4 -> (2, 2); NT = 8 -> (4, 2)
+@pytest.mark.parametrize("G,S", [(4, 4), (2, 2), (4, 2)])
+@pytest.mark.parametrize("nks", [2, 4, 8, 12, 16, 32, 64, 128])
+def test_schedule_is_in_range_and_complete(G, S, nks):
+    U = max(G, S)
+    if nks < U or nks % U:
+        pytest.skip("the kernel takes its unpipelined path for this k-step count")
+    replay(G, S, U, nks)
+
+
+def test_model_catches_a_prefetch_that_reaches_too_far():
+    """The schedule that refills a slot G+1 steps ahead (one more than the ring
+    allows) must be rejected: it reads one k-step past the end."""
+    G = S = U = 4
+    nks = 8
+    a_ks = G + 1          # prologue of that schedule: steps 0..G-1 plus one more
+    ks = 0
+    with pytest.raises(AssertionError):
+        for it in range(nks // U):
+            last = it == nks // U - 1
+            for p in range(U):
+                fetch_a = (not last) or (p + 1 + G < U)
+                if fetch_a:
+                    assert a_ks < nks, "out of range"
+                    a_ks += 1
+                ks += 1
