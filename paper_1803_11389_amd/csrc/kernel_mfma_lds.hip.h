@@ -1,4 +1,4 @@
-// Matrix-core kernel, weights staged through LDS (NT <= 8 time tiles).
+// Matrix-core kernel, weights staged through LDS.
 //
 // Same decomposition and epilogue as stage_mfma_kernel; what differs is how
 // the weight fragments reach the matrix cores.  A 16x16 MFMA wants 16 rows on
@@ -27,13 +27,13 @@ constexpr int MFMA_LDS_TILE = 48 * MFMA_LDS_ROW;        // 48 weight rows of one
 
 template <int NT>
 struct MfmaLdsCfg {
-  static constexpr int G = (NT <= 2 || NT >= 8) ? 4 : 2;  // k-steps of weight loads in flight
+  static constexpr int G = (NT <= 2 || NT == 8) ? 4 : 2;  // k-steps of weight loads in flight
   static constexpr int S = (NT <= 2) ? 4 : 2;             // B fragment ring slots
+  static constexpr int NBT = (NT > 8) ? 8 : NT;           // time tiles per B fetch (a k-step takes NT/NBT fetches)
 };
 
 template <int CELL, int WT, int NT>
 __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(Stage s, int d, int k) {
-  static_assert(NT <= 8, "the LDS-staged kernel holds all B tiles of a step at once");
   constexpr int NW = MfmaCfg<NT>::NW;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int KSTEP = (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
@@ -42,6 +42,8 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
   constexpr int CHUNK = NTC * 256;
   constexpr int G = MfmaLdsCfg<NT>::G;
   constexpr int S = MfmaLdsCfg<NT>::S;
+  constexpr int NBT = MfmaLdsCfg<NT>::NBT;
+  constexpr int NBH = NT / NBT;                      // B fetches ("sub-steps") per k-step
   constexpr int U = (G > S) ? G : S;                 // unroll: both rings and the fragment double buffer repeat
   static_assert(U % G == 0 && U % S == 0 && U % 2 == 0 && G <= U && S <= U, "ring sizes must divide the unroll factor");
 
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
 
   floatx4_t greg[G][6];          // weight lines in flight from memory
   floatx4_t afr[2][3][2];        // fragments of the current and the next k-step
-  BFrag<WT> bring[S][NT];
+  BFrag<WT> bring[S][NBT];
 
   // cursors of the two prefetch streams; the pipeline's last iteration issues no load past the last k-step
   int a_ks = 0;                                   // next k-step whose weight lines are requested
@@ -104,12 +106,9 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
   auto load_a_line = [&](int slot, int q) {
     greg[slot][q] = load_stream16(gptr[q] + static_cast<size_t>(a_ks) * KSTEP * ESIZE);
   };
-  auto load_b_piece = [&](int slot, int i) {      // i = tile * 2 + half
+  auto load_b_piece = [&](int slot, int tile0, int i) {      // i = (tile - tile0) * 2 + half
     const int n = i >> 1, h = i & 1;
-#ifdef SSRNN_EXP_BCONST
-    if constexpr (WT == W_F32) { bring[slot][n].v[h] = make_float4(lane * 1e-3f, 1.f, 2.f, n); return; }
-#endif
-    const long off = static_cast<long>(trow[n] - b_j) * s.ldx + b_m + h * (CW / 2);
+    const long off = static_cast<long>(trow[tile0 + n] - b_j) * s.ldx + b_m + h * (CW / 2);
     if constexpr (WT == W_BF16) bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
     else bring[slot][n].v[h] = *reinterpret_cast<const float4*>(s.xcur + off);
   };
@@ -124,59 +123,73 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
     const int g = i >> 1, h = i & 1;
     afr[buf][g][h] = *reinterpret_cast<const floatx4_t*>(rd_at + g * 16 * MFMA_LDS_ROW + h * 16);
   };
-  auto mfma_group = [&](int buf, int bslot, int grp) {
+  auto mfma_group = [&](int buf, int bslot, int tile0, int grp) {
     if constexpr (WT == W_BF16) {
       const int h = grp / 3, g = grp - 3 * (grp / 3);
       bf16x8_t ab;
       __builtin_memcpy(&ab, &afr[buf][g][h], sizeof ab);
 #pragma unroll
-      for (int n = 0; n < NT; ++n)
-        acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[h], acc[g][n], 0, 0, 0);
+      for (int n = 0; n < NBT; ++n)
+        acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[h], acc[g][tile0 + n], 0, 0, 0);
     } else {
       const int h = grp >> 2, q = grp & 3;
 #pragma unroll
       for (int g = 0; g < 3; ++g)
 #pragma unroll
-        for (int n = 0; n < NT; ++n) {
+        for (int n = 0; n < NBT; ++n) {
           const float4 bv = bring[bslot][n].v[h];
           const float bq = q == 0 ? bv.x : q == 1 ? bv.y : q == 2 ? bv.z : bv.w;
-          acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(afr[buf][g][h][q], bq, acc[g][n], 0, 0, 0);
+          acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(afr[buf][g][h][q], bq, acc[g][tile0 + n], 0, 0, 0);
         }
     }
   };
 
-  constexpr int NGRP = (WT == W_BF16) ? 6 : 8;
-  constexpr int NITEM = 6 + 6 + 2 * NT + 6;             // LDS writes, line loads, B pieces, LDS reads
-  // One k-step of the pipeline at ring position p.  Step ks multiplies fragments afr[ks&1] with
-  // bring[ks%S]; meanwhile, in this order, the lines of step ks+1 go from greg[(ks+1)%G] to LDS, slot
-  // ks%G (written out one step earlier) is refilled with step ks+G, the B pieces of step ks+S-1 are
-  // requested, and the fragments of step ks+1 are read back.  Every prefetch reaches at most G <= U
-  // steps ahead, so only the last iteration (LAST) can run past the end; there the work
-  // for steps that do not exist is left out at compile time.  No load is issued twice or out of range.
+  constexpr int NGRP = (WT == W_BF16) ? 6 : 8;          // MFMA groups per sub-step
+  // One k-step of the pipeline at ring position p.  Step ks multiplies fragments afr[ks&1] with the B
+  // fragments of its NBH sub-steps (sub-step ss = ks*NBH + hb sits in bring[ss%S]); meanwhile, in this
+  // order, the lines of step ks+1 go from greg[(ks+1)%G] to LDS, slot ks%G (written out one step
+  // earlier) is refilled with step ks+G, the B pieces of sub-step ss+S-1 are requested, and the
+  // fragments of step ks+1 are read back.  Every prefetch reaches at most G <= U steps ahead, so only
+  // the last iteration (LAST) can run past the end; there the work for steps that do not exist is left
+  // out at compile time.  No load is issued twice or out of range.
   auto pipeline_step = [&](auto last_tag, auto p_tag) {
     constexpr bool LAST = decltype(last_tag)::value;
     constexpr int p = decltype(p_tag)::value;
     constexpr bool stage_next = !LAST || (p + 1 < U);           // a step ks+1 exists
     constexpr bool fetch_a = !LAST || (p + G < U);              // a step ks+G exists
-    constexpr bool fetch_b = !LAST || (p + S - 1 < U);          // a step ks+S-1 exists
     constexpr int wslot = (p + 1) % G;                          // lines of step ks+1, fetched G-1 steps ago
     constexpr int aslot = p % G;                                // lines of step ks went to LDS one step ago: refill
-    constexpr int bslot = p % S;
-    constexpr int bnext = (p + S - 1) % S;
 #pragma unroll
-    for (int grp = 0; grp < NGRP; ++grp) {
-      mfma_group(p & 1, bslot, grp);
+    for (int hb = 0; hb < NBH; ++hb) {
+      const int ss = p * NBH + hb;                              // sub-step within the iteration
+      const int bslot = ss % S;
+      const int tgt = ss + S - 1;                               // sub-step whose B pieces are requested now
+      const bool fetch_b = !LAST || (tgt < U * NBH);
+      const int bnext = tgt % S;
+      const int btile0 = (tgt % NBH) * NBT;
+      // items of this sub-step: LDS writes and line loads ride on the first, LDS reads on the last
+      const int n_head = (hb == 0) ? 12 : 0;
+      const int n_tail = (hb == NBH - 1) ? 6 : 0;
+      const int nitem = n_head + 2 * NBT + n_tail;
 #pragma unroll
-      for (int it = (grp * NITEM) / NGRP; it < ((grp + 1) * NITEM) / NGRP; ++it) {
-        if (it < 6) { if constexpr (stage_next) lds_write(wslot, it); }
-        else if (it < 12) { if constexpr (fetch_a) load_a_line(aslot, it - 6); }
-        else if (it < 12 + 2 * NT) { if constexpr (fetch_b) load_b_piece(bnext, it - 12); }
-        else { if constexpr (stage_next) lds_read((p + 1) & 1, it - 12 - 2 * NT); }
+      for (int grp = 0; grp < NGRP; ++grp) {
+        mfma_group(p & 1, bslot, hb * NBT, grp);
+#pragma unroll
+        for (int it = (grp * nitem) / NGRP; it < ((grp + 1) * nitem) / NGRP; ++it) {
+          if (it < n_head) {
+            if (it < 6) { if constexpr (stage_next) lds_write(wslot, it); }
+            else { if constexpr (fetch_a) load_a_line(aslot, it - 6); }
+          } else if (it < n_head + 2 * NBT) {
+            if (fetch_b) load_b_piece(bnext, btile0, it - n_head);
+          } else {
+            if constexpr (stage_next) lds_read((p + 1) & 1, it - n_head - 2 * NBT);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
+      if (fetch_b && (tgt % NBH) == NBH - 1) advance_b();       // the column cursor moves once per k-step
     }
     if constexpr (fetch_a) ++a_ks;
-    if constexpr (fetch_b) advance_b();
   };
   auto pipeline_iteration = [&](auto last_tag) {
     static_assert(U == 2 || U == 4, "ring positions are spelled out below");
@@ -198,10 +211,10 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
       ++a_ks;
     }
 #pragma unroll
-    for (int p = 0; p < S - 1; ++p) {
+    for (int ss = 0; ss < S - 1; ++ss) {                  // B pieces of sub-steps 0..S-2
 #pragma unroll
-      for (int i = 0; i < 2 * NT; ++i) load_b_piece(p, i);
-      advance_b();
+      for (int i = 0; i < 2 * NBT; ++i) load_b_piece(ss % S, (ss % NBH) * NBT, i);
+      if (ss % NBH == NBH - 1) advance_b();
     }
 #pragma unroll
     for (int q = 0; q < 6; ++q) lds_write(0, q);
@@ -222,13 +235,16 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
       b_m = col - b_j * d + kg * CW;
     }
 #pragma unroll
-    for (int i = 0; i < 2 * NT; ++i) load_b_piece(0, i);
-#pragma unroll
     for (int q = 0; q < 6; ++q) lds_write(0, q);
 #pragma unroll
     for (int i = 0; i < 6; ++i) lds_read(0, i);
 #pragma unroll
-    for (int grp = 0; grp < NGRP; ++grp) mfma_group(0, 0, grp);
+    for (int hb = 0; hb < NBH; ++hb) {
+#pragma unroll
+      for (int i = 0; i < 2 * NBT; ++i) load_b_piece(0, hb * NBT, i);
+#pragma unroll
+      for (int grp = 0; grp < NGRP; ++grp) mfma_group(0, 0, hb * NBT, grp);
+    }
   }
 
   __syncthreads();      // the epilogue's LDS arrays overlay the waves' tiles

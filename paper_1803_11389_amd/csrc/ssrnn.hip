@@ -273,21 +273,23 @@ int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
       hipLaunchKernelGGL((stage_mfma_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
     return SSRNN_OK;                                                                                  \
   }
-  // Weights staged through LDS (whole-line streaming loads) measure faster except for fp32 at 64 steps.
-  const bool lds_default = !(p.wdt == SSRNN_F32 && p.nt_tiles == 4);
-  if (p.ksplit > 1 || g_tune_mfma_lds == 2 || (g_tune_mfma_lds == 0 && lds_default)) {
+  // Weights staged through LDS (whole-line streaming loads) measure faster at every block length.  The
+  // 16-tile fp32 instance does not fit the register file (it would spill), so fp32 blocks longer than
+  // 128 steps keep the direct-load kernel.
+  const bool lds_fits = !(p.nt_tiles == 16 && p.wdt == SSRNN_F32);
+  if (p.ksplit > 1 || (g_tune_mfma_lds != 1 && lds_fits)) {
 #define SSRNN_MFMA_LDS_CASE(NT_)                                                                          \
   if (p.nt_tiles == NT_) {                                                                                \
     const dim3 block(p.mfma_nw * 64);                                                                     \
     if (p.wdt == SSRNN_BF16)                                                                              \
       hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k);    \
-    else                                                                                                  \
+    else if constexpr (NT_ < 16)                                                                          \
       hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
     if (p.ksplit > 1)                                                                                     \
       hipLaunchKernelGGL((split_epilogue_kernel<CELL>), dim3(p.d / MFMA_F), dim3(512), 0, st, s, p.d, p.k); \
     return SSRNN_OK;                                                                                      \
   }
-    SSRNN_MFMA_LDS_CASE(1) SSRNN_MFMA_LDS_CASE(2) SSRNN_MFMA_LDS_CASE(4) SSRNN_MFMA_LDS_CASE(8)
+    SSRNN_MFMA_LDS_CASE(1) SSRNN_MFMA_LDS_CASE(2) SSRNN_MFMA_LDS_CASE(4) SSRNN_MFMA_LDS_CASE(8) SSRNN_MFMA_LDS_CASE(16)
 #undef SSRNN_MFMA_LDS_CASE
   }
   SSRNN_MFMA_CASE(1) SSRNN_MFMA_CASE(2) SSRNN_MFMA_CASE(4) SSRNN_MFMA_CASE(8) SSRNN_MFMA_CASE(16)

@@ -13,13 +13,14 @@ checked here, on the CPU, for every ring configuration the kernel instantiates.
 import pytest
 
 
-def replay(G, S, U, nks):
-    assert nks >= U and nks % U == 0
+def replay(G, S, U, nks, NBH=1):
+    """NBH: B fetches (sub-steps) per k-step; sub-step ss = ks*NBH + hb lives in B slot ss % S."""
+    assert nks >= U and nks % U == 0 and (U * NBH) % S == 0
     greg = [None] * G
     bring = [None] * S
     afr = [None, None]
     a_ks = 0
-    b_ks = 0
+    b_col = 0              # k-step the B column cursor points at
     loaded_a, loaded_b = [], []
 
     def load_a(slot):
@@ -27,18 +28,19 @@ def replay(G, S, U, nks):
         greg[slot] = a_ks
         loaded_a.append(a_ks)
 
-    def load_b(slot):
-        assert 0 <= b_ks < nks, ("B prefetch out of range", b_ks, nks)
-        bring[slot] = b_ks
-        loaded_b.append(b_ks)
+    def load_b(slot, hb):
+        assert 0 <= b_col < nks, ("B prefetch out of range", b_col, nks)
+        bring[slot] = (b_col, hb)
+        loaded_b.append((b_col, hb))
 
     # prologue
     for p in range(G):
         load_a(p)
         a_ks += 1
-    for p in range(S - 1):
-        load_b(p)
-        b_ks += 1
+    for ss in range(S - 1):
+        load_b(ss % S, ss % NBH)
+        if ss % NBH == NBH - 1:
+            b_col += 1
     lds = greg[0]
     afr[0] = lds
     ks = 0
@@ -48,34 +50,41 @@ def replay(G, S, U, nks):
         for p in range(U):
             stage_next = (not last) or (p + 1 < U)
             fetch_a = (not last) or (p + G < U)
-            fetch_b = (not last) or (p + S - 1 < U)
             assert afr[p & 1] == ks, ("fragments of the wrong step", afr[p & 1], ks)
-            assert bring[p % S] == ks, ("B fragments of the wrong step", bring[p % S], ks)
-            if stage_next:
-                assert greg[(p + 1) % G] == ks + 1, ("lines of the wrong step go to LDS", greg, ks)
-                lds = greg[(p + 1) % G]
+            for hb in range(NBH):
+                ss = p * NBH + hb
+                assert bring[ss % S] == (ks, hb), ("B fragments of the wrong sub-step", bring[ss % S], ks, hb)
+                tgt = ss + S - 1
+                fetch_b = (not last) or (tgt < U * NBH)
+                if hb == 0:
+                    if stage_next:
+                        assert greg[(p + 1) % G] == ks + 1, ("lines of the wrong step go to LDS", greg, ks)
+                        lds = greg[(p + 1) % G]
+                    if fetch_a:
+                        load_a(p % G)
+                if fetch_b:
+                    load_b(tgt % S, tgt % NBH)
+                    if tgt % NBH == NBH - 1:
+                        b_col += 1
+                if hb == NBH - 1 and stage_next:
+                    afr[(p + 1) & 1] = lds
             if fetch_a:
-                load_a(p % G)
                 a_ks += 1
-            if fetch_b:
-                load_b((p + S - 1) % S)
-                b_ks += 1
-            if stage_next:
-                afr[(p + 1) & 1] = lds
             ks += 1
     assert ks == nks
     assert sorted(loaded_a) == list(range(nks)), "each k-step's weight lines are loaded exactly once"
-    assert sorted(loaded_b) == list(range(nks)), "each k-step's B fragments are loaded exactly once"
+    assert sorted(loaded_b) == [(k, h) for k in range(nks) for h in range(NBH)], "each B sub-step is loaded exactly once"
 
 
-# (G, S) per number of time tiles as in MfmaLdsCfg: NT <= 2 -> (4, 4); NT = 4 -> (2, 2); NT = 8 -> (4, 2)
-@pytest.mark.parametrize("G,S", [(4, 4), (2, 2), (4, 2)])
+# (G, S, NBH) per number of time tiles as in MfmaLdsCfg:
+# NT <= 2 -> (4, 4, 1); NT = 4 -> (2, 2, 1); NT = 8 -> (4, 2, 1); NT = 16 -> (2, 2, 2)
+@pytest.mark.parametrize("G,S,NBH", [(4, 4, 1), (2, 2, 1), (4, 2, 1), (2, 2, 2)])
 @pytest.mark.parametrize("nks", [2, 4, 8, 12, 16, 32, 64, 128])
-def test_schedule_is_in_range_and_complete(G, S, nks):
+def test_schedule_is_in_range_and_complete(G, S, NBH, nks):
     U = max(G, S)
     if nks < U or nks % U:
         pytest.skip("the kernel takes its unpipelined path for this k-step count")
-    replay(G, S, U, nks)
+    replay(G, S, U, nks, NBH)
 
 
 def test_model_catches_a_prefetch_that_reaches_too_far():
