@@ -297,18 +297,11 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
   // B fragments of k-step ks for tiles nb0 .. nb0+NB-1.  Column col0 + ks*KSTEP
   // lies in lag block j = col / d (lag blocks are multiples of KSTEP wide).
   auto load_b = [&](int ks, int nb0, BFrag<WT> (&b)[NB]) {
-#ifdef SSRNN_EXP_B0
-    const int col = col0 + (ks & 1) * KSTEP;
-#else
     const int col = col0 + ks * KSTEP;
-#endif
     const int j = col / d;
     const int m = col - j * d;
 #pragma unroll
     for (int n = 0; n < NB; ++n) {
-#ifdef SSRNN_EXP_BCONST
-      if constexpr (WT == W_F32) { b[n].v[0] = make_float4(lane * 1e-3f, 1.f, 2.f, n); b[n].v[1] = b[n].v[0]; continue; }
-#endif
       const long off = static_cast<long>(trow[nb0 + n] - j) * s.ldx + m;
       if constexpr (WT == W_BF16) {
         b[n].v[0] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
@@ -387,10 +380,6 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
       if (i < 6) {
         const int g = i >> 1, h = i & 1;
         // plain (cached) load: the two halves of a 128-byte line are fetched by two instructions
-#ifdef SSRNN_EXP_NT2
-        if (h == 1) aring[slot][g][h] = load_stream16(arow[g] + static_cast<size_t>(lks) * KSTEP * ESIZE + h * 16);
-        else
-#endif
         aring[slot][g][h] = *reinterpret_cast<const floatx4_t*>(arow[g] + static_cast<size_t>(lks) * KSTEP * ESIZE + h * 16);
       } else {
         const int n = (i - 6) >> 1, h = (i - 6) & 1;
@@ -500,9 +489,6 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_kernel(Stage 
     }
   }
 
-#ifdef SSRNN_EXP_NOEPI
-  if (s.nt > 0) { if (acc[0][0][0] == 123.456f) s.hout[0] = acc[1][0][1] + acc[2][NT - 1][2]; return; }
-#endif
   mfma_epilogue<CELL, NT>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
 }
 
