@@ -50,6 +50,8 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="skip the other block sizes")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--flags", type=int, default=0, help="ssrnn flags (schedule / kernel override)")
+    ap.add_argument("--packed", action="store_true",
+                    help="pre-pack the weights (ssrnn_pack_weights, outside the timed region) and run every block size on the matrix-core kernel")
     ap.add_argument("--cpu-sample-steps", type=int, default=0, help="time steps of the CPU sample (0 = auto)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB three times and exit: the reference "
@@ -88,6 +90,9 @@ def main():
     inp = wl.make_inputs(cfg)
     W_host = inp["W"]
     W = [torch.from_numpy(w).to(dev) for w in W_host]
+    if args.packed:
+        W = [ss.pack_weights(w) for w in W]
+        args.flags |= ss.WEIGHTS_PACKED
     if cfg.d_feat:
         feat = torch.from_numpy(inp["feat"]).to(dev)
         P = torch.from_numpy(inp["P"]).to(dev)

@@ -57,7 +57,8 @@ enum {
   SSRNN_KERNEL_GENERIC = 1 << 4, /* any d, k, T: one wavefront per output feature            */
   SSRNN_KERNEL_VALU = 2 << 4,    /* bandwidth kernel, FMA on the vector ALU                  */
   SSRNN_KERNEL_MFMA = 3 << 4,    /* matrix-core kernel                                       */
-  SSRNN_KERNEL_MASK = 7 << 4
+  SSRNN_KERNEL_MASK = 7 << 4,
+  SSRNN_WEIGHTS_PACKED = 1 << 8  /* every W[l] was written by ssrnn_pack_weights                */
 };
 
 /* Library version, major*10000 + minor*100 + patch.  Host; never fails. */
@@ -110,6 +111,22 @@ int qrnn_forward(const void* const* W, const float* const* bias, const float* x,
  * (40-dim features -> d); not part of the paper's method. */
 int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
                          int d_in, long L, void* stream);
+
+/* Weight pre-pack (model-load time, once per layer): re-tiles a row-major
+ * [3d x k*d] matrix into the order the matrix-core kernel consumes it, so that
+ * each of that kernel's load instructions reads one contiguous KiB of whole
+ * cache lines.  It is the row-blocking of Section 3 (fetch a piece of a row
+ * once, use it for all T steps) applied to 16-row MFMA tiles.  The values are
+ * only permuted.  ssrnn_packed_weight_bytes: host; bytes of the packed buffer
+ * (equal to the matrix's size), or 0 if the shape cannot be packed (needs
+ * d % 16 == 0 and d*sizeof(weight) % 128 == 0).  ssrnn_pack_weights: W and
+ * W_packed are distinct 16-byte aligned device buffers of that size; the copy
+ * is enqueued on stream.  Pass the packed buffers as W[l] together with
+ * SSRNN_WEIGHTS_PACKED in flags; shapes the matrix-core kernel cannot take
+ * then fail with SSRNN_EUNSUPPORTED. */
+size_t ssrnn_packed_weight_bytes(int d, int k, int wdtype);
+int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype,
+                       void* stream);
 
 /* Measurement aid: override one launch-geometry choice of the kernels for the
  * calls that follow, process-wide (not thread-safe; 0 restores the default).

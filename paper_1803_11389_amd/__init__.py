@@ -17,10 +17,12 @@ LIB_PATH = os.path.join(_HERE, "libssrnn.so")
 F32, BF16 = 0, 1
 SCHED_AUTO, SCHED_STAGES, SCHED_PERSISTENT = 0, 1, 2
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_VALU, KERNEL_MFMA = 0, 1 << 4, 2 << 4, 3 << 4
+WEIGHTS_PACKED = 1 << 8
 
 # every symbol include/ssrnn.h declares
 EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",
-           "qrnn_forward", "ssrnn_linear_forward", "ssrnn_tune")
+           "qrnn_forward", "ssrnn_linear_forward", "ssrnn_packed_weight_bytes", "ssrnn_pack_weights",
+           "ssrnn_tune")
 
 _lib = None
 
@@ -52,6 +54,10 @@ def load_library():
     lib.qrnn_forward.argtypes = [vp] * 8 + [ip, ip, lp, ip, ip, ip, ip, vp, sz, vp]
     lib.ssrnn_linear_forward.restype = ip
     lib.ssrnn_linear_forward.argtypes = [vp] * 3 + [ip, ip, lp, vp]
+    lib.ssrnn_packed_weight_bytes.restype = sz
+    lib.ssrnn_packed_weight_bytes.argtypes = [ip] * 3
+    lib.ssrnn_pack_weights.restype = ip
+    lib.ssrnn_pack_weights.argtypes = [vp, vp, ip, ip, ip, vp]
     lib.ssrnn_tune.restype = ip
     lib.ssrnn_tune.argtypes = [ctypes.c_char_p, ip]
     _lib = lib
@@ -73,6 +79,27 @@ def tune(key: str, value: int) -> None:
 
 def workspace_bytes(n_layers: int, d: int, k: int, T: int, wdtype: int) -> int:
     return load_library().ssrnn_workspace_bytes(n_layers, d, k, T, wdtype)
+
+
+def packed_weight_bytes(d: int, k: int, wdtype: int) -> int:
+    return load_library().ssrnn_packed_weight_bytes(d, k, wdtype)
+
+
+def pack_weights(W, stream=None):
+    """ssrnn_pack_weights: returns a new device tensor of W's shape and dtype
+    that holds the [3d, k*d] matrix in the matrix-core kernel's order; pass it
+    to *_forward with flags | WEIGHTS_PACKED."""
+    import torch
+    lib = load_library()
+    _req(W, "W")
+    d = W.shape[0] // 3
+    if W.dim() != 2 or W.shape[0] != 3 * d or W.shape[1] % d != 0:
+        raise ValueError("W must be [3d, k*d]")
+    k = W.shape[1] // d
+    wdt = _wdtype(W)
+    out = torch.empty_like(W)
+    _check(lib.ssrnn_pack_weights(_p(W), _p(out), d, k, wdt, _stream_handle(stream)))
+    return out
 
 
 def _wdtype(w) -> int:

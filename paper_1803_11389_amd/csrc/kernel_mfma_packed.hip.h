@@ -1,0 +1,235 @@
+// Matrix-core kernel for pre-packed weights.
+//
+// Same decomposition and epilogue as the other matrix-core kernels; the weight
+// matrix has been re-tiled once, at model-load time, into the order the MFMA
+// fragments are consumed (pack_weights_kernel below): for feature tile ft and
+// k-step s the six 1 KiB fragments (gate 0..2 x half 0..1) lie back to back,
+//
+//   chunk index = (((ft * nks_total + s) * 3 + gate) * 2 + half) * 64 + lane,   16 bytes per chunk,
+//   chunk       = row (gate*d + ft*16 + lane%16), bytes [s*128 + (lane/16)*32 + half*16, +16) of that row,
+//
+// so that every load instruction of a wave reads one contiguous KiB (eight
+// whole cache lines, non-temporal) straight into the registers an MFMA takes
+// as its A operand: no LDS staging, no split lines.  A workgroup's weights are
+// one contiguous slab and a wave walks a contiguous piece of it.
+//
+// Pipeline: a ring of SA register slots holds the fragments of SA-1 future
+// k-steps; a ring of SB slots holds the input-block (B) fragments of SB-1
+// future sub-steps (a k-step takes NT/NBT sub-steps of NBT time tiles).  The
+// loads of one step are spread between the MFMA groups of the step in issue
+// order.  The last iteration is a compile-time specialisation that requests
+// nothing past the wave's last k-step.
+#pragma once
+
+#include <type_traits>
+
+#include "kernel_mfma.hip.h"
+
+namespace ssrnn {
+
+template <int NT>
+struct MfmaPkCfg {
+  static constexpr int SA = 4;                            // weight fragment ring slots (k-steps)
+  static constexpr int SB = (NT <= 2) ? 4 : 2;            // B fragment ring slots (sub-steps)
+  static constexpr int NBT = (NT > 8) ? 8 : NT;           // time tiles per B fetch
+};
+
+// One thread per 16-byte chunk of the packed matrix (see the layout above).
+__global__ void pack_weights_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int d, long row_chunks,
+                                    int nks_total, long nchunks) {
+  const long o = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (o >= nchunks) return;
+  const int lane = static_cast<int>(o & 63);
+  const int half = static_cast<int>((o >> 6) & 1);
+  const long r = o >> 7;
+  const int gate = static_cast<int>(r % 3);
+  const long r2 = r / 3;
+  const int s = static_cast<int>(r2 % nks_total);
+  const long ft = r2 / nks_total;
+  const long row = static_cast<long>(gate) * d + ft * 16 + (lane & 15);
+  dst[o] = src[row * row_chunks + static_cast<long>(s) * 8 + (lane >> 4) * 2 + half];
+}
+
+template <int CELL, int WT, int NT>
+__global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_packed_kernel(Stage s, int d, int k) {
+  constexpr int NW = MfmaCfg<NT>::NW;
+  constexpr int NTC = MfmaCfg<NT>::NTC;
+  constexpr int KSTEP = (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
+  constexpr int CW = KSTEP / 4;                      // columns per lane per step (32 bytes)
+  constexpr int CHUNK = NTC * 256;
+  constexpr int SA = MfmaPkCfg<NT>::SA;
+  constexpr int SB = MfmaPkCfg<NT>::SB;
+  constexpr int NBT = MfmaPkCfg<NT>::NBT;
+  constexpr int NBH = NT / NBT;                      // sub-steps per k-step
+  constexpr int U = (SA > SB) ? SA : SB;             // k-steps per unrolled iteration
+  static_assert(U % SA == 0 && (U * NBH) % SB == 0 && SB - 1 <= U * NBH, "ring sizes must repeat with the unrolled body");
+
+  __shared__ float part[NW * 3 * CHUNK];
+  __shared__ float g_a[MFMA_F * (NTC * 16 + 1)], g_b[MFMA_F * (NTC * 16 + 1)], g_o[MFMA_F * (NTC * 16 + 1)];
+  __shared__ float c_carry[MFMA_F];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int li = lane & 15;
+  const int kg = lane >> 4;
+  const int ncol = k * d;
+  const int ntile = d / MFMA_F;
+  const int ksp = blockIdx.x / ntile;                // which part of the columns (0 unless the stage is split)
+  const int ft = blockIdx.x - ksp * ntile;
+  const int f0 = ft * MFMA_F;
+  const int nw = blockDim.x >> 6;                    // waves launched (<= NW)
+  const int KS = ncol / (nw * s.ksplit);             // columns per wave
+  const int nks = KS / KSTEP;
+  const int wcol = (ksp * nw + wave) * KS;           // this wave's first column
+  const int nks_total = ncol / KSTEP;
+
+  if (CELL == CELL_QRNN && s.ksplit == 1 && tid < MFMA_F) refresh_history(s, d, k, f0 + tid);
+
+  // first fragment of this wave: k-step wcol / KSTEP of feature tile ft, 6 KiB per k-step
+  const char* aptr = static_cast<const char*>(s.W) +
+                     (static_cast<size_t>(ft) * nks_total + static_cast<size_t>(wcol / KSTEP)) * 6144 + lane * 16;
+
+  floatx4_t acc[3][NT];
+#pragma unroll
+  for (int g = 0; g < 3; ++g)
+#pragma unroll
+    for (int n = 0; n < NT; ++n) acc[g][n] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  int trow[NT];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) trow[n] = min(n * 16 + li, s.nt - 1);
+
+  floatx4_t aring[SA][6];        // [slot][gate * 2 + half]
+  BFrag<WT> bring[SB][NBT];
+
+  int a_ks = 0;                                   // next k-step whose fragments are requested
+  int b_j = wcol / d, b_m = wcol - (wcol / d) * d + kg * CW;
+  auto load_a_frag = [&](int slot, int i) {
+    aring[slot][i] = load_stream16(aptr + static_cast<size_t>(a_ks) * 6144 + i * 1024);
+  };
+  auto load_b_piece = [&](int slot, int tile0, int i) {      // i = (tile - tile0) * 2 + half
+    const int n = i >> 1, h = i & 1;
+    const long off = static_cast<long>(trow[tile0 + n] - b_j) * s.ldx + b_m + h * (CW / 2);
+    if constexpr (WT == W_BF16) bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
+    else bring[slot][n].v[h] = *reinterpret_cast<const float4*>(s.xcur + off);
+  };
+  auto advance_b = [&]() {
+    b_m += KSTEP;
+    if (b_m >= d) { b_m -= d; ++b_j; }
+  };
+  auto mfma_group = [&](int aslot, int bslot, int tile0, int grp) {
+    if constexpr (WT == W_BF16) {
+      const int h = grp / 3, g = grp - 3 * (grp / 3);
+      floatx4_t av = aring[aslot][g * 2 + h];
+      asm volatile("" : "+v"(av));         // keeps the fragment's load one dwordx4
+      bf16x8_t ab;
+      __builtin_memcpy(&ab, &av, sizeof ab);
+#pragma unroll
+      for (int n = 0; n < NBT; ++n)
+        acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[h], acc[g][tile0 + n], 0, 0, 0);
+    } else {
+      const int h = grp >> 2, q = grp & 3;
+#pragma unroll
+      for (int g = 0; g < 3; ++g) {
+        floatx4_t av = aring[aslot][g * 2 + h];
+        asm volatile("" : "+v"(av));       // keeps the fragment's load one dwordx4
+#pragma unroll
+        for (int n = 0; n < NBT; ++n) {
+          const float4 bv = bring[bslot][n].v[h];
+          const float bq = q == 0 ? bv.x : q == 1 ? bv.y : q == 2 ? bv.z : bv.w;
+          acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q], bq, acc[g][tile0 + n], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  constexpr int NGRP = (WT == W_BF16) ? 6 : 8;          // MFMA groups per sub-step
+  // One k-step at ring position p.  Step ks multiplies the fragments in aring[ks % SA] with the B
+  // fragments of its NBH sub-steps (sub-step ss = ks*NBH + hb sits in bring[ss % SB]).  Meanwhile the
+  // slot step ks-1 has just left is refilled with step ks+SA-1, and the B pieces of sub-step ss+SB-1
+  // are requested.  Prefetches reach at most U steps ahead, so only the last iteration (LAST) could
+  // run past the end; there the requests for steps that do not exist are left out at compile time.
+  auto pipeline_step = [&](auto last_tag, auto p_tag) {
+    constexpr bool LAST = decltype(last_tag)::value;
+    constexpr int p = decltype(p_tag)::value;
+    constexpr bool fetch_a = !LAST || (p + SA - 1 < U);
+    constexpr int aslot = (p + SA - 1) % SA;
+#pragma unroll
+    for (int hb = 0; hb < NBH; ++hb) {
+      const int ss = p * NBH + hb;
+      const int bslot = ss % SB;
+      const int tgt = ss + SB - 1;                              // sub-step whose B pieces are requested now
+      const bool fetch_b = !LAST || (tgt < U * NBH);
+      const int bnext = tgt % SB;
+      const int btile0 = (tgt % NBH) * NBT;
+      const int n_head = (hb == 0) ? 6 : 0;                     // weight fragments ride on the first sub-step
+      const int nitem = n_head + 2 * NBT;
+#pragma unroll
+      for (int grp = 0; grp < NGRP; ++grp) {
+        mfma_group(p % SA, bslot, hb * NBT, grp);
+#pragma unroll
+        for (int it = (grp * nitem) / NGRP; it < ((grp + 1) * nitem) / NGRP; ++it) {
+          if (it < n_head) { if constexpr (fetch_a) load_a_frag(aslot, it); }
+          else { if (fetch_b) load_b_piece(bnext, btile0, it - n_head); }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (fetch_b && (tgt % NBH) == NBH - 1) advance_b();       // the column cursor moves once per k-step
+    }
+    if constexpr (fetch_a) ++a_ks;
+  };
+  auto pipeline_iteration = [&](auto last_tag) {
+    static_assert(U == 4, "ring positions are spelled out below");
+    pipeline_step(last_tag, std::integral_constant<int, 0>{});
+    pipeline_step(last_tag, std::integral_constant<int, 1>{});
+    pipeline_step(last_tag, std::integral_constant<int, 2>{});
+    pipeline_step(last_tag, std::integral_constant<int, 3>{});
+  };
+
+  int ks_done = 0;
+  if (nks >= U && nks % U == 0) {
+    // ---- prologue: weight fragments of steps 0..SA-2, B pieces of sub-steps 0..SB-2
+#pragma unroll
+    for (int p = 0; p < SA - 1; ++p) {
+#pragma unroll
+      for (int i = 0; i < 6; ++i) load_a_frag(p, i);
+      ++a_ks;
+    }
+#pragma unroll
+    for (int ss = 0; ss < SB - 1; ++ss) {
+#pragma unroll
+      for (int i = 0; i < 2 * NBT; ++i) load_b_piece(ss % SB, (ss % NBH) * NBT, i);
+      if (ss % NBH == NBH - 1) advance_b();
+    }
+    for (int ks0 = 0; ks0 < nks - U; ks0 += U) pipeline_iteration(std::false_type{});
+    pipeline_iteration(std::true_type{});
+    ks_done = nks;
+  }
+  // ---- k-step counts the pipeline does not take (not a multiple of its depth): same data path, no overlap
+  for (int ks = ks_done; ks < nks; ++ks) {
+    a_ks = ks;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) load_a_frag(0, i);
+    {
+      const int col = wcol + ks * KSTEP;
+      b_j = col / d;
+      b_m = col - b_j * d + kg * CW;
+    }
+#pragma unroll
+    for (int hb = 0; hb < NBH; ++hb) {
+#pragma unroll
+      for (int i = 0; i < 2 * NBT; ++i) load_b_piece(0, hb * NBT, i);
+#pragma unroll
+      for (int grp = 0; grp < NGRP; ++grp) mfma_group(0, 0, hb * NBT, grp);
+    }
+  }
+
+  if (s.ksplit > 1) {
+    mfma_store_partials<NT>(s, d, f0, ksp, acc, part);
+    return;
+  }
+  mfma_epilogue<CELL, NT>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
+}
+
+}  // namespace ssrnn

@@ -21,6 +21,7 @@
 #include "kernel_valu.hip.h"
 #include "kernel_mfma.hip.h"
 #include "kernel_mfma_lds.hip.h"
+#include "kernel_mfma_packed.hip.h"
 
 using namespace ssrnn;
 
@@ -181,6 +182,7 @@ struct Plan {
   int nt_tiles;
   int ksplit;          // workgroups per feature tile (columns split), 1 unless the layer is narrow
   int mfma_nw;         // waves per workgroup of the matrix-core kernel
+  bool packed;         // weights are in the matrix-core fragment order (ssrnn_pack_weights)
 };
 
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
@@ -232,6 +234,14 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
   return fail(SSRNN_EUNSUPPORTED, "no vector-ALU kernel for T tile %d, NV %d", p.tt, p.nv);
 }
 
+// Shapes ssrnn_pack_weights takes: whole 16-feature tiles, and k-steps of 128 bytes that never straddle lag blocks.
+bool pack_shape_ok(int d, int k, int wdt) {
+  if (wdt != SSRNN_F32 && wdt != SSRNN_BF16) return false;
+  if (d < 1 || k < 1 || !shape_ok(1, d, k, 1, wdt)) return false;
+  const int kstep = wdt == SSRNN_BF16 ? 64 : 32;
+  return d % MFMA_F == 0 && d % kstep == 0;
+}
+
 bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
   if (p.d % MFMA_F != 0 || p.T > MFMA_MAX_T) return false;
   if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
@@ -248,7 +258,7 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   // up to KSPLIT_MAX workgroups per tile (LDS-staged kernel only) and a second kernel finishes.
   p.ksplit = 1;
   const int ntile = p.d / MFMA_F;
-  if (ntile < 128 && p.nt_tiles <= 8 && g_tune_mfma_lds != 1 && g_tune_ksplit != 1) {
+  if (ntile < 128 && p.nt_tiles <= 8 && (g_tune_mfma_lds != 1 || p.packed) && g_tune_ksplit != 1) {
     int ks = 1;
     while (ks < KSPLIT_MAX && ntile * ks * 2 <= 256 && ncol % (static_cast<long>(nw) * kstep * ks * 2) == 0) ks *= 2;
     if (g_tune_ksplit > 1 && g_tune_ksplit <= ks) ks = g_tune_ksplit;
@@ -276,6 +286,22 @@ int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
   // Weights staged through LDS (whole-line streaming loads) measure faster at every block length.  The
   // 16-tile fp32 instance does not fit the register file (it would spill), so fp32 blocks longer than
   // 128 steps keep the direct-load kernel.
+  if (p.packed) {
+#define SSRNN_MFMA_PK_CASE(NT_)                                                                           \
+  if (p.nt_tiles == NT_) {                                                                                \
+    const dim3 block(p.mfma_nw * 64);                                                                     \
+    if (p.wdt == SSRNN_BF16)                                                                              \
+      hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k); \
+    else                                                                                                  \
+      hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);  \
+    if (p.ksplit > 1)                                                                                     \
+      hipLaunchKernelGGL((split_epilogue_kernel<CELL>), dim3(p.d / MFMA_F), dim3(512), 0, st, s, p.d, p.k); \
+    return SSRNN_OK;                                                                                      \
+  }
+    SSRNN_MFMA_PK_CASE(1) SSRNN_MFMA_PK_CASE(2) SSRNN_MFMA_PK_CASE(4) SSRNN_MFMA_PK_CASE(8) SSRNN_MFMA_PK_CASE(16)
+#undef SSRNN_MFMA_PK_CASE
+    return fail(SSRNN_EUNSUPPORTED, "no matrix-core kernel for %d time tiles", p.nt_tiles);
+  }
   const bool lds_fits = !(p.nt_tiles == 16 && p.wdt == SSRNN_F32);
   if (p.ksplit > 1 || (g_tune_mfma_lds != 1 && lds_fits)) {
 #define SSRNN_MFMA_LDS_CASE(NT_)                                                                          \
@@ -334,8 +360,13 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     if (!W[l]) return fail(SSRNN_EINVAL, "%s: W[%d] is NULL", name, l);
   const int sched = flags & SSRNN_SCHED_MASK;
   const int kforce = flags & SSRNN_KERNEL_MASK;
-  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK)) != 0 || sched == 3)
+  const bool packed = (flags & SSRNN_WEIGHTS_PACKED) != 0;
+  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED)) != 0 || sched == 3)
     return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
+  if (packed && kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_MFMA)
+    return fail(SSRNN_EINVAL, "%s: packed weights are read by the matrix-core kernel only", name);
+  if (packed && !pack_shape_ok(d, k, wdt))
+    return fail(SSRNN_EUNSUPPORTED, "%s: no packed form exists for d = %d, k = %d", name, d, k);
   if (T > L && L > 0) T = static_cast<int>(L);   // one short block; buffers sized by the caller's T still suffice
   const int T_asked = T;
   const WorkspaceLayout wl = workspace_layout(n_layers, d, k, T, wdt);
@@ -363,7 +394,8 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   Plan p{};
   p.cell = cell; p.n_layers = n_layers; p.d = d; p.k = k; p.T = T; p.wdt = wdt; p.L = L;
   p.kind = K_GENERIC;
-  if (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU) {
+  p.packed = packed;
+  if (!packed && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU)) {
     if (plan_valu(p, W, x, xhist_init, workspace)) p.kind = K_VALU;
     else if (kforce == SSRNN_KERNEL_VALU)
       return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 16, d %% 256 == 0 and 16-byte aligned buffers", name);
@@ -374,7 +406,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     if (plan_mfma(p, W, x, xhist_init, workspace)) { p.kind = K_MFMA; T = p.T; }
     else {
       p.T = T;
-      if (kforce == SSRNN_KERNEL_MFMA)
+      if (kforce == SSRNN_KERNEL_MFMA || packed)
         return fail(SSRNN_EUNSUPPORTED, "%s: matrix-core kernel needs d %% 16 == 0, k*d %% 256 == 0 and 16-byte aligned buffers", name);
     }
   }
@@ -476,6 +508,27 @@ int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
   const long n = L * d_out;
   hipLaunchKernelGGL(linear_kernel, dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream), P, feat, y,
                      d_out, d_in, L);
+  HIP_TRY(hipGetLastError());
+  return SSRNN_OK;
+}
+
+size_t ssrnn_packed_weight_bytes(int d, int k, int wdtype) {
+  if (!pack_shape_ok(d, k, wdtype)) return 0;
+  return static_cast<size_t>(3) * d * k * d * (wdtype == SSRNN_BF16 ? 2 : 4);
+}
+
+int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype, void* stream) {
+  if (!W || !W_packed) return fail(SSRNN_EINVAL, "ssrnn_pack_weights: NULL pointer");
+  if (W == W_packed) return fail(SSRNN_EINVAL, "ssrnn_pack_weights: packing in place is not possible");
+  if (!aligned16(W) || !aligned16(W_packed)) return fail(SSRNN_EINVAL, "ssrnn_pack_weights: buffers must be 16-byte aligned");
+  if (!pack_shape_ok(d, k, wdtype))
+    return fail(SSRNN_EUNSUPPORTED, "ssrnn_pack_weights: needs d %% 16 == 0 and rows of whole 128-byte k-steps within a lag block");
+  const int esize = wdtype == SSRNN_BF16 ? 2 : 4;
+  const long row_chunks = static_cast<long>(k) * d * esize / 16;
+  const int nks_total = static_cast<int>(row_chunks / 8);
+  const long nchunks = 3L * d * row_chunks;
+  hipLaunchKernelGGL(pack_weights_kernel, dim3((nchunks + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(W), static_cast<uint4*>(W_packed), d, row_chunks, nks_total, nchunks);
   HIP_TRY(hipGetLastError());
   return SSRNN_OK;
 }

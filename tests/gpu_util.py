@@ -11,10 +11,18 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def gpu_sru(W, bias, x, c_init=None, T=1, flags=0):
-    import torch
+def _weights(W, packed):
+    """Device copies of the weight matrices; packed: re-tiled by ssrnn_pack_weights."""
     import paper_1803_11389_amd as ss
     Wd = [to_dev(w) for w in W]
+    return [ss.pack_weights(w) for w in Wd] if packed else Wd
+
+
+def gpu_sru(W, bias, x, c_init=None, T=1, flags=0, packed=False):
+    import torch
+    import paper_1803_11389_amd as ss
+    Wd = _weights(W, packed)
+    flags |= ss.WEIGHTS_PACKED if packed else 0
     bd = None if bias is None else [to_dev(b) for b in bias]
     h, c = ss.sru_forward(Wd, bd, to_dev(np.asarray(x, np.float32)), to_dev(None if c_init is None else np.asarray(c_init, np.float32)),
                           T=T, flags=flags)
@@ -22,10 +30,11 @@ def gpu_sru(W, bias, x, c_init=None, T=1, flags=0):
     return h.cpu().numpy(), c.cpu().numpy()
 
 
-def gpu_qrnn(W, bias, x, c_init=None, xhist_init=None, T=1, k=2, flags=0):
+def gpu_qrnn(W, bias, x, c_init=None, xhist_init=None, T=1, k=2, flags=0, packed=False):
     import torch
     import paper_1803_11389_amd as ss
-    Wd = [to_dev(w) for w in W]
+    Wd = _weights(W, packed)
+    flags |= ss.WEIGHTS_PACKED if packed else 0
     bd = None if bias is None else [to_dev(b) for b in bias]
     h, c, xh = ss.qrnn_forward(Wd, bd, to_dev(np.asarray(x, np.float32)),
                                to_dev(None if c_init is None else np.asarray(c_init, np.float32)),

@@ -69,7 +69,16 @@ def test_bad_arguments_fail_on_the_host(lib):
     assert call(n_layers=2, W=(ctypes.c_void_p * 2)(0x1000, 0x1000), ws_bytes=512) == 3 and b"needed" in lib.ssrnn_last_error()
     q = lib.qrnn_forward(tab, None, fake, None, None, fake, fake, None, 1, 128, 8, 4, 0, 0, 0, fake, 1 << 20, None)
     assert q == 1                                               # k = 0
+    assert call(flags=(1 << 8) | (2 << 4)) == 1 and b"packed" in lib.ssrnn_last_error()   # packed weights + vector-ALU kernel
+    assert call(flags=1 << 8, d=100) == 2                        # no packed form for this width
     assert lib.ssrnn_linear_forward(None, fake, fake, 4, 4, 4, None) == 1
+    assert lib.ssrnn_pack_weights(None, fake, 128, 1, 0, None) == 1
+    assert lib.ssrnn_pack_weights(fake, fake, 128, 1, 0, None) == 1          # in place
+    assert lib.ssrnn_pack_weights(fake, ctypes.c_void_p(0x2008), 128, 1, 0, None) == 1   # misaligned
+    assert lib.ssrnn_pack_weights(fake, ctypes.c_void_p(0x2000), 100, 1, 0, None) == 2
+    assert ss.packed_weight_bytes(128, 2, ss.F32) == 3 * 128 * 256 * 4
+    assert ss.packed_weight_bytes(1024, 1, ss.BF16) == 3 * 1024 * 1024 * 2
+    assert ss.packed_weight_bytes(100, 1, ss.F32) == 0 and ss.packed_weight_bytes(32, 1, ss.BF16) == 0
     assert lib.ssrnn_tune(b"no_such_key", 1) == 1
     assert lib.ssrnn_tune(None, 1) == 1
 
