@@ -131,9 +131,7 @@ int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype,
 /* Measurement aid: override one launch-geometry choice of the kernels for the
  * calls that follow, process-wide (not thread-safe; 0 restores the default).
  * Keys: "valu_F" (features per workgroup), "valu_nw" (wavefronts per
- * workgroup), "valu_nv" (column chunks per lane), "mfma_lds" (1: matrix-core
- * kernel loads weight fragments straight from memory instead of staging whole
- * lines through LDS), "ksplit" (1: never split a narrow layer's columns over
+ * workgroup), "valu_nv" (column chunks per lane), "ksplit" (1: never split a narrow layer's columns over
  * several workgroups; 2, 4, 8: at most that many parts).  A value the shape
  * does not allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
 int ssrnn_tune(const char* key, int value);

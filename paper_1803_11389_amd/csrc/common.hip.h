@@ -16,15 +16,23 @@ enum WType : int { W_F32 = 0, W_BF16 = 1 };
 // Input rows are addressed relative to the block's first step: row r >= 0 is
 // step r of the block, row r < 0 is |r| steps before it.  xcur points at row 0
 // of a buffer that holds the k-1 rows before it as well (the causal window of
-// Eq. 3), so every row r >= -(k-1) is a plain load.  xcur16, when not null, is
-// a bf16 copy of the same rows (operand of the bf16 matrix-core kernel).
+// Eq. 3), so every row r >= -(k-1) is a plain load.
+//
+// The matrix-core kernels read the block through a second copy, the operand
+// copy (xop), in the weights' element type and in chunk-column-major order:
+// the 16-byte chunk that holds columns [cc*VEC, (cc+1)*VEC) of row r (VEC = 4
+// fp32 or 8 bf16 values) lies at xop + (cc*ldt + r)*16 bytes, r >= -(k-1).  The
+// 16 lanes that hold the 16 time rows of one MFMA B fragment then read 256
+// contiguous bytes, where the row-major buffer would give each lane its own
+// cache line.  Whoever writes a block's rows (the staging kernel for layer 0,
+// the producing layer's epilogue otherwise) writes both copies.
 struct Stage {
   const void* W;           // [3d x k*d] row-major
   const float* bias;       // SRU [2d], QRNN [3d], or null
   const float* xcur;       // row r at xcur + r*ldx, r in [-(k-1), nt)
-  const uint16_t* xcur16;  // same rows as bf16 bit patterns, or null
+  const void* xop;         // operand copy of the same rows (chunk (0, row 0)), or null
   float* hout;             // [nt x d] rows of the layer's output
-  uint16_t* hout16;        // bf16 copy of the output rows for the next layer, or null
+  void* hop;               // operand copy of the output rows for the next layer, or null
   float* c;                // [d] running cell state, read and written
   // QRNN only: before the stage's outputs are written, the k-1 rows in front
   // of hout (the next layer's view of "earlier inputs") are refreshed by the
@@ -35,8 +43,10 @@ struct Stage {
   int hist_mode;
   int hist_shift;
   int nt;
-  int ldx;                 // row stride (elements) of xcur and xcur16
-  int ldh;                 // row stride (elements) of hout and hout16
+  int ldx;                 // row stride (elements) of xcur
+  int ldh;                 // row stride (elements) of hout
+  int ldt;                 // rows per chunk column of xop and hop
+  int op_bf16;             // element type of the operand copies: 0 fp32, 1 bf16
   // Narrow layers only: the k*d columns are split over ksplit workgroups per
   // feature tile; each writes its partial pre-activations to
   // upart[((part*3 + gate)*d + feature)*tp + t] and a second kernel finishes.
@@ -77,6 +87,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return static_cast<uint16_t>((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);   // finite inputs only
 }
 
+// Element (row r, column i) of an operand copy (see Stage).
+__device__ __forceinline__ void store_operand(void* op, int ldt, int op_bf16, int r, int i, float v) {
+  if (op_bf16) static_cast<uint16_t*>(op)[(static_cast<long>(i >> 3) * ldt + r) * 8 + (i & 7)] = f32_to_bf16_rne(v);
+  else static_cast<float*>(op)[(static_cast<long>(i >> 2) * ldt + r) * 4 + (i & 3)] = v;
+}
+
 // Logistic function and tanh from the hardware exp2; absolute error a few
 // 1e-7, both saturate cleanly (exp -> inf gives 0 / -1, exp -> 0 gives 1 / 1).
 __device__ __forceinline__ float sigmoidf_fast(float z) {
@@ -105,17 +121,16 @@ __device__ __forceinline__ float cell_step(float u0, float u1, float u2, float x
 }
 
 // Refresh the k-1 history rows in front of hout for column i (see Stage), in
-// the fp32 buffer and, when present, in its bf16 copy.
+// the fp32 buffer and, when present, in the operand copy.
 __device__ __forceinline__ void refresh_history(const Stage& s, int d, int k, int i) {
   if (s.hist_mode == 0 || k <= 1) return;
   float* hist = s.hout - static_cast<long>(k - 1) * s.ldh;   // rows 0..k-2, ascending time
-  uint16_t* hist16 = s.hout16 ? s.hout16 - static_cast<long>(k - 1) * s.ldh : nullptr;
   for (int r = 0; r < k - 1; ++r) {
     float v;
     if (s.hist_mode == 1) v = hist[static_cast<long>(r + s.hist_shift) * s.ldh + i];
     else v = s.hist_init ? s.hist_init[static_cast<long>(k - 2 - r) * d + i] : 0.0f;
     hist[static_cast<long>(r) * s.ldh + i] = v;
-    if (hist16) hist16[static_cast<long>(r) * s.ldh + i] = f32_to_bf16_rne(v);
+    if (s.hop) store_operand(s.hop, s.ldt, s.op_bf16, r - (k - 1), i, v);
   }
 }
 

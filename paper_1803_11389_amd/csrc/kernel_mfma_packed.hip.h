@@ -96,27 +96,37 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_packed_kernel
 #pragma unroll
     for (int n = 0; n < NT; ++n) acc[g][n] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  int trow[NT];
+  // B side: this lane's time row in each tile, as a byte offset within a chunk column of the operand
+  // copy.  Rows past the end of a short block repeat its last row; the columns they produce are never
+  // read out.
+  constexpr int VEC = CW / 2;                        // elements per 16-byte chunk
+  int brow[NT];
 #pragma unroll
-  for (int n = 0; n < NT; ++n) trow[n] = min(n * 16 + li, s.nt - 1);
+  for (int n = 0; n < NT; ++n) brow[n] = min(n * 16 + li, s.nt - 1) * 16;
+  const long ldtb = static_cast<long>(s.ldt) * 16;  // bytes per chunk column
+  const char* xop = static_cast<const char*>(s.xop);
 
   floatx4_t aring[SA][6];        // [slot][gate * 2 + half]
   BFrag<WT> bring[SB][NBT];
 
   int a_ks = 0;                                   // next k-step whose fragments are requested
+  // B cursor: lag block b_j, first column b_m of this lane within it, and the byte offset b_off of
+  // chunk column b_m / VEC shifted back by the lag
   int b_j = wcol / d, b_m = wcol - (wcol / d) * d + kg * CW;
+  long b_off = static_cast<long>(b_m / VEC) * ldtb - b_j * 16;
   auto load_a_frag = [&](int slot, int i) {
     aring[slot][i] = load_stream16(aptr + static_cast<size_t>(a_ks) * 6144 + i * 1024);
   };
   auto load_b_piece = [&](int slot, int tile0, int i) {      // i = (tile - tile0) * 2 + half
     const int n = i >> 1, h = i & 1;
-    const long off = static_cast<long>(trow[tile0 + n] - b_j) * s.ldx + b_m + h * (CW / 2);
-    if constexpr (WT == W_BF16) bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(s.xcur16 + off);
-    else bring[slot][n].v[h] = *reinterpret_cast<const float4*>(s.xcur + off);
+    const char* src = xop + b_off + h * ldtb + brow[tile0 + n];
+    if constexpr (WT == W_BF16) bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(src);
+    else bring[slot][n].v[h] = *reinterpret_cast<const float4*>(src);
   };
-  auto advance_b = [&]() {
+  auto advance_b = [&]() {                        // one k-step = 8 chunk columns further
     b_m += KSTEP;
-    if (b_m >= d) { b_m -= d; ++b_j; }
+    b_off += 8 * ldtb;
+    if (b_m >= d) { b_m -= d; ++b_j; b_off -= static_cast<long>(d / VEC) * ldtb + 16; }
   };
   auto mfma_group = [&](int aslot, int bslot, int tile0, int grp) {
     if constexpr (WT == W_BF16) {
@@ -215,6 +225,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_packed_kernel
       const int col = wcol + ks * KSTEP;
       b_j = col / d;
       b_m = col - b_j * d + kg * CW;
+      b_off = static_cast<long>(b_m / VEC) * ldtb - b_j * 16;
     }
 #pragma unroll
     for (int hb = 0; hb < NBH; ++hb) {

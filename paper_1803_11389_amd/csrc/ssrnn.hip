@@ -56,8 +56,9 @@ struct WorkspaceLayout {
   int ld;               // row stride (elements) of the hand-off buffers: d + ACT_PAD
   size_t act_stride;    // bytes of one fp32 hand-off buffer [(k-1)+T] x ld
   size_t act_offset;    // buffer 0 = staged input of layer 0, buffer l = output of layer l-1
-  size_t act16_stride;  // bytes of one bf16 copy (0 when the weight type does not use them)
-  size_t act16_offset;
+  int ldt;              // rows per chunk column of an operand copy
+  size_t op_stride;     // bytes of one operand copy (0 when d rules the matrix-core kernels out)
+  size_t op_offset;
   size_t upart_offset;  // partial pre-activations of split stages (narrow layers only)
   size_t upart_bytes;
   int upart_rows;       // rows per (part, gate) plane
@@ -68,18 +69,23 @@ constexpr int KSPLIT_MAX = 8;
 
 // Buffer b (0 <= b < n_layers) holds the input rows of layer b for the current
 // block, preceded by the k-1 rows before it.  Buffer 0 is filled from x by a
-// staging kernel (only when k > 1 or a bf16 copy is needed; otherwise layer 0
-// reads x in place).
+// staging kernel (only when k > 1 or a matrix-core kernel runs; otherwise
+// layer 0 reads x in place).
 WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
   WorkspaceLayout w;
   const size_t rows = static_cast<size_t>(k - 1 + T);
   w.ld = d + ACT_PAD;
   w.act_stride = align_up(rows * w.ld * sizeof(float), WS_ALIGN);
   w.act_offset = WS_CONTROL_BYTES;
-  w.act16_stride = (wdt == SSRNN_BF16) ? align_up(rows * w.ld * sizeof(uint16_t), WS_ALIGN) : 0;
-  w.act16_offset = w.act_offset + static_cast<size_t>(n_layers) * w.act_stride;
-  w.upart_offset = w.act16_offset + static_cast<size_t>(n_layers) * w.act16_stride;
+  // Operand copies of the matrix-core kernels (see Stage): d*esize/16 chunk columns of ldt 16-byte
+  // chunks.  ldt*16 is an odd multiple of 64 bytes, so the chunk columns a fragment load touches start
+  // in different halves of a cache line pair.
   const int tcap = T < MFMA_MAX_T ? T : MFMA_MAX_T;
+  w.ldt = (k - 1 + tcap + 7) / 8 * 8 + 4;
+  const size_t esize = (wdt == SSRNN_BF16) ? 2 : 4;
+  w.op_stride = (d % MFMA_F == 0) ? align_up(static_cast<size_t>(d) * esize / 16 * w.ldt * 16, WS_ALIGN) : 0;
+  w.op_offset = w.act_offset + static_cast<size_t>(n_layers) * w.act_stride;
+  w.upart_offset = w.op_offset + static_cast<size_t>(n_layers) * w.op_stride;
   w.upart_rows = (tcap + 15) / 16 * 16;
   w.upart_bytes = (d % MFMA_F == 0 && d / MFMA_F < 128)
                       ? align_up(static_cast<size_t>(KSPLIT_MAX) * 3 * w.upart_rows * d * sizeof(float), WS_ALIGN) : 0;
@@ -132,10 +138,10 @@ __global__ void gather_history_kernel(const float* x, const float* xhist_init, f
 }
 
 // Rows -(k-1) .. nt-1 of layer 0's input for the block that starts at time t0,
-// gathered from x (times >= 0) and xhist_init / zeros (times < 0), as fp32 and
-// optionally as bf16.  dst / dst16 point at row 0 of their buffers.
-__global__ void stage_input_kernel(const float* x, const float* xhist_init, float* dst, uint16_t* dst16,
-                                   int ld, int d, int k, long t0, int nt) {
+// gathered from x (times >= 0) and xhist_init / zeros (times < 0), as fp32 rows
+// and optionally as an operand copy.  dst / dst_op point at row 0 of their buffers.
+__global__ void stage_input_kernel(const float* x, const float* xhist_init, float* dst, void* dst_op, int ldt,
+                                   int op_bf16, int ld, int d, int k, long t0, int nt) {
   const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
   const long n = static_cast<long>(k - 1 + nt) * d;
   if (id >= n) return;
@@ -146,7 +152,7 @@ __global__ void stage_input_kernel(const float* x, const float* xhist_init, floa
   if (sabs >= 0) v = x[sabs * d + m];
   else v = xhist_init ? xhist_init[(-sabs - 1) * d + m] : 0.0f;
   dst[r * ld + m] = v;
-  if (dst16) dst16[r * ld + m] = f32_to_bf16_rne(v);
+  if (dst_op) store_operand(dst_op, ldt, op_bf16, static_cast<int>(r), m, v);
 }
 
 __global__ void copy_history_kernel(const float* src, float* dst, long n) {
@@ -187,7 +193,6 @@ struct Plan {
 
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
 int g_tune_ksplit = 0;     // 0 = default, 1 = never split, 2/4/8 = at most that many parts
-int g_tune_mfma_lds = 0;   // 0 = default (LDS-staged weights when the shape allows), 1 = off, 2 = on
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
   if (p.wdt != SSRNN_F32 || p.T > VALU_MAX_T || p.d % 256 != 0) return false;
@@ -234,6 +239,10 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
   return fail(SSRNN_EUNSUPPORTED, "no vector-ALU kernel for T tile %d, NV %d", p.tt, p.nv);
 }
 
+// Longest block the matrix-core kernels accumulate in one weight pass.  The LDS-staged kernel's
+// 16-tile fp32 instance does not fit the register file, so row-major fp32 weights stop at 8 tiles.
+int mfma_block_cap(int wdt, bool packed) { return (wdt == SSRNN_F32 && !packed) ? MFMA_MAX_T / 2 : MFMA_MAX_T; }
+
 // Shapes ssrnn_pack_weights takes: whole 16-feature tiles, and k-steps of 128 bytes that never straddle lag blocks.
 bool pack_shape_ok(int d, int k, int wdt) {
   if (wdt != SSRNN_F32 && wdt != SSRNN_BF16) return false;
@@ -243,7 +252,7 @@ bool pack_shape_ok(int d, int k, int wdt) {
 }
 
 bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
-  if (p.d % MFMA_F != 0 || p.T > MFMA_MAX_T) return false;
+  if (p.d % MFMA_F != 0 || p.T > mfma_block_cap(p.wdt, p.packed)) return false;
   if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
   for (int l = 0; l < p.n_layers; ++l)
     if (!aligned16(W[l])) return false;
@@ -258,7 +267,7 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   // up to KSPLIT_MAX workgroups per tile (LDS-staged kernel only) and a second kernel finishes.
   p.ksplit = 1;
   const int ntile = p.d / MFMA_F;
-  if (ntile < 128 && p.nt_tiles <= 8 && (g_tune_mfma_lds != 1 || p.packed) && g_tune_ksplit != 1) {
+  if (ntile < 128 && p.nt_tiles <= 8 && g_tune_ksplit != 1) {
     int ks = 1;
     while (ks < KSPLIT_MAX && ntile * ks * 2 <= 256 && ncol % (static_cast<long>(nw) * kstep * ks * 2) == 0) ks *= 2;
     if (g_tune_ksplit > 1 && g_tune_ksplit <= ks) ks = g_tune_ksplit;
@@ -274,49 +283,24 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
 template <int CELL>
 int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
   const dim3 grid(p.d / MFMA_F * p.ksplit);
-#define SSRNN_MFMA_CASE(NT_)                                                                          \
-  if (p.nt_tiles == NT_) {                                                                            \
-    const dim3 block(MfmaCfg<NT_>::NW * 64);                                                          \
-    if (p.wdt == SSRNN_BF16)                                                                          \
-      hipLaunchKernelGGL((stage_mfma_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k);    \
-    else                                                                                              \
-      hipLaunchKernelGGL((stage_mfma_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
-    return SSRNN_OK;                                                                                  \
-  }
-  // Weights staged through LDS (whole-line streaming loads) measure faster at every block length.  The
-  // 16-tile fp32 instance does not fit the register file (it would spill), so fp32 blocks longer than
-  // 128 steps keep the direct-load kernel.
-  if (p.packed) {
-#define SSRNN_MFMA_PK_CASE(NT_)                                                                           \
+  const dim3 block(p.mfma_nw * 64);
+#define SSRNN_MFMA_CASE(NT_)                                                                              \
   if (p.nt_tiles == NT_) {                                                                                \
-    const dim3 block(p.mfma_nw * 64);                                                                     \
-    if (p.wdt == SSRNN_BF16)                                                                              \
-      hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k); \
-    else                                                                                                  \
-      hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);  \
-    if (p.ksplit > 1)                                                                                     \
-      hipLaunchKernelGGL((split_epilogue_kernel<CELL>), dim3(p.d / MFMA_F), dim3(512), 0, st, s, p.d, p.k); \
-    return SSRNN_OK;                                                                                      \
-  }
-    SSRNN_MFMA_PK_CASE(1) SSRNN_MFMA_PK_CASE(2) SSRNN_MFMA_PK_CASE(4) SSRNN_MFMA_PK_CASE(8) SSRNN_MFMA_PK_CASE(16)
-#undef SSRNN_MFMA_PK_CASE
-    return fail(SSRNN_EUNSUPPORTED, "no matrix-core kernel for %d time tiles", p.nt_tiles);
-  }
-  const bool lds_fits = !(p.nt_tiles == 16 && p.wdt == SSRNN_F32);
-  if (p.ksplit > 1 || (g_tune_mfma_lds != 1 && lds_fits)) {
-#define SSRNN_MFMA_LDS_CASE(NT_)                                                                          \
-  if (p.nt_tiles == NT_) {                                                                                \
-    const dim3 block(p.mfma_nw * 64);                                                                     \
-    if (p.wdt == SSRNN_BF16)                                                                              \
+    if (p.packed) {                                                                                       \
+      if (p.wdt == SSRNN_BF16)                                                                            \
+        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k); \
+      else                                                                                                \
+        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k); \
+    } else if (p.wdt == SSRNN_BF16) {                                                                     \
       hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k);    \
-    else if constexpr (NT_ < 16)                                                                          \
+    } else if constexpr (NT_ < 16) {                                                                      \
       hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
+    } else {                                                                                              \
+      return fail(SSRNN_EUNSUPPORTED, "no matrix-core kernel for %d time tiles of row-major fp32 weights", p.nt_tiles); \
+    }                                                                                                     \
     if (p.ksplit > 1)                                                                                     \
       hipLaunchKernelGGL((split_epilogue_kernel<CELL>), dim3(p.d / MFMA_F), dim3(512), 0, st, s, p.d, p.k); \
     return SSRNN_OK;                                                                                      \
-  }
-    SSRNN_MFMA_LDS_CASE(1) SSRNN_MFMA_LDS_CASE(2) SSRNN_MFMA_LDS_CASE(4) SSRNN_MFMA_LDS_CASE(8) SSRNN_MFMA_LDS_CASE(16)
-#undef SSRNN_MFMA_LDS_CASE
   }
   SSRNN_MFMA_CASE(1) SSRNN_MFMA_CASE(2) SSRNN_MFMA_CASE(4) SSRNN_MFMA_CASE(8) SSRNN_MFMA_CASE(16)
 #undef SSRNN_MFMA_CASE
@@ -401,8 +385,9 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 16, d %% 256 == 0 and 16-byte aligned buffers", name);
   }
   if (p.kind == K_GENERIC && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_MFMA)) {
-    // the matrix-core kernel accumulates at most MFMA_MAX_T steps per weight pass: longer blocks are cut
-    p.T = T < MFMA_MAX_T ? T : MFMA_MAX_T;
+    // the matrix-core kernels accumulate a bounded number of steps per weight pass: longer blocks are cut
+    const int cap = mfma_block_cap(wdt, packed);
+    p.T = T < cap ? T : cap;
     if (plan_mfma(p, W, x, xhist_init, workspace)) { p.kind = K_MFMA; T = p.T; }
     else {
       p.T = T;
@@ -414,11 +399,12 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   if (sched == SSRNN_SCHED_PERSISTENT) return fail(SSRNN_EUNSUPPORTED, "%s: persistent schedule not available for this shape", name);
 
   char* act0 = static_cast<char*>(workspace) + wl.act_offset;
-  char* act16_0 = static_cast<char*>(workspace) + wl.act16_offset;
-  const bool use16 = (p.kind == K_MFMA && wdt == SSRNN_BF16);
+  char* op0 = static_cast<char*>(workspace) + wl.op_offset;
+  const bool use_op = (p.kind == K_MFMA);
+  const int op_bf16 = (wdt == SSRNN_BF16) ? 1 : 0;
   const bool stage_in = (k > 1) || p.kind == K_MFMA;   // the matrix-core kernel wants padded rows
   auto act = [&](int b) { return reinterpret_cast<float*>(act0 + static_cast<size_t>(b) * wl.act_stride) + static_cast<long>(k - 1) * wl.ld; };
-  auto act16 = [&](int b) { return reinterpret_cast<uint16_t*>(act16_0 + static_cast<size_t>(b) * wl.act16_stride) + static_cast<long>(k - 1) * wl.ld; };
+  auto opbuf = [&](int b) { return static_cast<void*>(op0 + static_cast<size_t>(b) * wl.op_stride + static_cast<size_t>(k - 1) * 16); };
   const long nblocks = (L + T - 1) / T;
   int nt_last = T;
   for (long b = 0; b < nblocks; ++b) {
@@ -428,7 +414,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     if (stage_in) {
       const long n = static_cast<long>(k - 1 + nt) * d;
       hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0),
-                         use16 ? act16(0) : nullptr, wl.ld, d, k, t0, nt);
+                         use_op ? opbuf(0) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, nt);
     }
     for (int l = 0; l < n_layers; ++l) {
       Stage s{};
@@ -436,26 +422,28 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       s.bias = (bias && bias[l]) ? bias[l] : nullptr;
       if (l == 0 && !stage_in) {
         s.xcur = x + t0 * d;
-        s.xcur16 = nullptr;
+        s.xop = nullptr;
         s.ldx = d;
       } else {
         s.xcur = act(l);
-        s.xcur16 = use16 ? act16(l) : nullptr;
+        s.xop = use_op ? opbuf(l) : nullptr;
         s.ldx = wl.ld;
       }
       if (l == n_layers - 1) {
         s.hout = h + t0 * d;
-        s.hout16 = nullptr;
+        s.hop = nullptr;
         s.ldh = d;
         s.hist_mode = 0;
       } else {
         s.hout = act(l + 1);
-        s.hout16 = use16 ? act16(l + 1) : nullptr;
+        s.hop = use_op ? opbuf(l + 1) : nullptr;
         s.ldh = wl.ld;
         s.hist_mode = (k > 1) ? (b == 0 ? 2 : 1) : 0;
         s.hist_shift = T;
         s.hist_init = xhist_init ? xhist_init + static_cast<long>(l + 1) * (k - 1) * d : nullptr;
       }
+      s.ldt = wl.ldt;
+      s.op_bf16 = op_bf16;
       s.c = c_final + static_cast<long>(l) * d;
       s.nt = nt;
       s.ksplit = (p.kind == K_MFMA) ? p.ksplit : 1;
@@ -538,7 +526,6 @@ int ssrnn_tune(const char* key, int value) {
   if (!strcmp(key, "valu_F")) g_tune_valu_F = value;
   else if (!strcmp(key, "valu_nw")) g_tune_valu_nw = value;
   else if (!strcmp(key, "valu_nv")) g_tune_valu_nv = value;
-  else if (!strcmp(key, "mfma_lds")) g_tune_mfma_lds = value;
   else if (!strcmp(key, "ksplit")) g_tune_ksplit = value;
   else return fail(SSRNN_EINVAL, "ssrnn_tune: unknown key %s", key);
   return SSRNN_OK;
