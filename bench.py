@@ -90,8 +90,15 @@ def main():
     inp = wl.make_inputs(cfg)
     W_host = inp["W"]
     W = [torch.from_numpy(w).to(dev) for w in W_host]
+    wdt = ss.BF16 if cfg.wdtype == "bf16" else ss.F32
+    # second copy of the weights in the matrix-core kernel's order (a model-load-time step, outside
+    # every timed region); the sweep times both layouts
+    W_packed = None
+    if ss.packed_weight_bytes(cfg.d, cfg.k, wdt) > 0 and (args.packed or (not args.no_sweep and args.flags == 0)):
+        W_packed = [ss.pack_weights(w) for w in W]
     if args.packed:
-        W = [ss.pack_weights(w) for w in W]
+        assert W_packed is not None, "this workload's weights cannot be packed"
+        W = W_packed
         args.flags |= ss.WEIGHTS_PACKED
     if cfg.d_feat:
         feat = torch.from_numpy(inp["feat"]).to(dev)
@@ -102,30 +109,31 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
-    wdt = ss.BF16 if cfg.wdtype == "bf16" else ss.F32
     h = torch.empty((cfg.L, cfg.d), dtype=torch.float32, device=dev)
     c_final = torch.empty((cfg.n_layers, cfg.d), dtype=torch.float32, device=dev)
     Tmax = max(max(cfg.Ts), args.T)
     ws = ss.Workspace.for_shape(cfg.n_layers, cfg.d, cfg.k, Tmax, wdt, dev)
 
-    def one_pass(T):
+    def one_pass(T, packed=False):
+        Wl = W_packed if packed else W
+        fl = args.flags | (ss.WEIGHTS_PACKED if packed else 0)
         if cfg.cell == "sru":
-            ss.sru_forward(W, None, x, None, T=T, flags=args.flags, h=h, c_final=c_final, workspace=ws)
+            ss.sru_forward(Wl, None, x, None, T=T, flags=fl, h=h, c_final=c_final, workspace=ws)
         else:
-            ss.qrnn_forward(W, None, x, None, None, T=T, k=cfg.k, flags=args.flags, h=h, c_final=c_final, workspace=ws)
+            ss.qrnn_forward(Wl, None, x, None, None, T=T, k=cfg.k, flags=fl, h=h, c_final=c_final, workspace=ws)
 
-    def measure(T, steps, warmup):
+    def measure(T, steps, warmup, packed=False):
         """Returns (seconds per pass by the host clock, ms per pass by HIP events
         recorded on the stream the kernels are launched on)."""
         for _ in range(warmup):
-            one_pass(T)
+            one_pass(T, packed)
         torch.cuda.synchronize()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         e0.record()
         for _ in range(steps):
-            one_pass(T)
+            one_pass(T, packed)
         e1.record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
@@ -144,14 +152,22 @@ def main():
     head = row(args.T, sec, ev_ms)
     h_head = h[: min(cfg.L, 512)].clone()
 
+    head["weights"] = "packed" if args.packed else "row-major"
     sweep = []
     if not args.no_sweep:
         for T in cfg.Ts:
             if T == args.T:
-                sweep.append(head)
-                continue
-            s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
-            sweep.append(row(T, s_, e_))
+                r = dict(head)
+            else:
+                s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
+                r = row(T, s_, e_)
+                r["weights"] = head["weights"]
+            if W_packed is not None and not args.packed:
+                # the same block size with pre-packed weights (matrix-core kernel at every T)
+                s_, e_ = measure(T, max(1, min(args.steps, 2)), 1, packed=True)
+                pk = row(T, s_, e_)
+                r["packed"] = {key: pk[key] for key in ("steps_per_s", "us_per_stage", "algorithmic_GBps", "frac_hbm_peak", "TFLOPps")}
+            sweep.append(r)
 
     # dominant kernel: the (block, layer) stage kernel.  Algorithmic bytes of one
     # stage = the layer's weights once + the input block read + the output block
@@ -161,7 +177,8 @@ def main():
     stage_bytes = cfg.weight_bytes_per_layer() + 2 * cfg.d * 4 * T
     stage_flops = 2.0 * 3 * cfg.d * cfg.ncol * T
     stage_s = ev_ms * 1e-3 / nstage
-    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name[:2], T)) if args.flags == 0 else None
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name[:2], T, "packed" if args.packed else "row-major")) \
+        if (args.flags & ~ss.WEIGHTS_PACKED) == 0 else None
     common = {"traffic": traffic, "kernel": "stage kernel (one per block and layer)", "launches_per_pass": nstage,
               "avg_launch_us": round(stage_s * 1e6, 2), "algorithmic_bytes_per_launch": stage_bytes,
               "flops_per_launch": stage_flops,
@@ -206,7 +223,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.n_layers}-layer {cfg.cell.upper()}, d={cfg.d}, k={cfg.k}, "
                                f"L={cfg.L}, batch 1, {cfg.wdtype} weights "
                                f"({cfg.n_layers * cfg.weight_bytes_per_layer() / 1e9:.2f} GB), block T={args.T}",
-                   "T": args.T, "schedule": "streaming (block-major)", "flags": args.flags},
+                   "T": args.T, "schedule": "streaming (block-major)", "weights": head["weights"], "flags": args.flags},
         "achieved_hbm_GBps": head["algorithmic_GBps"], "frac_hbm_peak": head["frac_hbm_peak"],
         "sweep": sweep, "roofline": roofline, "cpu_baseline": cpu,
         "setup_s": round(t_gen, 1),

@@ -48,27 +48,58 @@ struct BFrag<W_F32> { float4 v[2]; };
 template <>
 struct BFrag<W_BF16> { bf16x8_t v[2]; };
 
-// Epilogue shared by the matrix-core kernels.  acc[g][n]: this wave's partial
-// 16x16 tiles (gate g, time tile n) in the MFMA result layout (lane = time
-// n%16 + 16*(feature/4), register = feature%4).
+// Inclusive prefix scan of affine maps c -> a*c + b over groups of CT (16 or
+// 32) adjacent lanes, lane order = time order: afterwards (a, b) of a lane is
+// the composition of the maps of its group's lanes up to and including itself.
+// Data-parallel-primitive moves only: row_shr within rows of 16 lanes (lanes
+// without a source keep the identity map), then, for 32-lane groups, lane 15
+// of every even row broadcast to the odd row behind it.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_or(float fallback, float v) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(__float_as_uint(fallback), __float_as_uint(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CT>
+__device__ __forceinline__ void affine_scan(float& a, float& b) {
+  static_assert(CT == 16 || CT == 32, "scan groups are one or two DPP rows");
+#define SSRNN_SCAN_STEP(CTRL, ROW_MASK)                       \
+  {                                                           \
+    const float ap = dpp_or<CTRL, ROW_MASK>(1.0f, a);         \
+    const float bp = dpp_or<CTRL, ROW_MASK>(0.0f, b);         \
+    b = fmaf(a, bp, b);                                       \
+    a *= ap;                                                  \
+  }
+  SSRNN_SCAN_STEP(0x111, 0xf)   // row_shr:1
+  SSRNN_SCAN_STEP(0x112, 0xf)   // row_shr:2
+  SSRNN_SCAN_STEP(0x114, 0xf)   // row_shr:4
+  SSRNN_SCAN_STEP(0x118, 0xf)   // row_shr:8
+  if constexpr (CT == 32) SSRNN_SCAN_STEP(0x142, 0xa)   // row_bcast:15 into rows 1 and 3
+#undef SSRNN_SCAN_STEP
+}
+
+// Epilogue shared by the matrix-core kernels; the workgroup has exactly
+// MfmaCfg<NT>::NW waves.  acc[g][n]: this wave's partial 16x16 tiles (gate g,
+// time tile n) in the MFMA result layout (lane = time n%16 + 16*(feature/4),
+// register = feature%4).
 template <int CELL, int NT>
 __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, floatx4_t (&acc)[3][NT], float* part,
                                               float* g_a, float* g_b, float* g_o, float* c_carry) {
-  const int NW = blockDim.x >> 6;               // waves that split the columns
+  constexpr int NW = MfmaCfg<NT>::NW;           // waves that split the columns
+  constexpr int NTH = NW * 64;
   constexpr int NTC = MfmaCfg<NT>::NTC;
-  constexpr int CHUNK = NTC * 256;
+  constexpr int CHUNK = NTC * 256;              // (step, feature) pairs per chunk
+  constexpr int EPT = (CHUNK + NTH - 1) / NTH;  // pairs per thread
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int li = lane & 15;
   const int kg = lane >> 4;
-  // ---- epilogue: NTC tiles (CT = 16*NTC steps) at a time ------------------
+  // ---- NTC tiles (CT = 16*NTC steps) at a time -----------------------------
   // A: per-wave partial tiles -> LDS.  B: every thread finishes the split-K sum
-  // of one (step, feature) pair and applies the gate non-linearities, leaving
+  // of its (step, feature) pairs and applies the gate non-linearities, leaving
   // f_t, (1-f_t)*cand_t and the output gate in LDS transposed to
-  // [feature][step].  C: one thread per (feature, step), steps on adjacent
-  // lanes: the recurrence c_t = f_t c_{t-1} + b_t is a prefix scan of affine
-  // maps over CT lanes, then h_t.  The state crosses chunks through c_carry.
+  // [feature][step].  C: a thread per (feature, step), steps on adjacent lanes:
+  // the recurrence c_t = f_t c_{t-1} + b_t is a prefix scan of affine maps over
+  // CT lanes, then h_t.  The state crosses chunks through c_carry.
   constexpr int CT = NTC * 16;
   constexpr int TS = CT + 1;                   // padded row of the transposed arrays
   float b0 = 0.f, b1 = 0.f, b2 = 0.f;          // biases of the feature this thread handles in phase B
@@ -79,10 +110,21 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
     else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
   }
   if (tid < MFMA_F) c_carry[tid] = s.c[f0 + tid];
+  const int tl = tid % CT;                     // step within the chunk in phase C (NTH is a multiple of CT)
 
 #pragma unroll
   for (int n0 = 0; n0 < NT; n0 += NTC) {
     if (n0 * 16 < s.nt) {   // uniform over the workgroup
+      const int tlast = min(CT, s.nt - n0 * 16) - 1;      // last valid step of this chunk
+      const int t = n0 * 16 + tl;
+      // SRU: the layer's own input at this thread's (feature, step) pairs, fetched ahead of its use
+      float xh[EPT];
+#pragma unroll
+      for (int it = 0; it < EPT; ++it) {
+        const int id = tid + it * NTH;
+        xh[it] = 0.0f;
+        if (CELL == CELL_SRU && id < CHUNK && tl <= tlast) xh[it] = s.xcur[static_cast<long>(t) * s.ldx + f0 + id / CT];
+      }
 #pragma unroll
       for (int g = 0; g < 3; ++g)
 #pragma unroll
@@ -92,46 +134,47 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
           *reinterpret_cast<float4*>(dst) = make_float4(acc[g][n0 + q][0], acc[g][n0 + q][1], acc[g][n0 + q][2], acc[g][n0 + q][3]);
         }
       __syncthreads();
-      for (int e = tid; e < CHUNK; e += NW * 64) {      // e = local time * 16 + feature
-        float u0 = b0, u1 = b1, u2 = b2;
-        for (int w = 0; w < NW; ++w) {
+#pragma unroll
+      for (int it = 0; it < EPT; ++it) {
+        const int e = tid + it * NTH;                     // e = local time * 16 + feature
+        if (e < CHUNK) {
+          float u0 = b0, u1 = b1, u2 = b2;
           const int q = e >> 8, r = e & 255;
-          u0 += part[((w * 3 + 0) * NTC + q) * 256 + r];
-          u1 += part[((w * 3 + 1) * NTC + q) * 256 + r];
-          u2 += part[((w * 3 + 2) * NTC + q) * 256 + r];
+#pragma unroll
+          for (int w = 0; w < NW; ++w) {
+            u0 += part[((w * 3 + 0) * NTC + q) * 256 + r];
+            u1 += part[((w * 3 + 1) * NTC + q) * 256 + r];
+            u2 += part[((w * 3 + 2) * NTC + q) * 256 + r];
+          }
+          const float f = sigmoidf_fast(u1);
+          const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
+          const int at = (e & 15) * TS + (e >> 4);
+          g_a[at] = f;
+          g_b[at] = (1.0f - f) * cand;
+          g_o[at] = sigmoidf_fast(u2);
         }
-        const float f = sigmoidf_fast(u1);
-        const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
-        const int at = (e & 15) * TS + (e >> 4);
-        g_a[at] = f;
-        g_b[at] = (1.0f - f) * cand;
-        g_o[at] = sigmoidf_fast(u2);
       }
       __syncthreads();
-      const int tlast = min(CT, s.nt - n0 * 16) - 1;      // last valid step of this chunk
-      for (int id = tid; id < MFMA_F * CT; id += NW * 64) {
-        const int fi = id / CT;
-        const int tl = id - fi * CT;
-        float a = g_a[fi * TS + tl], b = g_b[fi * TS + tl];
-        const float o = g_o[fi * TS + tl];
-        const float cin = c_carry[fi];
 #pragma unroll
-        for (int off = 1; off < CT; off <<= 1) {
-          const float ap = __shfl_up(a, off, CT);
-          const float bp = __shfl_up(b, off, CT);
-          if (tl >= off) { b = fmaf(a, bp, b); a *= ap; }
+      for (int it = 0; it < EPT; ++it) {
+        const int id = tid + it * NTH;
+        if (id < CHUNK) {                                 // uniform per wave: whole scan groups are in or out
+          const int fi = id / CT;
+          float a = g_a[fi * TS + tl], b = g_b[fi * TS + tl];
+          const float o = g_o[fi * TS + tl];
+          const float cin = c_carry[fi];
+          affine_scan<CT>(a, b);
+          const float c = fmaf(a, cin, b);                // state after step tl of the chunk
+          const int i = f0 + fi;
+          if (tl <= tlast) {
+            float hv = o * tanhf_fast(c);
+            if (CELL == CELL_SRU) hv += (1.0f - o) * xh[it];
+            s.hout[static_cast<long>(t) * s.ldh + i] = hv;
+            if (s.hop) store_operand(s.hop, s.ldt, s.op_bf16, t, i, hv);
+          }
+          // the CT lanes of a feature sit in one wave and have read c_carry above
+          if (tl == tlast) { c_carry[fi] = c; s.c[i] = c; }
         }
-        const float c = fmaf(a, cin, b);                   // state after step tl of the chunk
-        const int t = n0 * 16 + tl;
-        const int i = f0 + fi;
-        if (tl <= tlast) {
-          float hv = o * tanhf_fast(c);
-          if (CELL == CELL_SRU) hv += (1.0f - o) * s.xcur[static_cast<long>(t) * s.ldx + i];
-          s.hout[static_cast<long>(t) * s.ldh + i] = hv;
-          if (s.hop) store_operand(s.hop, s.ldt, s.op_bf16, t, i, hv);
-        }
-        // the CT lanes of a feature sit in one wave and have read c_carry above
-        if (tl == tlast) { c_carry[fi] = c; s.c[i] = c; }
       }
       // the next chunk's phase A only writes `part`, which every wave has finished
       // reading; its first barrier orders this phase's reads before the next phase B
@@ -219,12 +262,7 @@ __global__ __launch_bounds__(512) void split_epilogue_kernel(Stage s, int d, int
     const float o = sigmoidf_fast(u2);
     const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
     float a = f, b = (1.0f - f) * cand;
-#pragma unroll
-    for (int off = 1; off < 32; off <<= 1) {
-      const float ap = __shfl_up(a, off, 32);
-      const float bp = __shfl_up(b, off, 32);
-      if (tl >= off) { b = fmaf(a, bp, b); a *= ap; }
-    }
+    affine_scan<32>(a, b);
     const float c = fmaf(a, cin, b);
     if (t < s.nt) {
       float hv = o * tanhf_fast(c);

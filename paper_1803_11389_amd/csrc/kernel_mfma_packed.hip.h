@@ -131,10 +131,8 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_packed_kernel
   auto mfma_group = [&](int aslot, int bslot, int tile0, int grp) {
     if constexpr (WT == W_BF16) {
       const int h = grp / 3, g = grp - 3 * (grp / 3);
-      floatx4_t av = aring[aslot][g * 2 + h];
-      asm volatile("" : "+v"(av));         // keeps the fragment's load one dwordx4
       bf16x8_t ab;
-      __builtin_memcpy(&ab, &av, sizeof ab);
+      __builtin_memcpy(&ab, &aring[aslot][g * 2 + h], sizeof ab);
 #pragma unroll
       for (int n = 0; n < NBT; ++n)
         acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[h], acc[g][tile0 + n], 0, 0, 0);
@@ -142,8 +140,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_packed_kernel
       const int h = grp >> 2, q = grp & 3;
 #pragma unroll
       for (int g = 0; g < 3; ++g) {
-        floatx4_t av = aring[aslot][g * 2 + h];
-        asm volatile("" : "+v"(av));       // keeps the fragment's load one dwordx4
+        const floatx4_t av = aring[aslot][g * 2 + h];
 #pragma unroll
         for (int n = 0; n < NBT; ++n) {
           const float4 bv = bring[bslot][n].v[h];
