@@ -155,6 +155,39 @@ __global__ void stage_input_kernel(const float* x, const float* xhist_init, floa
   if (dst_op) store_operand(dst_op, ldt, op_bf16, static_cast<int>(r), m, v);
 }
 
+// Same rows for widths that are multiples of 8 and 16-byte aligned buffers: a
+// thread moves 8 consecutive columns of one row (blockIdx.y = row + k-1) with
+// 16-byte accesses: two row-major stores and one (bf16) or two (fp32) operand chunks.
+__global__ void stage_input_vec_kernel(const float* x, const float* xhist_init, float* dst, void* dst_op, int ldt,
+                                       int op_bf16, int ld, int d, int k, long t0) {
+  const int m = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (m >= d) return;
+  const int r = static_cast<int>(blockIdx.y) - (k - 1);
+  const long sabs = t0 + r;
+  float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+  const float* src = sabs >= 0 ? x + sabs * d + m : (xhist_init ? xhist_init + (-sabs - 1) * d + m : nullptr);
+  if (src) {
+    v0 = *reinterpret_cast<const float4*>(src);
+    v1 = *reinterpret_cast<const float4*>(src + 4);
+  }
+  float* out = dst + static_cast<long>(r) * ld + m;
+  *reinterpret_cast<float4*>(out) = v0;
+  *reinterpret_cast<float4*>(out + 4) = v1;
+  if (!dst_op) return;
+  if (op_bf16) {
+    uint4 pk;
+    pk.x = f32_to_bf16_rne(v0.x) | (static_cast<uint32_t>(f32_to_bf16_rne(v0.y)) << 16);
+    pk.y = f32_to_bf16_rne(v0.z) | (static_cast<uint32_t>(f32_to_bf16_rne(v0.w)) << 16);
+    pk.z = f32_to_bf16_rne(v1.x) | (static_cast<uint32_t>(f32_to_bf16_rne(v1.y)) << 16);
+    pk.w = f32_to_bf16_rne(v1.z) | (static_cast<uint32_t>(f32_to_bf16_rne(v1.w)) << 16);
+    *reinterpret_cast<uint4*>(static_cast<char*>(dst_op) + (static_cast<long>(m >> 3) * ldt + r) * 16) = pk;
+  } else {
+    char* o = static_cast<char*>(dst_op) + (static_cast<long>(m >> 2) * ldt + r) * 16;
+    *reinterpret_cast<float4*>(o) = v0;
+    *reinterpret_cast<float4*>(o + static_cast<long>(ldt) * 16) = v1;
+  }
+}
+
 __global__ void copy_history_kernel(const float* src, float* dst, long n) {
   const long i = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
   if (i < n) dst[i] = src ? src[i] : 0.0f;
@@ -412,9 +445,16 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     const int nt = static_cast<int>(L - t0 < T ? L - t0 : T);
     nt_last = nt;
     if (stage_in) {
-      const long n = static_cast<long>(k - 1 + nt) * d;
-      hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0),
-                         use_op ? opbuf(0) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, nt);
+      if (d % 8 == 0 && aligned16(x) && aligned16(xhist_init) && k - 1 + nt <= 65535) {
+        const int per_row = d / 8;
+        const int bx = per_row < 256 ? (per_row + 63) / 64 * 64 : 256;
+        hipLaunchKernelGGL(stage_input_vec_kernel, dim3((per_row + bx - 1) / bx, k - 1 + nt), dim3(bx), 0, st, x,
+                           xhist_init, act(0), use_op ? opbuf(0) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0);
+      } else {
+        const long n = static_cast<long>(k - 1 + nt) * d;
+        hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0),
+                           use_op ? opbuf(0) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, nt);
+      }
     }
     for (int l = 0; l < n_layers; ++l) {
       Stage s{};
