@@ -153,7 +153,7 @@ def main():
 
     sec, ev_ms = measure(args.T, args.steps, args.warmup)
     head = row(args.T, sec, ev_ms)
-    h_head = h[: min(cfg.L, 512)].clone()
+    h_head = h[: min(cfg.L, 1024)].clone()
 
     head["weights"] = "packed" if args.packed else "row-major"
     sweep = []
@@ -201,7 +201,7 @@ def main():
     if not args.no_cpu:
         import oracle
         cores = oracle.num_threads()
-        n = args.cpu_sample_steps or (256 if cfg.d >= 4096 else 1000)
+        n = args.cpu_sample_steps or (1024 if cfg.d >= 4096 else 1000)   # about 15 s of CPU time on 16 cores at d = 4096
         n = min(n, cfg.L)
         xs = x[:n].cpu().numpy()
         t0 = time.perf_counter()
