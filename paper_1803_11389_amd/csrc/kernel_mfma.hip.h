@@ -37,7 +37,7 @@ constexpr int MFMA_MAX_T = 256;     // longest block one launch accumulates
 
 template <int NT>
 struct MfmaCfg {
-  static constexpr int NW = (NT >= 8) ? 4 : 8;      // waves: 512 registers each when NT is large
+  static constexpr int NW = (NT >= 8) ? 4 : 8;      // waves of the LDS-staged kernel: 512 registers each when NT is large
   static constexpr int NTC = (NT < 2) ? NT : 2;     // N tiles per epilogue chunk
 };
 
@@ -76,14 +76,13 @@ __device__ __forceinline__ void affine_scan(float& a, float& b) {
 #undef SSRNN_SCAN_STEP
 }
 
-// Epilogue shared by the matrix-core kernels; the workgroup has exactly
-// MfmaCfg<NT>::NW waves.  acc[g][n]: this wave's partial 16x16 tiles (gate g,
+// Epilogue shared by the matrix-core kernels; the workgroup has exactly NW
+// waves.  acc[g][n]: this wave's partial 16x16 tiles (gate g,
 // time tile n) in the MFMA result layout (lane = time n%16 + 16*(feature/4),
 // register = feature%4).
-template <int CELL, int NT>
+template <int CELL, int NT, int NW>
 __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, floatx4_t (&acc)[3][NT], float* part,
                                               float* g_a, float* g_b, float* g_o, float* c_carry) {
-  constexpr int NW = MfmaCfg<NT>::NW;           // waves that split the columns
   constexpr int NTH = NW * 64;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int CHUNK = NTC * 256;              // (step, feature) pairs per chunk

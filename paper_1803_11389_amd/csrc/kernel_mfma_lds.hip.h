@@ -177,22 +177,28 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
       const bool fetch_b = !LAST || (tgt < U * NBH);
       const int bnext = tgt % S;
       const int btile0 = (tgt % NBH) * NBT;
-      // items of this sub-step: LDS writes and line loads ride on the first, LDS reads on the last
-      const int n_head = (hb == 0) ? 12 : 0;
+      // Items of this sub-step: LDS writes and line loads ride on the first, LDS reads on the last.
+      // Loads complete in issue order (one counter per wave), so the B pieces, needed within a
+      // sub-step or two, are issued before the weight lines of the far k-step: the other order would
+      // make every wait for B pieces a wait for the whole weight prefetch.
+      const int n_wr = (hb == 0) ? 6 : 0;
+      const int n_b = 2 * NBT;
+      const int n_ld = (hb == 0) ? 6 : 0;
       const int n_tail = (hb == NBH - 1) ? 6 : 0;
-      const int nitem = n_head + 2 * NBT + n_tail;
+      const int nitem = n_wr + n_b + n_ld + n_tail;
 #pragma unroll
       for (int grp = 0; grp < NGRP; ++grp) {
         mfma_group(p & 1, bslot, hb * NBT, grp);
 #pragma unroll
         for (int it = (grp * nitem) / NGRP; it < ((grp + 1) * nitem) / NGRP; ++it) {
-          if (it < n_head) {
-            if (it < 6) { if constexpr (stage_next) lds_write(wslot, it); }
-            else { if constexpr (fetch_a) load_a_line(aslot, it - 6); }
-          } else if (it < n_head + 2 * NBT) {
-            if (fetch_b) load_b_piece(bnext, btile0, it - n_head);
+          if (it < n_wr) {
+            if constexpr (stage_next) lds_write(wslot, it);
+          } else if (it < n_wr + n_b) {
+            if (fetch_b) load_b_piece(bnext, btile0, it - n_wr);
+          } else if (it < n_wr + n_b + n_ld) {
+            if constexpr (fetch_a) load_a_line(aslot, it - n_wr - n_b);
           } else {
-            if constexpr (stage_next) lds_read((p + 1) & 1, it - n_head - 2 * NBT);
+            if constexpr (stage_next) lds_read((p + 1) & 1, it - n_wr - n_b - n_ld);
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -263,7 +269,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
     mfma_store_partials<NT>(s, d, f0, ksp, acc, part);
     return;
   }
-  mfma_epilogue<CELL, NT>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
+  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
 }
 
 }  // namespace ssrnn

@@ -27,10 +27,13 @@
 
 namespace ssrnn {
 
+// Four waves per workgroup, one per SIMD: a wave then has the SIMD's matrix pipe to itself.  Two waves per
+// SIMD measured slower from T = 32 on (fp32, T = 32: 43.5 -> 38.6 us per stage; T = 64: 66.7 -> 58.1 us).
 template <int NT>
 struct MfmaPkCfg {
+  static constexpr int NW = 4;                            // waves per workgroup
   static constexpr int SA = 4;                            // weight fragment ring slots (k-steps)
-  static constexpr int SB = (NT <= 2) ? 4 : 2;            // B fragment ring slots (sub-steps)
+  static constexpr int SB = (NT <= 4) ? 4 : 2;            // B fragment ring slots (sub-steps)
   static constexpr int NBT = (NT > 8) ? 8 : NT;           // time tiles per B fetch
 };
 
@@ -51,8 +54,8 @@ __global__ void pack_weights_kernel(const uint4* __restrict__ src, uint4* __rest
 }
 
 template <int CELL, int WT, int NT>
-__global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_packed_kernel(Stage s, int d, int k) {
-  constexpr int NW = MfmaCfg<NT>::NW;
+__global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kernel(Stage s, int d, int k) {
+  constexpr int NW = MfmaPkCfg<NT>::NW;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int KSTEP = (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
   constexpr int CW = KSTEP / 4;                      // columns per lane per step (32 bytes)
@@ -170,15 +173,18 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_packed_kernel
       const bool fetch_b = !LAST || (tgt < U * NBH);
       const int bnext = tgt % SB;
       const int btile0 = (tgt % NBH) * NBT;
-      const int n_head = (hb == 0) ? 6 : 0;                     // weight fragments ride on the first sub-step
-      const int nitem = n_head + 2 * NBT;
+      // Loads complete in issue order (one counter per wave), so they are issued in the order they are
+      // needed: the B pieces of the next sub-steps first, the weight fragments of the far k-step after
+      // them.  The other order would make the wait for the B pieces a wait for the weight prefetch too.
+      const int n_b = 2 * NBT;
+      const int nitem = n_b + ((hb == 0) ? 6 : 0);              // weight fragments ride on the first sub-step
 #pragma unroll
       for (int grp = 0; grp < NGRP; ++grp) {
         mfma_group(p % SA, bslot, hb * NBT, grp);
 #pragma unroll
         for (int it = (grp * nitem) / NGRP; it < ((grp + 1) * nitem) / NGRP; ++it) {
-          if (it < n_head) { if constexpr (fetch_a) load_a_frag(aslot, it); }
-          else { if (fetch_b) load_b_piece(bnext, btile0, it - n_head); }
+          if (it < n_b) { if (fetch_b) load_b_piece(bnext, btile0, it); }
+          else { if constexpr (fetch_a) load_a_frag(aslot, it - n_b); }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -237,7 +243,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_packed_kernel
     mfma_store_partials<NT>(s, d, f0, ksp, acc, part);
     return;
   }
-  mfma_epilogue<CELL, NT>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
+  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
 }
 
 }  // namespace ssrnn

@@ -276,6 +276,17 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
 // 16-tile fp32 instance does not fit the register file, so row-major fp32 weights stop at 8 tiles.
 int mfma_block_cap(int wdt, bool packed) { return (wdt == SSRNN_F32 && !packed) ? MFMA_MAX_T / 2 : MFMA_MAX_T; }
 
+// Waves per workgroup of the matrix-core kernel that takes this block length and weight layout.
+int mfma_waves(int nt_tiles, bool packed) {
+  switch (nt_tiles) {
+    case 1: return packed ? MfmaPkCfg<1>::NW : MfmaCfg<1>::NW;
+    case 2: return packed ? MfmaPkCfg<2>::NW : MfmaCfg<2>::NW;
+    case 4: return packed ? MfmaPkCfg<4>::NW : MfmaCfg<4>::NW;
+    case 8: return packed ? MfmaPkCfg<8>::NW : MfmaCfg<8>::NW;
+    default: return packed ? MfmaPkCfg<16>::NW : MfmaCfg<16>::NW;
+  }
+}
+
 // Shapes ssrnn_pack_weights takes: whole 16-feature tiles, and k-steps of 128 bytes that never straddle lag blocks.
 bool pack_shape_ok(int d, int k, int wdt) {
   if (wdt != SSRNN_F32 && wdt != SSRNN_BF16) return false;
@@ -291,7 +302,7 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
     if (!aligned16(W[l])) return false;
   const int tiles = (p.T + 15) / 16;
   p.nt_tiles = tiles <= 1 ? 1 : tiles <= 2 ? 2 : tiles <= 4 ? 4 : tiles <= 8 ? 8 : 16;
-  const int nw = p.nt_tiles >= 8 ? 4 : 8;
+  const int nw = mfma_waves(p.nt_tiles, p.packed);
   const int kstep = p.wdt == SSRNN_BF16 ? 64 : 32;
   const long ncol = static_cast<long>(p.k) * p.d;
   if (ncol % (nw * kstep) != 0) return false;
