@@ -45,13 +45,14 @@ typedef enum {
 
 typedef enum { SSRNN_F32 = 0, SSRNN_BF16 = 1 } ssrnn_wdtype;
 
-/* `flags` of *_forward: 0 picks the schedule and kernel by shape.  The other
- * values force one (tests and measurements use them); a forced choice that the
- * shape does not allow returns SSRNN_EUNSUPPORTED. */
+/* `flags` of *_forward: 0 picks the kernel by shape.  The other values force
+ * one (tests and measurements use them); a forced choice that the shape does
+ * not allow returns SSRNN_EUNSUPPORTED.  The schedule is always one kernel
+ * launch per (block, layer) stage on the given stream; SSRNN_SCHED_STAGES
+ * names it explicitly. */
 enum {
   SSRNN_SCHED_AUTO = 0,
   SSRNN_SCHED_STAGES = 1,     /* one kernel launch per (block, layer) stage                  */
-  SSRNN_SCHED_PERSISTENT = 2, /* one cooperative launch; stages separated by a grid barrier  */
   SSRNN_SCHED_MASK = 3,
   SSRNN_KERNEL_AUTO = 0,
   SSRNN_KERNEL_GENERIC = 1 << 4, /* any d, k, T: one wavefront per output feature            */
@@ -69,8 +70,8 @@ int ssrnn_version(void);
 const char* ssrnn_last_error(void);
 
 /* Bytes of device scratch *_forward needs for this shape (inter-layer
- * activations for one block, per-layer running state, barrier words).  Host.
- * Returns 0 for arguments *_forward would reject.  The workspace must be
+ * activations for one block, their operand copies for the matrix-core
+ * kernels, control words).  Host.  Returns 0 for arguments *_forward would reject.  The workspace must be
  * 256-byte aligned; its contents need not be initialised and are not preserved. */
 size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype);
 

@@ -389,14 +389,13 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   const int sched = flags & SSRNN_SCHED_MASK;
   const int kforce = flags & SSRNN_KERNEL_MASK;
   const bool packed = (flags & SSRNN_WEIGHTS_PACKED) != 0;
-  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED)) != 0 || sched == 3)
+  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED)) != 0 || sched > SSRNN_SCHED_STAGES)
     return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
   if (packed && kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_MFMA)
     return fail(SSRNN_EINVAL, "%s: packed weights are read by the matrix-core kernel only", name);
   if (packed && !pack_shape_ok(d, k, wdt))
     return fail(SSRNN_EUNSUPPORTED, "%s: no packed form exists for d = %d, k = %d", name, d, k);
   if (T > L && L > 0) T = static_cast<int>(L);   // one short block; buffers sized by the caller's T still suffice
-  const int T_asked = T;
   const WorkspaceLayout wl = workspace_layout(n_layers, d, k, T, wdt);
   if (L > 0) {
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % WS_ALIGN) != 0)
@@ -439,8 +438,6 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
         return fail(SSRNN_EUNSUPPORTED, "%s: matrix-core kernel needs d %% 16 == 0, k*d %% 256 == 0 and 16-byte aligned buffers", name);
     }
   }
-  (void)T_asked;
-  if (sched == SSRNN_SCHED_PERSISTENT) return fail(SSRNN_EUNSUPPORTED, "%s: persistent schedule not available for this shape", name);
 
   char* act0 = static_cast<char*>(workspace) + wl.act_offset;
   char* op0 = static_cast<char*>(workspace) + wl.op_offset;

@@ -14,13 +14,13 @@ from gpu_util import max_abs, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def _gpu_run(cfg, W_dev, x_dev, T, L):
+def _gpu_run(cfg, W_dev, x_dev, T, L, flags=0):
     import torch
     import paper_1803_11389_amd as ss
     if cfg.cell == "sru":
-        h, c = ss.sru_forward(W_dev, None, x_dev[:L].contiguous(), None, T=T)
+        h, c = ss.sru_forward(W_dev, None, x_dev[:L].contiguous(), None, T=T, flags=flags)
     else:
-        h, c, _ = ss.qrnn_forward(W_dev, None, x_dev[:L].contiguous(), None, None, T=T, k=cfg.k)
+        h, c, _ = ss.qrnn_forward(W_dev, None, x_dev[:L].contiguous(), None, None, T=T, k=cfg.k, flags=flags)
     torch.cuda.synchronize()
     return h.cpu().numpy(), c.cpu().numpy()
 
@@ -29,6 +29,7 @@ def _run_config(cfg, L, tol, relative):
     import paper_1803_11389_amd as ss
     inp = wl.make_inputs(cfg, L=L)
     W_dev = [to_dev(w) for w in inp["W"]]
+    W_packed = [ss.pack_weights(w) for w in W_dev]      # the same matrices in the matrix-core kernel's order
     if cfg.d_feat:
         x_ref = oracle.linear_forward(inp["P"], inp["feat"])
         x_dev = ss.linear_forward(to_dev(inp["P"]), to_dev(inp["feat"]))
@@ -43,11 +44,12 @@ def _run_config(cfg, L, tol, relative):
     scale_h = max(float(np.abs(h_ref).max()), 1e-6) if relative else 1.0
     scale_c = max(float(np.abs(c_ref).max()), 1e-6) if relative else 1.0
     for T in cfg.Ts:
-        h, c = _gpu_run(cfg, W_dev, x_dev, T, L)
-        eh, ec = max_abs(h, h_ref) / scale_h, max_abs(c, c_ref) / scale_c
-        print(f"{cfg.name} L={L} T={T}: err h {eh:.3e} c {ec:.3e}", flush=True)
-        assert np.all(np.isfinite(h))
-        assert eh <= tol and ec <= tol, (T, eh, ec)
+        for layout, Wl, flags in (("row-major", W_dev, 0), ("packed", W_packed, ss.WEIGHTS_PACKED)):
+            h, c = _gpu_run(cfg, Wl, x_dev, T, L, flags)
+            eh, ec = max_abs(h, h_ref) / scale_h, max_abs(c, c_ref) / scale_c
+            print(f"{cfg.name} L={L} T={T} {layout}: err h {eh:.3e} c {ec:.3e}", flush=True)
+            assert np.all(np.isfinite(h))
+            assert eh <= tol and ec <= tol, (T, layout, eh, ec)
 
 
 def test_config2_sru4_d1024_asr_full_length():
@@ -81,13 +83,16 @@ def _full_length(cfg, T_list, n_oracle, tol, relative):
     inp = wl.make_inputs(cfg)
     W_dev = [to_dev(w) for w in inp["W"]]
     x_dev = to_dev(inp["x"])
-    ws = ss.Workspace.for_shape(cfg.n_layers, cfg.d, cfg.k, max(T_list), ss.BF16 if cfg.wdtype == "bf16" else ss.F32)
+    W_packed = [ss.pack_weights(w) for w in W_dev]
+    ws = ss.Workspace.for_shape(cfg.n_layers, cfg.d, cfg.k, max(abs(T) for T in T_list), ss.BF16 if cfg.wdtype == "bf16" else ss.F32)
 
     def run(T):
+        """T > 0: row-major weights; T < 0: block size -T with packed weights."""
+        Wl, flags = (W_dev, 0) if T > 0 else (W_packed, ss.WEIGHTS_PACKED)
         if cfg.cell == "sru":
-            h, c = ss.sru_forward(W_dev, None, x_dev, None, T=T, workspace=ws)
+            h, c = ss.sru_forward(Wl, None, x_dev, None, T=abs(T), flags=flags, workspace=ws)
         else:
-            h, c, _ = ss.qrnn_forward(W_dev, None, x_dev, None, None, T=T, k=cfg.k, workspace=ws)
+            h, c, _ = ss.qrnn_forward(Wl, None, x_dev, None, None, T=abs(T), k=cfg.k, flags=flags, workspace=ws)
         torch.cuda.synchronize()
         return h, c
 
@@ -119,12 +124,12 @@ def _full_length(cfg, T_list, n_oracle, tol, relative):
 
 def test_config4_full_length_properties():
     cfg = wl.CONFIGS[3]
-    h = _full_length(cfg, [4, 1, 16, 128], 96, 1e-4, False)
+    h = _full_length(cfg, [4, 1, 16, 128, -4, -16, -64], 96, 1e-4, False)
     # SRU: h is a gate-weighted mix of tanh(c) in [-1, 1] and the layer input; bounded by max(1, |x|)
     assert float(h.abs().max()) <= max(1.0, 6.5)
 
 
 def test_config5_full_length_properties():
     cfg = wl.CONFIGS[4]
-    h = _full_length(cfg, [64, 16, 256], 80, 2e-2, True)
+    h = _full_length(cfg, [64, 16, 256, -16, -64, -256], 80, 2e-2, True)
     assert float(h.abs().max()) < 1.0        # QRNN: h = o * tanh(c), 0 < o < 1

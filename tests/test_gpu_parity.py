@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
 GENERIC, VALU, MFMA = 1 << 4, 2 << 4, 3 << 4
-STAGES, PERSISTENT = 1, 2
+STAGES = 1
 
 
 def _rng(seed):
