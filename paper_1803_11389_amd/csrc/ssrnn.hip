@@ -86,7 +86,10 @@ WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
   w.op_stride = (d % MFMA_F == 0) ? align_up(static_cast<size_t>(d) * esize / 16 * w.ldt * 16, WS_ALIGN) : 0;
   w.op_offset = w.act_offset + static_cast<size_t>(n_layers) * w.act_stride;
   w.upart_offset = w.op_offset + static_cast<size_t>(n_layers) * w.op_stride;
-  w.upart_rows = (tcap + 15) / 16 * 16;
+  // a split stage stores whole groups of time tiles, and the kernels take 1, 2, 4, 8 or 16 tiles
+  int tiles = 1;
+  while (tiles * 16 < tcap) tiles *= 2;
+  w.upart_rows = tiles * 16;
   w.upart_bytes = (d % MFMA_F == 0 && d / MFMA_F < 128)
                       ? align_up(static_cast<size_t>(KSPLIT_MAX) * 3 * w.upart_rows * d * sizeof(float), WS_ALIGN) : 0;
   w.total = w.upart_offset + w.upart_bytes;

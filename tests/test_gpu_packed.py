@@ -51,7 +51,7 @@ def test_pack_is_the_documented_permutation(d, k, bf16):
 @pytest.mark.parametrize("d,n_layers,L,T", [
     (256, 2, 40, 16), (256, 2, 23, 9), (512, 2, 70, 32), (1024, 2, 100, 64), (1024, 1, 150, 128),
     (512, 2, 300, 256), (256, 2, 600, 400), (4096, 1, 20, 16), (2048, 2, 64, 64), (4096, 2, 12, 4),
-    (1024, 2, 9, 1), (4096, 1, 130, 128),
+    (1024, 2, 9, 1), (4096, 1, 130, 128), (256, 2, 90, 40), (512, 2, 210, 100), (1024, 1, 75, 70),
 ])
 def test_sru_packed_fp32(d, n_layers, L, T):
     print(f"packed sru d={d} layers={n_layers} L={L} T={T}", flush=True)
@@ -65,6 +65,7 @@ def test_sru_packed_fp32(d, n_layers, L, T):
 @pytest.mark.parametrize("d,n_layers,L,T,k", [
     (256, 2, 40, 16, 2), (512, 2, 70, 32, 2), (1024, 2, 100, 64, 2), (256, 2, 50, 20, 3),
     (512, 1, 200, 128, 2), (256, 2, 300, 256, 2), (128, 2, 30, 4, 2), (256, 2, 10, 1, 2), (4096, 1, 40, 32, 2),
+    (256, 2, 500, 400, 2), (256, 2, 70, 33, 4), (512, 3, 37, 100, 3), (1024, 2, 5, 16, 2),
 ])
 def test_qrnn_packed_fp32(d, n_layers, L, T, k):
     print(f"packed qrnn d={d} layers={n_layers} L={L} T={T} k={k}", flush=True)
@@ -79,7 +80,7 @@ def test_qrnn_packed_fp32(d, n_layers, L, T, k):
 @pytest.mark.parametrize("cell,d,n_layers,L,T,k", [
     ("qrnn", 256, 2, 40, 16, 2), ("qrnn", 1024, 3, 100, 64, 2), ("qrnn", 512, 2, 300, 256, 2),
     ("sru", 512, 2, 70, 32, 1), ("qrnn", 256, 2, 30, 4, 2), ("sru", 1024, 2, 150, 128, 1),
-    ("qrnn", 4096, 1, 260, 256, 2),
+    ("qrnn", 4096, 1, 260, 256, 2), ("qrnn", 512, 2, 45, 17, 3), ("qrnn", 512, 2, 600, 400, 2),
 ])
 def test_packed_bf16(cell, d, n_layers, L, T, k):
     print(f"packed bf16 {cell} d={d} layers={n_layers} L={L} T={T} k={k}", flush=True)

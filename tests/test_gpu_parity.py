@@ -213,6 +213,7 @@ def _rel_err(a, ref):
 @pytest.mark.parametrize("d,n_layers,L,T", [
     (256, 2, 40, 16), (256, 2, 23, 9), (512, 2, 70, 32), (1024, 2, 100, 64), (1024, 1, 150, 128),
     (512, 2, 300, 256), (256, 2, 600, 400), (4096, 1, 20, 16), (256, 2, 33, 12), (2048, 2, 64, 64),
+    (256, 2, 90, 40), (512, 2, 210, 100), (1024, 1, 75, 70),   # narrow layers, tile counts that round up
 ])
 def test_sru_mfma_kernel_fp32(d, n_layers, L, T):
     W, b, x, c0 = _sru_inputs(800 + d + T, n_layers, d, L, scale=2.0)
@@ -222,6 +223,7 @@ def test_sru_mfma_kernel_fp32(d, n_layers, L, T):
 @pytest.mark.parametrize("d,n_layers,L,T,k", [
     (256, 2, 40, 16, 2), (512, 2, 70, 32, 2), (1024, 2, 100, 64, 2), (256, 2, 50, 20, 3),
     (512, 1, 200, 128, 2), (256, 2, 300, 256, 2), (128, 2, 30, 4, 2), (256, 2, 10, 1, 2),
+    (256, 2, 500, 400, 2), (256, 2, 70, 33, 4), (512, 3, 37, 100, 3), (1024, 2, 5, 16, 2),
 ])
 def test_qrnn_mfma_kernel_fp32(d, n_layers, L, T, k):
     W, b, x, c0, xh0 = _qrnn_inputs(900 + d + T + k, n_layers, d, L, k, scale=2.0)
@@ -231,6 +233,7 @@ def test_qrnn_mfma_kernel_fp32(d, n_layers, L, T, k):
 @pytest.mark.parametrize("cell,d,n_layers,L,T,k", [
     ("qrnn", 256, 2, 40, 16, 2), ("qrnn", 1024, 3, 100, 64, 2), ("qrnn", 512, 2, 300, 256, 2),
     ("sru", 512, 2, 70, 32, 1), ("qrnn", 256, 2, 30, 4, 2), ("sru", 1024, 2, 150, 128, 1),
+    ("qrnn", 512, 2, 45, 17, 3), ("qrnn", 512, 2, 600, 400, 2),
 ])
 def test_mfma_kernel_bf16_weights(cell, d, n_layers, L, T, k):
     """bf16 weights, inputs rounded to bf16 inside the kernel, fp32 accumulation
