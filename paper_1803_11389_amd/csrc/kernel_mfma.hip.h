@@ -19,10 +19,11 @@
 //     A pieces reach the registers is what the kernels differ in (LDS-staged
 //     lines of the row-major matrix, or pre-packed fragments); the B pieces
 //     come from the operand copy of the input block (see Stage).
-//   - epilogue, 32 steps of time at a time: per-wave partial tiles go to LDS,
-//     all threads finish the split-K sum and apply the gate non-linearities,
-//     then the recurrence c_t = f_t*c_{t-1} + b_t runs as a prefix scan over
-//     32 adjacent lanes per feature, and the same lanes form h_t.
+//   - epilogue, 16 to 64 steps of time at a time: per-wave partial tiles go
+//     to LDS, all threads finish the split-K sum and apply the gate
+//     non-linearities, then the recurrence c_t = f_t*c_{t-1} + b_t runs as a
+//     prefix scan over the adjacent lanes that hold a feature's steps, and
+//     the same lanes form h_t.
 #pragma once
 
 #include "common.hip.h"
@@ -38,7 +39,7 @@ constexpr int MFMA_MAX_T = 256;     // longest block one launch accumulates
 template <int NT>
 struct MfmaCfg {
   static constexpr int NW = (NT >= 8) ? 4 : 8;      // waves of the LDS-staged kernel: 512 registers each when NT is large
-  static constexpr int NTC = (NT < 2) ? NT : 2;     // N tiles per epilogue chunk
+  static constexpr int NTC = (NT < 2) ? NT : (NT >= 8) ? 4 : 2;   // N tiles per epilogue chunk
 };
 
 template <int WT>
@@ -48,19 +49,20 @@ struct BFrag<W_F32> { float4 v[2]; };
 template <>
 struct BFrag<W_BF16> { bf16x8_t v[2]; };
 
-// Inclusive prefix scan of affine maps c -> a*c + b over groups of CT (16 or
-// 32) adjacent lanes, lane order = time order: afterwards (a, b) of a lane is
+// Inclusive prefix scan of affine maps c -> a*c + b over groups of CT (16, 32
+// or 64) adjacent lanes, lane order = time order: afterwards (a, b) of a lane is
 // the composition of the maps of its group's lanes up to and including itself.
 // Data-parallel-primitive moves only: row_shr within rows of 16 lanes (lanes
-// without a source keep the identity map), then, for 32-lane groups, lane 15
-// of every even row broadcast to the odd row behind it.
+// without a source keep the identity map), then lane 15 of every even row
+// broadcast to the odd row behind it (groups of 32 and 64), then lane 31
+// broadcast to the upper half of the wave (groups of 64).
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_or(float fallback, float v) {
   return __uint_as_float(__builtin_amdgcn_update_dpp(__float_as_uint(fallback), __float_as_uint(v), CTRL, ROW_MASK, 0xf, false));
 }
 template <int CT>
 __device__ __forceinline__ void affine_scan(float& a, float& b) {
-  static_assert(CT == 16 || CT == 32, "scan groups are one or two DPP rows");
+  static_assert(CT == 16 || CT == 32 || CT == 64, "scan groups are one, two or four DPP rows");
 #define SSRNN_SCAN_STEP(CTRL, ROW_MASK)                       \
   {                                                           \
     const float ap = dpp_or<CTRL, ROW_MASK>(1.0f, a);         \
@@ -72,7 +74,8 @@ __device__ __forceinline__ void affine_scan(float& a, float& b) {
   SSRNN_SCAN_STEP(0x112, 0xf)   // row_shr:2
   SSRNN_SCAN_STEP(0x114, 0xf)   // row_shr:4
   SSRNN_SCAN_STEP(0x118, 0xf)   // row_shr:8
-  if constexpr (CT == 32) SSRNN_SCAN_STEP(0x142, 0xa)   // row_bcast:15 into rows 1 and 3
+  if constexpr (CT >= 32) SSRNN_SCAN_STEP(0x142, 0xa)   // row_bcast:15 into rows 1 and 3
+  if constexpr (CT == 64) SSRNN_SCAN_STEP(0x143, 0xc)   // row_bcast:31 into rows 2 and 3
 #undef SSRNN_SCAN_STEP
 }
 
