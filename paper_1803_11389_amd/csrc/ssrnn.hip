@@ -425,11 +425,18 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   p.cell = cell; p.n_layers = n_layers; p.d = d; p.k = k; p.T = T; p.wdt = wdt; p.L = L;
   p.kind = K_GENERIC;
   p.packed = packed;
+  // Kernel choice.  Forced: that kernel or an error.  Otherwise: the vector-ALU kernel where it applies
+  // (fp32, T <= 16), except that from T = 5 on a layer wide enough to give the matrix-core kernel one
+  // workgroup per CU (d >= 4096) goes there (measured at d = 4096: 34.8 us per stage against 36.3 at
+  // T = 8 and 40.0 at T = 16); the matrix-core kernel for everything else it takes; the generic kernel last.
+  bool valu_ok = false;
   if (!packed && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU)) {
-    if (plan_valu(p, W, x, xhist_init, workspace)) p.kind = K_VALU;
-    else if (kforce == SSRNN_KERNEL_VALU)
+    valu_ok = plan_valu(p, W, x, xhist_init, workspace);
+    if (!valu_ok && kforce == SSRNN_KERNEL_VALU)
       return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 16, d %% 256 == 0 and 16-byte aligned buffers", name);
   }
+  const bool prefer_mfma = kforce == SSRNN_KERNEL_AUTO && T > 4 && d / MFMA_F >= 256;
+  if (valu_ok && !prefer_mfma) p.kind = K_VALU;
   if (p.kind == K_GENERIC && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_MFMA)) {
     // the matrix-core kernels accumulate a bounded number of steps per weight pass: longer blocks are cut
     const int cap = mfma_block_cap(wdt, packed);
@@ -439,6 +446,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       p.T = T;
       if (kforce == SSRNN_KERNEL_MFMA || packed)
         return fail(SSRNN_EUNSUPPORTED, "%s: matrix-core kernel needs d %% 16 == 0, k*d %% 256 == 0 and 16-byte aligned buffers", name);
+      if (valu_ok) p.kind = K_VALU;
     }
   }
 
