@@ -44,6 +44,8 @@ def load_library(path: str):
     vp, ip, lp = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
     lib.oracle_num_threads.restype = ip
     lib.oracle_set_num_threads.argtypes = [ip]
+    lib.oracle_set_operand_rounding.argtypes = [ip]
+    lib.oracle_set_operand_rounding.restype = None
     lib.oracle_sru_forward.argtypes = [vp] * 7 + [ip, ip, lp, ip, ip]
     lib.oracle_qrnn_forward.argtypes = [vp] * 9 + [ip, ip, lp, ip, ip, ip]
     lib.oracle_sru_step.argtypes = [vp] * 5 + [ip, ip]
@@ -70,6 +72,13 @@ def _load():
 
 def num_threads() -> int:
     return _load().oracle_num_threads()
+
+
+def set_operand_rounding(mode: int) -> None:
+    """0 (default): exact arithmetic.  1: the block X of Eq. 4 enters the matrix
+    product rounded to bfloat16 (what a bf16 matrix-core kernel does); all else
+    stays double.  Callers restore 0 when done."""
+    _load().oracle_set_operand_rounding(int(mode))
 
 
 def set_num_threads(n: int) -> None:

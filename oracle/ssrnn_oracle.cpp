@@ -22,7 +22,13 @@
 // Arithmetic: every sum, gate and state is IEEE double; weights are given in
 // their storage type (fp32, or bf16 bit patterns) and widened exactly.  Each dot product adds its terms in ascending column
 // order whatever T is, so the result is bit-identical for every block size.
-// Nothing is rounded between layers.
+// Nothing is rounded between layers.  The paper does not state the precision
+// of its runs (Section 4).  For kernels that hand the block X of Eq. 4 to the
+// matrix product in bfloat16, oracle_set_operand_rounding(1) makes this
+// oracle round exactly that operand the same way (double -> float ->
+// bfloat16, both round-to-nearest-even) and nothing else: the highway term,
+// the state and the sums stay double.  The default, 0, rounds nothing, and
+// every pin below is stated for it.
 //
 // Pins (tests/test_oracle_*.py): hand-worked d=2 examples for both cells,
 // step-by-step brute force (oracle_*_step below, written separately),
@@ -67,6 +73,22 @@ inline double weight_at(const void* W, int wdt, size_t idx) {
 
 inline double sigma(double z) { return 1.0 / (1.0 + std::exp(-z)); }
 
+int g_round_operand = 0;   // 0: X of Eq. 4 enters the product as it is; 1: rounded to bfloat16
+
+// Nearest bfloat16 (ties to even) of the nearest float of v, as a double.
+inline double to_bf16_value(double v) {
+  const float f = static_cast<float>(v);
+  uint32_t u;
+  std::memcpy(&u, &f, sizeof u);
+  if ((u & 0x7F800000u) == 0x7F800000u) return static_cast<double>(f);   // inf / nan pass through
+  u = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+  float r;
+  std::memcpy(&r, &u, sizeof r);
+  return static_cast<double>(r);
+}
+
+inline double operand(double v) { return g_round_operand ? to_bf16_value(v) : v; }
+
 // U[g][i][t] = sum_col W[g*d+i][col] * X[col][t]   (Eq. 4 for all three gates)
 // X is the [ncol x nt] block, column t contiguous in t for a fixed col.
 // One weight is read once and applied to all nt columns (Section 3).
@@ -96,7 +118,7 @@ void sru_layer(const void* W, int wdt, const float* bias, const double* xin,
     // X = [x_{t0} ... x_{t0+nt-1}] as columns
     for (int j = 0; j < d; ++j)
       for (int t = 0; t < nt; ++t)
-        X[static_cast<size_t>(j) * nt + t] = xin[(t0 + t) * d + j];
+        X[static_cast<size_t>(j) * nt + t] = operand(xin[(t0 + t) * d + j]);
     gate_block(W, wdt, d, d, X.data(), nt, U.data());
     const double* Ux = U.data();
     const double* Uf = U.data() + static_cast<size_t>(d) * nt;
@@ -137,7 +159,7 @@ void qrnn_layer(const void* W, int wdt, const float* bias, const double* xin,
     for (int j = 0; j < k; ++j)
       for (int m = 0; m < d; ++m)
         for (int t = 0; t < nt; ++t)
-          X[(static_cast<size_t>(j) * d + m) * nt + t] = x_at(t0 + t - j, m);
+          X[(static_cast<size_t>(j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m));
     gate_block(W, wdt, d, ncol, X.data(), nt, U.data());
     const double* Uz = U.data();
     const double* Uf = U.data() + static_cast<size_t>(d) * nt;
@@ -178,6 +200,9 @@ int oracle_num_threads(void) {
   return 1;
 #endif
 }
+
+// mode 0 (default): exact operands; 1: the block X of Eq. 4 is rounded to bfloat16 before the product.
+void oracle_set_operand_rounding(int mode) { g_round_operand = mode ? 1 : 0; }
 
 void oracle_set_num_threads(int n) {
 #ifdef _OPENMP

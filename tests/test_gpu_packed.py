@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 from gpu_util import gpu_qrnn, gpu_sru, max_abs, to_dev
-from test_gpu_parity import BF16_TOL, TOL, _qrnn_inputs, _rel_err, _sru_inputs
+from test_gpu_parity import BF16_TOL, TOL, _check_against_rounding_oracle, _qrnn_inputs, _rel_err, _sru_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -95,6 +95,7 @@ def test_packed_bf16(cell, d, n_layers, L, T, k):
     assert np.all(np.isfinite(h))
     assert _rel_err(h, h_ref) <= BF16_TOL, _rel_err(h, h_ref)
     assert _rel_err(c, c_ref) <= BF16_TOL, _rel_err(c, c_ref)
+    _check_against_rounding_oracle(cell, W, b, x, c0, xh0 if cell == "qrnn" else None, T, k, h, c)
 
 
 def test_packed_flag_is_refused_where_no_matrix_core_kernel_applies():

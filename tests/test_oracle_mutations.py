@@ -26,9 +26,13 @@ MUTATIONS = [
     ("sigmoid sign", "return 1.0 / (1.0 + std::exp(-z));", "return 1.0 / (1.0 + std::exp(z));"),
     ("weights read transposed (square case)", "const size_t base = static_cast<size_t>(row) * ncol;\n    for (int col = 0; col < ncol; ++col) {\n      const double w = weight_at(W, wdt, base + col);",
      "const size_t base = static_cast<size_t>(row) * ncol;\n    for (int col = 0; col < ncol; ++col) {\n      const double w = weight_at(W, wdt, ncol == d ? (static_cast<size_t>(row / d) * d + col) * ncol + row % d : base + col);"),
-    ("qrnn: lag blocks reversed", "X[(static_cast<size_t>(j) * d + m) * nt + t] = x_at(t0 + t - j, m);",
-     "X[(static_cast<size_t>(k - 1 - j) * d + m) * nt + t] = x_at(t0 + t - j, m);"),
-    ("qrnn: looks ahead instead of back", "= x_at(t0 + t - j, m);", "= x_at(t0 + t + j < L ? t0 + t + j : L - 1, m);"),
+    ("qrnn: lag blocks reversed", "X[(static_cast<size_t>(j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m));",
+     "X[(static_cast<size_t>(k - 1 - j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m));"),
+    ("qrnn: looks ahead instead of back", "= operand(x_at(t0 + t - j, m));", "= operand(x_at(t0 + t + j < L ? t0 + t + j : L - 1, m));"),
+    ("rounding mode: default rounds", "int g_round_operand = 0;", "int g_round_operand = 1;"),
+    ("rounding mode: truncates instead of rounding to nearest even", "u = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;", "u = u & 0xFFFF0000u;"),
+    ("rounding mode: highway term rounded too", "const double xt = xin[(t0 + t) * d + i];", "const double xt = operand(xin[(t0 + t) * d + i]);"),
+    ("rounding mode: qrnn window not rounded", "= operand(x_at(t0 + t - j, m));", "= x_at(t0 + t - j, m);"),
     ("qrnn: candidate not squashed", "const double z = std::tanh(Uz[static_cast<size_t>(i) * nt + t] + bz);",
      "const double z = Uz[static_cast<size_t>(i) * nt + t] + bz;"),
     ("qrnn: output without tanh", "hout[(t0 + t) * d + i] = o * std::tanh(ci);", "hout[(t0 + t) * d + i] = o * ci;"),
@@ -60,6 +64,7 @@ BATTERY = [
     pins.test_bf16_weights_are_widened_exactly,
     pins.test_linear_projection_against_numpy,
     pins.test_future_inputs_do_not_change_past_outputs,
+    pins.test_operand_rounding_mode_rounds_only_the_matrix_operand,
 ]
 
 

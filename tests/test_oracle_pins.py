@@ -417,6 +417,73 @@ def test_bf16_weights_are_widened_exactly():
     assert np.abs(oracle.sru_forward(W, b, x, T=4)[0] - oracle.sru_forward(Wf, b, x, T=4)[0]).max() > 1e-6
 
 
+def _bf16_round_numpy(a):
+    """Nearest bfloat16, ties to even, of a float32 array, by integer arithmetic
+    on the bit patterns (written here, not taken from workloads or the oracle)."""
+    u = np.asarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    keep = u >> 16
+    rest = u & 0xFFFF
+    up = (rest > 0x8000) | ((rest == 0x8000) & ((keep & 1) == 1))
+    out = ((keep + up.astype(np.uint64)) << 16).astype(np.uint32)
+    return out.view(np.float32)
+
+
+def test_operand_rounding_mode_rounds_only_the_matrix_operand():
+    """oracle.set_operand_rounding(1): the block X of Eq. (4) enters the products
+    as bfloat16; the SRU highway term still uses the exact x_t.  Pinned by
+    (i) inputs that bfloat16 holds exactly: nothing changes, bit for bit;
+    (ii) 1 + 2^-9, a quarter of a bfloat16 step above 1: the gates are those of
+    x = 1 while the highway term keeps 1 + 2^-9; (iii) a random layer against
+    numpy products of explicitly rounded inputs."""
+    rng = _rng(77)
+    d, L = 6, 9
+    W, b = _rand_sru(rng, 1, d, 2.0)
+    try:
+        # (i)
+        x_exact = _bf16_round_numpy(rng.standard_normal((L, d)).astype(np.float32))
+        ref = oracle.sru_forward(W, b, x_exact, T=4)
+        oracle.set_operand_rounding(1)
+        got = oracle.sru_forward(W, b, x_exact, T=4)
+        np.testing.assert_array_equal(got[0], ref[0])
+        np.testing.assert_array_equal(got[1], ref[1])
+        # (ii) r = 1/2 exactly (W_r = 0, b_r = 0): h = tanh(c)/2 + x/2
+        W1 = [np.zeros((3, 1), np.float32)]
+        W1[0][0, 0] = 1.0                                   # candidate = x
+        xq = np.array([[1.0 + 2.0 ** -9]], np.float32)
+        h, c = oracle.sru_forward(W1, None, xq, T=1)        # f = 1/2: c = (rounded x) / 2
+        assert c[0, 0] == 0.5
+        assert h[0, 0] == 0.5 * math.tanh(0.5) + 0.5 * float(xq[0, 0])
+        oracle.set_operand_rounding(0)
+        h0, c0 = oracle.sru_forward(W1, None, xq, T=1)
+        assert c0[0, 0] == 0.5 * float(xq[0, 0])
+        # (iii)
+        x = rng.standard_normal((L, d)).astype(np.float32)
+        Xr = _bf16_round_numpy(x).astype(np.float64)
+        U = Xr @ W[0].astype(np.float64).T
+        f = _sigmoid(U[:, d:2 * d] + b[0][:d])
+        r = _sigmoid(U[:, 2 * d:] + b[0][d:])
+        cc = _recurrence_closed_form(f, U[:, :d], np.zeros(d))
+        h_expect = r * np.tanh(cc) + (1.0 - r) * x.astype(np.float64)
+        oracle.set_operand_rounding(1)
+        h, _ = oracle.sru_forward(W, b, x, T=3)
+        np.testing.assert_allclose(h, h_expect, rtol=1e-11, atol=1e-12)
+        # QRNN: window rows are rounded too
+        k = 2
+        Wq, bq = _rand_qrnn(rng, 1, d, k, 2.0)
+        xh0 = rng.standard_normal((1, k - 1, d)).astype(np.float32)
+        padded = np.concatenate([_bf16_round_numpy(xh0[0][::-1]).astype(np.float64), Xr], 0)
+        Wd = Wq[0].astype(np.float64)
+        U = np.zeros((L, 3 * d))
+        for j in range(k):
+            U += padded[k - 1 - j: k - 1 - j + L] @ Wd[:, j * d:(j + 1) * d].T
+        U += bq[0]
+        cc = _recurrence_closed_form(_sigmoid(U[:, d:2 * d]), np.tanh(U[:, :d]), np.zeros(d))
+        hq, _, _ = oracle.qrnn_forward(Wq, bq, x, xhist_init=xh0, T=4, k=k)
+        np.testing.assert_allclose(hq, _sigmoid(U[:, 2 * d:]) * np.tanh(cc), rtol=1e-11, atol=1e-12)
+    finally:
+        oracle.set_operand_rounding(0)
+
+
 def test_edge_cases():
     d = 4
     rng = _rng(55)
