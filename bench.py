@@ -197,6 +197,27 @@ def main():
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), **common}
 
+    # What a kernel that only reads reaches on this device, at the stage kernels' launch size: one probe
+    # launch per layer's weight matrix, layers in turn so that nothing stays in cache between launches.
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    for w in W:
+        ss.read_probe(w, sink)
+    torch.cuda.synchronize()
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(1, 64 // len(W))
+    p0.record()
+    for _ in range(reps):
+        for w in W:
+            ss.read_probe(w, sink)
+    p1.record()
+    torch.cuda.synchronize()
+    probe_s = p0.elapsed_time(p1) * 1e-3 / (reps * len(W))
+    probe_gbs = cfg.weight_bytes_per_layer() / probe_s / 1e9
+    roofline["read_probe_GBps"] = round(probe_gbs, 1)
+    roofline["read_probe_us_per_layer"] = round(probe_s * 1e6, 2)
+    if roofline["bound"] == "hbm":
+        roofline["frac_of_read_probe"] = round(roofline["achieved"] / probe_gbs, 4)
+
     cpu = None
     if not args.no_cpu:
         import oracle

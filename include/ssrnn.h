@@ -129,6 +129,13 @@ size_t ssrnn_packed_weight_bytes(int d, int k, int wdtype);
 int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype,
                        void* stream);
 
+/* Measurement aid: one kernel that reads buf[0, bytes) once with streaming
+ * 16-byte loads and keeps nothing: the rate a pure read reaches on this device,
+ * against which bench.py quotes the stage kernels next to the published HBM
+ * peak.  buf: device, 16-byte aligned, bytes a multiple of 16; sink: 4 bytes of
+ * device memory the kernel may write; enqueued on stream. */
+int ssrnn_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+
 /* Measurement aid: override one launch-geometry choice of the kernels for the
  * calls that follow, process-wide (not thread-safe; 0 restores the default).
  * Keys: "valu_F" (features per workgroup), "valu_nw" (wavefronts per

@@ -22,7 +22,7 @@ WEIGHTS_PACKED = 1 << 8
 # every symbol include/ssrnn.h declares
 EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",
            "qrnn_forward", "ssrnn_linear_forward", "ssrnn_packed_weight_bytes", "ssrnn_pack_weights",
-           "ssrnn_tune")
+           "ssrnn_read_probe", "ssrnn_tune")
 
 _lib = None
 
@@ -58,6 +58,8 @@ def load_library():
     lib.ssrnn_packed_weight_bytes.argtypes = [ip] * 3
     lib.ssrnn_pack_weights.restype = ip
     lib.ssrnn_pack_weights.argtypes = [vp, vp, ip, ip, ip, vp]
+    lib.ssrnn_read_probe.restype = ip
+    lib.ssrnn_read_probe.argtypes = [vp, sz, vp, vp]
     lib.ssrnn_tune.restype = ip
     lib.ssrnn_tune.argtypes = [ctypes.c_char_p, ip]
     _lib = lib
@@ -100,6 +102,13 @@ def pack_weights(W, stream=None):
     out = torch.empty_like(W)
     _check(lib.ssrnn_pack_weights(_p(W), _p(out), d, k, wdt, _stream_handle(stream)))
     return out
+
+
+def read_probe(buf, sink, stream=None) -> None:
+    """ssrnn_read_probe over a contiguous device tensor; sink: a device tensor of at least 4 bytes."""
+    _req(buf, "buf")
+    _req(sink, "sink")
+    _check(load_library().ssrnn_read_probe(_p(buf), buf.numel() * buf.element_size(), _p(sink), _stream_handle(stream)))
 
 
 def _wdtype(w) -> int:

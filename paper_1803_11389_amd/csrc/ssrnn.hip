@@ -196,6 +196,31 @@ __global__ void copy_history_kernel(const float* src, float* dst, long n) {
   if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
+// Measurement aid: every 16-byte chunk of a buffer is read once with streaming loads, four in flight per
+// thread, and folded into a word that is stored only if it takes one particular value (so the loads cannot
+// be dropped).  Its rate is what a kernel that does nothing but read reaches on the device at hand.
+typedef unsigned ssrnn_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(512) void read_probe_kernel(const ssrnn_u32x4* __restrict__ p, size_t n16, unsigned* sink) {
+  // every wave streams its own contiguous piece, 16 KiB (sixteen 1 KiB loads) in flight at a time
+  const size_t nwave = static_cast<size_t>(gridDim.x) * (blockDim.x >> 6);
+  const size_t wave = static_cast<size_t>(blockIdx.x) * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const size_t per_wave = (n16 + nwave - 1) / nwave;               // chunks per wave
+  const size_t begin = wave * per_wave;
+  const size_t end = begin + per_wave < n16 ? begin + per_wave : n16;
+  const unsigned lane = threadIdx.x & 63;
+  ssrnn_u32x4 acc = {0u, 0u, 0u, 0u};
+  size_t i = begin + lane;
+  for (; i + 15 * 64 < end; i += 16 * 64) {
+    ssrnn_u32x4 v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = __builtin_nontemporal_load(p + i + j * 64);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc ^= v[j];
+  }
+  for (; i < end; i += 64) acc ^= __builtin_nontemporal_load(p + i);
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u) *sink = acc[0];
+}
+
 // y[t][i] = sum_j P[i][j] * feat[t][j]; one thread per output, d_in is small.
 __global__ void linear_kernel(const float* __restrict__ P, const float* __restrict__ feat,
                               float* __restrict__ y, int d_out, int d_in, long L) {
@@ -576,6 +601,17 @@ int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype, 
   const long nchunks = 3L * d * row_chunks;
   hipLaunchKernelGGL(pack_weights_kernel, dim3((nchunks + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const uint4*>(W), static_cast<uint4*>(W_packed), d, row_chunks, nks_total, nchunks);
+  HIP_TRY(hipGetLastError());
+  return SSRNN_OK;
+}
+
+int ssrnn_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink) return fail(SSRNN_EINVAL, "ssrnn_read_probe: NULL pointer");
+  if (!aligned16(buf) || bytes % 16 != 0) return fail(SSRNN_EINVAL, "ssrnn_read_probe: buffer must be 16-byte aligned and a multiple of 16 bytes long");
+  if (bytes == 0) return SSRNN_OK;
+  const size_t n16 = bytes / 16;
+  hipLaunchKernelGGL(read_probe_kernel, dim3(256), dim3(512), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const ssrnn_u32x4*>(buf), n16, static_cast<unsigned*>(sink));
   HIP_TRY(hipGetLastError());
   return SSRNN_OK;
 }

@@ -79,6 +79,9 @@ def test_bad_arguments_fail_on_the_host(lib):
     assert ss.packed_weight_bytes(128, 2, ss.F32) == 3 * 128 * 256 * 4
     assert ss.packed_weight_bytes(1024, 1, ss.BF16) == 3 * 1024 * 1024 * 2
     assert ss.packed_weight_bytes(100, 1, ss.F32) == 0 and ss.packed_weight_bytes(32, 1, ss.BF16) == 0
+    assert lib.ssrnn_read_probe(None, 1024, fake, None) == 1
+    assert lib.ssrnn_read_probe(fake, 1000, fake, None) == 1                 # not a multiple of 16 bytes
+    assert lib.ssrnn_read_probe(ctypes.c_void_p(0x1004), 1024, fake, None) == 1
     assert lib.ssrnn_tune(b"no_such_key", 1) == 1
     assert lib.ssrnn_tune(None, 1) == 1
 

@@ -275,6 +275,18 @@ def _check_against_rounding_oracle(cell, W, b, x, c0, xh0, T, k, h, c):
     assert _rel_err(c, c_ref) <= BF16_MATCHED_TOL, _rel_err(c, c_ref)
 
 
+def test_read_probe_runs_and_leaves_its_input_alone():
+    import torch
+    import paper_1803_11389_amd as ss
+    buf = torch.arange(3 * 4096 + 4, dtype=torch.float32, device="cuda")      # 16-byte multiple, ragged for the waves
+    keep = buf.clone()
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    ss.read_probe(buf, sink)
+    ss.read_probe(buf[:4], sink)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep)
+
+
 def test_kernels_agree_with_each_other():
     """Same inputs through the generic, vector-ALU and matrix-core kernels."""
     W, b, x, c0 = _sru_inputs(1101, 2, 512, 24, scale=2.0)
