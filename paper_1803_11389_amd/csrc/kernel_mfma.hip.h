@@ -83,8 +83,44 @@ __device__ __forceinline__ void affine_scan(float& a, float& b) {
 // waves.  acc[g][n]: this wave's partial 16x16 tiles (gate g,
 // time tile n) in the MFMA result layout (lane = time n%16 + 16*(feature/4),
 // register = feature%4).
+// Operands of the epilogue that live in memory and do not depend on the stage's own product: this
+// thread's biases, the old cell state, and the SRU's own input for the first chunk of steps.  The
+// kernels fetch them before their main loop, so that the memory latency is not paid after it.
+template <int NT, int NW>
+struct MfmaEpilogueOperands {
+  static constexpr int EPT = (MfmaCfg<NT>::NTC * 256 + NW * 64 - 1) / (NW * 64);
+  float b0, b1, b2;     // biases of feature tid % 16
+  float c_old;          // s.c[f0 + tid] for tid < 16
+  float xh[EPT];        // SRU: x_t of this thread's (feature, step) pairs of chunk 0
+};
+
 template <int CELL, int NT, int NW>
-__device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, floatx4_t (&acc)[3][NT], float* part,
+__device__ __forceinline__ MfmaEpilogueOperands<NT, NW> mfma_epilogue_fetch(const Stage& s, int d, int f0) {
+  constexpr int NTH = NW * 64;
+  constexpr int CT = MfmaCfg<NT>::NTC * 16;
+  constexpr int CHUNK = MfmaCfg<NT>::NTC * 256;
+  MfmaEpilogueOperands<NT, NW> o;
+  const int tid = threadIdx.x;
+  o.b0 = o.b1 = o.b2 = 0.0f;
+  if (s.bias) {
+    const int i = f0 + (tid & 15);
+    if (CELL == CELL_SRU) { o.b1 = s.bias[i]; o.b2 = s.bias[d + i]; }
+    else { o.b0 = s.bias[i]; o.b1 = s.bias[d + i]; o.b2 = s.bias[2 * d + i]; }
+  }
+  o.c_old = (tid < MFMA_F) ? s.c[f0 + tid] : 0.0f;
+  const int tl = tid % CT;
+#pragma unroll
+  for (int it = 0; it < MfmaEpilogueOperands<NT, NW>::EPT; ++it) {
+    const int id = tid + it * NTH;
+    o.xh[it] = 0.0f;
+    if (CELL == CELL_SRU && id < CHUNK && tl < s.nt) o.xh[it] = s.xcur[static_cast<long>(tl) * s.ldx + f0 + id / CT];
+  }
+  return o;
+}
+
+template <int CELL, int NT, int NW>
+__device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, floatx4_t (&acc)[3][NT],
+                                              const MfmaEpilogueOperands<NT, NW>& ops, float* part,
                                               float* g_a, float* g_b, float* g_o, float* c_carry) {
   constexpr int NTH = NW * 64;
   constexpr int NTC = MfmaCfg<NT>::NTC;
@@ -104,14 +140,8 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
   // CT lanes, then h_t.  The state crosses chunks through c_carry.
   constexpr int CT = NTC * 16;
   constexpr int TS = CT + 1;                   // padded row of the transposed arrays
-  float b0 = 0.f, b1 = 0.f, b2 = 0.f;          // biases of the feature this thread handles in phase B
-  const int fe = tid & 15;
-  if (s.bias) {
-    const int i = f0 + fe;
-    if (CELL == CELL_SRU) { b1 = s.bias[i]; b2 = s.bias[d + i]; }
-    else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
-  }
-  if (tid < MFMA_F) c_carry[tid] = s.c[f0 + tid];
+  const float b0 = ops.b0, b1 = ops.b1, b2 = ops.b2;   // biases of the feature this thread handles in phase B
+  if (tid < MFMA_F) c_carry[tid] = ops.c_old;
   const int tl = tid % CT;                     // step within the chunk in phase C (NTH is a multiple of CT)
 
 #pragma unroll
@@ -125,7 +155,8 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
       for (int it = 0; it < EPT; ++it) {
         const int id = tid + it * NTH;
         xh[it] = 0.0f;
-        if (CELL == CELL_SRU && id < CHUNK && tl <= tlast) xh[it] = s.xcur[static_cast<long>(t) * s.ldx + f0 + id / CT];
+        if (n0 == 0) xh[it] = ops.xh[it];
+        else if (CELL == CELL_SRU && id < CHUNK && tl <= tlast) xh[it] = s.xcur[static_cast<long>(t) * s.ldx + f0 + id / CT];
       }
 #pragma unroll
       for (int g = 0; g < 3; ++g)

@@ -86,6 +86,9 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
   unsigned char* wr_at = tile + lrow * MFMA_LDS_ROW + lchunk;              // + q * 8 rows
   const unsigned char* rd_at = tile + li * MFMA_LDS_ROW + kg * 32;         // + gate * 16 rows + half * 16
 
+  // epilogue operands from memory, requested before the main loop (unused when the stage is split)
+  const MfmaEpilogueOperands<NT, NW> epi_ops = mfma_epilogue_fetch<CELL, NT, NW>(s, d, f0);
+
   floatx4_t acc[3][NT];
 #pragma unroll
   for (int g = 0; g < 3; ++g)
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(St
     mfma_store_partials<NT>(s, d, f0, ksp, acc, part);
     return;
   }
-  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
+  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, epi_ops, part, g_a, g_b, g_o, c_carry);
 }
 
 }  // namespace ssrnn

@@ -93,6 +93,9 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   const char* aptr = static_cast<const char*>(s.W) +
                      (static_cast<size_t>(ft) * nks_total + static_cast<size_t>(wcol / KSTEP)) * 6144 + lane * 16;
 
+  // epilogue operands from memory, requested before the main loop (unused when the stage is split)
+  const MfmaEpilogueOperands<NT, NW> epi_ops = mfma_epilogue_fetch<CELL, NT, NW>(s, d, f0);
+
   floatx4_t acc[3][NT];
 #pragma unroll
   for (int g = 0; g < 3; ++g)
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
     mfma_store_partials<NT>(s, d, f0, ksp, acc, part);
     return;
   }
-  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, part, g_a, g_b, g_o, c_carry);
+  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, epi_ops, part, g_a, g_b, g_o, c_carry);
 }
 
 }  // namespace ssrnn
