@@ -32,13 +32,16 @@ FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 (vector / matrix) peak
 # HBM bytes per stage launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
 # scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same workloads).
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", 1, "row-major"): 201_630_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
+    ("C4", 1, "row-major"): 201_620_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
     ("C4", 4, "row-major"): 202_140_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
-    ("C4", 16, "packed"): 205_140_000,      # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T16.txt
-    ("C4", 64, "row-major"): 214_530_000,   # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T64.txt
+    ("C4", 16, "row-major"): 205_150_000,   # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T16.txt
+    ("C4", 16, "packed"): 205_130_000,      # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T16.txt
+    ("C4", 64, "row-major"): 214_540_000,   # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T64.txt
+    ("C4", 64, "packed"): 214_630_000,      # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T64.txt
     ("C4", 128, "packed"): 227_280_000,     # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T128.txt
     ("C5", 16, "packed"): 203_490_000,      # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T16.txt
-    ("C5", 64, "packed"): 207_840_000,      # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T64.txt
+    ("C5", 64, "packed"): 207_870_000,      # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T64.txt
+    ("C5", 256, "packed"): 225_710_000,     # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T256.txt
     ("C5", 256, "row-major"): 225_320_000,  # profiles/stage_mfma_lds_kernel_bf16_C5_qrnn8_d4096_T256.txt
 }
 
