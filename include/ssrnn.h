@@ -45,14 +45,18 @@ typedef enum {
 
 typedef enum { SSRNN_F32 = 0, SSRNN_BF16 = 1 } ssrnn_wdtype;
 
-/* `flags` of *_forward: 0 picks the kernel by shape.  The other values force
- * one (tests and measurements use them); a forced choice that the shape does
- * not allow returns SSRNN_EUNSUPPORTED.  The schedule is always one kernel
- * launch per (block, layer) stage on the given stream; SSRNN_SCHED_STAGES
- * names it explicitly. */
+/* `flags` of *_forward: 0 picks the schedule and kernel by shape.  The other
+ * values force one (tests and measurements use them); a forced choice that the
+ * shape does not allow returns SSRNN_EUNSUPPORTED. */
 enum {
   SSRNN_SCHED_AUTO = 0,
   SSRNN_SCHED_STAGES = 1,     /* one kernel launch per (block, layer) stage                  */
+  SSRNN_SCHED_PERSISTENT = 2, /* one cooperative launch for the whole call; stages are
+                                 separated by a grid barrier and the next stage's first
+                                 weights are requested across it.  Stacked SRU with fp32
+                                 row-major weights, T <= 8, d a multiple of 256 with at
+                                 most one workgroup per compute unit.  Its waits are bounded:
+                                 see ssrnn_workspace_status.                                 */
   SSRNN_SCHED_MASK = 3,
   SSRNN_KERNEL_AUTO = 0,
   SSRNN_KERNEL_GENERIC = 1 << 4, /* any d, k, T: one wavefront per output feature            */
@@ -74,6 +78,12 @@ const char* ssrnn_last_error(void);
  * kernels, control words).  Host.  Returns 0 for arguments *_forward would reject.  The workspace must be
  * 256-byte aligned; its contents need not be initialised and are not preserved. */
 size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype);
+
+/* After a *_forward call that ran the persistent schedule: synchronizes the
+ * stream and reports whether one of the kernel's bounded waits ran out
+ * (SSRNN_EDEVICE; the outputs of that call are then incomplete) or not
+ * (SSRNN_OK).  workspace: the one given to that call. */
+int ssrnn_workspace_status(const void* workspace, void* stream);
 
 /* Stacked SRU forward, Eq. 2 per layer, T steps per weight pass (Section 3).
  *   xh = W x_t;  f = sigma(W_f x_t + b_f);  r = sigma(W_r x_t + b_r);
@@ -140,8 +150,10 @@ int ssrnn_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
  * calls that follow, process-wide (not thread-safe; 0 restores the default).
  * Keys: "valu_F" (features per workgroup), "valu_nw" (wavefronts per
  * workgroup), "valu_nv" (column chunks per lane), "ksplit" (1: never split a narrow layer's columns over
- * several workgroups; 2, 4, 8: at most that many parts).  A value the shape
- * does not allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
+ * several workgroups; 2, 4, 8: at most that many parts), "spin_limit"
+ * (ticks of the 100 MHz wall clock that one grid-barrier wait of the
+ * persistent schedule may take before the kernel gives up; default one
+ * second).  A value the shape does not allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
 int ssrnn_tune(const char* key, int value);
 
 #ifdef __cplusplus

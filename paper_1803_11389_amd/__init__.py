@@ -15,14 +15,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssrnn.so")
 
 F32, BF16 = 0, 1
-SCHED_AUTO, SCHED_STAGES = 0, 1
+SCHED_AUTO, SCHED_STAGES, SCHED_PERSISTENT = 0, 1, 2
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_VALU, KERNEL_MFMA = 0, 1 << 4, 2 << 4, 3 << 4
 WEIGHTS_PACKED = 1 << 8
 
 # every symbol include/ssrnn.h declares
 EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",
            "qrnn_forward", "ssrnn_linear_forward", "ssrnn_packed_weight_bytes", "ssrnn_pack_weights",
-           "ssrnn_read_probe", "ssrnn_tune")
+           "ssrnn_read_probe", "ssrnn_workspace_status", "ssrnn_tune")
 
 _lib = None
 
@@ -60,6 +60,8 @@ def load_library():
     lib.ssrnn_pack_weights.argtypes = [vp, vp, ip, ip, ip, vp]
     lib.ssrnn_read_probe.restype = ip
     lib.ssrnn_read_probe.argtypes = [vp, sz, vp, vp]
+    lib.ssrnn_workspace_status.restype = ip
+    lib.ssrnn_workspace_status.argtypes = [vp, vp]
     lib.ssrnn_tune.restype = ip
     lib.ssrnn_tune.argtypes = [ctypes.c_char_p, ip]
     _lib = lib
@@ -102,6 +104,12 @@ def pack_weights(W, stream=None):
     out = torch.empty_like(W)
     _check(lib.ssrnn_pack_weights(_p(W), _p(out), d, k, wdt, _stream_handle(stream)))
     return out
+
+
+def workspace_status(workspace: "Workspace", stream=None) -> None:
+    """ssrnn_workspace_status: synchronizes the stream; raises SsrnnError if a
+    bounded wait of the persistent schedule ran out in the last call."""
+    _check(load_library().ssrnn_workspace_status(workspace.buf.data_ptr(), _stream_handle(stream)))
 
 
 def read_probe(buf, sink, stream=None) -> None:

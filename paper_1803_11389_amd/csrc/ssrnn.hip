@@ -22,6 +22,7 @@
 #include "kernel_mfma.hip.h"
 #include "kernel_mfma_lds.hip.h"
 #include "kernel_mfma_packed.hip.h"
+#include "kernel_valu_persistent.hip.h"
 
 using namespace ssrnn;
 
@@ -253,6 +254,7 @@ struct Plan {
 };
 
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
+long long g_tune_spin_limit = 0;   // 0 = default (one second); otherwise wall-clock ticks a grid-barrier wait may take
 int g_tune_ksplit = 0;     // 0 = default, 1 = never split, 2/4/8 = at most that many parts
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
@@ -352,6 +354,55 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   return true;
 }
 
+// ---- persistent schedule (vector-ALU kernel, stacked SRU) -----------------------
+constexpr size_t WS_CTR_OFFSET = 0, WS_ABORT_OFFSET = 64;   // control words at the start of the workspace
+
+__global__ void zero_control_kernel(unsigned* ctr, unsigned* abort_flag) {
+  if (threadIdx.x == 0) { *ctr = 0u; *abort_flag = 0u; }
+}
+
+// The whole call as one cooperative launch.  Returns SSRNN_EUNSUPPORTED (without launching) when the
+// shape or the device does not allow it, so that the caller can take the per-stage schedule instead.
+int launch_persistent(const Plan& p, const void* const* W, const float* const* bias, const float* x, const float* c_init,
+                      float* h, float* c_final, void* workspace, const WorkspaceLayout& wl, hipStream_t st) {
+  const int fg = p.tt >= 16 ? 1 : 2;
+  const int nitems = p.F / fg;
+  if (p.cell != CELL_SRU || p.k != 1 || p.npass != 1 || p.tt > 8 || p.n_layers > PERSIST_MAX_LAYERS || nitems < 2 || nitems % 2 != 0 ||
+      p.F * p.tt > p.nw * 64)
+    return fail(SSRNN_EUNSUPPORTED, "persistent schedule: stacked SRU with T <= 8, one column pass and an even number of feature groups per workgroup");
+  PersistArgs a{};
+  for (int l = 0; l < p.n_layers; ++l) {
+    a.W[l] = static_cast<const float*>(W[l]);
+    a.bias[l] = (bias && bias[l]) ? bias[l] : nullptr;
+  }
+  a.x = x; a.c_init = c_init; a.h = h; a.c_final = c_final;
+  a.act = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.act_offset);
+  a.act_stride = wl.act_stride / sizeof(float);
+  a.ctr = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + WS_CTR_OFFSET);
+  a.abort_flag = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + WS_ABORT_OFFSET);
+  a.spin_limit = g_tune_spin_limit > 0 ? g_tune_spin_limit : 100000000LL;   // default: one second of the 100 MHz wall clock
+  a.L = p.L; a.n_layers = p.n_layers; a.d = p.d; a.T = p.T; a.F = p.F; a.ld = wl.ld;
+  const size_t lds = (static_cast<size_t>(p.nw) * 3 * p.F * p.tt + static_cast<size_t>(p.n_layers) * p.F + 1) * sizeof(float);
+  const void* fn = nullptr;
+#define SSRNN_PERSIST_CASE(TT_, NV_) \
+  if (p.tt == TT_ && p.nv == NV_) fn = reinterpret_cast<const void*>(&persistent_sru_kernel<TT_, NV_>);
+  SSRNN_PERSIST_CASE(1, 1) SSRNN_PERSIST_CASE(2, 1) SSRNN_PERSIST_CASE(4, 1) SSRNN_PERSIST_CASE(8, 1)
+  SSRNN_PERSIST_CASE(1, 2) SSRNN_PERSIST_CASE(2, 2) SSRNN_PERSIST_CASE(4, 2) SSRNN_PERSIST_CASE(8, 2)
+#undef SSRNN_PERSIST_CASE
+  if (!fn) return fail(SSRNN_EUNSUPPORTED, "persistent schedule: no kernel for T tile %d, NV %d", p.tt, p.nv);
+  // every workgroup must be resident at once: ask the runtime how many fit
+  int dev = 0, ncu = 0, per_cu = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, p.nw * 64, lds));
+  if (static_cast<long>(per_cu) * ncu < p.grid)
+    return fail(SSRNN_EUNSUPPORTED, "persistent schedule: %d workgroups do not fit the device at once", p.grid);
+  hipLaunchKernelGGL(zero_control_kernel, dim3(1), dim3(64), 0, st, a.ctr, a.abort_flag);
+  void* args[] = {&a};
+  HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(p.grid), dim3(p.nw * 64), args, static_cast<unsigned>(lds), st));
+  return SSRNN_OK;
+}
+
 template <int CELL>
 int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
   const dim3 grid(p.d / MFMA_F * p.ksplit);
@@ -417,7 +468,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   const int sched = flags & SSRNN_SCHED_MASK;
   const int kforce = flags & SSRNN_KERNEL_MASK;
   const bool packed = (flags & SSRNN_WEIGHTS_PACKED) != 0;
-  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED)) != 0 || sched > SSRNN_SCHED_STAGES)
+  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED)) != 0 || sched > SSRNN_SCHED_PERSISTENT)
     return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
   if (packed && kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_MFMA)
     return fail(SSRNN_EINVAL, "%s: packed weights are read by the matrix-core kernel only", name);
@@ -454,6 +505,15 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   // (fp32, T <= 16), except that from T = 5 on a layer wide enough to give the matrix-core kernel one
   // workgroup per CU (d >= 4096) goes there (measured at d = 4096: 34.8 us per stage against 36.3 at
   // T = 8 and 40.0 at T = 16); the matrix-core kernel for everything else it takes; the generic kernel last.
+  if (sched == SSRNN_SCHED_PERSISTENT) {
+    if (packed || (kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_VALU))
+      return fail(SSRNN_EUNSUPPORTED, "%s: the persistent schedule runs the vector-ALU kernel on row-major weights", name);
+    if (!plan_valu(p, W, x, xhist_init, workspace))
+      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 16, d %% 256 == 0 and 16-byte aligned buffers", name);
+    p.kind = K_VALU;
+    // c_final already holds the initial state (init_state_kernel above)
+    return launch_persistent(p, W, bias, x, c_final, h, c_final, workspace, wl, st);
+  }
   bool valu_ok = false;
   if (!packed && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU)) {
     valu_ok = plan_valu(p, W, x, xhist_init, workspace);
@@ -605,6 +665,15 @@ int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype, 
   return SSRNN_OK;
 }
 
+int ssrnn_workspace_status(const void* workspace, void* stream) {
+  if (!workspace) return fail(SSRNN_EINVAL, "ssrnn_workspace_status: workspace is NULL");
+  unsigned flag = 0;
+  HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  HIP_TRY(hipMemcpy(&flag, static_cast<const char*>(workspace) + WS_ABORT_OFFSET, sizeof flag, hipMemcpyDeviceToHost));
+  if (flag != 0) return fail(SSRNN_EDEVICE, "a grid barrier of the persistent schedule timed out; the outputs of that call are incomplete");
+  return SSRNN_OK;
+}
+
 int ssrnn_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf || !sink) return fail(SSRNN_EINVAL, "ssrnn_read_probe: NULL pointer");
   if (!aligned16(buf) || bytes % 16 != 0) return fail(SSRNN_EINVAL, "ssrnn_read_probe: buffer must be 16-byte aligned and a multiple of 16 bytes long");
@@ -622,6 +691,7 @@ int ssrnn_tune(const char* key, int value) {
   else if (!strcmp(key, "valu_nw")) g_tune_valu_nw = value;
   else if (!strcmp(key, "valu_nv")) g_tune_valu_nv = value;
   else if (!strcmp(key, "ksplit")) g_tune_ksplit = value;
+  else if (!strcmp(key, "spin_limit")) g_tune_spin_limit = value;
   else return fail(SSRNN_EINVAL, "ssrnn_tune: unknown key %s", key);
   return SSRNN_OK;
 }
