@@ -251,6 +251,7 @@ struct Plan {
   int ksplit;          // workgroups per feature tile (columns split), 1 unless the layer is narrow
   int mfma_nw;         // waves per workgroup of the matrix-core kernel
   bool packed;         // weights are in the matrix-core fragment order (ssrnn_pack_weights)
+  bool one_wg_per_cu;  // vector-ALU geometry for a launch whose workgroups must all be resident
 };
 
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
@@ -273,9 +274,13 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
     if (qq % w == 0) p.nw = w;
   if (g_tune_valu_nw >= 1 && g_tune_valu_nw <= VALU_MAX_WAVES && qq % g_tune_valu_nw == 0) p.nw = g_tune_valu_nw;
   p.npass = qq / p.nw;
+  // Features per workgroup: the smallest even count that gives at most one workgroup per CU; wide layers
+  // (d >= 4096) with short blocks take two workgroups per CU instead, which lets the hardware even out
+  // the workgroups' unequal memory rates (measured at d = 4096: 32.8 against 33.5 us per stage at T = 4).
+  const int wg_target = (p.d >= 4096 && p.tt <= 8 && !p.one_wg_per_cu) ? 512 : 256;
   int F = 0;
   for (int f = fg; f <= 64; f += fg)
-    if (p.d % f == 0 && f * 256 >= p.d) { F = f; break; }
+    if (p.d % f == 0 && f * wg_target >= p.d) { F = f; break; }
   if (F == 0) F = fg;
   if (g_tune_valu_F > 0 && g_tune_valu_F % fg == 0 && g_tune_valu_F <= 64 && p.d % g_tune_valu_F == 0) F = g_tune_valu_F;
   if (p.d % F != 0) return false;
@@ -508,6 +513,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   if (sched == SSRNN_SCHED_PERSISTENT) {
     if (packed || (kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_VALU))
       return fail(SSRNN_EUNSUPPORTED, "%s: the persistent schedule runs the vector-ALU kernel on row-major weights", name);
+    p.one_wg_per_cu = true;
     if (!plan_valu(p, W, x, xhist_init, workspace))
       return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 16, d %% 256 == 0 and 16-byte aligned buffers", name);
     p.kind = K_VALU;
