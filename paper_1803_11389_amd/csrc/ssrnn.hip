@@ -275,9 +275,11 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
   if (g_tune_valu_nw >= 1 && g_tune_valu_nw <= VALU_MAX_WAVES && qq % g_tune_valu_nw == 0) p.nw = g_tune_valu_nw;
   p.npass = qq / p.nw;
   // Features per workgroup: the smallest even count that gives at most one workgroup per CU; wide layers
-  // (d >= 4096) with short blocks take two workgroups per CU instead, which lets the hardware even out
-  // the workgroups' unequal memory rates (measured at d = 4096: 32.8 against 33.5 us per stage at T = 4).
-  const int wg_target = (p.d >= 4096 && p.tt <= 8 && !p.one_wg_per_cu) ? 512 : 256;
+  // (d >= 4096) with short blocks take more, smaller workgroups instead, which lets the hardware's
+  // dispatcher even out the workgroups' unequal memory rates (measured at d = 4096, us per stage: T = 4,
+  // 512 workgroups 32.8 against 33.5 with 256; T = 1, 2048 workgroups of one work item 31.5 against 32.5
+  // with 512; from T = 3 on the single-item workgroups lose, 39 us).
+  const int wg_target = (p.d < 4096 || p.tt > 8 || p.one_wg_per_cu) ? 256 : (p.tt <= 2 ? 2048 : 512);
   int F = 0;
   for (int f = fg; f <= 64; f += fg)
     if (p.d % f == 0 && f * wg_target >= p.d) { F = f; break; }
