@@ -70,6 +70,12 @@ def test_config5_qrnn8_d4096_bf16_prefix():
     _run_config(wl.CONFIGS[4], 272, 2e-2, True)
 
 
+def test_extra_workload_sru8_d4096_bf16_prefix():
+    """Configuration 4 with bf16 weights (the small-T, low-precision-weight point bench.py can also time):
+    every block size, both weight layouts, against the oracle on the same bf16 weights."""
+    _run_config(wl.by_name("X1"), 100, 2e-2, True)
+
+
 def test_config5_first_layer_against_the_operand_rounding_oracle():
     """One layer of C5 at full width, every block size and both weight layouts,
     against the oracle run that rounds the matrix operand X to bfloat16 exactly
