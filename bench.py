@@ -69,7 +69,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this path is a single-stream, single-GPU kernel; run with --gpus 1 "
-              "(sharding across GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+              "(sharding across GPUs is not built)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
