@@ -60,7 +60,7 @@ enum {
   SSRNN_SCHED_MASK = 3,
   SSRNN_KERNEL_AUTO = 0,
   SSRNN_KERNEL_GENERIC = 1 << 4, /* any d, k, T: one wavefront per output feature            */
-  SSRNN_KERNEL_VALU = 2 << 4,    /* bandwidth kernel, FMA on the vector ALU                  */
+  SSRNN_KERNEL_VALU = 2 << 4,    /* bandwidth kernel, FMA on the vector ALU (short blocks)   */
   SSRNN_KERNEL_MFMA = 3 << 4,    /* matrix-core kernel                                       */
   SSRNN_KERNEL_MASK = 7 << 4,
   SSRNN_WEIGHTS_PACKED = 1 << 8  /* every W[l] was written by ssrnn_pack_weights                */

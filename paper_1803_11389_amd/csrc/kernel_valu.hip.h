@@ -119,9 +119,16 @@ __device__ __forceinline__ int butterfly_index(int lane) {
 
 // MP = false: one pass covers all k*d columns (npass == 1), X stays in registers.
 // MP = true: several passes; X is re-read (from cache) per feature group and pass.
-template <int CELL, int TT, int NV, bool MP>
+// WT: weights are fp32 (a 16-byte load = 4 columns per lane, 256 per wave) or
+// bfloat16 bit patterns (8 columns per lane, 512 per wave; widened to fp32 in
+// registers, so that the input block and every product stay fp32).
+template <int CELL, int WT, int TT, int NV, bool MP>
 __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s, int d, int k, int F, int npass_arg) {
   const int npass = MP ? npass_arg : 1;
+  constexpr int CPL = (WT == W_BF16) ? 8 : 4;     // columns per lane per 16-byte load
+  constexpr int CHW = 64 * CPL;                   // columns per wave-wide load
+  constexpr int XQ = CPL / 4;                     // float4 pieces of X per lane and chunk
+  constexpr int ESIZE = (WT == W_BF16) ? 2 : 4;
   constexpr int FG = valu_fg(TT);
   constexpr int VB = FG * TT;                // values per gate entering the butterfly
   extern __shared__ float part[];            // [NW][3][F][TT]
@@ -130,9 +137,9 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
   const int NW = blockDim.x >> 6;
   const int ncol = k * d;
   const int f0 = blockIdx.x * F;
-  const int passw = NW * NV * 256;
-  const int lanecol = wave * NV * 256 + lane * 4;
-  const float* __restrict__ Wf = static_cast<const float*>(s.W);
+  const int passw = NW * NV * CHW;
+  const int lanecol = wave * NV * CHW + lane * CPL;
+  const char* __restrict__ Wb = static_cast<const char*>(s.W);
 
   // Global operands of the epilogue (old state, bias, the SRU's own input) are
   // fetched now, so their latency hides behind the weight stream instead of
@@ -150,41 +157,40 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
     if (CELL == CELL_SRU && t < s.nt) ep_x = s.xcur[static_cast<long>(t) * s.ldx + i];
   }
 
-  float4 xr[NV][TT];
+  float4 xr[NV][TT][XQ];
   auto load_x = [&](int p) {
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      const int col = p * passw + lanecol + v * 256;
+      const int col = p * passw + lanecol + v * CHW;
       const int j = col / d;
       const int m = col - j * d;
 #pragma unroll
       for (int t = 0; t < TT; ++t)
-        xr[v][t] = (t < s.nt) ? x_at4(s, d, t - j, m) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int q = 0; q < XQ; ++q)
+          xr[v][t][q] = (t < s.nt) ? x_at4(s, d, t - j, m + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
 
   // work item it = (feature group, pass): FG features x one pass of columns
   const int nitems = (F / FG) * npass;
-  auto load_w = [&](float4 (&w)[3][FG][NV], int it) {
+  auto load_w = [&](ssrnn_f32x4 (&w)[3][FG][NV], int it) {
     const int g = (it / npass) * FG;
     const int p = it - (it / npass) * npass;
 #pragma unroll
     for (int gate = 0; gate < 3; ++gate)
 #pragma unroll
       for (int f = 0; f < FG; ++f) {
-        const float* row = Wf + static_cast<size_t>(gate * d + f0 + g + f) * ncol + p * passw + lanecol;
+        const char* row = Wb + (static_cast<size_t>(gate * d + f0 + g + f) * ncol + p * passw + lanecol) * ESIZE;
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-          const ssrnn_f32x4 t4 = load_stream16(row + v * 256);
-          w[gate][f][v] = make_float4(t4[0], t4[1], t4[2], t4[3]);
-        }
+        for (int v = 0; v < NV; ++v) w[gate][f][v] = load_stream16(row + static_cast<size_t>(v) * CHW * ESIZE);
       }
   };
 
   float acc[3][VB];
   const int idx = butterfly_index<VB>(lane);
   const bool writer = (lane & (64 / VB - 1)) == 0;
-  auto process = [&](const float4 (&w)[3][FG][NV], int it) {
+  auto process = [&](const ssrnn_f32x4 (&w)[3][FG][NV], int it) {
     const int gi = it / npass;
     const int p = it - gi * npass;
     if (MP) load_x(p);
@@ -199,10 +205,25 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
 #pragma unroll
       for (int f = 0; f < FG; ++f)
 #pragma unroll
-        for (int v = 0; v < NV; ++v)
+        for (int v = 0; v < NV; ++v) {
+          float4 wq[XQ];
+          if constexpr (WT == W_BF16) {
+            // a 32-bit word holds two bfloat16 weights: the lower half is the column at the lower address
+            const uint32_t u0 = __float_as_uint(w[gate][f][v][0]), u1 = __float_as_uint(w[gate][f][v][1]);
+            const uint32_t u2 = __float_as_uint(w[gate][f][v][2]), u3 = __float_as_uint(w[gate][f][v][3]);
+            wq[0] = make_float4(__uint_as_float(u0 << 16), __uint_as_float(u0 & 0xFFFF0000u),
+                                __uint_as_float(u1 << 16), __uint_as_float(u1 & 0xFFFF0000u));
+            wq[XQ - 1] = make_float4(__uint_as_float(u2 << 16), __uint_as_float(u2 & 0xFFFF0000u),
+                                     __uint_as_float(u3 << 16), __uint_as_float(u3 & 0xFFFF0000u));
+          } else {
+            wq[0] = make_float4(w[gate][f][v][0], w[gate][f][v][1], w[gate][f][v][2], w[gate][f][v][3]);
+          }
 #pragma unroll
           for (int t = 0; t < TT; ++t)
-            acc[gate][f * TT + t] = dot4(w[gate][f][v], xr[v][t], acc[gate][f * TT + t]);
+#pragma unroll
+            for (int q = 0; q < XQ; ++q)
+              acc[gate][f * TT + t] = dot4(wq[q], xr[v][t][q], acc[gate][f * TT + t]);
+        }
     if (!MP || p == npass - 1) {
 #pragma unroll
       for (int gate = 0; gate < 3; ++gate) {
@@ -212,7 +233,7 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
     }
   };
 
-  float4 wa[3][FG][NV], wb[3][FG][NV];
+  ssrnn_f32x4 wa[3][FG][NV], wb[3][FG][NV];
   load_w(wa, 0);
   if (!MP) load_x(0);
   int it = 0;

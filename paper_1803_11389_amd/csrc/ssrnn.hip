@@ -259,13 +259,15 @@ long long g_tune_spin_limit = 0;   // 0 = default (one second); otherwise wall-c
 int g_tune_ksplit = 0;     // 0 = default, 1 = never split, 2/4/8 = at most that many parts
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
-  if (p.wdt != SSRNN_F32 || p.T > VALU_MAX_T || p.d % 256 != 0) return false;
+  // a wave-wide 16-byte load covers 256 fp32 or 512 bf16 columns; bf16 weights are taken up to T = 8
+  const int chw = p.wdt == SSRNN_BF16 ? 512 : 256;
+  if (p.T > (p.wdt == SSRNN_BF16 ? 8 : VALU_MAX_T) || p.d % chw != 0) return false;
   if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
   for (int l = 0; l < p.n_layers; ++l)
     if (!aligned16(W[l])) return false;
   p.tt = p.T <= 1 ? 1 : p.T <= 2 ? 2 : p.T <= 4 ? 4 : p.T <= 8 ? 8 : 16;
   const int fg = 2;   // F is kept even for every T so that one workgroup shape serves all block sizes
-  const int q = p.k * p.d / 256;
+  const int q = p.k * p.d / chw;
   p.nv = (q % 2 == 0 && q >= 16) ? 2 : 1;
   if (g_tune_valu_nv == 1 || (g_tune_valu_nv == 2 && q % 2 == 0)) p.nv = g_tune_valu_nv;
   const int qq = q / p.nv;
@@ -279,7 +281,8 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
   // dispatcher even out the workgroups' unequal memory rates (measured at d = 4096, us per stage: T = 4,
   // 512 workgroups 32.8 against 33.5 with 256; T = 1, 2048 workgroups of one work item 31.5 against 32.5
   // with 512; from T = 3 on the single-item workgroups lose, 39 us).
-  const int wg_target = (p.d < 4096 || p.tt > 8 || p.one_wg_per_cu) ? 256 : (p.tt <= 2 ? 2048 : 512);
+  int wg_target = (p.d < 4096 || p.tt > 8 || p.one_wg_per_cu) ? 256 : (p.tt <= 2 ? 2048 : 512);
+  if (p.wdt == SSRNN_BF16 && wg_target > 256) wg_target /= 2;   // half the bytes per feature: twice the features
   int F = 0;
   for (int f = fg; f <= 64; f += fg)
     if (p.d % f == 0 && f * wg_target >= p.d) { F = f; break; }
@@ -297,11 +300,21 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
   const size_t lds = static_cast<size_t>(p.nw) * 3 * p.F * p.tt * sizeof(float);
 #define SSRNN_VALU_CASE(TT_, NV_)                                                          \
   if (p.tt == TT_ && p.nv == NV_) {                                                        \
-    if (p.npass == 1)                                                                      \
-      hipLaunchKernelGGL((stage_valu_kernel<CELL, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
-    else                                                                                   \
-      hipLaunchKernelGGL((stage_valu_kernel<CELL, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
-    return SSRNN_OK;                                                                       \
+    if (p.wdt == SSRNN_BF16) {                                                             \
+      if constexpr (TT_ <= 8) {                                                            \
+        if (p.npass == 1)                                                                  \
+          hipLaunchKernelGGL((stage_valu_kernel<CELL, W_BF16, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
+        else                                                                               \
+          hipLaunchKernelGGL((stage_valu_kernel<CELL, W_BF16, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
+        return SSRNN_OK;                                                                   \
+      }                                                                                    \
+    } else {                                                                               \
+      if (p.npass == 1)                                                                    \
+        hipLaunchKernelGGL((stage_valu_kernel<CELL, W_F32, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
+      else                                                                                 \
+        hipLaunchKernelGGL((stage_valu_kernel<CELL, W_F32, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
+      return SSRNN_OK;                                                                     \
+    }                                                                                      \
   }
   SSRNN_VALU_CASE(1, 1) SSRNN_VALU_CASE(2, 1) SSRNN_VALU_CASE(4, 1) SSRNN_VALU_CASE(8, 1) SSRNN_VALU_CASE(16, 1)
   SSRNN_VALU_CASE(1, 2) SSRNN_VALU_CASE(2, 2) SSRNN_VALU_CASE(4, 2) SSRNN_VALU_CASE(8, 2) SSRNN_VALU_CASE(16, 2)
@@ -374,9 +387,9 @@ int launch_persistent(const Plan& p, const void* const* W, const float* const* b
                       float* h, float* c_final, void* workspace, const WorkspaceLayout& wl, hipStream_t st) {
   const int fg = p.tt >= 16 ? 1 : 2;
   const int nitems = p.F / fg;
-  if (p.cell != CELL_SRU || p.k != 1 || p.npass != 1 || p.tt > 8 || p.n_layers > PERSIST_MAX_LAYERS || nitems < 2 || nitems % 2 != 0 ||
+  if (p.cell != CELL_SRU || p.wdt != SSRNN_F32 || p.k != 1 || p.npass != 1 || p.tt > 8 || p.n_layers > PERSIST_MAX_LAYERS || nitems < 2 || nitems % 2 != 0 ||
       p.F * p.tt > p.nw * 64)
-    return fail(SSRNN_EUNSUPPORTED, "persistent schedule: stacked SRU with T <= 8, one column pass and an even number of feature groups per workgroup");
+    return fail(SSRNN_EUNSUPPORTED, "persistent schedule: stacked SRU with fp32 weights, T <= 8, one column pass and an even number of feature groups per workgroup");
   PersistArgs a{};
   for (int l = 0; l < p.n_layers; ++l) {
     a.W[l] = static_cast<const float*>(W[l]);
@@ -517,7 +530,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       return fail(SSRNN_EUNSUPPORTED, "%s: the persistent schedule runs the vector-ALU kernel on row-major weights", name);
     p.one_wg_per_cu = true;
     if (!plan_valu(p, W, x, xhist_init, workspace))
-      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 16, d %% 256 == 0 and 16-byte aligned buffers", name);
+      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs T <= 16 and d %% 256 == 0 (fp32 weights) or T <= 8 and d %% 512 == 0 (bf16 weights), and 16-byte aligned buffers", name);
     p.kind = K_VALU;
     // c_final already holds the initial state (init_state_kernel above)
     return launch_persistent(p, W, bias, x, c_final, h, c_final, workspace, wl, st);
@@ -526,9 +539,12 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   if (!packed && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU)) {
     valu_ok = plan_valu(p, W, x, xhist_init, workspace);
     if (!valu_ok && kforce == SSRNN_KERNEL_VALU)
-      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs fp32 weights, T <= 16, d %% 256 == 0 and 16-byte aligned buffers", name);
+      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs T <= 16 and d %% 256 == 0 (fp32 weights) or T <= 8 and d %% 512 == 0 (bf16 weights), and 16-byte aligned buffers", name);
   }
-  const bool prefer_mfma = kforce == SSRNN_KERNEL_AUTO && T > 4 && d / MFMA_F >= 256;
+  // bf16 weights: the vector-ALU kernel (weights widened in registers, input block exact) wins up to T = 2
+  // (17.1 against 18.4 us per stage at d = 4096, T = 1); beyond that its conversions and FMAs no longer hide
+  const bool prefer_mfma = kforce == SSRNN_KERNEL_AUTO &&
+                           (wdt == SSRNN_BF16 ? T > 2 : (T > 4 && d / MFMA_F >= 256));
   if (valu_ok && !prefer_mfma) p.kind = K_VALU;
   if (p.kind == K_GENERIC && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_MFMA)) {
     // the matrix-core kernels accumulate a bounded number of steps per weight pass: longer blocks are cut

@@ -139,6 +139,26 @@ def test_qrnn_valu_kernel(d, n_layers, L, T, k):
     _check_qrnn(W, b, x, c0, xh0, T, k, VALU | STAGES)
 
 
+@pytest.mark.parametrize("cell,d,n_layers,L,T,k", [
+    ("sru", 512, 2, 23, 4, 1), ("sru", 1024, 3, 30, 1, 1), ("sru", 4096, 1, 9, 2, 1), ("sru", 2048, 2, 21, 8, 1),
+    ("qrnn", 512, 2, 26, 4, 2), ("qrnn", 1024, 2, 17, 3, 3), ("qrnn", 4096, 1, 10, 4, 2), ("sru", 8192, 1, 6, 4, 1),
+])
+def test_valu_kernel_bf16_weights(cell, d, n_layers, L, T, k):
+    """bf16 weights on the vector-ALU kernel: the weights are widened in registers
+    and the input block stays fp32, so the result meets the fp32 bar against the
+    oracle on the same bf16 weights."""
+    print(f"valu bf16 {cell} d={d} layers={n_layers} L={L} T={T} k={k}", flush=True)
+    if cell == "sru":
+        W, b, x, c0 = _sru_inputs(1300 + d + T, n_layers, d, L, bf16=True)
+        h_ref, c_ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
+        h, c = gpu_sru(W, b, x, c0, T=T, flags=VALU)
+    else:
+        W, b, x, c0, xh0 = _qrnn_inputs(1300 + d + T + k, n_layers, d, L, k, bf16=True)
+        h_ref, c_ref, _ = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
+        h, c, _ = gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, flags=VALU)
+    assert max_abs(h, h_ref) <= TOL and max_abs(c, c_ref) <= TOL, (max_abs(h, h_ref), max_abs(c, c_ref))
+
+
 def test_valu_kernel_refuses_what_it_cannot_take():
     import paper_1803_11389_amd as ss
     W, b, x, c0 = _sru_inputs(601, 1, 100, 4)
