@@ -1,4 +1,5 @@
-// Bandwidth kernel for short blocks (T <= 16, fp32 weights): the skinny product
+// Bandwidth kernel for short blocks (T <= 16 with fp32 weights, T <= 8 with
+// bfloat16 weights, which are widened to fp32 in registers): the skinny product
 // U = W * X of Eq. 4 (arXiv 1803.11389) on the vector ALU, with the gates and
 // the recurrence of Eq. 2 / Eq. 3 fused behind it.
 //
@@ -7,9 +8,9 @@
 //     2d+i of W for those features; it is the only reader of those rows, so
 //     every weight leaves HBM exactly once per block;
 //   - the NW wavefronts of the workgroup split the k*d columns: in pass p,
-//     wave w covers NV chunks of 256 consecutive columns, lane l four
-//     consecutive columns of each chunk, so one wave-wide load instruction
-//     reads 1 KiB of one row contiguously (global_load_dwordx4);
+//     wave w covers NV chunks of 256 (fp32) or 512 (bf16) consecutive columns,
+//     lane l 16 consecutive bytes of each chunk, so one wave-wide load
+//     instruction reads 1 KiB of one row contiguously (global_load_dwordx4);
 //   - the wave's slice of the input block X (4*NV columns x TT steps per lane)
 //     stays in registers for the whole stage when one pass covers all columns;
 //   - weights are double-buffered in registers: the loads of the next group of
