@@ -15,7 +15,9 @@
  *   - The caller owns every buffer.  *_forward never allocates or frees device
  *     memory and never synchronises with the host: all work is queued on
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream).
- *     Buffers must stay valid until that work has finished.
+ *     Buffers must stay valid until that work has finished.  The work is
+ *     kernel launches only, so a call on a capturing stream records into a HIP
+ *     graph (the persistent schedule, a cooperative launch, excepted).
  *   - x, h: time-major [L x d] fp32, row t = time step t.  State c: fp32.
  *   - Weights: row-major, fp32 (SSRNN_F32) or bfloat16 bit patterns
  *     (SSRNN_BF16; products accumulate in fp32, state stays fp32).

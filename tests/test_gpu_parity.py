@@ -12,7 +12,7 @@ import pytest
 import oracle
 import workloads as wl
 from golden_io import load_example
-from gpu_util import gpu_qrnn, gpu_sru, max_abs
+from gpu_util import gpu_qrnn, gpu_sru, max_abs, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -293,6 +293,54 @@ def _check_against_rounding_oracle(cell, W, b, x, c0, xh0, T, k, h, c):
         oracle.set_operand_rounding(0)
     assert _rel_err(h, h_ref) <= BF16_MATCHED_TOL, _rel_err(h, h_ref)
     assert _rel_err(c, c_ref) <= BF16_MATCHED_TOL, _rel_err(c, c_ref)
+
+
+@pytest.mark.parametrize("T,packed", [(2, False), (24, False), (24, True)])
+def test_forward_can_be_recorded_into_a_graph(T, packed):
+    """*_forward only enqueues kernels on the given stream (no memset, no host
+    synchronisation, no allocation), so a call can be captured into a HIP graph:
+    every replay, with new inputs and with eager work in between, gives the eager
+    result bit for bit."""
+    import torch
+    import paper_1803_11389_amd as ss
+    d, n_layers, L, k = 512, 3, 61, 2
+    W, b, x0, c0, xh0 = _qrnn_inputs(1500 + T, n_layers, d, L, k, scale=2.0)
+    Wd = [to_dev(w) for w in W]
+    flags = 0
+    if packed:
+        Wd = [ss.pack_weights(w) for w in Wd]
+        flags = ss.WEIGHTS_PACKED
+    bd = [to_dev(v) for v in b]
+    x, c_in, xh_in = to_dev(x0), to_dev(c0), to_dev(xh0)
+    ws = ss.Workspace.for_shape(n_layers, d, k, T, ss.F32)
+    h = torch.empty((L, d), dtype=torch.float32, device="cuda")
+    c = torch.empty((n_layers, d), dtype=torch.float32, device="cuda")
+    xh = torch.empty((n_layers, k - 1, d), dtype=torch.float32, device="cuda")
+
+    def call():
+        ss.qrnn_forward(Wd, bd, x, c_in, xh_in, T=T, k=k, flags=flags, h=h, c_final=c, xhist_final=xh, workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for rep in range(3):
+        x.copy_(to_dev(rng.standard_normal((L, d)).astype(np.float32)))
+        c_in.copy_(to_dev(rng.standard_normal((n_layers, d)).astype(np.float32)))
+        h.zero_(); c.zero_(); xh.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (h.clone(), c.clone(), xh.clone())
+        call()                                   # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], h) and torch.equal(got[1], c) and torch.equal(got[2], xh), rep
+    h_ref, c_ref, _ = oracle.qrnn_forward(W, b, x.cpu().numpy(), c_init=c_in.cpu().numpy(), xhist_init=xh0, T=T, k=k)
+    assert max_abs(h.cpu().numpy(), h_ref) <= TOL and max_abs(c.cpu().numpy(), c_ref) <= TOL
 
 
 def test_read_probe_runs_and_leaves_its_input_alone():
