@@ -1,4 +1,5 @@
-"""CPU model of the software pipeline in csrc/kernel_mfma_lds.hip.h.
+"""CPU models of the software pipelines in csrc/kernel_mfma_lds.hip.h and
+csrc/kernel_mfma_packed.hip.h.
 
 The kernel keeps three rings per wavefront -- G register slots of weight lines
 in flight from memory, S slots of B fragments, two fragment buffers fed from
@@ -85,6 +86,70 @@ def test_schedule_is_in_range_and_complete(G, S, NBH, nks):
     if nks < U or nks % U:
         pytest.skip("the kernel takes its unpipelined path for this k-step count")
     replay(G, S, U, nks, NBH)
+
+
+def replay_packed(SA, SB, U, nks, NBH=1):
+    """The packed-weight kernel: SA register slots of weight fragments (step ks in
+    slot ks % SA, refilled SA-1 steps ahead while step ks is multiplied), SB slots
+    of B fragments (sub-step ss in slot ss % SB, requested SB-1 sub-steps ahead)."""
+    assert nks >= U and nks % U == 0 and U % SA == 0 and (U * NBH) % SB == 0
+    aring = [None] * SA
+    bring = [None] * SB
+    a_ks = 0
+    b_col = 0
+    loaded_a, loaded_b = [], []
+
+    def load_a(slot):
+        assert 0 <= a_ks < nks, ("weight prefetch out of range", a_ks, nks)
+        aring[slot] = a_ks
+        loaded_a.append(a_ks)
+
+    def load_b(slot, hb):
+        assert 0 <= b_col < nks, ("B prefetch out of range", b_col, nks)
+        bring[slot] = (b_col, hb)
+        loaded_b.append((b_col, hb))
+
+    for p in range(SA - 1):
+        load_a(p)
+        a_ks += 1
+    for ss in range(SB - 1):
+        load_b(ss % SB, ss % NBH)
+        if ss % NBH == NBH - 1:
+            b_col += 1
+    ks = 0
+    niter = nks // U
+    for it in range(niter):
+        last = it == niter - 1
+        for p in range(U):
+            fetch_a = (not last) or (p + SA - 1 < U)
+            assert aring[p % SA] == ks, ("weight fragments of the wrong step", aring, ks)
+            for hb in range(NBH):
+                ss = p * NBH + hb
+                assert bring[ss % SB] == (ks, hb), ("B fragments of the wrong sub-step", bring[ss % SB], ks, hb)
+                tgt = ss + SB - 1
+                fetch_b = (not last) or (tgt < U * NBH)
+                if fetch_b:
+                    # the slot being refilled must not be the one this sub-step multiplies from
+                    assert tgt % SB != ss % SB or SB == 1
+                    load_b(tgt % SB, tgt % NBH)
+                    if tgt % NBH == NBH - 1:
+                        b_col += 1
+                if hb == 0 and fetch_a:
+                    assert (p + SA - 1) % SA != p % SA
+                    load_a((p + SA - 1) % SA)
+            if fetch_a:
+                a_ks += 1
+            ks += 1
+    assert ks == nks
+    assert sorted(loaded_a) == list(range(nks))
+    assert sorted(loaded_b) == [(k, h) for k in range(nks) for h in range(NBH)]
+
+
+# (SA, SB, NBH) per number of time tiles as in MfmaPkCfg: NT <= 4 -> (4, 4, 1); NT = 8 -> (4, 2, 1); NT = 16 -> (4, 2, 2)
+@pytest.mark.parametrize("SA,SB,NBH", [(4, 4, 1), (4, 2, 1), (4, 2, 2)])
+@pytest.mark.parametrize("nks", [4, 8, 16, 32, 64])
+def test_packed_schedule_is_in_range_and_complete(SA, SB, NBH, nks):
+    replay_packed(SA, SB, max(SA, SB), nks, NBH)
 
 
 def test_model_catches_a_prefetch_that_reaches_too_far():
