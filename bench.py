@@ -236,7 +236,20 @@ def main():
         dt = time.perf_counter() - t0
         m = min(n, h_head.shape[0])
         err = float(np.abs(h_head[:m].cpu().numpy().astype(np.float64) - h_ref[:m]).max())
+        # the same oracle on one thread, on a short prefix (a few seconds)
+        n1 = max(4, min(n, int(4.0 * n / dt / max(cores, 1))))
+        oracle.set_num_threads(1)
+        try:
+            t1 = time.perf_counter()
+            if cfg.cell == "sru":
+                oracle.sru_forward(W_host, None, xs[:n1], T=args.T)
+            else:
+                oracle.qrnn_forward(W_host, None, xs[:n1], T=args.T, k=cfg.k)
+            dt1 = time.perf_counter() - t1
+        finally:
+            oracle.set_num_threads(cores)
         cpu = {"value": round(n / dt, 2), "unit": "time steps/s", "cores": cores, "kind": "oracle",
+               "single_thread_value": round(n1 / dt1, 2), "single_thread_sample": f"first {n1} time steps, {dt1:.1f} s",
                "sample": f"first {n} of {cfg.L} time steps, all {cfg.n_layers} layers, T={args.T}, "
                          f"{dt:.1f} s of CPU time",
                "gpu_vs_oracle_max_abs_err_on_sample": err}
