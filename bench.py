@@ -32,7 +32,7 @@ FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 (vector / matrix) peak
 # HBM bytes per stage launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
 # scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same workloads).
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", 1, "row-major"): 201_660_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
+    ("C4", 1, "row-major"): 201_810_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
     ("C4", 4, "row-major"): 202_160_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
     ("C4", 16, "row-major"): 205_150_000,   # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T16.txt
     ("C4", 16, "packed"): 205_130_000,      # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T16.txt

@@ -77,8 +77,9 @@ const char* ssrnn_last_error(void);
 
 /* Bytes of device scratch *_forward needs for this shape (inter-layer
  * activations for one block, their operand copies for the matrix-core
- * kernels, control words).  Host.  Returns 0 for arguments *_forward would reject.  The workspace must be
- * 256-byte aligned; its contents need not be initialised and are not preserved. */
+ * kernels, control words).  Host.  Returns 0 for arguments *_forward would
+ * reject.  The workspace must be 256-byte aligned; its contents need not be
+ * initialised and are not preserved. */
 size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype);
 
 /* After a *_forward call that ran the persistent schedule: synchronizes the
@@ -151,11 +152,13 @@ int ssrnn_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
 /* Measurement aid: override one launch-geometry choice of the kernels for the
  * calls that follow, process-wide (not thread-safe; 0 restores the default).
  * Keys: "valu_F" (features per workgroup), "valu_nw" (wavefronts per
- * workgroup), "valu_nv" (column chunks per lane), "ksplit" (1: never split a narrow layer's columns over
- * several workgroups; 2, 4, 8: at most that many parts), "spin_limit"
- * (ticks of the 100 MHz wall clock that one grid-barrier wait of the
- * persistent schedule may take before the kernel gives up; default one
- * second).  A value the shape does not allow is ignored.  Results are unaffected beyond fp32 re-association.  Host. */
+ * workgroup), "valu_nv" (column chunks per lane), "ksplit" (1: never split a
+ * narrow layer's columns over several workgroups; 2, 4, 8: at most that many
+ * parts), "spin_limit" (ticks of the 100 MHz wall clock that one grid-barrier
+ * wait of the persistent schedule may take before the kernel gives up; default
+ * one second).  A value the shape does not allow is ignored.  Results are
+ * unaffected beyond fp32 re-association.  Host.  Returns SSRNN_EINVAL for an
+ * unknown key. */
 int ssrnn_tune(const char* key, int value);
 
 #ifdef __cplusplus
