@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ssrnn_oracle.cpp")
 _LIB = os.path.join(_HERE, "libssrnn_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, FP8 = 0, 1, 2
 
 _lib = None
 
@@ -85,12 +85,28 @@ def set_num_threads(n: int) -> None:
     _load().oracle_set_num_threads(int(n))
 
 
-def _wdt_of(w: np.ndarray) -> int:
+def _is_fp8(w) -> bool:
+    """8-bit weights come as an object with codes `q` [rows, cols] uint8, `scale`
+    [rows] float32 and `blob()`, the byte layout ssrnn_oracle.cpp documents."""
+    return hasattr(w, "q") and hasattr(w, "scale") and hasattr(w, "blob")
+
+
+def _wdt_of(w) -> int:
+    if _is_fp8(w):
+        return FP8
     if w.dtype == np.float32:
         return F32
     if w.dtype == np.uint16:
         return BF16
-    raise TypeError("weights must be float32 or uint16 (bf16 bit patterns)")
+    raise TypeError("weights must be float32, uint16 (bf16 bit patterns) or 8-bit codes with row scales")
+
+
+def _storage(w):
+    """(array handed to the C side, logical [rows, cols] shape)."""
+    if _is_fp8(w):
+        return w.blob(), tuple(w.q.shape)
+    w = np.ascontiguousarray(w)
+    return w, tuple(w.shape)
 
 
 def _ptr(a):
@@ -117,15 +133,17 @@ def _as(a, dtype, shape=None):
 
 
 def sru_forward(W, bias, x, c_init=None, T=1, return_all=False):
-    """W: list of [3d, d] float32 / uint16 arrays; bias: None or list of
+    """W: list of [3d, d] float32 / uint16 arrays or 8-bit weight objects; bias: None or list of
     None / [2d] float32; x: [L, d].  Returns (h, c_final[, h_all]) as float64."""
     lib = _load()
     n_layers = len(W)
-    W = [np.ascontiguousarray(w) for w in W]
     wdt = _wdt_of(W[0])
-    d = W[0].shape[1]
     for w in W:
-        assert w.shape == (3 * d, d) and _wdt_of(w) == wdt
+        assert _wdt_of(w) == wdt
+    W, shapes = zip(*[_storage(w) for w in W])
+    d = shapes[0][1]
+    for sh in shapes:
+        assert sh == (3 * d, d)
     x = _as(x, np.float64)
     L = x.shape[0]
     assert x.shape == (L, d)
@@ -149,11 +167,13 @@ def qrnn_forward(W, bias, x, c_init=None, xhist_init=None, T=1, k=2, return_all=
     Returns (h, c_final, xhist_final[, h_all]) as float64."""
     lib = _load()
     n_layers = len(W)
-    W = [np.ascontiguousarray(w) for w in W]
     wdt = _wdt_of(W[0])
-    d = W[0].shape[0] // 3
     for w in W:
-        assert w.shape == (3 * d, k * d) and _wdt_of(w) == wdt
+        assert _wdt_of(w) == wdt
+    W, shapes = zip(*[_storage(w) for w in W])
+    d = shapes[0][0] // 3
+    for sh in shapes:
+        assert sh == (3 * d, k * d)
     x = _as(x, np.float64)
     L = x.shape[0]
     assert x.shape == (L, d)
@@ -178,13 +198,14 @@ def qrnn_forward(W, bias, x, c_init=None, xhist_init=None, T=1, k=2, return_all=
 def sru_step(W, bias, x_t, c):
     """One layer, one step, no blocking.  Returns (h_t, c_new) as float64."""
     lib = _load()
-    W = np.ascontiguousarray(W)
-    d = W.shape[1]
+    wdt = _wdt_of(W)
+    W, shape = _storage(W)
+    d = shape[1]
     x_t = _as(x_t, np.float64, (d,))
     c = _as(c, np.float64, (d,)).copy()
     bias = _as(bias, np.float32)
     h = np.empty(d, np.float64)
-    rc = lib.oracle_sru_step(_ptr(W), _ptr(bias), _ptr(x_t), _ptr(c), _ptr(h), d, _wdt_of(W))
+    rc = lib.oracle_sru_step(_ptr(W), _ptr(bias), _ptr(x_t), _ptr(c), _ptr(h), d, wdt)
     assert rc == 0
     return h, c
 
@@ -192,13 +213,14 @@ def sru_step(W, bias, x_t, c):
 def qrnn_step(W, bias, xwin, c, k):
     """xwin: [k, d], row j = x_{t-j}.  Returns (h_t, c_new) as float64."""
     lib = _load()
-    W = np.ascontiguousarray(W)
-    d = W.shape[0] // 3
+    wdt = _wdt_of(W)
+    W, shape = _storage(W)
+    d = shape[0] // 3
     xwin = _as(xwin, np.float64, (k, d))
     c = _as(c, np.float64, (d,)).copy()
     bias = _as(bias, np.float32)
     h = np.empty(d, np.float64)
-    rc = lib.oracle_qrnn_step(_ptr(W), _ptr(bias), _ptr(xwin), _ptr(c), _ptr(h), d, int(k), _wdt_of(W))
+    rc = lib.oracle_qrnn_step(_ptr(W), _ptr(bias), _ptr(xwin), _ptr(c), _ptr(h), d, int(k), wdt)
     assert rc == 0
     return h, c
 

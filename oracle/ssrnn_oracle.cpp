@@ -20,7 +20,8 @@
 //   * A stack feeds layer l's h_t to layer l+1 as x_t.
 //
 // Arithmetic: every sum, gate and state is IEEE double; weights are given in
-// their storage type (fp32, or bf16 bit patterns) and widened exactly.  Each dot product adds its terms in ascending column
+// their storage type (fp32, bf16 bit patterns, or 8-bit floats with a scale per
+// row) and widened exactly.  Each dot product adds its terms in ascending column
 // order whatever T is, so the result is bit-identical for every block size.
 // Nothing is rounded between layers.  The paper does not state the precision
 // of its runs (Section 4).  For kernels that hand the block X of Eq. 4 to the
@@ -35,6 +36,13 @@
 // closed forms (f==0, f==1/2, f==1, r==0, W==0), the non-iterative solution of
 // the linear recurrence, an independent library matrix product for the weight
 // layout, block-size invariance, chunk chaining and boundedness.
+//
+// 8-bit weights (not in the paper; they serve its argument that the bytes of
+// weights per step decide the speed, Sections 1 and 3): the matrix is stored as
+// OCP FP8 E4M3 codes q (1 sign, 4 exponent bits with bias 7, 3 mantissa bits,
+// subnormals, no infinities, S.1111.111 = NaN) row-major, padded with zeros to
+// a multiple of 256 bytes, followed by one fp32 scale per row;
+// W[row][col] = scale[row] * value(q[row][col]).
 //
 // Storage conventions
 //   SRU  W  : row-major [3d x d],   rows [0,d) = W, [d,2d) = W_f, [2d,3d) = W_r
@@ -57,7 +65,7 @@
 
 namespace {
 
-enum { WDT_F32 = 0, WDT_BF16 = 1 };
+enum { WDT_F32 = 0, WDT_BF16 = 1, WDT_FP8 = 2 };
 
 inline double widen_bf16(uint16_t bits) {
   uint32_t u = static_cast<uint32_t>(bits) << 16;
@@ -66,8 +74,27 @@ inline double widen_bf16(uint16_t bits) {
   return static_cast<double>(f);
 }
 
-inline double weight_at(const void* W, int wdt, size_t idx) {
+// Value of an E4M3 code, from the format's definition.
+inline double value_e4m3(uint8_t code) {
+  const int e = (code >> 3) & 15;
+  const int m = code & 7;
+  double v;
+  if (e == 15 && m == 7) v = std::nan("");
+  else if (e == 0) v = std::ldexp(m / 8.0, 1 - 7);          // subnormal: exponent of the smallest normal, no hidden one
+  else v = std::ldexp(1.0 + m / 8.0, e - 7);
+  return (code & 0x80) ? -v : v;
+}
+
+// Element (row, col) of a [rows x ncol] weight matrix in storage type wdt.
+inline double weight_at(const void* W, int wdt, size_t rows, size_t ncol, size_t row, size_t col) {
+  const size_t idx = row * ncol + col;
   if (wdt == WDT_BF16) return widen_bf16(static_cast<const uint16_t*>(W)[idx]);
+  if (wdt == WDT_FP8) {
+    const size_t scale_offset = (rows * ncol + 255) / 256 * 256;
+    float scale;
+    std::memcpy(&scale, static_cast<const char*>(W) + scale_offset + row * sizeof(float), sizeof scale);
+    return static_cast<double>(scale) * value_e4m3(static_cast<const uint8_t*>(W)[idx]);
+  }
   return static_cast<double>(static_cast<const float*>(W)[idx]);
 }
 
@@ -98,9 +125,8 @@ void gate_block(const void* W, int wdt, int d, int ncol, const double* X,
   for (int row = 0; row < 3 * d; ++row) {
     double* acc = U + static_cast<size_t>(row) * nt;
     for (int t = 0; t < nt; ++t) acc[t] = 0.0;
-    const size_t base = static_cast<size_t>(row) * ncol;
     for (int col = 0; col < ncol; ++col) {
-      const double w = weight_at(W, wdt, base + col);
+      const double w = weight_at(W, wdt, static_cast<size_t>(3) * d, ncol, row, col);
       const double* xc = X + static_cast<size_t>(col) * nt;
       for (int t = 0; t < nt; ++t) acc[t] += w * xc[t];
     }
@@ -213,7 +239,7 @@ void oracle_set_num_threads(int n) {
 }
 
 // Stacked SRU forward (Eq. 2 per layer, Section 3 blocking with block size T).
-// W[l]: fp32 or bf16-bit [3d x d]; bias: NULL, or array whose entries may be
+// W[l]: [3d x d] in storage type wdt; bias: NULL, or array whose entries may be
 // NULL; x: double [L x d] (fp32 inputs are widened exactly by the caller);
 // c_init: double [n_layers x d] or NULL; outputs double:
 // h [L x d] (top layer), c_final [n_layers x d], h_all optional
@@ -224,7 +250,7 @@ int oracle_sru_forward(const void* const* W, const float* const* bias,
                        long L, int T, int wdt) {
   if (!W || !c_final || n_layers < 1 || d < 1 || L < 0 || T < 1) return 1;
   if (L > 0 && (!x || !h)) return 1;
-  if (wdt != WDT_F32 && wdt != WDT_BF16) return 1;
+  if (wdt != WDT_F32 && wdt != WDT_BF16 && wdt != WDT_FP8) return 1;
   const size_t n = static_cast<size_t>(L) * d;
   std::vector<double> cur(n), nxt(n);
   for (size_t i = 0; i < n; ++i) cur[i] = x[i];
@@ -252,7 +278,7 @@ int oracle_qrnn_forward(const void* const* W, const float* const* bias,
                         int d, long L, int T, int k, int wdt) {
   if (!W || !c_final || n_layers < 1 || d < 1 || L < 0 || T < 1 || k < 1) return 1;
   if (L > 0 && (!x || !h)) return 1;
-  if (wdt != WDT_F32 && wdt != WDT_BF16) return 1;
+  if (wdt != WDT_F32 && wdt != WDT_BF16 && wdt != WDT_FP8) return 1;
   const size_t n = static_cast<size_t>(L) * d;
   const size_t nh = static_cast<size_t>(k - 1) * d;
   std::vector<double> cur(n), nxt(n);
@@ -284,9 +310,10 @@ int oracle_sru_step(const void* W, const float* bias, const double* x_t,
   if (!W || !x_t || !c || !h_t || d < 1) return 1;
   for (int i = 0; i < d; ++i) {
     double ux = 0.0, uf = 0.0, ur = 0.0;
-    for (int j = 0; j < d; ++j) ux += weight_at(W, wdt, static_cast<size_t>(i) * d + j) * x_t[j];
-    for (int j = 0; j < d; ++j) uf += weight_at(W, wdt, static_cast<size_t>(d + i) * d + j) * x_t[j];
-    for (int j = 0; j < d; ++j) ur += weight_at(W, wdt, static_cast<size_t>(2 * d + i) * d + j) * x_t[j];
+    const size_t rows = static_cast<size_t>(3) * d;
+    for (int j = 0; j < d; ++j) ux += weight_at(W, wdt, rows, d, i, j) * x_t[j];
+    for (int j = 0; j < d; ++j) uf += weight_at(W, wdt, rows, d, d + i, j) * x_t[j];
+    for (int j = 0; j < d; ++j) ur += weight_at(W, wdt, rows, d, 2 * d + i, j) * x_t[j];
     if (bias) { uf += bias[i]; ur += bias[d + i]; }
     const double f = 1.0 / (1.0 + std::exp(-uf));
     const double r = 1.0 / (1.0 + std::exp(-ur));
@@ -306,7 +333,8 @@ int oracle_qrnn_step(const void* W, const float* bias, const double* xwin,
     for (int g = 0; g < 3; ++g)
       for (int j = 0; j < k; ++j)
         for (int m = 0; m < d; ++m)
-          u[g] += weight_at(W, wdt, (static_cast<size_t>(g) * d + i) * ld + static_cast<size_t>(j) * d + m) *
+          u[g] += weight_at(W, wdt, static_cast<size_t>(3) * d, ld, static_cast<size_t>(g) * d + i,
+                            static_cast<size_t>(j) * d + m) *
                   xwin[static_cast<size_t>(j) * d + m];
     if (bias) { u[0] += bias[i]; u[1] += bias[d + i]; u[2] += bias[2 * d + i]; }
     const double z = std::tanh(u[0]);

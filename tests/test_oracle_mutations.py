@@ -24,8 +24,8 @@ MUTATIONS = [
     ("sru: biases swapped", "const double bf = bias ? static_cast<double>(bias[i]) : 0.0;\n      const double br = bias ? static_cast<double>(bias[d + i]) : 0.0;\n      double ci = c[i];\n      for (int t = 0; t < nt; ++t) {\n        const double xh",
      "const double br = bias ? static_cast<double>(bias[i]) : 0.0;\n      const double bf = bias ? static_cast<double>(bias[d + i]) : 0.0;\n      double ci = c[i];\n      for (int t = 0; t < nt; ++t) {\n        const double xh"),
     ("sigmoid sign", "return 1.0 / (1.0 + std::exp(-z));", "return 1.0 / (1.0 + std::exp(z));"),
-    ("weights read transposed (square case)", "const size_t base = static_cast<size_t>(row) * ncol;\n    for (int col = 0; col < ncol; ++col) {\n      const double w = weight_at(W, wdt, base + col);",
-     "const size_t base = static_cast<size_t>(row) * ncol;\n    for (int col = 0; col < ncol; ++col) {\n      const double w = weight_at(W, wdt, ncol == d ? (static_cast<size_t>(row / d) * d + col) * ncol + row % d : base + col);"),
+    ("weights read transposed (square case)", "const double w = weight_at(W, wdt, static_cast<size_t>(3) * d, ncol, row, col);",
+     "const double w = ncol == d ? weight_at(W, wdt, static_cast<size_t>(3) * d, ncol, (row / d) * d + col, row % d) : weight_at(W, wdt, static_cast<size_t>(3) * d, ncol, row, col);"),
     ("qrnn: lag blocks reversed", "X[(static_cast<size_t>(j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m));",
      "X[(static_cast<size_t>(k - 1 - j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m));"),
     ("qrnn: looks ahead instead of back", "= operand(x_at(t0 + t - j, m));", "= operand(x_at(t0 + t + j < L ? t0 + t + j : L - 1, m));"),
@@ -41,6 +41,14 @@ MUTATIONS = [
     ("state not carried across blocks", "      c[i] = ci;\n    }\n  }\n}\n\n// One QRNN layer.", "    }\n  }\n}\n\n// One QRNN layer."),
     ("initial state ignored (sru)", "c[i] = c_init ? c_init[static_cast<size_t>(l) * d + i] : 0.0;\n    sru_layer", "c[i] = 0.0;\n    sru_layer"),
     ("bf16 widened with the wrong shift", "static_cast<uint32_t>(bits) << 16;", "static_cast<uint32_t>(bits) << 15;"),
+    ("fp8: exponent bias 8 (the other 8-bit float format)", "v = std::ldexp(1.0 + m / 8.0, e - 7);", "v = std::ldexp(1.0 + m / 8.0, e - 8);"),
+    ("fp8: subnormals given the hidden one", "else if (e == 0) v = std::ldexp(m / 8.0, 1 - 7);", "else if (e == 0) v = std::ldexp(1.0 + m / 8.0, 0 - 7);"),
+    ("fp8: subnormal exponent off by one", "v = std::ldexp(m / 8.0, 1 - 7);", "v = std::ldexp(m / 8.0, 0 - 7);"),
+    ("fp8: mantissa of 4 bits", "const int m = code & 7;", "const int m = code & 15;"),
+    ("fp8: sign ignored", "return (code & 0x80) ? -v : v;", "return v;"),
+    ("fp8: scale of the wrong row", "scale_offset + row * sizeof(float), sizeof scale);", "scale_offset + (row ^ 1) * sizeof(float), sizeof scale);"),
+    ("fp8: scales taken to start right behind the codes", "const size_t scale_offset = (rows * ncol + 255) / 256 * 256;", "const size_t scale_offset = (rows * ncol + 3) / 4 * 4;"),
+    ("fp8: scale dropped", "return static_cast<double>(scale) * value_e4m3(", "return value_e4m3("),
     ("stack: every layer reads the external input", "    cur.swap(nxt);\n  }\n  if (n) std::memcpy(h, cur.data(), n * sizeof(double));\n  return 0;\n}\n\n// Stacked QRNN",
      "    if (l == n_layers - 1) cur.swap(nxt);\n  }\n  if (n) std::memcpy(h, cur.data(), n * sizeof(double));\n  return 0;\n}\n\n// Stacked QRNN"),
     ("step function: bias dropped", "if (bias) { uf += bias[i]; ur += bias[d + i]; }", ""),
@@ -65,6 +73,9 @@ BATTERY = [
     pins.test_linear_projection_against_numpy,
     pins.test_future_inputs_do_not_change_past_outputs,
     pins.test_operand_rounding_mode_rounds_only_the_matrix_operand,
+    pins.test_fp8_code_values_follow_the_format,
+    pins.test_fp8_weights_equal_their_fp32_values_bitwise,
+    pins.test_fp8_row_scales_are_applied_per_row,
 ]
 
 

@@ -417,6 +417,94 @@ def test_bf16_weights_are_widened_exactly():
     assert np.abs(oracle.sru_forward(W, b, x, T=4)[0] - oracle.sru_forward(Wf, b, x, T=4)[0]).max() > 1e-6
 
 
+# ------------------------------------------------------- 8-bit float weights
+
+# Values of OCP FP8 E4M3 codes as the format's specification lists them (bias 7, subnormals
+# m/8 * 2^-6, no infinities, largest finite 0x7E = 448), typed here by hand.
+E4M3_SPEC_VALUES = {
+    0x00: 0.0, 0x01: 2.0 ** -9, 0x02: 2.0 ** -8, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x09: 1.125 * 2.0 ** -6,
+    0x0F: 1.875 * 2.0 ** -6, 0x10: 2.0 ** -5, 0x30: 0.5, 0x37: 0.9375, 0x38: 1.0, 0x39: 1.125, 0x3C: 1.5, 0x40: 2.0,
+    0x44: 3.0, 0x48: 4.0, 0x70: 128.0, 0x77: 240.0, 0x78: 256.0, 0x7D: 416.0, 0x7E: 448.0,
+    0x81: -(2.0 ** -9), 0xB8: -1.0, 0xC0: -2.0, 0xFE: -448.0,
+}
+
+
+class _Fp8:
+    """Codes and row scales in the byte layout oracle/ssrnn_oracle.cpp documents, assembled here."""
+
+    def __init__(self, q, scale):
+        self.q = np.ascontiguousarray(q, np.uint8)
+        self.scale = np.ascontiguousarray(scale, np.float32)
+
+    def blob(self):
+        n = self.q.size
+        off = (n + 255) // 256 * 256
+        out = np.zeros(off + 4 * self.scale.size, np.uint8)
+        out[:n] = self.q.reshape(-1)
+        out[off:] = self.scale.view(np.uint8)
+        return out
+
+
+def test_fp8_code_values_follow_the_format():
+    """One code at a time through a d = 1 QRNN step (k = 1): with the forget row 0 (f = 1/2), c_0 = 0
+    and the output row 0 (o = 1/2), h = tanh(tanh(w * x) / 2) / 2 where w is the candidate weight."""
+    for code, value in E4M3_SPEC_VALUES.items():
+        for scale in (1.0, 0.75):
+            W = _Fp8(np.array([[code], [0x00], [0x00]], np.uint8), np.array([scale, 1.0, 1.0], np.float32))
+            x = 0.001953125 if abs(value) > 4 else 0.5
+            h, c = oracle.qrnn_step(W, None, np.array([[x]]), np.zeros(1), 1)
+            assert c[0] == pytest.approx(0.5 * math.tanh(scale * value * x), rel=1e-14, abs=1e-300), hex(code)
+            assert h[0] == pytest.approx(0.5 * math.tanh(c[0]), rel=1e-14, abs=1e-300), hex(code)
+
+
+def test_fp8_weights_equal_their_fp32_values_bitwise():
+    """Every non-NaN code, decoded by torch's float8_e4m3fn and scaled by powers of two (exact in
+    fp32), run as fp32 weights, must give the same bits as the 8-bit path: pins the decoding of all
+    254 codes, the row a scale belongs to and where the scales start (with and without padding)."""
+    import torch
+    rng = _rng(58)
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)
+    for cell, d, k, L, T in (("sru", 16, 1, 9, 4), ("sru", 6, 1, 7, 3), ("qrnn", 8, 2, 9, 4), ("qrnn", 5, 3, 6, 2)):
+        ncol = k * d
+        q = rng.choice(codes, size=(3 * d, ncol))
+        q.reshape(-1)[:min(q.size, codes.size)] = codes[:min(q.size, codes.size)]     # every code at least once where it fits
+        scale = (2.0 ** rng.integers(-9, -3, 3 * d)).astype(np.float32)
+        dec = torch.from_numpy(q.copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+        Wf = (dec * scale[:, None]).astype(np.float32)
+        assert np.array_equal(Wf.astype(np.float64), dec.astype(np.float64) * scale[:, None].astype(np.float64))
+        W8 = _Fp8(q, scale)
+        x = rng.standard_normal((L, d)).astype(np.float32)
+        if cell == "sru":
+            a, b = oracle.sru_forward([W8, W8], None, x, T=T), oracle.sru_forward([Wf, Wf], None, x, T=T)
+        else:
+            a, b = oracle.qrnn_forward([W8, W8], None, x, T=T, k=k), oracle.qrnn_forward([Wf, Wf], None, x, T=T, k=k)
+        for u, v in zip(a, b):
+            np.testing.assert_array_equal(u, v)
+        # the step functions read the same storage
+        if cell == "sru":
+            np.testing.assert_array_equal(oracle.sru_step(W8, None, x[0], np.zeros(d))[0], oracle.sru_step(Wf, None, x[0], np.zeros(d))[0])
+        else:
+            xw = rng.standard_normal((k, d))
+            np.testing.assert_array_equal(oracle.qrnn_step(W8, None, xw, np.zeros(d), k)[0], oracle.qrnn_step(Wf, None, xw, np.zeros(d), k)[0])
+
+
+def test_fp8_row_scales_are_applied_per_row():
+    """Scales that are not powers of two: u = diag(scale) * Q * x, checked through the SRU with the
+    reset row at 0 (r = 1/2) and the forget row at 0 (f = 1/2): c_1 = (scale_i * (Q x)_i) / 2."""
+    rng = _rng(59)
+    d = 12
+    q = np.zeros((3 * d, d), np.uint8)
+    q[:d] = rng.integers(0x20, 0x50, (d, d)).astype(np.uint8) | (rng.integers(0, 2, (d, d)).astype(np.uint8) << 7)
+    scale = rng.uniform(0.01, 0.2, 3 * d).astype(np.float32)
+    import torch
+    Q = torch.from_numpy(q[:d].copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    x = rng.standard_normal(d)
+    h, c = oracle.sru_step(_Fp8(q, scale), None, x, np.zeros(d))
+    want_c = 0.5 * scale[:d].astype(np.float64) * (Q @ x)
+    np.testing.assert_allclose(c, want_c, rtol=1e-13, atol=0)
+    np.testing.assert_allclose(h, 0.5 * np.tanh(want_c) + 0.5 * x, rtol=1e-13, atol=0)
+
+
 def _bf16_round_numpy(a):
     """Nearest bfloat16, ties to even, of a float32 array, by integer arithmetic
     on the bit patterns (written here, not taken from workloads or the oracle)."""

@@ -2,7 +2,8 @@
 
 This module holds NO arithmetic of the method (no gates, no recurrence, no
 matrix products): only a counter-based random generator, fp32 -> bf16
-rounding of stored weights, and the table of workload shapes.  It serves both
+rounding and fp32 -> scaled 8-bit float encoding of stored weights, and the
+table of workload shapes.  It serves both
 the CPU oracle's tests and the GPU tests / bench, so both sides read the same
 tensors; numpy only.
 
@@ -84,6 +85,60 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+# ---- 8-bit float weights (OCP FP8 E4M3: 1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no
+# infinities, S.1111.111 is NaN, largest finite value 448, subnormals m/8 * 2^-6) with one fp32 scale per
+# matrix row: stored value = scale[row] * e4m3(code).
+
+FP8_MAX = 448.0
+FP8_SCALE_ALIGN = 256
+
+
+def to_fp8_e4m3_bits(a: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 code (ties to even, magnitudes above 448 saturate to 448) of each float32; uint8."""
+    a = np.ascontiguousarray(a, np.float32)
+    sign = ((a.view(np.uint32) >> np.uint32(24)) & np.uint32(0x80)).astype(np.uint8)
+    mag = np.minimum(np.abs(a), np.float32(FP8_MAX))
+    u = mag.view(np.uint32)
+    # normal range (>= 2^-6): drop 20 of the 23 mantissa bits with round-to-nearest-even, re-bias 127 -> 7
+    r = u + np.uint32(0x7FFFF) + ((u >> np.uint32(20)) & np.uint32(1))
+    normal = ((r >> np.uint32(20)).astype(np.int64) - ((127 - 7) << 3))
+    # below 2^-6: multiples of 2^-9 (code 8 = 2^-6 is the smallest normal, so the two ranges join)
+    sub = np.rint(mag.astype(np.float64) * 512.0).astype(np.int64)
+    code = np.where(mag >= np.float32(2.0 ** -6), normal, sub)
+    code = np.clip(code, 0, 0x7E).astype(np.uint8)
+    return code | sign
+
+
+@dataclass(frozen=True)
+class Fp8Weight:
+    """A [rows, cols] matrix as E4M3 codes q (uint8) and one fp32 scale per row."""
+    q: np.ndarray
+    scale: np.ndarray
+
+    @property
+    def shape(self):
+        return self.q.shape
+
+    def blob(self) -> np.ndarray:
+        """The byte layout the libraries take for 8-bit weights: the codes row-major,
+        zero padding up to a multiple of 256 bytes, then the rows' fp32 scales."""
+        n = self.q.size
+        off = (n + FP8_SCALE_ALIGN - 1) // FP8_SCALE_ALIGN * FP8_SCALE_ALIGN
+        out = np.zeros(off + 4 * self.scale.size, np.uint8)
+        out[:n] = np.ascontiguousarray(self.q).reshape(-1)
+        out[off:] = np.ascontiguousarray(self.scale, np.float32).view(np.uint8)
+        return out
+
+
+def quantize_fp8(w: np.ndarray) -> Fp8Weight:
+    """Per-row absmax scaling: scale = max|row| / 448 (1 for an all-zero row), codes = e4m3(w / scale),
+    both in float32."""
+    w = np.ascontiguousarray(w, np.float32)
+    amax = np.abs(w).max(axis=1)
+    scale = np.where(amax > 0, amax / np.float32(FP8_MAX), np.float32(1.0)).astype(np.float32)
+    return Fp8Weight(to_fp8_e4m3_bits(w / scale[:, None]), scale)
+
+
 # tensor ids within one configuration's seed
 TID_X, TID_FEAT, TID_PROJ, TID_W0 = 1, 2, 3, 100
 
@@ -97,7 +152,7 @@ class Workload:
     L: int
     Ts: Tuple[int, ...]
     k: int = 1                # causal window (QRNN); 1 for SRU
-    wdtype: str = "f32"       # "f32" | "bf16" storage type of the weights
+    wdtype: str = "f32"       # "f32" | "bf16" | "fp8" storage type of the weights
     d_feat: int = 0           # >0: inputs are d_feat-dim features projected to d
     index: int = 0            # position in the benchmark's config list
 
@@ -110,7 +165,8 @@ class Workload:
         return self.k * self.d
 
     def weight_bytes_per_layer(self) -> int:
-        return 3 * self.d * self.ncol * (2 if self.wdtype == "bf16" else 4)
+        """Matrix bytes (the 12*d bytes of row scales of 8-bit weights are left out)."""
+        return 3 * self.d * self.ncol * {"f32": 4, "bf16": 2, "fp8": 1}[self.wdtype]
 
     def algorithmic_bytes_per_step(self, T: int) -> float:
         """Bytes the method must move per time step for the whole stack: every
@@ -131,10 +187,13 @@ CONFIGS: Tuple[Workload, ...] = (
 )
 
 
-# Not one of the benchmark's five: configuration 4 with its weights stored in bf16 — the small-T,
-# low-precision-weight point (half the bytes per step of C4, so twice the steps/s while HBM-bound).
+# Not among the benchmark's five: configuration 4 with its weights stored in bf16 and in scaled 8-bit
+# floats — the small-T, low-precision-weight points (a half and a quarter of C4's bytes per step, so
+# twice and four times the steps/s while HBM-bound) — and configuration 5 in 8-bit floats.
 EXTRA: Tuple[Workload, ...] = (
     Workload("X1_sru8_d4096_bf16", "sru", 8, 4096, 2048, (1, 2, 4, 8, 16, 64), wdtype="bf16", index=5),
+    Workload("X2_sru8_d4096_fp8", "sru", 8, 4096, 2048, (1, 2, 4, 8, 16, 64), wdtype="fp8", index=6),
+    Workload("X3_qrnn8_d4096_k2_fp8", "qrnn", 8, 4096, 4096, (16, 64, 256), k=2, wdtype="fp8", index=7),
 )
 
 
@@ -147,8 +206,10 @@ def by_name(prefix: str) -> Workload:
 
 def layer_weight(wl: Workload, layer: int) -> np.ndarray:
     """[3d, k*d] weights of one layer, U(+-1/sqrt(k*d)); uint16 bf16 bits if the
-    workload stores bf16."""
+    workload stores bf16, an Fp8Weight if it stores 8-bit floats."""
     w = uniform(wl.seed, TID_W0 + layer, (3 * wl.d, wl.ncol), 1.0 / math.sqrt(wl.ncol))
+    if wl.wdtype == "fp8":
+        return quantize_fp8(w)
     return to_bf16_bits(w) if wl.wdtype == "bf16" else w
 
 
