@@ -19,8 +19,12 @@
  *     kernel launches only, so a call on a capturing stream records into a HIP
  *     graph (the persistent schedule, a cooperative launch, excepted).
  *   - x, h: time-major [L x d] fp32, row t = time step t.  State c: fp32.
- *   - Weights: row-major, fp32 (SSRNN_F32) or bfloat16 bit patterns
- *     (SSRNN_BF16; products accumulate in fp32, state stays fp32).
+ *   - Weights: row-major, fp32 (SSRNN_F32), bfloat16 bit patterns (SSRNN_BF16)
+ *     or 8-bit floats with one fp32 scale per row (SSRNN_FP8, see
+ *     ssrnn_weight_bytes); products accumulate in fp32, state stays fp32.  The
+ *     paper's point is that the bytes of weights fetched per time step decide
+ *     the speed (Sections 1 and 3); narrower weights cut those bytes the same
+ *     way a larger T does, and the two multiply.
  *   - Return value: an ssrnn_status.  On failure nothing (EINVAL, EUNSUPPORTED,
  *     EWORKSPACE) or an unspecified part (EDEVICE) of the work was queued, and
  *     ssrnn_last_error() describes the cause.  No exception crosses the ABI.
@@ -45,7 +49,7 @@ typedef enum {
   SSRNN_EDEVICE = 4       /* a HIP call failed, or a kernel reported a failed wait */
 } ssrnn_status;
 
-typedef enum { SSRNN_F32 = 0, SSRNN_BF16 = 1 } ssrnn_wdtype;
+typedef enum { SSRNN_F32 = 0, SSRNN_BF16 = 1, SSRNN_FP8 = 2 } ssrnn_wdtype;
 
 /* `flags` of *_forward: 0 picks the schedule and kernel by shape.  The other
  * values force one (tests and measurements use them); a forced choice that the
@@ -81,6 +85,17 @@ const char* ssrnn_last_error(void);
  * reject.  The workspace must be 256-byte aligned; its contents need not be
  * initialised and are not preserved. */
 size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype);
+
+/* Bytes of one layer's weight buffer W[l] for a [3d x k*d] matrix.  Host; 0 for
+ * sizes out of range.  SSRNN_F32: 12*d*k*d.  SSRNN_BF16: 6*d*k*d.  SSRNN_FP8:
+ * the 3*d*k*d OCP FP8 E4M3 codes (1 sign, 4 exponent bits with bias 7, 3
+ * mantissa bits, subnormals, no infinities, largest finite value 448),
+ * row-major, zero padding up to the next multiple of 256 bytes, then 3*d fp32
+ * scales, one per matrix row: W[row][col] = scale[row] * value(code[row][col]).
+ * NaN codes (0x7F, 0xFF) are the caller's to avoid.  The kernels widen the
+ * codes exactly (to fp32 on the vector ALU, to bf16 on the matrix cores) and
+ * apply the scale to the finished fp32 sum of a row. */
+size_t ssrnn_weight_bytes(int d, int k, int wdtype);
 
 /* After a *_forward call that ran the persistent schedule: synchronizes the
  * stream and reports whether one of the kernel's bounded waits ran out
@@ -131,13 +146,16 @@ int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
  * each of that kernel's load instructions reads one contiguous KiB of whole
  * cache lines.  It is the row-blocking of Section 3 (fetch a piece of a row
  * once, use it for all T steps) applied to 16-row MFMA tiles.  The values are
- * only permuted.  ssrnn_packed_weight_bytes: host; bytes of the packed buffer
- * (equal to the matrix's size), or 0 if the shape cannot be packed (needs
+ * only permuted (the row scales of SSRNN_FP8 stay where they are, behind the
+ * matrix).  ssrnn_packed_weight_bytes: host; bytes of the packed buffer
+ * (equal to ssrnn_weight_bytes), or 0 if the shape cannot be packed (needs
  * d % 16 == 0 and d*sizeof(weight) % 128 == 0).  ssrnn_pack_weights: W and
  * W_packed are distinct 16-byte aligned device buffers of that size; the copy
  * is enqueued on stream.  Pass the packed buffers as W[l] together with
  * SSRNN_WEIGHTS_PACKED in flags; shapes the matrix-core kernel cannot take
- * then fail with SSRNN_EUNSUPPORTED. */
+ * then fail with SSRNN_EUNSUPPORTED.  SSRNN_FP8 weights reach the matrix
+ * cores in packed form only: row-major, they run on the vector ALU for T <= 8
+ * (d % 1024 == 0) and on the generic kernel otherwise. */
 size_t ssrnn_packed_weight_bytes(int d, int k, int wdtype);
 int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype,
                        void* stream);

@@ -14,7 +14,7 @@ from typing import List, Optional, Sequence
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssrnn.so")
 
-F32, BF16 = 0, 1
+F32, BF16, FP8 = 0, 1, 2
 SCHED_AUTO, SCHED_STAGES, SCHED_PERSISTENT = 0, 1, 2
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_VALU, KERNEL_MFMA = 0, 1 << 4, 2 << 4, 3 << 4
 WEIGHTS_PACKED = 1 << 8
@@ -22,7 +22,7 @@ WEIGHTS_PACKED = 1 << 8
 # every symbol include/ssrnn.h declares
 EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",
            "qrnn_forward", "ssrnn_linear_forward", "ssrnn_packed_weight_bytes", "ssrnn_pack_weights",
-           "ssrnn_read_probe", "ssrnn_workspace_status", "ssrnn_tune")
+           "ssrnn_read_probe", "ssrnn_workspace_status", "ssrnn_tune", "ssrnn_weight_bytes")
 
 _lib = None
 
@@ -54,6 +54,8 @@ def load_library():
     lib.qrnn_forward.argtypes = [vp] * 8 + [ip, ip, lp, ip, ip, ip, ip, vp, sz, vp]
     lib.ssrnn_linear_forward.restype = ip
     lib.ssrnn_linear_forward.argtypes = [vp] * 3 + [ip, ip, lp, vp]
+    lib.ssrnn_weight_bytes.restype = sz
+    lib.ssrnn_weight_bytes.argtypes = [ip] * 3
     lib.ssrnn_packed_weight_bytes.restype = sz
     lib.ssrnn_packed_weight_bytes.argtypes = [ip] * 3
     lib.ssrnn_pack_weights.restype = ip
@@ -89,6 +91,32 @@ def packed_weight_bytes(d: int, k: int, wdtype: int) -> int:
     return load_library().ssrnn_packed_weight_bytes(d, k, wdtype)
 
 
+def weight_bytes(d: int, k: int, wdtype: int) -> int:
+    return load_library().ssrnn_weight_bytes(d, k, wdtype)
+
+
+class Fp8Weights:
+    """One layer's SSRNN_FP8 weight buffer on the device (codes, padding, row
+    scales: the layout ssrnn_weight_bytes documents) with its logical shape."""
+
+    def __init__(self, buf, d: int, k: int):
+        import torch
+        if buf.dtype != torch.uint8 or buf.dim() != 1 or buf.numel() != weight_bytes(d, k, FP8):
+            raise ValueError(f"an 8-bit weight buffer for d={d}, k={k} is {weight_bytes(d, k, FP8)} bytes of uint8")
+        self.buf, self.d, self.k = buf, int(d), int(k)
+        self.shape = (3 * self.d, self.k * self.d)
+        self.is_cuda = buf.is_cuda
+
+    def data_ptr(self):
+        return self.buf.data_ptr()
+
+    def is_contiguous(self):
+        return self.buf.is_contiguous()
+
+    def dim(self):
+        return 2
+
+
 def pack_weights(W, stream=None):
     """ssrnn_pack_weights: returns a new device tensor of W's shape and dtype
     that holds the [3d, k*d] matrix in the matrix-core kernel's order; pass it
@@ -101,7 +129,7 @@ def pack_weights(W, stream=None):
         raise ValueError("W must be [3d, k*d]")
     k = W.shape[1] // d
     wdt = _wdtype(W)
-    out = torch.empty_like(W)
+    out = Fp8Weights(torch.empty_like(W.buf), d, k) if wdt == FP8 else torch.empty_like(W)
     _check(lib.ssrnn_pack_weights(_p(W), _p(out), d, k, wdt, _stream_handle(stream)))
     return out
 
@@ -121,6 +149,8 @@ def read_probe(buf, sink, stream=None) -> None:
 
 def _wdtype(w) -> int:
     import torch
+    if isinstance(w, Fp8Weights):
+        return FP8
     if w.dtype == torch.float32:
         return F32
     if w.dtype in (torch.bfloat16, torch.uint16, torch.int16):
@@ -148,7 +178,7 @@ def _req(t, name, shape=None, dtype=None):
         return
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError(f"{name} must be a contiguous device tensor")
-    if dtype is not None and t.dtype != dtype:
+    if dtype is not None and (isinstance(t, Fp8Weights) or t.dtype != dtype):
         raise TypeError(f"{name} must be {dtype}")
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")

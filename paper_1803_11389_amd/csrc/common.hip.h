@@ -9,7 +9,7 @@
 namespace ssrnn {
 
 enum Cell : int { CELL_SRU = 0, CELL_QRNN = 1 };
-enum WType : int { W_F32 = 0, W_BF16 = 1 };
+enum WType : int { W_F32 = 0, W_BF16 = 1, W_FP8 = 2 };
 
 // One (block, layer) stage: nt consecutive time steps of one layer.
 //
@@ -19,7 +19,8 @@ enum WType : int { W_F32 = 0, W_BF16 = 1 };
 // Eq. 3), so every row r >= -(k-1) is a plain load.
 //
 // The matrix-core kernels read the block through a second copy, the operand
-// copy (xop), in the weights' element type and in chunk-column-major order:
+// copy (xop), in the type the matrix cores multiply in (fp32 for fp32 weights,
+// bf16 for bf16 and 8-bit weights) and in chunk-column-major order:
 // the 16-byte chunk that holds columns [cc*VEC, (cc+1)*VEC) of row r (VEC = 4
 // fp32 or 8 bf16 values) lies at xop + (cc*ldt + r)*16 bytes, r >= -(k-1).  The
 // 16 lanes that hold the 16 time rows of one MFMA B fragment then read 256
@@ -28,6 +29,7 @@ enum WType : int { W_F32 = 0, W_BF16 = 1 };
 // the producing layer's epilogue otherwise) writes both copies.
 struct Stage {
   const void* W;           // [3d x k*d] row-major
+  const float* wscale;     // 8-bit weights: [3d] scale per weight row (pre-activation = scale * product); else null
   const float* bias;       // SRU [2d], QRNN [3d], or null
   const float* xcur;       // row r at xcur + r*ldx, r in [-(k-1), nt)
   const void* xop;         // operand copy of the same rows (chunk (0, row 0)), or null
@@ -59,9 +61,22 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
   return __uint_as_float(static_cast<uint32_t>(b) << 16);
 }
 
+// 8-bit weights are OCP FP8 E4M3 codes; the hardware's converters widen them exactly.
+typedef float ssrnn_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float fp8_to_f32(uint8_t b) {
+  return __builtin_amdgcn_cvt_f32_fp8(static_cast<uint32_t>(b), 0);
+}
+// The four codes of a 32-bit word, lowest address first.
+__device__ __forceinline__ float4 fp8x4_to_f32(uint32_t u) {
+  const ssrnn_f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(u, false);
+  const ssrnn_f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(u, true);
+  return make_float4(lo[0], lo[1], hi[0], hi[1]);
+}
+
 template <int WT>
 __device__ __forceinline__ float load_w(const void* W, size_t idx) {
-  if constexpr (WT == W_BF16) return bf16_to_f32(static_cast<const uint16_t*>(W)[idx]);
+  if constexpr (WT == W_FP8) return fp8_to_f32(static_cast<const uint8_t*>(W)[idx]);
+  else if constexpr (WT == W_BF16) return bf16_to_f32(static_cast<const uint16_t*>(W)[idx]);
   else return static_cast<const float*>(W)[idx];
 }
 

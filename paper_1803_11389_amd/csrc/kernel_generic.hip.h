@@ -1,4 +1,4 @@
-// Generic stage kernel: any d, k, T, either weight type.  One wavefront per
+// Generic stage kernel: any d, k, T, any weight type.  One wavefront per
 // output feature; its 64 lanes stride over the k*d columns of the feature's
 // three weight rows, eight time steps of the block at a time, then a
 // wave-level sum and the recurrence on lane 0.  It is the fallback for shapes
@@ -63,6 +63,11 @@ __global__ __launch_bounds__(GENERIC_WAVES * 64) void stage_generic_kernel(Stage
         if (s.bias) {
           if (CELL == CELL_SRU) { b1 = s.bias[i]; b2 = s.bias[d + i]; }
           else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
+        }
+        if (s.wscale) {
+          const float s0 = s.wscale[i], s1 = s.wscale[d + i], s2 = s.wscale[2 * d + i];
+#pragma unroll
+          for (int t = 0; t < GENERIC_TSUB; ++t) { a0[t] *= s0; a1[t] *= s1; a2[t] *= s2; }
         }
 #pragma unroll
         for (int t = 0; t < GENERIC_TSUB; ++t) {

@@ -2,7 +2,8 @@
 // Eq. 4 (arXiv 1803.11389) on MFMA, gates and recurrence of Eq. 2 / Eq. 3 fused
 // behind it.  fp32 weights use v_mfma_f32_16x16x4_f32; bf16 weights use
 // v_mfma_f32_16x16x32_bf16 on a bf16 copy of the input block, with fp32
-// accumulation.
+// accumulation; 8-bit (E4M3) weights are widened to bf16 in registers, exactly,
+// and take the bf16 path, their row scales being applied to the finished sums.
 //
 // Decomposition of one (block, layer) stage
 //   - a workgroup owns 16 consecutive features = three 16-row M tiles (the
@@ -48,6 +49,8 @@ template <>
 struct BFrag<W_F32> { float4 v[2]; };
 template <>
 struct BFrag<W_BF16> { bf16x8_t v[2]; };
+template <>
+struct BFrag<W_FP8> { bf16x8_t v[4]; };   // 32 columns per lane and k-step: four chunks of 8 bf16
 
 // Inclusive prefix scan of affine maps c -> a*c + b over groups of CT (16, 32
 // or 64) adjacent lanes, lane order = time order: afterwards (a, b) of a lane is
@@ -90,6 +93,7 @@ template <int NT, int NW>
 struct MfmaEpilogueOperands {
   static constexpr int EPT = (MfmaCfg<NT>::NTC * 256 + NW * 64 - 1) / (NW * 64);
   float b0, b1, b2;     // biases of feature tid % 16
+  float s0, s1, s2;     // 8-bit weights: row scales of that feature's three rows
   float c_old;          // s.c[f0 + tid] for tid < 16
   float xh[EPT];        // SRU: x_t of this thread's (feature, step) pairs of chunk 0
 };
@@ -106,6 +110,11 @@ __device__ __forceinline__ MfmaEpilogueOperands<NT, NW> mfma_epilogue_fetch(cons
     const int i = f0 + (tid & 15);
     if (CELL == CELL_SRU) { o.b1 = s.bias[i]; o.b2 = s.bias[d + i]; }
     else { o.b0 = s.bias[i]; o.b1 = s.bias[d + i]; o.b2 = s.bias[2 * d + i]; }
+  }
+  o.s0 = o.s1 = o.s2 = 1.0f;
+  if (s.wscale) {
+    const int i = f0 + (tid & 15);
+    o.s0 = s.wscale[i]; o.s1 = s.wscale[d + i]; o.s2 = s.wscale[2 * d + i];
   }
   o.c_old = (tid < MFMA_F) ? s.c[f0 + tid] : 0.0f;
   const int tl = tid % CT;
@@ -141,6 +150,7 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
   constexpr int CT = NTC * 16;
   constexpr int TS = CT + 1;                   // padded row of the transposed arrays
   const float b0 = ops.b0, b1 = ops.b1, b2 = ops.b2;   // biases of the feature this thread handles in phase B
+  const bool scaled = s.wscale != nullptr;             // 8-bit weights: u = scale * sum + bias
   if (tid < MFMA_F) c_carry[tid] = ops.c_old;
   const int tl = tid % CT;                     // step within the chunk in phase C (NTH is a multiple of CT)
 
@@ -171,7 +181,7 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
       for (int it = 0; it < EPT; ++it) {
         const int e = tid + it * NTH;                     // e = local time * 16 + feature
         if (e < CHUNK) {
-          float u0 = b0, u1 = b1, u2 = b2;
+          float u0 = scaled ? 0.0f : b0, u1 = scaled ? 0.0f : b1, u2 = scaled ? 0.0f : b2;
           const int q = e >> 8, r = e & 255;
 #pragma unroll
           for (int w = 0; w < NW; ++w) {
@@ -179,6 +189,7 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
             u1 += part[((w * 3 + 1) * NTC + q) * 256 + r];
             u2 += part[((w * 3 + 2) * NTC + q) * 256 + r];
           }
+          if (scaled) { u0 = fmaf(u0, ops.s0, b0); u1 = fmaf(u1, ops.s1, b1); u2 = fmaf(u2, ops.s2, b2); }
           const float f = sigmoidf_fast(u1);
           const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
           const int at = (e & 15) * TS + (e >> 4);
@@ -279,18 +290,22 @@ __global__ __launch_bounds__(512) void split_epilogue_kernel(Stage s, int d, int
     if (CELL == CELL_SRU) { b1 = s.bias[i]; b2 = s.bias[d + i]; }
     else { b0 = s.bias[i]; b1 = s.bias[d + i]; b2 = s.bias[2 * d + i]; }
   }
+  const bool scaled = s.wscale != nullptr;               // 8-bit weights: u = scale * sum + bias
+  float sc0 = 1.f, sc1 = 1.f, sc2 = 1.f;
+  if (scaled) { sc0 = s.wscale[i]; sc1 = s.wscale[d + i]; sc2 = s.wscale[2 * d + i]; }
   float cin = s.c[i];
   const long plane = static_cast<long>(s.tp) * d;
   for (int t0 = 0; t0 < s.nt; t0 += 32) {
     const int t = t0 + tl;
     const int tr = min(t, s.nt - 1);                     // rows past the end repeat the last one and are not written
-    float u0 = b0, u1 = b1, u2 = b2;
+    float u0 = scaled ? 0.0f : b0, u1 = scaled ? 0.0f : b1, u2 = scaled ? 0.0f : b2;
     for (int p = 0; p < s.ksplit; ++p) {
       const long at = static_cast<long>(i) * s.tp + tr;
       u0 += s.upart[(p * 3 + 0) * plane + at];
       u1 += s.upart[(p * 3 + 1) * plane + at];
       u2 += s.upart[(p * 3 + 2) * plane + at];
     }
+    if (scaled) { u0 = fmaf(u0, sc0, b0); u1 = fmaf(u1, sc1, b1); u2 = fmaf(u2, sc2, b2); }
     const float f = sigmoidf_fast(u1);
     const float o = sigmoidf_fast(u2);
     const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);

@@ -11,7 +11,11 @@
 // so that every load instruction of a wave reads one contiguous KiB (eight
 // whole cache lines, non-temporal) straight into the registers an MFMA takes
 // as its A operand: no LDS staging, no split lines.  A workgroup's weights are
-// one contiguous slab and a wave walks a contiguous piece of it.
+// one contiguous slab and a wave walks a contiguous piece of it.  The layout is
+// stated in bytes and is the same for 4-, 2- and 1-byte weights; a lane's 32
+// bytes of a k-step are 8 fp32, 16 bf16 or 32 E4M3 columns.  E4M3 fragments are
+// widened to bf16 in registers (exactly: 3 mantissa bits into 7), eight codes
+// per MFMA, right before the multiply.
 //
 // Pipeline: a ring of SA register slots holds the fragments of SA-1 future
 // k-steps; a ring of SB slots holds the input-block (B) fragments of SB-1
@@ -29,12 +33,14 @@ namespace ssrnn {
 
 // Four waves per workgroup, one per SIMD: a wave then has the SIMD's matrix pipe to itself.  Two waves per
 // SIMD measured slower from T = 32 on (fp32, T = 32: 43.5 -> 38.6 us per stage; T = 64: 66.7 -> 58.1 us).
-template <int NT>
+// An 8-bit k-step holds twice the columns of a bf16 one, so its B fragments take twice the registers per
+// time tile: its B ring is shorter and fetches fewer tiles at a time.
+template <int NT, int WT = W_F32>
 struct MfmaPkCfg {
   static constexpr int NW = 4;                            // waves per workgroup
   static constexpr int SA = 4;                            // weight fragment ring slots (k-steps)
-  static constexpr int SB = (NT <= 4) ? 4 : 2;            // B fragment ring slots (sub-steps)
-  static constexpr int NBT = (NT > 8) ? 8 : NT;           // time tiles per B fetch
+  static constexpr int SB = (WT == W_FP8) ? ((NT <= 1) ? 4 : 2) : ((NT <= 4) ? 4 : 2);   // B fragment ring slots (sub-steps)
+  static constexpr int NBT = (WT == W_FP8) ? ((NT > 4) ? 4 : NT) : ((NT > 8) ? 8 : NT);   // time tiles per B fetch
 };
 
 // One thread per 16-byte chunk of the packed matrix (see the layout above).
@@ -53,16 +59,26 @@ __global__ void pack_weights_kernel(const uint4* __restrict__ src, uint4* __rest
   dst[o] = src[row * row_chunks + static_cast<long>(s) * 8 + (lane >> 4) * 2 + half];
 }
 
+// Eight E4M3 codes (two 32-bit words, lowest address first) as eight bf16 values.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x8_t fp8x8_to_bf16(uint32_t w0, uint32_t w1) {
+  const bf16x2_t a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, false);
+  const bf16x2_t b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, true);
+  const bf16x2_t c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, false);
+  const bf16x2_t e = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, true);
+  return bf16x8_t{a[0], a[1], b[0], b[1], c[0], c[1], e[0], e[1]};
+}
+
 template <int CELL, int WT, int NT>
 __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kernel(Stage s, int d, int k) {
-  constexpr int NW = MfmaPkCfg<NT>::NW;
+  constexpr int NW = MfmaPkCfg<NT, WT>::NW;
   constexpr int NTC = MfmaCfg<NT>::NTC;
-  constexpr int KSTEP = (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
+  constexpr int KSTEP = (WT == W_FP8) ? 128 : (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
   constexpr int CW = KSTEP / 4;                      // columns per lane per step (32 bytes)
   constexpr int CHUNK = NTC * 256;
-  constexpr int SA = MfmaPkCfg<NT>::SA;
-  constexpr int SB = MfmaPkCfg<NT>::SB;
-  constexpr int NBT = MfmaPkCfg<NT>::NBT;
+  constexpr int SA = MfmaPkCfg<NT, WT>::SA;
+  constexpr int SB = MfmaPkCfg<NT, WT>::SB;
+  constexpr int NBT = MfmaPkCfg<NT, WT>::NBT;
   constexpr int NBH = NT / NBT;                      // sub-steps per k-step
   constexpr int U = (SA > SB) ? SA : SB;             // k-steps per unrolled iteration
   static_assert(U % SA == 0 && (U * NBH) % SB == 0 && SB - 1 <= U * NBH, "ring sizes must repeat with the unrolled body");
@@ -105,7 +121,8 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   // B side: this lane's time row in each tile, as a byte offset within a chunk column of the operand
   // copy.  Rows past the end of a short block repeat its last row; the columns they produce are never
   // read out.
-  constexpr int VEC = CW / 2;                        // elements per 16-byte chunk
+  constexpr int VEC = (WT == W_F32) ? 4 : 8;         // elements per 16-byte chunk of the operand copy
+  constexpr int NPC = CW / VEC;                      // B pieces per lane, k-step and time tile (2; 4 for 8-bit weights)
   int brow[NT];
 #pragma unroll
   for (int n = 0; n < NT; ++n) brow[n] = min(n * 16 + li, s.nt - 1) * 16;
@@ -123,19 +140,28 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   auto load_a_frag = [&](int slot, int i) {
     aring[slot][i] = load_stream16(aptr + static_cast<size_t>(a_ks) * 6144 + i * 1024);
   };
-  auto load_b_piece = [&](int slot, int tile0, int i) {      // i = (tile - tile0) * 2 + half
-    const int n = i >> 1, h = i & 1;
+  auto load_b_piece = [&](int slot, int tile0, int i) {      // i = (tile - tile0) * NPC + piece
+    const int n = i / NPC, h = i % NPC;
     const char* src = xop + b_off + h * ldtb + brow[tile0 + n];
-    if constexpr (WT == W_BF16) bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(src);
-    else bring[slot][n].v[h] = *reinterpret_cast<const float4*>(src);
+    if constexpr (WT == W_F32) bring[slot][n].v[h] = *reinterpret_cast<const float4*>(src);
+    else bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(src);
   };
-  auto advance_b = [&]() {                        // one k-step = 8 chunk columns further
+  auto advance_b = [&]() {                        // one k-step = KSTEP / VEC chunk columns further
     b_m += KSTEP;
-    b_off += 8 * ldtb;
+    b_off += (KSTEP / VEC) * ldtb;
     if (b_m >= d) { b_m -= d; ++b_j; b_off -= static_cast<long>(d / VEC) * ldtb + 16; }
   };
   auto mfma_group = [&](int aslot, int bslot, int tile0, int grp) {
-    if constexpr (WT == W_BF16) {
+    if constexpr (WT == W_FP8) {
+      // piece q = bytes [q*8, q*8+8) of the lane's 32 bytes of this k-step: the half q/2 of the fragment pair,
+      // words (q%2)*2 and (q%2)*2+1 of it
+      const int q = grp / 3, g = grp - 3 * (grp / 3);
+      const floatx4_t a4 = aring[aslot][g * 2 + (q >> 1)];
+      const bf16x8_t ab = fp8x8_to_bf16(__float_as_uint(a4[(q & 1) * 2]), __float_as_uint(a4[(q & 1) * 2 + 1]));
+#pragma unroll
+      for (int n = 0; n < NBT; ++n)
+        acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[q], acc[g][tile0 + n], 0, 0, 0);
+    } else if constexpr (WT == W_BF16) {
       const int h = grp / 3, g = grp - 3 * (grp / 3);
       bf16x8_t ab;
       __builtin_memcpy(&ab, &aring[aslot][g * 2 + h], sizeof ab);
@@ -157,7 +183,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
     }
   };
 
-  constexpr int NGRP = (WT == W_BF16) ? 6 : 8;          // MFMA groups per sub-step
+  constexpr int NGRP = (WT == W_FP8) ? 12 : (WT == W_BF16) ? 6 : 8;          // MFMA groups per sub-step
   // One k-step at ring position p.  Step ks multiplies the fragments in aring[ks % SA] with the B
   // fragments of its NBH sub-steps (sub-step ss = ks*NBH + hb sits in bring[ss % SB]).  Meanwhile the
   // slot step ks-1 has just left is refilled with step ks+SA-1, and the B pieces of sub-step ss+SB-1
@@ -179,7 +205,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
       // Loads complete in issue order (one counter per wave), so they are issued in the order they are
       // needed: the B pieces of the next sub-steps first, the weight fragments of the far k-step after
       // them.  The other order would make the wait for the B pieces a wait for the weight prefetch too.
-      const int n_b = 2 * NBT;
+      const int n_b = NPC * NBT;
       const int nitem = n_b + ((hb == 0) ? 6 : 0);              // weight fragments ride on the first sub-step
 #pragma unroll
       for (int grp = 0; grp < NGRP; ++grp) {
@@ -215,7 +241,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
 #pragma unroll
     for (int ss = 0; ss < SB - 1; ++ss) {
 #pragma unroll
-      for (int i = 0; i < 2 * NBT; ++i) load_b_piece(ss % SB, (ss % NBH) * NBT, i);
+      for (int i = 0; i < NPC * NBT; ++i) load_b_piece(ss % SB, (ss % NBH) * NBT, i);
       if (ss % NBH == NBH - 1) advance_b();
     }
     for (int ks0 = 0; ks0 < nks - U; ks0 += U) pipeline_iteration(std::false_type{});
@@ -236,7 +262,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
 #pragma unroll
     for (int hb = 0; hb < NBH; ++hb) {
 #pragma unroll
-      for (int i = 0; i < 2 * NBT; ++i) load_b_piece(0, hb * NBT, i);
+      for (int i = 0; i < NPC * NBT; ++i) load_b_piece(0, hb * NBT, i);
 #pragma unroll
       for (int grp = 0; grp < NGRP; ++grp) mfma_group(0, 0, hb * NBT, grp);
     }

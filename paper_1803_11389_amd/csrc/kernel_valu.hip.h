@@ -1,5 +1,5 @@
 // Bandwidth kernel for short blocks (T <= 16 with fp32 weights, T <= 8 with
-// bfloat16 weights, which are widened to fp32 in registers): the skinny product
+// bfloat16 or 8-bit weights, which are widened to fp32 in registers): the skinny product
 // U = W * X of Eq. 4 (arXiv 1803.11389) on the vector ALU, with the gates and
 // the recurrence of Eq. 2 / Eq. 3 fused behind it.
 //
@@ -8,7 +8,7 @@
 //     2d+i of W for those features; it is the only reader of those rows, so
 //     every weight leaves HBM exactly once per block;
 //   - the NW wavefronts of the workgroup split the k*d columns: in pass p,
-//     wave w covers NV chunks of 256 (fp32) or 512 (bf16) consecutive columns,
+//     wave w covers NV chunks of 256 (fp32), 512 (bf16) or 1024 (8-bit) consecutive columns,
 //     lane l 16 consecutive bytes of each chunk, so one wave-wide load
 //     instruction reads 1 KiB of one row contiguously (global_load_dwordx4);
 //   - the wave's slice of the input block X (4*NV columns x TT steps per lane)
@@ -120,16 +120,18 @@ __device__ __forceinline__ int butterfly_index(int lane) {
 
 // MP = false: one pass covers all k*d columns (npass == 1), X stays in registers.
 // MP = true: several passes; X is re-read (from cache) per feature group and pass.
-// WT: weights are fp32 (a 16-byte load = 4 columns per lane, 256 per wave) or
-// bfloat16 bit patterns (8 columns per lane, 512 per wave; widened to fp32 in
-// registers, so that the input block and every product stay fp32).
+// WT: weights are fp32 (a 16-byte load = 4 columns per lane, 256 per wave),
+// bfloat16 bit patterns (8 columns per lane, 512 per wave) or E4M3 codes (16
+// columns per lane, 1024 per wave; their row scales are applied to the finished
+// sums); the narrow types are widened to fp32 in registers, so that the input
+// block and every product stay fp32.
 template <int CELL, int WT, int TT, int NV, bool MP>
 __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s, int d, int k, int F, int npass_arg) {
   const int npass = MP ? npass_arg : 1;
-  constexpr int CPL = (WT == W_BF16) ? 8 : 4;     // columns per lane per 16-byte load
+  constexpr int CPL = (WT == W_FP8) ? 16 : (WT == W_BF16) ? 8 : 4;     // columns per lane per 16-byte load
   constexpr int CHW = 64 * CPL;                   // columns per wave-wide load
   constexpr int XQ = CPL / 4;                     // float4 pieces of X per lane and chunk
-  constexpr int ESIZE = (WT == W_BF16) ? 2 : 4;
+  constexpr int ESIZE = (WT == W_FP8) ? 1 : (WT == W_BF16) ? 2 : 4;
   constexpr int FG = valu_fg(TT);
   constexpr int VB = FG * TT;                // values per gate entering the butterfly
   extern __shared__ float part[];            // [NW][3][F][TT]
@@ -146,11 +148,13 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
   // fetched now, so their latency hides behind the weight stream instead of
   // sitting in the kernel's tail.
   float ep_c = 0.f, ep_x = 0.f, ep_b0 = 0.f, ep_b1 = 0.f, ep_b2 = 0.f;
+  float ep_s0 = 1.f, ep_s1 = 1.f, ep_s2 = 1.f;
   if (static_cast<int>(threadIdx.x) < F * TT) {
     const int e = threadIdx.x / TT;
     const int t = threadIdx.x - e * TT;
     const int i = f0 + e;
     ep_c = s.c[i];
+    if (WT == W_FP8 && s.wscale) { ep_s0 = s.wscale[i]; ep_s1 = s.wscale[d + i]; ep_s2 = s.wscale[2 * d + i]; }
     if (s.bias) {
       if (CELL == CELL_SRU) { ep_b1 = s.bias[i]; ep_b2 = s.bias[d + i]; }
       else { ep_b0 = s.bias[i]; ep_b1 = s.bias[d + i]; ep_b2 = s.bias[2 * d + i]; }
@@ -208,7 +212,10 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
           float4 wq[XQ];
-          if constexpr (WT == W_BF16) {
+          if constexpr (WT == W_FP8) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) wq[q % XQ] = fp8x4_to_f32(__float_as_uint(w[gate][f][v][q]));
+          } else if constexpr (WT == W_BF16) {
             // a 32-bit word holds two bfloat16 weights: the lower half is the column at the lower address
             const uint32_t u0 = __float_as_uint(w[gate][f][v][0]), u1 = __float_as_uint(w[gate][f][v][1]);
             const uint32_t u2 = __float_as_uint(w[gate][f][v][2]), u3 = __float_as_uint(w[gate][f][v][3]);
@@ -268,6 +275,10 @@ __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(Stage s
       u2 += part[((w * 3 + 2) * F + e) * TT + t];
     }
     const bool first = id == static_cast<int>(threadIdx.x);     // operands fetched at kernel start
+    if (WT == W_FP8 && s.wscale) {
+      if (first) { u0 *= ep_s0; u1 *= ep_s1; u2 *= ep_s2; }
+      else { u0 *= s.wscale[i]; u1 *= s.wscale[d + i]; u2 *= s.wscale[2 * d + i]; }
+    }
     if (first) { u0 += ep_b0; u1 += ep_b1; u2 += ep_b2; }
     else if (s.bias) {
       if (CELL == CELL_SRU) { u1 += s.bias[i]; u2 += s.bias[d + i]; }

@@ -83,7 +83,7 @@ WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
   // in different halves of a cache line pair.
   const int tcap = T < MFMA_MAX_T ? T : MFMA_MAX_T;
   w.ldt = (k - 1 + tcap + 7) / 8 * 8 + 4;
-  const size_t esize = (wdt == SSRNN_BF16) ? 2 : 4;
+  const size_t esize = (wdt == SSRNN_F32) ? 4 : 2;   // bf16 and 8-bit weights multiply a bf16 copy
   w.op_stride = (d % MFMA_F == 0) ? align_up(static_cast<size_t>(d) * esize / 16 * w.ldt * 16, WS_ALIGN) : 0;
   w.op_offset = w.act_offset + static_cast<size_t>(n_layers) * w.act_stride;
   w.upart_offset = w.op_offset + static_cast<size_t>(n_layers) * w.op_stride;
@@ -99,13 +99,23 @@ WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
 
 bool shape_ok(int n_layers, int d, int k, int T, int wdt) {
   if (n_layers < 1 || d < 1 || k < 1 || T < 1) return false;
-  if (wdt != SSRNN_F32 && wdt != SSRNN_BF16) return false;
+  if (wdt != SSRNN_F32 && wdt != SSRNN_BF16 && wdt != SSRNN_FP8) return false;
   if (static_cast<long long>(k) * d > (1LL << 24)) return false;          // 3d * k*d must index in size_t comfortably
   if (static_cast<long long>(k - 1 + T) * d > (1LL << 40)) return false;
   return true;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t weight_esize(int wdt) { return wdt == SSRNN_F32 ? 4 : wdt == SSRNN_BF16 ? 2 : 1; }
+
+// 8-bit weights: the fp32 row scales follow the [3d x k*d] codes at the next multiple of 256 bytes.
+size_t fp8_scale_offset(int d, int k) { return align_up(static_cast<size_t>(3) * d * k * d, 256); }
+
+size_t weight_buffer_bytes(int d, int k, int wdt) {
+  if (wdt == SSRNN_FP8) return fp8_scale_offset(d, k) + static_cast<size_t>(3) * d * sizeof(float);
+  return static_cast<size_t>(3) * d * k * d * weight_esize(wdt);
+}
 
 // ------------------------------------------------------------ small kernels
 
@@ -192,6 +202,11 @@ __global__ void stage_input_vec_kernel(const float* x, const float* xhist_init, 
   }
 }
 
+__global__ void copy_scales_kernel(const float* src, float* dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
 __global__ void copy_history_kernel(const float* src, float* dst, long n) {
   const long i = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
   if (i < n) dst[i] = src ? src[i] : 0.0f;
@@ -259,9 +274,9 @@ long long g_tune_spin_limit = 0;   // 0 = default (one second); otherwise wall-c
 int g_tune_ksplit = 0;     // 0 = default, 1 = never split, 2/4/8 = at most that many parts
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
-  // a wave-wide 16-byte load covers 256 fp32 or 512 bf16 columns; bf16 weights are taken up to T = 8
-  const int chw = p.wdt == SSRNN_BF16 ? 512 : 256;
-  if (p.T > (p.wdt == SSRNN_BF16 ? 8 : VALU_MAX_T) || p.d % chw != 0) return false;
+  // a wave-wide 16-byte load covers 256 fp32, 512 bf16 or 1024 8-bit columns; the narrow types are taken up to T = 8
+  const int chw = 1024 / static_cast<int>(weight_esize(p.wdt));
+  if (p.T > (p.wdt == SSRNN_F32 ? VALU_MAX_T : 8) || p.d % chw != 0) return false;
   if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
   for (int l = 0; l < p.n_layers; ++l)
     if (!aligned16(W[l])) return false;
@@ -270,6 +285,7 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
   const int q = p.k * p.d / chw;
   p.nv = (q % 2 == 0 && q >= 16) ? 2 : 1;
   if (g_tune_valu_nv == 1 || (g_tune_valu_nv == 2 && q % 2 == 0)) p.nv = g_tune_valu_nv;
+  if (p.wdt == SSRNN_FP8) p.nv = 1;   // 16 columns per lane and chunk already: one chunk per lane
   const int qq = q / p.nv;
   p.nw = 1;
   for (int w = 1; w <= VALU_MAX_WAVES; ++w)
@@ -283,6 +299,7 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
   // with 512; from T = 3 on the single-item workgroups lose, 39 us).
   int wg_target = (p.d < 4096 || p.tt > 8 || p.one_wg_per_cu) ? 256 : (p.tt <= 2 ? 2048 : 512);
   if (p.wdt == SSRNN_BF16 && wg_target > 256) wg_target /= 2;   // half the bytes per feature: twice the features
+  if (p.wdt == SSRNN_FP8 && wg_target > 256) wg_target = wg_target / 4 > 256 ? wg_target / 4 : 256;
   int F = 0;
   for (int f = fg; f <= 64; f += fg)
     if (p.d % f == 0 && f * wg_target >= p.d) { F = f; break; }
@@ -308,6 +325,14 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
           hipLaunchKernelGGL((stage_valu_kernel<CELL, W_BF16, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
         return SSRNN_OK;                                                                   \
       }                                                                                    \
+    } else if (p.wdt == SSRNN_FP8) {                                                       \
+      if constexpr (TT_ <= 8 && NV_ == 1) {                                                \
+        if (p.npass == 1)                                                                  \
+          hipLaunchKernelGGL((stage_valu_kernel<CELL, W_FP8, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
+        else                                                                               \
+          hipLaunchKernelGGL((stage_valu_kernel<CELL, W_FP8, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
+        return SSRNN_OK;                                                                   \
+      }                                                                                    \
     } else {                                                                               \
       if (p.npass == 1)                                                                    \
         hipLaunchKernelGGL((stage_valu_kernel<CELL, W_F32, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
@@ -326,6 +351,9 @@ int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
 // 16-tile fp32 instance does not fit the register file, so row-major fp32 weights stop at 8 tiles.
 int mfma_block_cap(int wdt, bool packed) { return (wdt == SSRNN_F32 && !packed) ? MFMA_MAX_T / 2 : MFMA_MAX_T; }
 
+// Columns per k-step of the matrix-core kernels: 128 bytes of a weight row.
+int mfma_kstep(int wdt) { return 128 / static_cast<int>(weight_esize(wdt)); }
+
 // Waves per workgroup of the matrix-core kernel that takes this block length and weight layout.
 int mfma_waves(int nt_tiles, bool packed) {
   switch (nt_tiles) {
@@ -339,21 +367,20 @@ int mfma_waves(int nt_tiles, bool packed) {
 
 // Shapes ssrnn_pack_weights takes: whole 16-feature tiles, and k-steps of 128 bytes that never straddle lag blocks.
 bool pack_shape_ok(int d, int k, int wdt) {
-  if (wdt != SSRNN_F32 && wdt != SSRNN_BF16) return false;
   if (d < 1 || k < 1 || !shape_ok(1, d, k, 1, wdt)) return false;
-  const int kstep = wdt == SSRNN_BF16 ? 64 : 32;
-  return d % MFMA_F == 0 && d % kstep == 0;
+  return d % MFMA_F == 0 && d % mfma_kstep(wdt) == 0;
 }
 
 bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
   if (p.d % MFMA_F != 0 || p.T > mfma_block_cap(p.wdt, p.packed)) return false;
+  if (p.wdt == SSRNN_FP8 && !p.packed) return false;   // 8-bit weights reach the matrix cores in packed form only
   if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
   for (int l = 0; l < p.n_layers; ++l)
     if (!aligned16(W[l])) return false;
   const int tiles = (p.T + 15) / 16;
   p.nt_tiles = tiles <= 1 ? 1 : tiles <= 2 ? 2 : tiles <= 4 ? 4 : tiles <= 8 ? 8 : 16;
   const int nw = mfma_waves(p.nt_tiles, p.packed);
-  const int kstep = p.wdt == SSRNN_BF16 ? 64 : 32;
+  const int kstep = mfma_kstep(p.wdt);
   const long ncol = static_cast<long>(p.k) * p.d;
   if (ncol % (nw * kstep) != 0) return false;
   if (p.d % kstep != 0) return false;   // a k-step never straddles two lag blocks
@@ -430,7 +457,9 @@ int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
 #define SSRNN_MFMA_CASE(NT_)                                                                              \
   if (p.nt_tiles == NT_) {                                                                                \
     if (p.packed) {                                                                                       \
-      if (p.wdt == SSRNN_BF16)                                                                            \
+      if (p.wdt == SSRNN_FP8)                                                                             \
+        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_FP8, NT_>), grid, block, 0, st, s, p.d, p.k); \
+      else if (p.wdt == SSRNN_BF16)                                                                       \
         hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k); \
       else                                                                                                \
         hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k); \
@@ -454,7 +483,9 @@ template <int CELL>
 int launch_generic(const Plan& p, const Stage& s, hipStream_t st) {
   const int grid = (p.d + GENERIC_WAVES - 1) / GENERIC_WAVES;
   const dim3 g(grid < 4096 ? grid : 4096), b(GENERIC_WAVES * 64);
-  if (p.wdt == SSRNN_BF16)
+  if (p.wdt == SSRNN_FP8)
+    hipLaunchKernelGGL((stage_generic_kernel<CELL, W_FP8>), g, b, 0, st, s, p.d, p.k);
+  else if (p.wdt == SSRNN_BF16)
     hipLaunchKernelGGL((stage_generic_kernel<CELL, W_BF16>), g, b, 0, st, s, p.d, p.k);
   else
     hipLaunchKernelGGL((stage_generic_kernel<CELL, W_F32>), g, b, 0, st, s, p.d, p.k);
@@ -480,7 +511,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   if (n_layers < 1 || d < 1 || L < 0 || T < 1 || k < 1)
     return fail(SSRNN_EINVAL, "%s: need n_layers >= 1, d >= 1, L >= 0, T >= 1, k >= 1 (got %d, %d, %ld, %d, %d)",
                 name, n_layers, d, L, T, k);
-  if (wdt != SSRNN_F32 && wdt != SSRNN_BF16) return fail(SSRNN_EINVAL, "%s: unknown weight type %d", name, wdt);
+  if (wdt != SSRNN_F32 && wdt != SSRNN_BF16 && wdt != SSRNN_FP8) return fail(SSRNN_EINVAL, "%s: unknown weight type %d", name, wdt);
   if (!shape_ok(n_layers, d, k, T, wdt)) return fail(SSRNN_EUNSUPPORTED, "%s: shape too large", name);
   if (L > 0 && (!x || !h)) return fail(SSRNN_EINVAL, "%s: x and h are required when L > 0", name);
   for (int l = 0; l < n_layers; ++l)
@@ -530,7 +561,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       return fail(SSRNN_EUNSUPPORTED, "%s: the persistent schedule runs the vector-ALU kernel on row-major weights", name);
     p.one_wg_per_cu = true;
     if (!plan_valu(p, W, x, xhist_init, workspace))
-      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs T <= 16 and d %% 256 == 0 (fp32 weights) or T <= 8 and d %% 512 == 0 (bf16 weights), and 16-byte aligned buffers", name);
+      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs T <= 16 and d %% 256 == 0 (fp32 weights) or T <= 8 and d %% 512 == 0 (bf16) or d %% 1024 == 0 (8-bit), and 16-byte aligned buffers", name);
     p.kind = K_VALU;
     // c_final already holds the initial state (init_state_kernel above)
     return launch_persistent(p, W, bias, x, c_final, h, c_final, workspace, wl, st);
@@ -539,12 +570,12 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   if (!packed && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU)) {
     valu_ok = plan_valu(p, W, x, xhist_init, workspace);
     if (!valu_ok && kforce == SSRNN_KERNEL_VALU)
-      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs T <= 16 and d %% 256 == 0 (fp32 weights) or T <= 8 and d %% 512 == 0 (bf16 weights), and 16-byte aligned buffers", name);
+      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs T <= 16 and d %% 256 == 0 (fp32 weights) or T <= 8 and d %% 512 == 0 (bf16) or d %% 1024 == 0 (8-bit), and 16-byte aligned buffers", name);
   }
   // bf16 weights: the vector-ALU kernel (weights widened in registers, input block exact) wins up to T = 2
   // (17.1 against 18.4 us per stage at d = 4096, T = 1); beyond that its conversions and FMAs no longer hide
   const bool prefer_mfma = kforce == SSRNN_KERNEL_AUTO &&
-                           (wdt == SSRNN_BF16 ? T > 2 : (T > 4 && d / MFMA_F >= 256));
+                           (wdt != SSRNN_F32 ? T > 2 : (T > 4 && d / MFMA_F >= 256));
   if (valu_ok && !prefer_mfma) p.kind = K_VALU;
   if (p.kind == K_GENERIC && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_MFMA)) {
     // the matrix-core kernels accumulate a bounded number of steps per weight pass: longer blocks are cut
@@ -554,7 +585,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     else {
       p.T = T;
       if (kforce == SSRNN_KERNEL_MFMA || packed)
-        return fail(SSRNN_EUNSUPPORTED, "%s: matrix-core kernel needs d %% 16 == 0, k*d %% 256 == 0 and 16-byte aligned buffers", name);
+        return fail(SSRNN_EUNSUPPORTED, "%s: matrix-core kernel needs d %% 16 == 0, k*d %% 256 == 0 (512 for 8-bit weights, which it takes in packed form only) and 16-byte aligned buffers", name);
       if (valu_ok) p.kind = K_VALU;
     }
   }
@@ -562,7 +593,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   char* act0 = static_cast<char*>(workspace) + wl.act_offset;
   char* op0 = static_cast<char*>(workspace) + wl.op_offset;
   const bool use_op = (p.kind == K_MFMA);
-  const int op_bf16 = (wdt == SSRNN_BF16) ? 1 : 0;
+  const int op_bf16 = (wdt == SSRNN_F32) ? 0 : 1;
   const bool stage_in = (k > 1) || p.kind == K_MFMA;   // the matrix-core kernel wants padded rows
   auto act = [&](int b) { return reinterpret_cast<float*>(act0 + static_cast<size_t>(b) * wl.act_stride) + static_cast<long>(k - 1) * wl.ld; };
   auto opbuf = [&](int b) { return static_cast<void*>(op0 + static_cast<size_t>(b) * wl.op_stride + static_cast<size_t>(k - 1) * 16); };
@@ -587,6 +618,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     for (int l = 0; l < n_layers; ++l) {
       Stage s{};
       s.W = W[l];
+      s.wscale = (wdt == SSRNN_FP8) ? reinterpret_cast<const float*>(static_cast<const char*>(W[l]) + fp8_scale_offset(d, k)) : nullptr;
       s.bias = (bias && bias[l]) ? bias[l] : nullptr;
       if (l == 0 && !stage_in) {
         s.xcur = x + t0 * d;
@@ -668,9 +700,14 @@ int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
   return SSRNN_OK;
 }
 
+size_t ssrnn_weight_bytes(int d, int k, int wdtype) {
+  if (d < 1 || k < 1 || !shape_ok(1, d, k, 1, wdtype)) return 0;
+  return weight_buffer_bytes(d, k, wdtype);
+}
+
 size_t ssrnn_packed_weight_bytes(int d, int k, int wdtype) {
   if (!pack_shape_ok(d, k, wdtype)) return 0;
-  return static_cast<size_t>(3) * d * k * d * (wdtype == SSRNN_BF16 ? 2 : 4);
+  return weight_buffer_bytes(d, k, wdtype);
 }
 
 int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype, void* stream) {
@@ -679,12 +716,18 @@ int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype, 
   if (!aligned16(W) || !aligned16(W_packed)) return fail(SSRNN_EINVAL, "ssrnn_pack_weights: buffers must be 16-byte aligned");
   if (!pack_shape_ok(d, k, wdtype))
     return fail(SSRNN_EUNSUPPORTED, "ssrnn_pack_weights: needs d %% 16 == 0 and rows of whole 128-byte k-steps within a lag block");
-  const int esize = wdtype == SSRNN_BF16 ? 2 : 4;
+  const int esize = static_cast<int>(weight_esize(wdtype));
   const long row_chunks = static_cast<long>(k) * d * esize / 16;
   const int nks_total = static_cast<int>(row_chunks / 8);
   const long nchunks = 3L * d * row_chunks;
   hipLaunchKernelGGL(pack_weights_kernel, dim3((nchunks + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const uint4*>(W), static_cast<uint4*>(W_packed), d, row_chunks, nks_total, nchunks);
+  if (wdtype == SSRNN_FP8) {
+    const size_t off = fp8_scale_offset(d, k);
+    hipLaunchKernelGGL(copy_scales_kernel, dim3((3 * d + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<const float*>(static_cast<const char*>(W) + off),
+                       reinterpret_cast<float*>(static_cast<char*>(W_packed) + off), 3 * d);
+  }
   HIP_TRY(hipGetLastError());
   return SSRNN_OK;
 }

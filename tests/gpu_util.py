@@ -11,10 +11,21 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+def weight_to_dev(w):
+    """A weight matrix on the device: float32 / uint16 arrays as they are, 8-bit
+    weights (codes + row scales) as the library's single buffer."""
+    import paper_1803_11389_amd as ss
+    if hasattr(w, "blob"):
+        rows, cols = w.q.shape
+        d = rows // 3
+        return ss.Fp8Weights(to_dev(w.blob()), d, cols // d)
+    return to_dev(w)
+
+
 def _weights(W, packed):
     """Device copies of the weight matrices; packed: re-tiled by ssrnn_pack_weights."""
     import paper_1803_11389_amd as ss
-    Wd = [to_dev(w) for w in W]
+    Wd = [weight_to_dev(w) for w in W]
     return [ss.pack_weights(w) for w in Wd] if packed else Wd
 
 

@@ -79,6 +79,15 @@ def test_bad_arguments_fail_on_the_host(lib):
     assert ss.packed_weight_bytes(128, 2, ss.F32) == 3 * 128 * 256 * 4
     assert ss.packed_weight_bytes(1024, 1, ss.BF16) == 3 * 1024 * 1024 * 2
     assert ss.packed_weight_bytes(100, 1, ss.F32) == 0 and ss.packed_weight_bytes(32, 1, ss.BF16) == 0
+    # 8-bit weights: codes, padding to 256 bytes, one fp32 scale per row
+    assert ss.weight_bytes(128, 1, ss.FP8) == 3 * 128 * 128 + 12 * 128
+    assert ss.weight_bytes(10, 1, ss.FP8) == 512 + 120                      # 300 codes are padded to 512
+    assert ss.weight_bytes(128, 2, ss.F32) == 3 * 128 * 256 * 4 and ss.weight_bytes(64, 1, ss.BF16) == 3 * 64 * 64 * 2
+    assert ss.weight_bytes(0, 1, ss.FP8) == 0 and ss.weight_bytes(16, 1, 9) == 0
+    assert ss.packed_weight_bytes(256, 1, ss.FP8) == ss.weight_bytes(256, 1, ss.FP8)
+    assert ss.packed_weight_bytes(64, 1, ss.FP8) == 0                        # rows shorter than a 128-byte k-step
+    assert ss.workspace_bytes(2, 1024, 2, 64, ss.FP8) == ss.workspace_bytes(2, 1024, 2, 64, ss.BF16)
+    assert call(wdt=2, flags=3 << 4) == 2                                    # row-major 8-bit weights + matrix-core kernel
     assert lib.ssrnn_read_probe(None, 1024, fake, None) == 1
     assert lib.ssrnn_read_probe(fake, 1000, fake, None) == 1                 # not a multiple of 16 bytes
     assert lib.ssrnn_read_probe(ctypes.c_void_p(0x1004), 1024, fake, None) == 1

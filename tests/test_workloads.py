@@ -65,3 +65,34 @@ def test_make_inputs_shapes_and_bounds():
     c2 = wl.CONFIGS[1]
     inp2 = wl.make_inputs(c2, L=8, n_layers=1)
     assert inp2["feat"].shape == (8, 40) and inp2["P"].shape == (1024, 40) and len(inp2["W"]) == 1
+
+
+def test_fp8_encoder_against_library_conversion():
+    """to_fp8_e4m3_bits against torch's float8_e4m3fn conversion: random values over seven decades,
+    every code's own value, every midpoint between neighbouring codes (ties go to the even code),
+    saturation at 448."""
+    import torch
+    rng = np.random.default_rng(3)
+    a = np.concatenate([rng.standard_normal(50000).astype(np.float32) * s for s in (1e-3, 1e-2, 0.1, 1, 10, 100, 300)])
+    want = torch.from_numpy(a).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(wl.to_fp8_e4m3_bits(a), want)
+    codes = np.arange(256, dtype=np.uint8)
+    dec = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
+    ok = ~np.isnan(dec)
+    np.testing.assert_array_equal(wl.to_fp8_e4m3_bits(dec[ok]), codes[ok])
+    pos = np.sort(dec[ok & (codes < 0x80)])
+    mid = ((pos[1:].astype(np.float64) + pos[:-1]) / 2).astype(np.float32)
+    np.testing.assert_array_equal(wl.to_fp8_e4m3_bits(mid), torch.from_numpy(mid).to(torch.float8_e4m3fn).view(torch.uint8).numpy())
+    np.testing.assert_array_equal(wl.to_fp8_e4m3_bits(np.array([449, 1000, -1e9], np.float32)), [0x7E, 0x7E, 0xFE])
+
+
+def test_fp8_quantizer_scales_rows_to_the_format_maximum():
+    rng = np.random.default_rng(4)
+    w = (rng.standard_normal((12, 40)) * rng.uniform(0.01, 3, (12, 1))).astype(np.float32)
+    w[5] = 0
+    q = wl.quantize_fp8(w)
+    assert q.q.dtype == np.uint8 and q.scale.dtype == np.float32 and q.scale[5] == 1.0 and not q.q[5].any()
+    assert ((q.q & 0x7F).max(axis=1)[np.arange(12) != 5] == 0x7E).all()      # each row's largest magnitude maps to 448
+    blob = q.blob()
+    assert blob.size == 512 + 48 and np.array_equal(blob[:480], q.q.reshape(-1)) and not blob[480:512].any()
+    np.testing.assert_array_equal(blob[512:].view(np.float32), q.scale)
