@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
 FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 (vector / matrix) peak
+BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 MFMA peak (8-bit weights are multiplied as bf16)
 
 # HBM bytes per stage launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
 # scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same workloads).
@@ -43,6 +44,11 @@ MEASURED_TRAFFIC_BYTES = {
     ("C5", 64, "packed"): 207_870_000,      # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T64.txt
     ("C5", 256, "packed"): 225_710_000,     # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T256.txt
     ("C5", 256, "row-major"): 225_320_000,  # profiles/stage_mfma_lds_kernel_bf16_C5_qrnn8_d4096_T256.txt
+    ("X1", 1, "row-major"): 101_080_000,     # profiles/stage_valu_kernel_bf16_X1_sru8_d4096_T1.txt
+    ("X2", 1, "row-major"): 50_900_000,      # profiles/stage_valu_kernel_fp8_X2_sru8_d4096_T1.txt
+    ("X2", 16, "packed"): 52_870_000,        # profiles/stage_mfma_packed_kernel_fp8_X2_sru8_d4096_T16.txt
+    ("X3", 64, "packed"): 107_410_000,       # profiles/stage_mfma_packed_kernel_fp8_X3_qrnn8_d4096_T64.txt
+    ("X3", 256, "packed"): 163_160_000,      # profiles/stage_mfma_packed_kernel_fp8_X3_qrnn8_d4096_T256.txt
 }
 
 
@@ -51,7 +57,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="C4", help="workload name prefix (C1..C5)")
+    ap.add_argument("--config", default="C4", help="workload name prefix (C1..C5, X1..X3)")
     ap.add_argument("--T", type=int, default=4, help="block size of the headline number")
     ap.add_argument("--no-sweep", action="store_true", help="skip the other block sizes")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -95,8 +101,13 @@ def main():
     t_gen = time.perf_counter()
     inp = wl.make_inputs(cfg)
     W_host = inp["W"]
-    W = [torch.from_numpy(w).to(dev) for w in W_host]
-    wdt = ss.BF16 if cfg.wdtype == "bf16" else ss.F32
+    wdt = {"f32": ss.F32, "bf16": ss.BF16, "fp8": ss.FP8}[cfg.wdtype]
+    if wdt == ss.FP8:
+        W = [ss.Fp8Weights(torch.from_numpy(w.blob()).to(dev), cfg.d, cfg.k) for w in W_host]
+        if args.T > 8:
+            args.packed = True      # 8-bit weights reach the matrix cores in packed form only
+    else:
+        W = [torch.from_numpy(w).to(dev) for w in W_host]
     # second copy of the weights in the matrix-core kernel's order (a model-load-time step, outside
     # every timed region); the sweep times both layouts
     W_packed = None
@@ -164,6 +175,8 @@ def main():
         for T in cfg.Ts:
             if T == args.T:
                 r = dict(head)
+            elif wdt == ss.FP8 and T > 8 and not args.packed:
+                r = {"T": T, "weights": "row-major", "note": "no row-major kernel for 8-bit weights beyond T = 8; see packed"}
             else:
                 s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
                 r = row(T, s_, e_)
@@ -191,10 +204,12 @@ def main():
               "weights_vs_infinity_cache": round(cfg.n_layers * cfg.weight_bytes_per_layer() / 256e6, 2)}
     # fp32 weights cross the ridge (157.3 TFLOP/s against 8 TB/s) near T = 39; bf16 weights stay
     # HBM-bound up to T = 256 (ridge near T = 310 against 2.5 PFLOP/s)
-    if cfg.wdtype == "f32" and T >= 64:
+    # 8-bit weights (multiplied as bf16) cross near T = 156
+    if (cfg.wdtype == "f32" and T >= 64) or (cfg.wdtype == "fp8" and T >= 160):
+        peak = FP32_PEAK_TFLOPS if cfg.wdtype == "f32" else BF16_PEAK_TFLOPS
         achieved = stage_flops / stage_s / 1e12
-        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / FP32_PEAK_TFLOPS, 4), **common}
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                    "frac": round(achieved / peak, 4), **common}
     else:
         achieved = stage_bytes / stage_s / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -203,14 +218,15 @@ def main():
     # What a kernel that only reads reaches on this device, at the stage kernels' launch size: one probe
     # launch per layer's weight matrix, layers in turn so that nothing stays in cache between launches.
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
-    for w in W:
+    probe_bufs = [w.buf if wdt == ss.FP8 else w for w in W]
+    for w in probe_bufs:
         ss.read_probe(w, sink)
     torch.cuda.synchronize()
     p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     reps = max(1, 64 // len(W))
     p0.record()
     for _ in range(reps):
-        for w in W:
+        for w in probe_bufs:
             ss.read_probe(w, sink)
     p1.record()
     torch.cuda.synchronize()
@@ -258,7 +274,7 @@ def main():
         "metric": "single-stream time steps/sec vs block T; achieved HBM GB/s (% of peak)",
         "value": head["steps_per_s"], "unit": "time steps/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": head["ms_per_pass"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if cfg.wdtype == "f32" else "bf16 weights, f32 accumulate",
+        "scaling": "weak", "vs_baseline": None, "dtype": {"f32": "f32", "bf16": "bf16 weights, f32 accumulate", "fp8": "fp8 (E4M3, row-scaled) weights, f32 accumulate"}[cfg.wdtype],
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_layers}-layer {cfg.cell.upper()}, d={cfg.d}, k={cfg.k}, "
                                f"L={cfg.L}, batch 1, {cfg.wdtype} weights "

@@ -292,3 +292,43 @@ def linear_forward(P, feat, y=None, stream=None):
     _req(y, "y", (L, d_out), torch.float32)
     _check(lib.ssrnn_linear_forward(_p(P), _p(feat), _p(y), d_out, d_in, L, _stream_handle(stream)))
     return y
+
+
+class StreamSession:
+    """A single input stream fed in chunks of any length (the on-device use the
+    paper motivates, Section 1: inputs arrive over time, T steps are processed
+    per weight pass).  Holds the weights, one workspace and the state carried
+    between calls -- every layer's cell state and, for the QRNN, its last k-1
+    inputs -- and passes that state to *_forward as both the initial and the
+    final state (the ABI allows the aliasing), so a chunk boundary changes
+    nothing in the results.  Marshalling only: all arithmetic is in the library."""
+
+    def __init__(self, cell: str, W: List, bias: Optional[List] = None, *, T: int, k: int = 1, flags: int = 0,
+                 c_init=None, xhist_init=None, device="cuda"):
+        import torch
+        if cell not in ("sru", "qrnn"):
+            raise ValueError("cell must be 'sru' or 'qrnn'")
+        self.cell, self.W, self.bias, self.T, self.flags = cell, W, bias, int(T), int(flags)
+        self.k = 1 if cell == "sru" else int(k)
+        self.n_layers = len(W)
+        self.d = W[0].shape[0] // 3
+        wdt = _wdtype(W[0])
+        self.c = torch.zeros((self.n_layers, self.d), dtype=torch.float32, device=device)
+        if c_init is not None:
+            self.c.copy_(c_init)
+        self.xhist = torch.zeros((self.n_layers, self.k - 1, self.d), dtype=torch.float32, device=device)
+        if xhist_init is not None:
+            self.xhist.copy_(xhist_init)
+        self.workspace = Workspace.for_shape(self.n_layers, self.d, self.k, self.T, wdt, device)
+        self.steps = 0
+
+    def feed(self, x, h=None, stream=None):
+        """Process the next x.shape[0] time steps of the stream; returns their outputs [len, d]."""
+        if self.cell == "sru":
+            h, _ = sru_forward(self.W, self.bias, x, self.c, T=self.T, flags=self.flags, h=h, c_final=self.c,
+                               workspace=self.workspace, stream=stream)
+        else:
+            h, _, _ = qrnn_forward(self.W, self.bias, x, self.c, self.xhist, T=self.T, k=self.k, flags=self.flags, h=h,
+                                   c_final=self.c, xhist_final=self.xhist, workspace=self.workspace, stream=stream)
+        self.steps += int(x.shape[0])
+        return h

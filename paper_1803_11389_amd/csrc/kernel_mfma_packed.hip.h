@@ -34,13 +34,14 @@ namespace ssrnn {
 // Four waves per workgroup, one per SIMD: a wave then has the SIMD's matrix pipe to itself.  Two waves per
 // SIMD measured slower from T = 32 on (fp32, T = 32: 43.5 -> 38.6 us per stage; T = 64: 66.7 -> 58.1 us).
 // An 8-bit k-step holds twice the columns of a bf16 one, so its B fragments take twice the registers per
-// time tile: its B ring is shorter and fetches fewer tiles at a time.
+// time tile: its B ring is shorter and fetches fewer tiles at a time (16 tiles: 2 per fetch, which ends
+// most of the register spilling of 4 per fetch and measured 75 against 79.5 us per stage at d = 4096, k = 2).
 template <int NT, int WT = W_F32>
 struct MfmaPkCfg {
   static constexpr int NW = 4;                            // waves per workgroup
   static constexpr int SA = 4;                            // weight fragment ring slots (k-steps)
   static constexpr int SB = (WT == W_FP8) ? ((NT <= 1) ? 4 : 2) : ((NT <= 4) ? 4 : 2);   // B fragment ring slots (sub-steps)
-  static constexpr int NBT = (WT == W_FP8) ? ((NT > 4) ? 4 : NT) : ((NT > 8) ? 8 : NT);   // time tiles per B fetch
+  static constexpr int NBT = (WT == W_FP8) ? ((NT > 8) ? 2 : (NT > 4) ? 4 : NT) : ((NT > 8) ? 8 : NT);   // time tiles per B fetch
 };
 
 // One thread per 16-byte chunk of the packed matrix (see the layout above).

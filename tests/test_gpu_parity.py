@@ -187,6 +187,45 @@ def test_chunk_chaining_on_gpu():
         assert max_abs(c2, c) <= 1e-5 and max_abs(xh2, xh) <= 1e-5
 
 
+@pytest.mark.parametrize("cell,d,k,T,bf16,packed", [
+    ("sru", 256, 1, 4, False, False), ("qrnn", 256, 3, 4, False, False), ("qrnn", 512, 2, 16, False, True),
+    ("sru", 512, 1, 32, True, False), ("qrnn", 256, 4, 2, False, False),
+])
+def test_stream_session_chunks_of_any_length(cell, d, k, T, bf16, packed):
+    """One stream fed through StreamSession in chunks of 1, 5, 0, 17, ... steps (shorter and longer than
+    T, and shorter than the QRNN window) against the oracle run over the whole sequence at once."""
+    import torch
+    import paper_1803_11389_amd as ss
+    from gpu_util import _weights
+    chunks = [1, 5, 0, 17, 3, 1, 1, 40, 2, 9]
+    L = sum(chunks)
+    if cell == "sru":
+        W, b, x, c0 = _sru_inputs(720 + d + T, 2, d, L, scale=2.0, bf16=bf16)
+        xh0 = None
+        h_ref, c_ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
+    else:
+        W, b, x, c0, xh0 = _qrnn_inputs(720 + d + T + k, 2, d, L, k, scale=2.0, bf16=bf16)
+        h_ref, c_ref, xh_ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
+    sess = ss.StreamSession(cell, _weights(W, packed), [to_dev(v) for v in b], T=T, k=k,
+                            flags=ss.WEIGHTS_PACKED if packed else 0, c_init=to_dev(c0), xhist_init=to_dev(xh0))
+    xd = to_dev(x)
+    outs, at = [], 0
+    for n in chunks:
+        print(f"session {cell} d={d} chunk {n} at {at}", flush=True)
+        outs.append(sess.feed(xd[at:at + n]).cpu().numpy())
+        at += n
+    torch.cuda.synchronize()
+    h = np.concatenate(outs)
+    assert sess.steps == L and h.shape == (L, d)
+    if bf16:
+        assert _rel_err(h, h_ref) <= BF16_TOL and _rel_err(sess.c.cpu().numpy(), c_ref) <= BF16_TOL
+    else:
+        assert max_abs(h, h_ref) <= TOL, max_abs(h, h_ref)
+        assert max_abs(sess.c.cpu().numpy(), c_ref) <= TOL
+        if cell == "qrnn":
+            assert max_abs(sess.xhist.cpu().numpy(), xh_ref) <= TOL
+
+
 def test_empty_sequence_returns_initial_state():
     W, b, x, c0, xh0 = _qrnn_inputs(703, 2, 64, 0, 3)
     h, c, xh = gpu_qrnn(W, b, x, c0, xh0, T=4, k=3)
