@@ -176,7 +176,7 @@ def main():
             if T == args.T:
                 r = dict(head)
             elif wdt == ss.FP8 and T > 8 and not args.packed:
-                r = {"T": T, "weights": "row-major", "note": "no row-major kernel for 8-bit weights beyond T = 8; see packed"}
+                r = {"T": T, "weights": "row-major", "note": "row-major 8-bit weights run 8 steps per weight pass beyond T = 8 (the T = 8 row); see packed"}
             else:
                 s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
                 r = row(T, s_, e_)

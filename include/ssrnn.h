@@ -154,8 +154,9 @@ int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
  * is enqueued on stream.  Pass the packed buffers as W[l] together with
  * SSRNN_WEIGHTS_PACKED in flags; shapes the matrix-core kernel cannot take
  * then fail with SSRNN_EUNSUPPORTED.  SSRNN_FP8 weights reach the matrix
- * cores in packed form only: row-major, they run on the vector ALU for T <= 8
- * (d % 1024 == 0) and on the generic kernel otherwise. */
+ * cores in packed form only: row-major, they run on the vector ALU
+ * (d % 1024 == 0; blocks longer than 8 steps are processed 8 steps per weight
+ * pass) and on the generic kernel otherwise. */
 size_t ssrnn_packed_weight_bytes(int d, int k, int wdtype);
 int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype,
                        void* stream);

@@ -589,6 +589,17 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       if (valu_ok) p.kind = K_VALU;
     }
   }
+  // Nothing tiled takes the block as it is, but the vector-ALU kernel would take a shorter one (row-major
+  // 8-bit weights beyond T = 8, which have no matrix-core kernel): cut the block to that kernel's longest.
+  // Results do not depend on the block size; the weights are then fetched once per 8 (16) steps.
+  if (p.kind == K_GENERIC && kforce == SSRNN_KERNEL_AUTO && !packed) {
+    const int cap = (wdt == SSRNN_F32) ? VALU_MAX_T : 8;
+    if (T > cap) {
+      p.T = cap;
+      if (plan_valu(p, W, x, xhist_init, workspace)) { p.kind = K_VALU; T = cap; }
+      else p.T = T;
+    }
+  }
 
   char* act0 = static_cast<char*>(workspace) + wl.act_offset;
   char* op0 = static_cast<char*>(workspace) + wl.op_offset;

@@ -76,6 +76,32 @@ def test_extra_workload_sru8_d4096_bf16_prefix():
     _run_config(wl.by_name("X1"), 100, 2e-2, True)
 
 
+def test_extra_workload_sru8_d4096_fp8_prefix():
+    """Configuration 4's width with 8-bit float weights (four of its layers, to bound the time the
+    quantiser and the oracle take): row-major codes on the vector-ALU kernel up to T = 8 (fp32 bar, the
+    input block is not rounded) and packed codes on the matrix cores at every block size (bf16 bar)."""
+    import paper_1803_11389_amd as ss
+    from gpu_util import weight_to_dev
+    cfg = wl.by_name("X2")
+    L = 70
+    inp = wl.make_inputs(cfg, L=L, n_layers=4)
+    W_dev = [weight_to_dev(w) for w in inp["W"]]
+    W_packed = [ss.pack_weights(w) for w in W_dev]
+    x_dev = to_dev(inp["x"])
+    h_ref, c_ref = oracle.sru_forward(inp["W"], None, inp["x"], T=64)
+    sh, sc = float(np.abs(h_ref).max()), float(np.abs(c_ref).max())
+    for T in cfg.Ts:
+        if T <= 8:
+            h, c = _gpu_run(cfg, W_dev, x_dev, T, L)
+            eh, ec = max_abs(h, h_ref), max_abs(c, c_ref)
+            print(f"{cfg.name} L={L} T={T} row-major: err h {eh:.3e} c {ec:.3e}", flush=True)
+            assert eh <= 1e-4 and ec <= 1e-4, (T, eh, ec)
+        h, c = _gpu_run(cfg, W_packed, x_dev, T, L, ss.WEIGHTS_PACKED)
+        eh, ec = max_abs(h, h_ref) / sh, max_abs(c, c_ref) / sc
+        print(f"{cfg.name} L={L} T={T} packed: err h {eh:.3e} c {ec:.3e}", flush=True)
+        assert eh <= 2e-2 and ec <= 2e-2, (T, eh, ec)
+
+
 def test_config5_first_layer_against_the_operand_rounding_oracle():
     """One layer of C5 at full width, every block size and both weight layouts,
     against the oracle run that rounds the matrix operand X to bfloat16 exactly

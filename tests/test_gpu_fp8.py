@@ -96,6 +96,17 @@ def test_generic_kernel_fp8(cell, d, n_layers, L, T, k):
     """Shapes whose code count is not a multiple of 256 put padding before the scales."""
     print(f"fp8 generic {cell} d={d} layers={n_layers} L={L} T={T} k={k}", flush=True)
     W, b, x, c0, xh0 = _inputs(3100 + d + T + k, cell, n_layers, d, L, k)
+    h, c, h_ref, c_ref = _run(cell, W, b, x, c0, xh0, T, k, flags=GENERIC)
+    assert max_abs(h, h_ref) <= TOL, max_abs(h, h_ref)
+    assert max_abs(c, c_ref) <= TOL, max_abs(c, c_ref)
+
+
+@pytest.mark.parametrize("cell,d,L,T,k", [("sru", 1024, 45, 20, 1), ("qrnn", 1024, 70, 64, 2), ("sru", 2048, 30, 9, 1)])
+def test_row_major_fp8_long_blocks_are_cut_to_the_vector_alu_kernels_length(cell, d, L, T, k):
+    """Row-major codes have no matrix-core kernel: a block longer than 8 steps is processed 8 steps per
+    weight pass on the vector-ALU kernel (same results, fp32 bar) instead of falling to the generic kernel."""
+    print(f"fp8 row-major long block {cell} d={d} L={L} T={T} k={k}", flush=True)
+    W, b, x, c0, xh0 = _inputs(3300 + d + T + k, cell, 2, d, L, k)
     h, c, h_ref, c_ref = _run(cell, W, b, x, c0, xh0, T, k)
     assert max_abs(h, h_ref) <= TOL, max_abs(h, h_ref)
     assert max_abs(c, c_ref) <= TOL, max_abs(c, c_ref)
