@@ -4,8 +4,9 @@ size T, and achieved HBM bandwidth against the 8 TB/s peak.
 
 A "step" of this benchmark (--steps K) is one pass of the whole hot path over
 one batch of synthetic input: the full L-step sequence through the whole layer
-stack, in streaming order (block b goes through all layers before block b+1),
-with one block size T.  The headline workload is the benchmark's HBM-roofline
+stack with one block size T, every layer's weights read once per block, in the
+library's default schedule (independent (block, layer) stages share a launch;
+--flags 1 times the one-launch-per-stage schedule in streaming order).  The headline workload is the benchmark's HBM-roofline
 configuration (8-layer SRU, d = 4096, fp32 weights, 1.6 GB, L = 2048) at T = 4.
 Inputs and weights are resident in HBM before the timed region starts.
 
@@ -30,8 +31,9 @@ HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
 FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 (vector / matrix) peak
 BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 MFMA peak (8-bit weights are multiplied as bf16)
 
-# HBM bytes per stage launch (read + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
-# scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same workloads).
+# HBM bytes per launch of the stage kernel (read + written) measured with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE and scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same
+# workloads, default schedule: a launch holds up to n_layers stages).
 MEASURED_TRAFFIC_BYTES = {
     ("C4", 1, "row-major"): 201_810_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
     ("C4", 4, "row-major"): 202_160_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
@@ -156,6 +158,22 @@ def main():
         dt = time.perf_counter() - t0
         return dt / steps, e0.elapsed_time(e1) / steps
 
+    def launches(T):
+        """(stages, launches of the stage kernel) of one pass at block size T under args.flags."""
+        nblocks = (cfg.L + T - 1) // T
+        nstage = cfg.n_layers * nblocks
+        sched = args.flags & 3
+        if sched == ss.SCHED_PERSISTENT:
+            return nstage, 1
+        if sched == ss.SCHED_STAGES or cfg.n_layers == 1 or nblocks == 1:
+            return nstage, nstage
+        # wavefront: one launch per anti-diagonal of the (block, layer) grid, at most 8 stages per launch
+        n = 0
+        for step in range(nblocks + cfg.n_layers - 1):
+            active = min(step, cfg.n_layers - 1) - max(0, step - (nblocks - 1)) + 1
+            n += (active + 7) // 8
+        return nstage, n
+
     def row(T, sec, ev_ms):
         nstage = cfg.n_layers * ((cfg.L + T - 1) // T)
         steps_s = cfg.L / sec
@@ -188,18 +206,31 @@ def main():
                 r["packed"] = {key: pk[key] for key in ("steps_per_s", "us_per_stage", "algorithmic_GBps", "frac_hbm_peak", "TFLOPps")}
             sweep.append(r)
 
-    # dominant kernel: the (block, layer) stage kernel.  Algorithmic bytes of one
+    # dominant kernel: the stage kernel.  Algorithmic bytes of one (block, layer)
     # stage = the layer's weights once + the input block read + the output block
-    # written (fp32).  Duration = event time of the timed region / stages in it.
+    # written (fp32); a launch holds nstage / nlaunch stages on average.
+    # Duration = event time of the timed region / launches in it.
     T = args.T
-    nstage = cfg.n_layers * ((cfg.L + T - 1) // T)
-    stage_bytes = cfg.weight_bytes_per_layer() + 2 * cfg.d * 4 * T
-    stage_flops = 2.0 * 3 * cfg.d * cfg.ncol * T
-    stage_s = ev_ms * 1e-3 / nstage
+    nstage, nlaunch = launches(T)
+    per_launch = nstage / nlaunch
+    stage_bytes = (cfg.weight_bytes_per_layer() + 2 * cfg.d * 4 * T) * per_launch
+    stage_flops = 2.0 * 3 * cfg.d * cfg.ncol * T * per_launch
+    stage_s = ev_ms * 1e-3 / nlaunch
     traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name[:2], T, "packed" if args.packed else "row-major")) \
         if (args.flags & ~ss.WEIGHTS_PACKED) == 0 else None
-    common = {"traffic": traffic, "kernel": "stage kernel (one per block and layer)", "launches_per_pass": nstage,
-              "avg_launch_us": round(stage_s * 1e6, 2), "algorithmic_bytes_per_launch": stage_bytes,
+    # the same block size in the one-launch-per-stage schedule, for comparison
+    per_stage_schedule = None
+    if (args.flags & 3) == 0 and nlaunch != nstage:
+        keep = args.flags
+        args.flags |= ss.SCHED_STAGES
+        s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
+        args.flags = keep
+        r_ = row(T, s_, e_)
+        per_stage_schedule = {key: r_[key] for key in ("steps_per_s", "us_per_stage", "algorithmic_GBps", "frac_hbm_peak")}
+    common = {"traffic": traffic, "kernel": "stage kernel (a launch holds the independent (block, layer) stages of one step)",
+              "launches_per_pass": nlaunch, "stages_per_launch": round(per_launch, 3),
+              "avg_launch_us": round(stage_s * 1e6, 2), "us_per_stage": head["us_per_stage"],
+              "algorithmic_bytes_per_launch": round(stage_bytes),
               "flops_per_launch": stage_flops,
               "weights_vs_infinity_cache": round(cfg.n_layers * cfg.weight_bytes_per_layer() / 256e6, 2)}
     # fp32 weights cross the ridge (157.3 TFLOP/s against 8 TB/s) near T = 39; bf16 weights stay
@@ -279,8 +310,11 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.n_layers}-layer {cfg.cell.upper()}, d={cfg.d}, k={cfg.k}, "
                                f"L={cfg.L}, batch 1, {cfg.wdtype} weights "
                                f"({cfg.n_layers * cfg.weight_bytes_per_layer() / 1e9:.2f} GB), block T={args.T}",
-                   "T": args.T, "schedule": "streaming (block-major)", "weights": head["weights"], "flags": args.flags},
+                   "T": args.T, "schedule": {0: "wavefront (independent stages share a launch)" if nlaunch != nstage else "one launch per stage",
+                                             1: "one launch per stage, streaming order", 2: "persistent", 3: "wavefront"}[args.flags & 3],
+                   "weights": head["weights"], "flags": args.flags},
         "achieved_hbm_GBps": head["algorithmic_GBps"], "frac_hbm_peak": head["frac_hbm_peak"],
+        "per_stage_schedule": per_stage_schedule,
         "sweep": sweep, "roofline": roofline, "cpu_baseline": cpu,
         "setup_s": round(t_gen, 1),
     }

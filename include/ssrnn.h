@@ -6,8 +6,14 @@
  * of the T steps are one skinny matrix product U = W * X, X = [x_0 ... x_{T-1}],
  * so that each weight fetched from memory is used T times; the element-wise
  * recurrence of Eq. 2 (SRU) / Eq. 3 (QRNN) then ripples over the T steps.
- * Blocks are taken in streaming order: block b goes through every layer before
- * block b+1 starts, so the whole stack's weights are re-read once per block.
+ * Every layer's weights are read once per block.  A (block, layer) pair is a
+ * stage; stage (b, l) depends on (b, l-1) for its input and on (b-1, l) for its
+ * state, so the stages with equal b + l are independent.  By default a call
+ * that holds more than one block runs those together, one launch per value of
+ * b + l (the wavefront schedule: block b+1 enters the first layer while block b
+ * is in the second); a call of one block, or SSRNN_SCHED_STAGES, takes the
+ * stages one by one in streaming order (block b through every layer before
+ * block b+1 starts).  The results are the same bits either way.
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless it says "host".  W[] and bias[]
@@ -56,13 +62,15 @@ typedef enum { SSRNN_F32 = 0, SSRNN_BF16 = 1, SSRNN_FP8 = 2 } ssrnn_wdtype;
  * shape does not allow returns SSRNN_EUNSUPPORTED. */
 enum {
   SSRNN_SCHED_AUTO = 0,
-  SSRNN_SCHED_STAGES = 1,     /* one kernel launch per (block, layer) stage                  */
+  SSRNN_SCHED_STAGES = 1,     /* one kernel launch per (block, layer) stage, streaming order */
   SSRNN_SCHED_PERSISTENT = 2, /* one cooperative launch for the whole call; stages are
                                  separated by a grid barrier and the next stage's first
                                  weights are requested across it.  Stacked SRU with fp32
                                  row-major weights, T <= 8, d a multiple of 256 with at
                                  most one workgroup per compute unit.  Its waits are bounded:
                                  see ssrnn_workspace_status.                                 */
+  SSRNN_SCHED_WAVEFRONT = 3,  /* one launch per anti-diagonal b + l of the (block, layer)
+                                 grid: up to n_layers independent stages side by side       */
   SSRNN_SCHED_MASK = 3,
   SSRNN_KERNEL_AUTO = 0,
   SSRNN_KERNEL_GENERIC = 1 << 4, /* any d, k, T: one wavefront per output feature            */
@@ -80,8 +88,8 @@ int ssrnn_version(void);
 const char* ssrnn_last_error(void);
 
 /* Bytes of device scratch *_forward needs for this shape (inter-layer
- * activations for one block, their operand copies for the matrix-core
- * kernels, control words).  Host.  Returns 0 for arguments *_forward would
+ * activations for two blocks in flight, their operand copies for the
+ * matrix-core kernels, control words).  Host.  Returns 0 for arguments *_forward would
  * reject.  The workspace must be 256-byte aligned; its contents need not be
  * initialised and are not preserved. */
 size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype);

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssrnn.so")
 
 F32, BF16, FP8 = 0, 1, 2
-SCHED_AUTO, SCHED_STAGES, SCHED_PERSISTENT = 0, 1, 2
+SCHED_AUTO, SCHED_STAGES, SCHED_PERSISTENT, SCHED_WAVEFRONT = 0, 1, 2, 3
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_VALU, KERNEL_MFMA = 0, 1 << 4, 2 << 4, 3 << 4
 WEIGHTS_PACKED = 1 << 8
 

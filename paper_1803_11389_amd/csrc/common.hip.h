@@ -38,12 +38,13 @@ struct Stage {
   float* c;                // [d] running cell state, read and written
   // QRNN only: before the stage's outputs are written, the k-1 rows in front
   // of hout (the next layer's view of "earlier inputs") are refreshed by the
-  // owner of each column.  hist_mode 0: nothing; 1: rows move down by
-  // hist_shift rows (previous block's tail becomes history); 2: filled from
-  // hist_init (lag j+1 at row j) or with zeros if that is null.
+  // owner of each column.  hist_mode 0: nothing; 1: copied from hist_src, the
+  // last k-1 rows of the previous block's output (row r at hist_src + r*ldh,
+  // ascending time; another buffer than hout's, see the wavefront schedule);
+  // 2: filled from hist_init (lag j+1 at row j) or with zeros if that is null.
   const float* hist_init;
+  const float* hist_src;
   int hist_mode;
-  int hist_shift;
   int nt;
   int ldx;                 // row stride (elements) of xcur
   int ldh;                 // row stride (elements) of hout
@@ -55,6 +56,13 @@ struct Stage {
   float* upart;
   int ksplit;              // 1: no split (upart unused)
   int tp;                  // steps per feature row of upart
+};
+
+// Stages that do not depend on each other -- (block b, layer l) pairs with the
+// same b + l -- go into one launch: blockIdx.y picks the stage.
+constexpr int MAX_BATCH_STAGES = 8;
+struct StageBatch {
+  Stage s[MAX_BATCH_STAGES];
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
@@ -142,7 +150,7 @@ __device__ __forceinline__ void refresh_history(const Stage& s, int d, int k, in
   float* hist = s.hout - static_cast<long>(k - 1) * s.ldh;   // rows 0..k-2, ascending time
   for (int r = 0; r < k - 1; ++r) {
     float v;
-    if (s.hist_mode == 1) v = hist[static_cast<long>(r + s.hist_shift) * s.ldh + i];
+    if (s.hist_mode == 1) v = s.hist_src[static_cast<long>(r) * s.ldh + i];
     else v = s.hist_init ? s.hist_init[static_cast<long>(k - 2 - r) * d + i] : 0.0f;
     hist[static_cast<long>(r) * s.ldh + i] = v;
     if (s.hop) store_operand(s.hop, s.ldt, s.op_bf16, r - (k - 1), i, v);

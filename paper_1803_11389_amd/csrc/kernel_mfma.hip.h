@@ -279,7 +279,8 @@ __device__ __forceinline__ void mfma_store_partials(const Stage& s, int d, int f
 // bias, applies the gates, scans the recurrence over 32 adjacent lanes and
 // writes h (and its bf16 copy).
 template <int CELL>
-__global__ __launch_bounds__(512) void split_epilogue_kernel(Stage s, int d, int k) {
+__global__ __launch_bounds__(512) void split_epilogue_kernel(const StageBatch batch, int d, int k) {
+  const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
   const int tid = threadIdx.x;
   const int fi = tid >> 5;
   const int tl = tid & 31;

@@ -33,7 +33,8 @@ struct MfmaLdsCfg {
 };
 
 template <int CELL, int WT, int NT>
-__global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(Stage s, int d, int k) {
+__global__ __launch_bounds__(MfmaCfg<NT>::NW * 64) void stage_mfma_lds_kernel(const StageBatch batch, int d, int k) {
+  const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
   constexpr int NW = MfmaCfg<NT>::NW;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int KSTEP = (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row

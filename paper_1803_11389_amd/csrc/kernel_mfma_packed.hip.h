@@ -71,7 +71,8 @@ __device__ __forceinline__ bf16x8_t fp8x8_to_bf16(uint32_t w0, uint32_t w1) {
 }
 
 template <int CELL, int WT, int NT>
-__global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kernel(Stage s, int d, int k) {
+__global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kernel(const StageBatch batch, int d, int k) {
+  const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
   constexpr int NW = MfmaPkCfg<NT, WT>::NW;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int KSTEP = (WT == W_FP8) ? 128 : (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
@@ -87,8 +88,14 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   __shared__ float part[NW * 3 * CHUNK];
   __shared__ float g_a[MFMA_F * (NTC * 16 + 1)], g_b[MFMA_F * (NTC * 16 + 1)], g_o[MFMA_F * (NTC * 16 + 1)];
   __shared__ float c_carry[MFMA_F];
+  // Two time tiles leave registers for two workgroups per CU, and when a launch holds several stages two
+  // do land on a CU; their waves then share each SIMD's matrix pipe, which measured slower (see MfmaPkCfg).
+  // This instance therefore claims more than half of the CU's LDS, so that one workgroup is resident.
+  constexpr int OCC_PAD = (NT == 2) ? 21 * 1024 : 1;
+  __shared__ float occupancy_pad[OCC_PAD];
 
   const int tid = threadIdx.x;
+  if (s.nt < 0) occupancy_pad[tid] = 0.0f;          // never taken (nt >= 1): keeps the allocation
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int li = lane & 15;

@@ -2,11 +2,18 @@
 // stage schedule and kernel selection behind the C ABI of include/ssrnn.h.
 //
 // Schedule (arXiv 1803.11389, Section 3): the sequence is cut into blocks of T
-// steps; block b passes through all layers before block b+1 starts (streaming
-// order), each (block, layer) pair being one "stage" that reads the layer's
-// weights once.  Layer l's output block is handed to layer l+1 through a
-// [(k-1)+T] x d buffer in the workspace whose first k-1 rows keep the tail of
-// the previous block (the QRNN's causal window, Eq. 3).
+// steps; each (block, layer) pair is one "stage" that reads the layer's weights
+// once.  Stage (b, l) needs the output of (b, l-1) as its input and the state
+// (b-1, l) left behind, nothing else, so the stages with the same b + l are
+// independent of each other: the wavefront schedule runs them as one launch
+// (step s = b + l, at most n_layers stages wide), the per-stage schedule runs
+// them one launch each in streaming order (block b through all layers before
+// block b+1 starts).  Both read every layer's weights once per block and give
+// the same bits.  Layer l's output block is handed to layer l+1 through a
+// [(k-1)+T] x d buffer in the workspace whose first k-1 rows hold the tail of
+// the previous block (the QRNN's causal window, Eq. 3); there are two such
+// buffers per layer, used by even and odd blocks, because block b+1 is written
+// while block b is still being read.
 #include "../../include/ssrnn.h"
 
 #include <hip/hip_runtime.h>
@@ -56,22 +63,23 @@ constexpr int ACT_PAD = 64;   // extra elements per row of a hand-off buffer (25
 struct WorkspaceLayout {
   int ld;               // row stride (elements) of the hand-off buffers: d + ACT_PAD
   size_t act_stride;    // bytes of one fp32 hand-off buffer [(k-1)+T] x ld
-  size_t act_offset;    // buffer 0 = staged input of layer 0, buffer l = output of layer l-1
+  size_t act_offset;    // buffer (l, parity) at act_offset + (2*l + parity) * act_stride: the input of layer l
+                        // (l = 0: staged from x) for the blocks of that parity
   int ldt;              // rows per chunk column of an operand copy
   size_t op_stride;     // bytes of one operand copy (0 when d rules the matrix-core kernels out)
   size_t op_offset;
-  size_t upart_offset;  // partial pre-activations of split stages (narrow layers only)
-  size_t upart_bytes;
+  size_t upart_offset;  // partial pre-activations of split stages (narrow layers only): one area per
+  size_t upart_bytes;   // stage of a launch, upart_bytes each
   int upart_rows;       // rows per (part, gate) plane
   size_t total;
 };
 
 constexpr int KSPLIT_MAX = 8;
 
-// Buffer b (0 <= b < n_layers) holds the input rows of layer b for the current
-// block, preceded by the k-1 rows before it.  Buffer 0 is filled from x by a
-// staging kernel (only when k > 1 or a matrix-core kernel runs; otherwise
-// layer 0 reads x in place).
+// Buffer (l, parity) (0 <= l < n_layers) holds the input rows of layer l for a
+// block of that parity, preceded by the k-1 rows before it.  Buffers (0, .) are
+// filled from x by a staging kernel (only when k > 1 or a matrix-core kernel
+// runs; otherwise layer 0 reads x in place).
 WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
   WorkspaceLayout w;
   const size_t rows = static_cast<size_t>(k - 1 + T);
@@ -85,15 +93,16 @@ WorkspaceLayout workspace_layout(int n_layers, int d, int k, int T, int wdt) {
   w.ldt = (k - 1 + tcap + 7) / 8 * 8 + 4;
   const size_t esize = (wdt == SSRNN_F32) ? 4 : 2;   // bf16 and 8-bit weights multiply a bf16 copy
   w.op_stride = (d % MFMA_F == 0) ? align_up(static_cast<size_t>(d) * esize / 16 * w.ldt * 16, WS_ALIGN) : 0;
-  w.op_offset = w.act_offset + static_cast<size_t>(n_layers) * w.act_stride;
-  w.upart_offset = w.op_offset + static_cast<size_t>(n_layers) * w.op_stride;
+  w.op_offset = w.act_offset + static_cast<size_t>(2 * n_layers) * w.act_stride;
+  w.upart_offset = w.op_offset + static_cast<size_t>(2 * n_layers) * w.op_stride;
   // a split stage stores whole groups of time tiles, and the kernels take 1, 2, 4, 8 or 16 tiles
   int tiles = 1;
   while (tiles * 16 < tcap) tiles *= 2;
   w.upart_rows = tiles * 16;
   w.upart_bytes = (d % MFMA_F == 0 && d / MFMA_F < 128)
                       ? align_up(static_cast<size_t>(KSPLIT_MAX) * 3 * w.upart_rows * d * sizeof(float), WS_ALIGN) : 0;
-  w.total = w.upart_offset + w.upart_bytes;
+  const int slots = n_layers < MAX_BATCH_STAGES ? n_layers : MAX_BATCH_STAGES;
+  w.total = w.upart_offset + static_cast<size_t>(slots) * w.upart_bytes;
   return w;
 }
 
@@ -144,7 +153,7 @@ __global__ void gather_history_kernel(const float* x, const float* xhist_init, f
       if (s >= 0) v = x[s * d + m];
       else v = xhist_init ? xhist_init[(-s - 1) * d + m] : 0.0f;
     } else {
-      const float* a = reinterpret_cast<const float*>(act0 + static_cast<size_t>(l) * act_stride);
+      const float* a = reinterpret_cast<const float*>(act0 + static_cast<size_t>(2 * l) * act_stride);   // act0: parity of the last block
       v = a[static_cast<long>(k - 1 + nt_last - 1 - j) * ld + m];
     }
     out[static_cast<long>(j) * d + m] = v;
@@ -312,8 +321,8 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
 }
 
 template <int CELL>
-int launch_valu(const Plan& p, const Stage& s, hipStream_t st) {
-  const dim3 grid(p.grid), block(p.nw * 64);
+int launch_valu(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
+  const dim3 grid(p.grid, nstage), block(p.nw * 64);
   const size_t lds = static_cast<size_t>(p.nw) * 3 * p.F * p.tt * sizeof(float);
 #define SSRNN_VALU_CASE(TT_, NV_)                                                          \
   if (p.tt == TT_ && p.nv == NV_) {                                                        \
@@ -424,7 +433,7 @@ int launch_persistent(const Plan& p, const void* const* W, const float* const* b
   }
   a.x = x; a.c_init = c_init; a.h = h; a.c_final = c_final;
   a.act = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.act_offset);
-  a.act_stride = wl.act_stride / sizeof(float);
+  a.act_stride = 2 * wl.act_stride / sizeof(float);   // the even-block buffer of every layer
   a.ctr = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + WS_CTR_OFFSET);
   a.abort_flag = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + WS_ABORT_OFFSET);
   a.spin_limit = g_tune_spin_limit > 0 ? g_tune_spin_limit : 100000000LL;   // default: one second of the 100 MHz wall clock
@@ -451,8 +460,8 @@ int launch_persistent(const Plan& p, const void* const* W, const float* const* b
 }
 
 template <int CELL>
-int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
-  const dim3 grid(p.d / MFMA_F * p.ksplit);
+int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
+  const dim3 grid(p.d / MFMA_F * p.ksplit, nstage);
   const dim3 block(p.mfma_nw * 64);
 #define SSRNN_MFMA_CASE(NT_)                                                                              \
   if (p.nt_tiles == NT_) {                                                                                \
@@ -471,7 +480,7 @@ int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
       return fail(SSRNN_EUNSUPPORTED, "no matrix-core kernel for %d time tiles of row-major fp32 weights", p.nt_tiles); \
     }                                                                                                     \
     if (p.ksplit > 1)                                                                                     \
-      hipLaunchKernelGGL((split_epilogue_kernel<CELL>), dim3(p.d / MFMA_F), dim3(512), 0, st, s, p.d, p.k); \
+      hipLaunchKernelGGL((split_epilogue_kernel<CELL>), dim3(p.d / MFMA_F, nstage), dim3(512), 0, st, s, p.d, p.k); \
     return SSRNN_OK;                                                                                      \
   }
   SSRNN_MFMA_CASE(1) SSRNN_MFMA_CASE(2) SSRNN_MFMA_CASE(4) SSRNN_MFMA_CASE(8) SSRNN_MFMA_CASE(16)
@@ -480,9 +489,9 @@ int launch_mfma(const Plan& p, const Stage& s, hipStream_t st) {
 }
 
 template <int CELL>
-int launch_generic(const Plan& p, const Stage& s, hipStream_t st) {
+int launch_generic(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
   const int grid = (p.d + GENERIC_WAVES - 1) / GENERIC_WAVES;
-  const dim3 g(grid < 4096 ? grid : 4096), b(GENERIC_WAVES * 64);
+  const dim3 g(grid < 4096 ? grid : 4096, nstage), b(GENERIC_WAVES * 64);
   if (p.wdt == SSRNN_FP8)
     hipLaunchKernelGGL((stage_generic_kernel<CELL, W_FP8>), g, b, 0, st, s, p.d, p.k);
   else if (p.wdt == SSRNN_BF16)
@@ -492,12 +501,13 @@ int launch_generic(const Plan& p, const Stage& s, hipStream_t st) {
   return SSRNN_OK;
 }
 
+// One launch (two for split stages) for nstage <= MAX_BATCH_STAGES stages that do not depend on each other.
 template <int CELL>
-int launch_stage(const Plan& p, const Stage& s, hipStream_t st) {
+int launch_stages(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
   switch (p.kind) {
-    case K_VALU: return launch_valu<CELL>(p, s, st);
-    case K_MFMA: return launch_mfma<CELL>(p, s, st);
-    default: return launch_generic<CELL>(p, s, st);
+    case K_VALU: return launch_valu<CELL>(p, s, nstage, st);
+    case K_MFMA: return launch_mfma<CELL>(p, s, nstage, st);
+    default: return launch_generic<CELL>(p, s, nstage, st);
   }
 }
 
@@ -519,7 +529,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   const int sched = flags & SSRNN_SCHED_MASK;
   const int kforce = flags & SSRNN_KERNEL_MASK;
   const bool packed = (flags & SSRNN_WEIGHTS_PACKED) != 0;
-  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED)) != 0 || sched > SSRNN_SCHED_PERSISTENT)
+  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED)) != 0 || sched > SSRNN_SCHED_WAVEFRONT)
     return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
   if (packed && kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_MFMA)
     return fail(SSRNN_EINVAL, "%s: packed weights are read by the matrix-core kernel only", name);
@@ -606,67 +616,108 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   const bool use_op = (p.kind == K_MFMA);
   const int op_bf16 = (wdt == SSRNN_F32) ? 0 : 1;
   const bool stage_in = (k > 1) || p.kind == K_MFMA;   // the matrix-core kernel wants padded rows
-  auto act = [&](int b) { return reinterpret_cast<float*>(act0 + static_cast<size_t>(b) * wl.act_stride) + static_cast<long>(k - 1) * wl.ld; };
-  auto opbuf = [&](int b) { return static_cast<void*>(op0 + static_cast<size_t>(b) * wl.op_stride + static_cast<size_t>(k - 1) * 16); };
+  // row 0 of the hand-off buffer (operand copy) that holds layer l's input for block b
+  auto act = [&](int l, long b) {
+    return reinterpret_cast<float*>(act0 + static_cast<size_t>(2 * l + (b & 1)) * wl.act_stride) + static_cast<long>(k - 1) * wl.ld;
+  };
+  auto opbuf = [&](int l, long b) {
+    return static_cast<void*>(op0 + static_cast<size_t>(2 * l + (b & 1)) * wl.op_stride + static_cast<size_t>(k - 1) * 16);
+  };
   const long nblocks = (L + T - 1) / T;
-  int nt_last = T;
-  for (long b = 0; b < nblocks; ++b) {
+  auto block_len = [&](long b) { return static_cast<int>(L - b * T < T ? L - b * T : T); };
+  const int nt_last = block_len(nblocks - 1);
+
+  // layer 0's input rows of block b into its hand-off buffer
+  auto stage_input = [&](long b) {
     const long t0 = b * T;
-    const int nt = static_cast<int>(L - t0 < T ? L - t0 : T);
-    nt_last = nt;
-    if (stage_in) {
-      if (d % 8 == 0 && aligned16(x) && aligned16(xhist_init) && k - 1 + nt <= 65535) {
-        const int per_row = d / 8;
-        const int bx = per_row < 256 ? (per_row + 63) / 64 * 64 : 256;
-        hipLaunchKernelGGL(stage_input_vec_kernel, dim3((per_row + bx - 1) / bx, k - 1 + nt), dim3(bx), 0, st, x,
-                           xhist_init, act(0), use_op ? opbuf(0) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0);
-      } else {
-        const long n = static_cast<long>(k - 1 + nt) * d;
-        hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0),
-                           use_op ? opbuf(0) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, nt);
+    const int nt = block_len(b);
+    if (d % 8 == 0 && aligned16(x) && aligned16(xhist_init) && k - 1 + nt <= 65535) {
+      const int per_row = d / 8;
+      const int bx = per_row < 256 ? (per_row + 63) / 64 * 64 : 256;
+      hipLaunchKernelGGL(stage_input_vec_kernel, dim3((per_row + bx - 1) / bx, k - 1 + nt), dim3(bx), 0, st, x,
+                         xhist_init, act(0, b), use_op ? opbuf(0, b) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0);
+    } else {
+      const long n = static_cast<long>(k - 1 + nt) * d;
+      hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0, b),
+                         use_op ? opbuf(0, b) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, nt);
+    }
+  };
+
+  // stage (block b, layer l); slot: its position in the launch (picks the split-K scratch area)
+  auto make_stage = [&](long b, int l, int slot) {
+    Stage s{};
+    const long t0 = b * T;
+    s.W = W[l];
+    s.wscale = (wdt == SSRNN_FP8) ? reinterpret_cast<const float*>(static_cast<const char*>(W[l]) + fp8_scale_offset(d, k)) : nullptr;
+    s.bias = (bias && bias[l]) ? bias[l] : nullptr;
+    if (l == 0 && !stage_in) {
+      s.xcur = x + t0 * d;
+      s.xop = nullptr;
+      s.ldx = d;
+    } else {
+      s.xcur = act(l, b);
+      s.xop = use_op ? opbuf(l, b) : nullptr;
+      s.ldx = wl.ld;
+    }
+    if (l == n_layers - 1) {
+      s.hout = h + t0 * d;
+      s.hop = nullptr;
+      s.ldh = d;
+      s.hist_mode = 0;
+    } else {
+      s.hout = act(l + 1, b);
+      s.hop = use_op ? opbuf(l + 1, b) : nullptr;
+      s.ldh = wl.ld;
+      s.hist_mode = (k > 1) ? (b == 0 ? 2 : 1) : 0;
+      // the k-1 rows before this block in layer l+1's input: the end of block b-1 (a full block), which
+      // lies in the other buffer of the pair; rows below 0 there are that buffer's own history rows
+      s.hist_src = (k > 1 && b > 0) ? act(l + 1, b - 1) + static_cast<long>(T - (k - 1)) * wl.ld : nullptr;
+      s.hist_init = xhist_init ? xhist_init + static_cast<long>(l + 1) * (k - 1) * d : nullptr;
+    }
+    s.ldt = wl.ldt;
+    s.op_bf16 = op_bf16;
+    s.c = c_final + static_cast<long>(l) * d;
+    s.nt = block_len(b);
+    s.ksplit = (p.kind == K_MFMA) ? p.ksplit : 1;
+    s.upart = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.upart_offset + static_cast<size_t>(slot) * wl.upart_bytes);
+    s.tp = wl.upart_rows;
+    return s;
+  };
+  auto launch = [&](const StageBatch& sb, int n) {
+    return (cell == CELL_SRU) ? launch_stages<CELL_SRU>(p, sb, n, st) : launch_stages<CELL_QRNN>(p, sb, n, st);
+  };
+
+  const bool wavefront = sched == SSRNN_SCHED_WAVEFRONT || (sched == SSRNN_SCHED_AUTO && n_layers > 1 && nblocks > 1);
+  if (!wavefront) {
+    // streaming order, one launch per stage
+    for (long b = 0; b < nblocks; ++b) {
+      if (stage_in) stage_input(b);
+      for (int l = 0; l < n_layers; ++l) {
+        StageBatch sb{};
+        sb.s[0] = make_stage(b, l, 0);
+        const int rc = launch(sb, 1);
+        if (rc != SSRNN_OK) return rc;
       }
     }
-    for (int l = 0; l < n_layers; ++l) {
-      Stage s{};
-      s.W = W[l];
-      s.wscale = (wdt == SSRNN_FP8) ? reinterpret_cast<const float*>(static_cast<const char*>(W[l]) + fp8_scale_offset(d, k)) : nullptr;
-      s.bias = (bias && bias[l]) ? bias[l] : nullptr;
-      if (l == 0 && !stage_in) {
-        s.xcur = x + t0 * d;
-        s.xop = nullptr;
-        s.ldx = d;
-      } else {
-        s.xcur = act(l);
-        s.xop = use_op ? opbuf(l) : nullptr;
-        s.ldx = wl.ld;
+  } else {
+    // step s runs the stages (b, l) with b + l = s: their inputs were written in step s-1 (or staged from x),
+    // their states were left by step s-1, and no two of them touch the same buffer
+    for (long step = 0; step < nblocks + n_layers - 1; ++step) {
+      if (stage_in && step < nblocks) stage_input(step);
+      const int l_lo = step >= nblocks ? static_cast<int>(step - (nblocks - 1)) : 0;
+      const int l_hi = step < n_layers ? static_cast<int>(step) : n_layers - 1;
+      for (int l0 = l_lo; l0 <= l_hi; l0 += MAX_BATCH_STAGES) {
+        StageBatch sb{};
+        int n = 0;
+        for (int l = l0; l <= l_hi && n < MAX_BATCH_STAGES; ++l, ++n) sb.s[n] = make_stage(step - l, l, n);
+        const int rc = launch(sb, n);
+        if (rc != SSRNN_OK) return rc;
       }
-      if (l == n_layers - 1) {
-        s.hout = h + t0 * d;
-        s.hop = nullptr;
-        s.ldh = d;
-        s.hist_mode = 0;
-      } else {
-        s.hout = act(l + 1);
-        s.hop = use_op ? opbuf(l + 1) : nullptr;
-        s.ldh = wl.ld;
-        s.hist_mode = (k > 1) ? (b == 0 ? 2 : 1) : 0;
-        s.hist_shift = T;
-        s.hist_init = xhist_init ? xhist_init + static_cast<long>(l + 1) * (k - 1) * d : nullptr;
-      }
-      s.ldt = wl.ldt;
-      s.op_bf16 = op_bf16;
-      s.c = c_final + static_cast<long>(l) * d;
-      s.nt = nt;
-      s.ksplit = (p.kind == K_MFMA) ? p.ksplit : 1;
-      s.upart = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.upart_offset);
-      s.tp = wl.upart_rows;
-      const int rc = (cell == CELL_SRU) ? launch_stage<CELL_SRU>(p, s, st) : launch_stage<CELL_QRNN>(p, s, st);
-      if (rc != SSRNN_OK) return rc;
     }
   }
   if (xhist_final && k > 1)
     hipLaunchKernelGGL(gather_history_kernel, dim3((nstate + 255) / 256), dim3(256), 0, st, x, xhist_init, xhist_final,
-                       act0, wl.act_stride, wl.ld, n_layers, d, k, L, nt_last);
+                       act0 + static_cast<size_t>((nblocks - 1) & 1) * wl.act_stride, wl.act_stride, wl.ld, n_layers, d, k, L, nt_last);
   HIP_TRY(hipGetLastError());
   return SSRNN_OK;
 }

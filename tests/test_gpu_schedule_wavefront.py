@@ -1,0 +1,76 @@
+"""The wavefront schedule (independent (block, layer) stages share a launch)
+against the per-stage schedule in streaming order: the same kernels do the same
+arithmetic per stage, so the outputs, the final state and the final window
+must be the same bits; plus oracle parity where the stack is deeper than one
+launch holds and where blocks are shorter than the QRNN window."""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import gpu_qrnn, gpu_sru, max_abs
+from test_gpu_parity import BF16_TOL, TOL, _qrnn_inputs, _rel_err, _sru_inputs
+
+pytestmark = pytest.mark.gpu
+
+STAGES, WAVEFRONT = 1, 3
+GENERIC, VALU, MFMA = 1 << 4, 2 << 4, 3 << 4
+
+
+@pytest.mark.parametrize("cell,d,n_layers,L,T,k,bf16,packed,kernel", [
+    ("sru", 256, 3, 37, 4, 1, False, False, 0), ("sru", 512, 5, 50, 1, 1, False, False, VALU),
+    ("sru", 256, 4, 100, 16, 1, False, False, MFMA), ("sru", 1024, 3, 130, 64, 1, False, True, 0),
+    ("qrnn", 256, 3, 41, 4, 2, False, False, 0), ("qrnn", 256, 4, 23, 2, 4, False, False, 0),
+    ("qrnn", 256, 3, 9, 1, 3, False, False, VALU), ("qrnn", 512, 3, 90, 20, 3, False, False, MFMA),
+    ("qrnn", 512, 4, 300, 100, 2, True, True, 0), ("sru", 100, 3, 19, 5, 1, False, False, 0),
+    ("qrnn", 48, 4, 30, 3, 3, False, False, GENERIC), ("sru", 256, 2, 600, 256, 1, True, False, 0),
+    ("qrnn", 128, 3, 50, 16, 2, False, False, MFMA),       # narrow layer: columns split over workgroups
+])
+def test_wavefront_equals_stage_by_stage_bitwise(cell, d, n_layers, L, T, k, bf16, packed, kernel):
+    print(f"wavefront {cell} d={d} layers={n_layers} L={L} T={T} k={k} bf16={bf16} packed={packed} kernel={kernel:#x}", flush=True)
+    if cell == "sru":
+        W, b, x, c0 = _sru_inputs(4000 + d + T, n_layers, d, L, scale=2.0, bf16=bf16)
+        a = gpu_sru(W, b, x, c0, T=T, flags=STAGES | kernel, packed=packed)
+        w = gpu_sru(W, b, x, c0, T=T, flags=WAVEFRONT | kernel, packed=packed)
+        auto = gpu_sru(W, b, x, c0, T=T, flags=kernel, packed=packed)
+        ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
+    else:
+        W, b, x, c0, xh0 = _qrnn_inputs(4000 + d + T + k, n_layers, d, L, k, scale=2.0, bf16=bf16)
+        a = gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, flags=STAGES | kernel, packed=packed)
+        w = gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, flags=WAVEFRONT | kernel, packed=packed)
+        auto = gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, flags=kernel, packed=packed)
+        ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
+    for u, v, z in zip(a, w, auto):
+        np.testing.assert_array_equal(u, v)
+        np.testing.assert_array_equal(u, z)      # the default of a call with several blocks and layers is the wavefront
+    for u, r in zip(w, ref):
+        if bf16:
+            assert _rel_err(u, r) <= BF16_TOL
+        else:
+            assert max_abs(u, r) <= TOL, max_abs(u, r)
+
+
+@pytest.mark.parametrize("cell,k", [("sru", 1), ("qrnn", 3)])
+def test_stacks_deeper_than_one_launch_holds(cell, k):
+    """19 layers: a step of the wavefront is up to 19 stages wide and goes out as three launches."""
+    n_layers, d, L, T = 19, 256, 45, 2
+    print(f"deep stack {cell}", flush=True)
+    if cell == "sru":
+        W, b, x, c0 = _sru_inputs(4100, n_layers, d, L, scale=2.0)
+        got = gpu_sru(W, b, x, c0, T=T)
+        ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
+    else:
+        W, b, x, c0, xh0 = _qrnn_inputs(4101, n_layers, d, L, k, scale=2.0)
+        got = gpu_qrnn(W, b, x, c0, xh0, T=T, k=k)
+        ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
+    for u, r in zip(got, ref):
+        assert max_abs(u, r) <= TOL, max_abs(u, r)
+
+
+def test_fewer_blocks_than_layers_and_single_block():
+    W, b, x, c0, xh0 = _qrnn_inputs(4102, 6, 256, 7, 2, scale=2.0)
+    for T in (4, 7, 16):          # two blocks, one block, one short block
+        print(f"few blocks T={T}", flush=True)
+        got = gpu_qrnn(W, b, x, c0, xh0, T=T, k=2, flags=WAVEFRONT)
+        ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=2)
+        for u, r in zip(got, ref):
+            assert max_abs(u, r) <= TOL, max_abs(u, r)
