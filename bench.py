@@ -35,22 +35,23 @@ BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 MFMA peak (8-bit weigh
 # WRITE_SIZE and scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same
 # workloads, default schedule: a launch holds up to n_layers stages).
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", 1, "row-major"): 201_810_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
-    ("C4", 4, "row-major"): 202_160_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
-    ("C4", 16, "row-major"): 205_150_000,   # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T16.txt
-    ("C4", 16, "packed"): 205_130_000,      # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T16.txt
-    ("C4", 64, "row-major"): 214_540_000,   # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T64.txt
-    ("C4", 64, "packed"): 214_630_000,      # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T64.txt
-    ("C4", 128, "packed"): 227_280_000,     # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T128.txt
-    ("C5", 16, "packed"): 203_490_000,      # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T16.txt
-    ("C5", 64, "packed"): 207_870_000,      # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T64.txt
-    ("C5", 256, "packed"): 225_710_000,     # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T256.txt
-    ("C5", 256, "row-major"): 225_320_000,  # profiles/stage_mfma_lds_kernel_bf16_C5_qrnn8_d4096_T256.txt
-    ("X1", 1, "row-major"): 101_080_000,     # profiles/stage_valu_kernel_bf16_X1_sru8_d4096_T1.txt
-    ("X2", 1, "row-major"): 50_900_000,      # profiles/stage_valu_kernel_fp8_X2_sru8_d4096_T1.txt
-    ("X2", 16, "packed"): 52_870_000,        # profiles/stage_mfma_packed_kernel_fp8_X2_sru8_d4096_T16.txt
-    ("X3", 64, "packed"): 107_410_000,       # profiles/stage_mfma_packed_kernel_fp8_X3_qrnn8_d4096_T64.txt
-    ("X3", 256, "packed"): 135_770_000,      # profiles/stage_mfma_packed_kernel_fp8_X3_qrnn8_d4096_T256.txt
+    ("C4", 1, "row-major"): 1_608_320_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
+    ("C4", 4, "row-major"): 1_594_350_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
+    ("C4", 16, "row-major"): 1_555_170_000,    # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T16.txt
+    ("C4", 16, "packed"): 1_555_160_000,    # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T16.txt
+    ("C4", 64, "row-major"): 1_407_210_000,    # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T64.txt
+    ("C4", 64, "packed"): 1_407_300_000,    # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T64.txt
+    ("C4", 128, "packed"): 1_262_680_000,    # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T128.txt
+    ("C5", 16, "packed"): 1_583_890_000,    # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T16.txt
+    ("C5", 64, "packed"): 1_497_710_000,    # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T64.txt
+    ("C5", 256, "packed"): 1_251_560_000,    # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T256.txt
+    ("C5", 256, "row-major"): 1_251_490_000,    # profiles/stage_mfma_lds_kernel_bf16_C5_qrnn8_d4096_T256.txt
+    ("X1", 1, "row-major"): 805_270_000,    # profiles/stage_valu_kernel_bf16_X1_sru8_d4096_T1.txt
+    ("X2", 1, "row-major"): 404_830_000,    # profiles/stage_valu_kernel_fp8_X2_sru8_d4096_T1.txt
+    ("X2", 16, "packed"): 399_850_000,    # profiles/stage_mfma_packed_kernel_fp8_X2_sru8_d4096_T16.txt
+    ("X3", 64, "packed"): 772_610_000,    # profiles/stage_mfma_packed_kernel_fp8_X3_qrnn8_d4096_T64.txt
+    ("X3", 256, "packed"): 732_460_000,    # profiles/stage_mfma_packed_kernel_fp8_X3_qrnn8_d4096_T256.txt
+    ("C2", 4, "row-major"): 50_660_000,    # profiles/stage_valu_kernel_C2_sru4_d1024_T4.txt
 }
 
 
@@ -218,9 +219,9 @@ def main():
     stage_s = ev_ms * 1e-3 / nlaunch
     traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name[:2], T, "packed" if args.packed else "row-major")) \
         if (args.flags & ~ss.WEIGHTS_PACKED) == 0 else None
-    # the same block size in the one-launch-per-stage schedule, for comparison
+    # the same block size in the one-launch-per-stage schedule, for comparison (part of the sweep)
     per_stage_schedule = None
-    if (args.flags & 3) == 0 and nlaunch != nstage:
+    if not args.no_sweep and (args.flags & 3) == 0 and nlaunch != nstage:
         keep = args.flags
         args.flags |= ss.SCHED_STAGES
         s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
