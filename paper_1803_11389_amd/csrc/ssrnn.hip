@@ -276,6 +276,7 @@ struct Plan {
   int mfma_nw;         // waves per workgroup of the matrix-core kernel
   bool packed;         // weights are in the matrix-core fragment order (ssrnn_pack_weights)
   bool one_wg_per_cu;  // vector-ALU geometry for a launch whose workgroups must all be resident
+  int concurrent;      // stages per launch in the steady state of the schedule (1: one launch per stage)
 };
 
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
@@ -394,12 +395,15 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   if (ncol % (nw * kstep) != 0) return false;
   if (p.d % kstep != 0) return false;   // a k-step never straddles two lag blocks
   // Narrow layers: d/16 feature tiles do not fill 256 CUs, so the columns are split over
-  // up to KSPLIT_MAX workgroups per tile (LDS-staged kernel only) and a second kernel finishes.
+  // up to KSPLIT_MAX workgroups per tile and a second kernel finishes -- unless the launch holds
+  // enough independent stages to fill the chip with whole tiles (measured at d = 1024, T = 64, four
+  // stages per launch: 7.9 us per stage unsplit against 11.4 split four ways).
   p.ksplit = 1;
   const int ntile = p.d / MFMA_F;
+  const int conc = p.concurrent > 1 ? p.concurrent : 1;
   if (ntile < 128 && p.nt_tiles <= 8 && g_tune_ksplit != 1) {
     int ks = 1;
-    while (ks < KSPLIT_MAX && ntile * ks * 2 <= 256 && ncol % (static_cast<long>(nw) * kstep * ks * 2) == 0) ks *= 2;
+    while (ks < KSPLIT_MAX && ntile * conc * ks * 2 <= 256 && ncol % (static_cast<long>(nw) * kstep * ks * 2) == 0) ks *= 2;
     if (g_tune_ksplit > 1 && g_tune_ksplit <= ks) ks = g_tune_ksplit;
     p.ksplit = ks;
   }
@@ -584,13 +588,24 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   }
   // bf16 weights: the vector-ALU kernel (weights widened in registers, input block exact) wins up to T = 2
   // (17.1 against 18.4 us per stage at d = 4096, T = 1); beyond that its conversions and FMAs no longer hide
+  // fp32, narrow layers: when a launch holds enough stages to give every CU an unsplit matrix-core
+  // workgroup, that kernel wins from T = 9 on (d = 1024, k = 2, T = 16: 5.6 against 6.8 us per stage)
+  auto stages_per_launch = [&](int t) {
+    const long nb = (L + t - 1) / t;
+    const bool wf = sched == SSRNN_SCHED_WAVEFRONT || (sched == SSRNN_SCHED_AUTO && n_layers > 1 && nb > 1);
+    const long width = nb < n_layers ? nb : n_layers;
+    return wf ? static_cast<int>(width < MAX_BATCH_STAGES ? width : MAX_BATCH_STAGES) : 1;
+  };
   const bool prefer_mfma = kforce == SSRNN_KERNEL_AUTO &&
-                           (wdt != SSRNN_F32 ? T > 2 : (T > 4 && d / MFMA_F >= 256));
+                           (wdt != SSRNN_F32 ? T > 2
+                                             : (T > 4 && d / MFMA_F >= 256) ||
+                                               (T > 8 && d % MFMA_F == 0 && d / MFMA_F * stages_per_launch(T) >= 256));
   if (valu_ok && !prefer_mfma) p.kind = K_VALU;
   if (p.kind == K_GENERIC && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_MFMA)) {
     // the matrix-core kernels accumulate a bounded number of steps per weight pass: longer blocks are cut
     const int cap = mfma_block_cap(wdt, packed);
     p.T = T < cap ? T : cap;
+    p.concurrent = stages_per_launch(p.T);
     if (plan_mfma(p, W, x, xhist_init, workspace)) { p.kind = K_MFMA; T = p.T; }
     else {
       p.T = T;
