@@ -200,6 +200,14 @@ def main():
                 s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
                 r = row(T, s_, e_)
                 r["weights"] = head["weights"]
+            if (args.flags & 3) == 0 and launches(T)[0] != launches(T)[1] and "steps_per_s" in r:
+                # the same block size with one launch per stage in streaming (block-major) order
+                keep = args.flags
+                args.flags |= ss.SCHED_STAGES
+                s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
+                args.flags = keep
+                ps = row(T, s_, e_)
+                r["per_stage_schedule"] = {key: ps[key] for key in ("steps_per_s", "us_per_stage", "frac_hbm_peak")}
             if W_packed is not None and not args.packed:
                 # the same block size with pre-packed weights (matrix-core kernel at every T)
                 s_, e_ = measure(T, max(1, min(args.steps, 2)), 1, packed=True)
@@ -219,15 +227,7 @@ def main():
     stage_s = ev_ms * 1e-3 / nlaunch
     traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name[:2], T, "packed" if args.packed else "row-major")) \
         if (args.flags & ~ss.WEIGHTS_PACKED) == 0 else None
-    # the same block size in the one-launch-per-stage schedule, for comparison (part of the sweep)
-    per_stage_schedule = None
-    if not args.no_sweep and (args.flags & 3) == 0 and nlaunch != nstage:
-        keep = args.flags
-        args.flags |= ss.SCHED_STAGES
-        s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
-        args.flags = keep
-        r_ = row(T, s_, e_)
-        per_stage_schedule = {key: r_[key] for key in ("steps_per_s", "us_per_stage", "algorithmic_GBps", "frac_hbm_peak")}
+    per_stage_schedule = next((r_.get("per_stage_schedule") for r_ in sweep if r_["T"] == T), None)
     common = {"traffic": traffic, "kernel": "stage kernel (a launch holds the independent (block, layer) stages of one step)",
               "launches_per_pass": nlaunch, "stages_per_launch": round(per_launch, 3),
               "avg_launch_us": round(stage_s * 1e6, 2), "us_per_stage": head["us_per_stage"],
