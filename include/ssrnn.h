@@ -91,7 +91,8 @@ const char* ssrnn_last_error(void);
  * activations for two blocks in flight, their operand copies for the
  * matrix-core kernels, control words).  Host.  Returns 0 for arguments *_forward would
  * reject.  The workspace must be 256-byte aligned; its contents need not be
- * initialised and are not preserved. */
+ * initialised and are not preserved.  Calls that share a workspace must not
+ * overlap in time (queue them on one stream, or order the streams). */
 size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype);
 
 /* Bytes of one layer's weight buffer W[l] for a [3d x k*d] matrix.  Host; 0 for
