@@ -741,7 +741,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
 
 extern "C" {
 
-int ssrnn_version(void) { return 100; }
+int ssrnn_version(void) { return 200; }   // 0.2.0: 8-bit weights, wavefront schedule
 
 const char* ssrnn_last_error(void) { return g_last_error.c_str(); }
 
