@@ -39,7 +39,7 @@ constexpr int MFMA_MAX_T = 256;     // longest block one launch accumulates
 
 template <int NT>
 struct MfmaCfg {
-  static constexpr int NW = (NT >= 8) ? 4 : 8;      // waves of the LDS-staged kernel: 512 registers each when NT is large
+  static constexpr int NW = (NT >= 4) ? 4 : 8;      // waves of the LDS-staged kernel: one per SIMD from four time tiles on (8 tiles: 512 registers each)
   static constexpr int NTC = (NT < 2) ? NT : (NT >= 8) ? 4 : 2;   // N tiles per epilogue chunk
 };
 
