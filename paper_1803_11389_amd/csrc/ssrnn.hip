@@ -275,6 +275,7 @@ struct Plan {
   int ksplit;          // workgroups per feature tile (columns split), 1 unless the layer is narrow
   int mfma_nw;         // waves per workgroup of the matrix-core kernel
   bool packed;         // weights are in the matrix-core fragment order (ssrnn_pack_weights)
+  bool lds_four_waves; // LDS-staged kernel, one or two time tiles: the four-wave instance (short rows)
   bool one_wg_per_cu;  // vector-ALU geometry for a launch whose workgroups must all be resident
   int concurrent;      // stages per launch in the steady state of the schedule (1: one launch per stage)
 };
@@ -389,9 +390,12 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
     if (!aligned16(W[l])) return false;
   const int tiles = (p.T + 15) / 16;
   p.nt_tiles = tiles <= 1 ? 1 : tiles <= 2 ? 2 : tiles <= 4 ? 4 : tiles <= 8 ? 8 : 16;
-  const int nw = mfma_waves(p.nt_tiles, p.packed);
+  int nw = mfma_waves(p.nt_tiles, p.packed);
   const int kstep = mfma_kstep(p.wdt);
   const long ncol = static_cast<long>(p.k) * p.d;
+  // short rows: eight waves would get at most four k-steps each, too few for their pipelines
+  p.lds_four_waves = !p.packed && p.nt_tiles <= 2 && nw == 8 && ncol / (8L * kstep) <= 8 && ncol % (4L * kstep) == 0;
+  if (p.lds_four_waves) nw = 4;
   if (ncol % (nw * kstep) != 0) return false;
   if (p.d % kstep != 0) return false;   // a k-step never straddles two lag blocks
   // Narrow layers: d/16 feature tiles do not fill 256 CUs, so the columns are split over
@@ -476,6 +480,12 @@ int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) 
         hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k); \
       else                                                                                                \
         hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k); \
+    } else if (NT_ <= 2 && p.lds_four_waves) {                                                            \
+      constexpr int NTL = NT_ <= 2 ? NT_ : 1;                                                             \
+      if (p.wdt == SSRNN_BF16)                                                                            \
+        hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_BF16, NTL, 4>), grid, block, 0, st, s, p.d, p.k); \
+      else                                                                                                \
+        hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_F32, NTL, 4>), grid, block, 0, st, s, p.d, p.k); \
     } else if (p.wdt == SSRNN_BF16) {                                                                     \
       hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k);    \
     } else if constexpr (NT_ < 16) {                                                                      \
