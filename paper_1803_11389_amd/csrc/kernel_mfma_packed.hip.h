@@ -36,11 +36,15 @@ namespace ssrnn {
 // An 8-bit k-step holds twice the columns of a bf16 one, so its B fragments take twice the registers per
 // time tile: its B ring is shorter and fetches fewer tiles at a time (16 tiles: 2 per fetch, which ends
 // most of the register spilling of 4 per fetch and measured 75 against 79.5 us per stage at d = 4096, k = 2).
-template <int NT, int WT = W_F32>
+// FT: feature tiles (of 16) per workgroup.  Every workgroup reads the whole input block, so with two tiles a
+// stage moves half the B bytes through the L2-to-CU fabric; that needs twice the accumulators and weight
+// slots (a shorter B ring makes room) and leaves d/32 workgroups per stage, which fill the chip only when a
+// launch holds several stages.
+template <int NT, int WT = W_F32, int FT = 1>
 struct MfmaPkCfg {
   static constexpr int NW = 4;                            // waves per workgroup
   static constexpr int SA = 4;                            // weight fragment ring slots (k-steps)
-  static constexpr int SB = (WT == W_FP8) ? ((NT <= 1) ? 4 : 2) : ((NT <= 4) ? 4 : 2);   // B fragment ring slots (sub-steps)
+  static constexpr int SB = (FT > 1) ? 2 : (WT == W_FP8) ? ((NT <= 1) ? 4 : 2) : ((NT <= 4) ? 4 : 2);   // B fragment ring slots (sub-steps)
   static constexpr int NBT = (WT == W_FP8) ? ((NT > 8) ? 2 : (NT > 4) ? 4 : NT) : ((NT > 8) ? 8 : NT);   // time tiles per B fetch
 };
 
@@ -70,17 +74,19 @@ __device__ __forceinline__ bf16x8_t fp8x8_to_bf16(uint32_t w0, uint32_t w1) {
   return bf16x8_t{a[0], a[1], b[0], b[1], c[0], c[1], e[0], e[1]};
 }
 
-template <int CELL, int WT, int NT>
+template <int CELL, int WT, int NT, int FT = 1>
 __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kernel(const StageBatch batch, int d, int k) {
+  static_assert(FT == 1 || FT == 2, "one or two feature tiles per workgroup");
   const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
   constexpr int NW = MfmaPkCfg<NT, WT>::NW;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int KSTEP = (WT == W_FP8) ? 128 : (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row
   constexpr int CW = KSTEP / 4;                      // columns per lane per step (32 bytes)
   constexpr int CHUNK = NTC * 256;
-  constexpr int SA = MfmaPkCfg<NT, WT>::SA;
-  constexpr int SB = MfmaPkCfg<NT, WT>::SB;
-  constexpr int NBT = MfmaPkCfg<NT, WT>::NBT;
+  constexpr int SA = MfmaPkCfg<NT, WT, FT>::SA;
+  constexpr int SB = MfmaPkCfg<NT, WT, FT>::SB;
+  constexpr int NBT = MfmaPkCfg<NT, WT, FT>::NBT;
+  constexpr int NA = 6 * FT;                         // weight fragments (1 KiB each) per k-step
   constexpr int NBH = NT / NBT;                      // sub-steps per k-step
   constexpr int U = (SA > SB) ? SA : SB;             // k-steps per unrolled iteration
   static_assert(U % SA == 0 && (U * NBH) % SB == 0 && SB - 1 <= U * NBH, "ring sizes must repeat with the unrolled body");
@@ -101,9 +107,9 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   const int li = lane & 15;
   const int kg = lane >> 4;
   const int ncol = k * d;
-  const int ntile = d / MFMA_F;
+  const int ntile = d / (MFMA_F * FT);               // workgroups per part of the columns
   const int ksp = blockIdx.x / ntile;                // which part of the columns (0 unless the stage is split)
-  const int ft = blockIdx.x - ksp * ntile;
+  const int ft = (blockIdx.x - ksp * ntile) * FT;    // first feature tile of this workgroup
   const int f0 = ft * MFMA_F;
   const int nw = blockDim.x >> 6;                    // waves launched (<= NW)
   const int KS = ncol / (nw * s.ksplit);             // columns per wave
@@ -111,20 +117,25 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   const int wcol = (ksp * nw + wave) * KS;           // this wave's first column
   const int nks_total = ncol / KSTEP;
 
-  if (CELL == CELL_QRNN && s.ksplit == 1 && tid < MFMA_F) refresh_history(s, d, k, f0 + tid);
+  if (CELL == CELL_QRNN && s.ksplit == 1 && tid < MFMA_F * FT) refresh_history(s, d, k, f0 + tid);
 
   // first fragment of this wave: k-step wcol / KSTEP of feature tile ft, 6 KiB per k-step
   const char* aptr = static_cast<const char*>(s.W) +
                      (static_cast<size_t>(ft) * nks_total + static_cast<size_t>(wcol / KSTEP)) * 6144 + lane * 16;
+  const size_t tile_stride = static_cast<size_t>(nks_total) * 6144;   // bytes from a feature tile's fragments to the next tile's
 
   // epilogue operands from memory, requested before the main loop (unused when the stage is split)
-  const MfmaEpilogueOperands<NT, NW> epi_ops = mfma_epilogue_fetch<CELL, NT, NW>(s, d, f0);
+  MfmaEpilogueOperands<NT, NW> epi_ops[FT];
+#pragma unroll
+  for (int j = 0; j < FT; ++j) epi_ops[j] = mfma_epilogue_fetch<CELL, NT, NW>(s, d, f0 + j * MFMA_F);
 
-  floatx4_t acc[3][NT];
+  floatx4_t acc[FT][3][NT];
 #pragma unroll
-  for (int g = 0; g < 3; ++g)
+  for (int j = 0; j < FT; ++j)
 #pragma unroll
-    for (int n = 0; n < NT; ++n) acc[g][n] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+      for (int n = 0; n < NT; ++n) acc[j][g][n] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
   // B side: this lane's time row in each tile, as a byte offset within a chunk column of the operand
   // copy.  Rows past the end of a short block repeat its last row; the columns they produce are never
@@ -137,7 +148,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   const long ldtb = static_cast<long>(s.ldt) * 16;  // bytes per chunk column
   const char* xop = static_cast<const char*>(s.xop);
 
-  floatx4_t aring[SA][6];        // [slot][gate * 2 + half]
+  floatx4_t aring[SA][NA];       // [slot][tile * 6 + gate * 2 + half]
   BFrag<WT> bring[SB][NBT];
 
   int a_ks = 0;                                   // next k-step whose fragments are requested
@@ -146,7 +157,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   int b_j = wcol / d, b_m = wcol - (wcol / d) * d + kg * CW;
   long b_off = static_cast<long>(b_m / VEC) * ldtb - b_j * 16;
   auto load_a_frag = [&](int slot, int i) {
-    aring[slot][i] = load_stream16(aptr + static_cast<size_t>(a_ks) * 6144 + i * 1024);
+    aring[slot][i] = load_stream16(aptr + (i / 6) * tile_stride + static_cast<size_t>(a_ks) * 6144 + (i % 6) * 1024);
   };
   auto load_b_piece = [&](int slot, int tile0, int i) {      // i = (tile - tile0) * NPC + piece
     const int n = i / NPC, h = i % NPC;
@@ -164,30 +175,38 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
       // piece q = bytes [q*8, q*8+8) of the lane's 32 bytes of this k-step: the half q/2 of the fragment pair,
       // words (q%2)*2 and (q%2)*2+1 of it
       const int q = grp / 3, g = grp - 3 * (grp / 3);
-      const floatx4_t a4 = aring[aslot][g * 2 + (q >> 1)];
-      const bf16x8_t ab = fp8x8_to_bf16(__float_as_uint(a4[(q & 1) * 2]), __float_as_uint(a4[(q & 1) * 2 + 1]));
 #pragma unroll
-      for (int n = 0; n < NBT; ++n)
-        acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[q], acc[g][tile0 + n], 0, 0, 0);
+      for (int j = 0; j < FT; ++j) {
+        const floatx4_t a4 = aring[aslot][j * 6 + g * 2 + (q >> 1)];
+        const bf16x8_t ab = fp8x8_to_bf16(__float_as_uint(a4[(q & 1) * 2]), __float_as_uint(a4[(q & 1) * 2 + 1]));
+#pragma unroll
+        for (int n = 0; n < NBT; ++n)
+          acc[j][g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[q], acc[j][g][tile0 + n], 0, 0, 0);
+      }
     } else if constexpr (WT == W_BF16) {
       const int h = grp / 3, g = grp - 3 * (grp / 3);
-      bf16x8_t ab;
-      __builtin_memcpy(&ab, &aring[aslot][g * 2 + h], sizeof ab);
 #pragma unroll
-      for (int n = 0; n < NBT; ++n)
-        acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[h], acc[g][tile0 + n], 0, 0, 0);
+      for (int j = 0; j < FT; ++j) {
+        bf16x8_t ab;
+        __builtin_memcpy(&ab, &aring[aslot][j * 6 + g * 2 + h], sizeof ab);
+#pragma unroll
+        for (int n = 0; n < NBT; ++n)
+          acc[j][g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bring[bslot][n].v[h], acc[j][g][tile0 + n], 0, 0, 0);
+      }
     } else {
       const int h = grp >> 2, q = grp & 3;
 #pragma unroll
-      for (int g = 0; g < 3; ++g) {
-        const floatx4_t av = aring[aslot][g * 2 + h];
+      for (int j = 0; j < FT; ++j)
 #pragma unroll
-        for (int n = 0; n < NBT; ++n) {
-          const float4 bv = bring[bslot][n].v[h];
-          const float bq = q == 0 ? bv.x : q == 1 ? bv.y : q == 2 ? bv.z : bv.w;
-          acc[g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q], bq, acc[g][tile0 + n], 0, 0, 0);
+        for (int g = 0; g < 3; ++g) {
+          const floatx4_t av = aring[aslot][j * 6 + g * 2 + h];
+#pragma unroll
+          for (int n = 0; n < NBT; ++n) {
+            const float4 bv = bring[bslot][n].v[h];
+            const float bq = q == 0 ? bv.x : q == 1 ? bv.y : q == 2 ? bv.z : bv.w;
+            acc[j][g][tile0 + n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q], bq, acc[j][g][tile0 + n], 0, 0, 0);
+          }
         }
-      }
     }
   };
 
@@ -214,7 +233,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
       // needed: the B pieces of the next sub-steps first, the weight fragments of the far k-step after
       // them.  The other order would make the wait for the B pieces a wait for the weight prefetch too.
       const int n_b = NPC * NBT;
-      const int nitem = n_b + ((hb == 0) ? 6 : 0);              // weight fragments ride on the first sub-step
+      const int nitem = n_b + ((hb == 0) ? NA : 0);             // weight fragments ride on the first sub-step
 #pragma unroll
       for (int grp = 0; grp < NGRP; ++grp) {
         mfma_group(p % SA, bslot, hb * NBT, grp);
@@ -243,7 +262,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
 #pragma unroll
     for (int p = 0; p < SA - 1; ++p) {
 #pragma unroll
-      for (int i = 0; i < 6; ++i) load_a_frag(p, i);
+      for (int i = 0; i < NA; ++i) load_a_frag(p, i);
       ++a_ks;
     }
 #pragma unroll
@@ -260,7 +279,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   for (int ks = ks_done; ks < nks; ++ks) {
     a_ks = ks;
 #pragma unroll
-    for (int i = 0; i < 6; ++i) load_a_frag(0, i);
+    for (int i = 0; i < NA; ++i) load_a_frag(0, i);
     {
       const int col = wcol + ks * KSTEP;
       b_j = col / d;
@@ -277,10 +296,15 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   }
 
   if (s.ksplit > 1) {
-    mfma_store_partials<NT>(s, d, f0, ksp, acc, part);
+#pragma unroll
+    for (int j = 0; j < FT; ++j) mfma_store_partials<NT>(s, d, f0 + j * MFMA_F, ksp, acc[j], part);
     return;
   }
-  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, epi_ops, part, g_a, g_b, g_o, c_carry);
+#pragma unroll
+  for (int j = 0; j < FT; ++j) {
+    if (j > 0) __syncthreads();   // the previous tile's last phase still reads what this tile's first phase writes
+    mfma_epilogue<CELL, NT, NW>(s, d, f0 + j * MFMA_F, acc[j], epi_ops[j], part, g_a, g_b, g_o, c_carry);
+  }
 }
 
 }  // namespace ssrnn

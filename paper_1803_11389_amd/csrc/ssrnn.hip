@@ -276,6 +276,7 @@ struct Plan {
   int mfma_nw;         // waves per workgroup of the matrix-core kernel
   bool packed;         // weights are in the matrix-core fragment order (ssrnn_pack_weights)
   bool lds_four_waves; // LDS-staged kernel, one or two time tiles: the four-wave instance (short rows)
+  int ft;              // packed kernel: feature tiles (of 16) per workgroup, 1 or 2
   bool one_wg_per_cu;  // vector-ALU geometry for a launch whose workgroups must all be resident
   int concurrent;      // stages per launch in the steady state of the schedule (1: one launch per stage)
 };
@@ -283,6 +284,7 @@ struct Plan {
 int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
 long long g_tune_spin_limit = 0;   // 0 = default (one second); otherwise wall-clock ticks a grid-barrier wait may take
 int g_tune_ksplit = 0;     // 0 = default, 1 = never split, 2/4/8 = at most that many parts
+int g_tune_ft = 0;         // 0 = default, 1 = always one feature tile per workgroup
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
   // a wave-wide 16-byte load covers 256 fp32, 512 bf16 or 1024 8-bit columns; the narrow types are taken up to T = 8
@@ -415,6 +417,14 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   p.mfma_nw = nw;
   if (p.ksplit > 1)
     while (p.mfma_nw > 4 && ncol / (static_cast<long>(p.mfma_nw) * p.ksplit * kstep) < 2) p.mfma_nw /= 2;
+  // Two feature tiles per workgroup halve the input-block bytes every CU pulls through the L2; that pays
+  // where those bytes weigh against the weights' (17..64 steps; measured at d = 4096, us per stage:
+  // bf16 k = 2, T = 64: 43.4 -> 38.6; 8-bit: 29.7 -> 25.5; fp32 T = 32: 38.1 -> 37.0, T = 64 unchanged and
+  // left alone) and needs a launch with enough stages to fill the chip with d/32 workgroups each.
+  p.ft = 1;
+  if (p.packed && (p.nt_tiles == 2 || (p.nt_tiles == 4 && p.wdt != SSRNN_F32)) && p.ksplit == 1 && ntile % 2 == 0 &&
+      conc >= 2 && ntile / 2 * conc >= 256 && g_tune_ft != 1)
+    p.ft = 2;
   return true;
 }
 
@@ -469,11 +479,19 @@ int launch_persistent(const Plan& p, const void* const* W, const float* const* b
 
 template <int CELL>
 int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
-  const dim3 grid(p.d / MFMA_F * p.ksplit, nstage);
+  const dim3 grid(p.d / (MFMA_F * (p.packed ? p.ft : 1)) * p.ksplit, nstage);
   const dim3 block(p.mfma_nw * 64);
 #define SSRNN_MFMA_CASE(NT_)                                                                              \
   if (p.nt_tiles == NT_) {                                                                                \
-    if (p.packed) {                                                                                       \
+    if (p.packed && p.ft == 2 && (NT_ == 2 || NT_ == 4)) {                                                \
+      constexpr int NTF = (NT_ == 2 || NT_ == 4) ? NT_ : 2;                                               \
+      if (p.wdt == SSRNN_FP8)                                                                             \
+        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_FP8, NTF, 2>), grid, block, 0, st, s, p.d, p.k); \
+      else if (p.wdt == SSRNN_BF16)                                                                       \
+        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_BF16, NTF, 2>), grid, block, 0, st, s, p.d, p.k); \
+      else                                                                                                \
+        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_F32, NTF, 2>), grid, block, 0, st, s, p.d, p.k); \
+    } else if (p.packed) {                                                                                \
       if (p.wdt == SSRNN_FP8)                                                                             \
         hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_FP8, NT_>), grid, block, 0, st, s, p.d, p.k); \
       else if (p.wdt == SSRNN_BF16)                                                                       \
@@ -845,6 +863,7 @@ int ssrnn_tune(const char* key, int value) {
   else if (!strcmp(key, "valu_nw")) g_tune_valu_nw = value;
   else if (!strcmp(key, "valu_nv")) g_tune_valu_nv = value;
   else if (!strcmp(key, "ksplit")) g_tune_ksplit = value;
+  else if (!strcmp(key, "feature_tiles")) g_tune_ft = value;
   else if (!strcmp(key, "spin_limit")) g_tune_spin_limit = value;
   else return fail(SSRNN_EINVAL, "ssrnn_tune: unknown key %s", key);
   return SSRNN_OK;

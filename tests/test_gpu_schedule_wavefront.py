@@ -81,3 +81,37 @@ def test_fewer_blocks_than_layers_and_single_block():
         ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=2)
         for u, r in zip(got, ref):
             assert max_abs(u, r) <= TOL, max_abs(u, r)
+
+
+@pytest.mark.parametrize("cell,k,T,fp8", [("sru", 1, 64, False), ("qrnn", 2, 32, False), ("qrnn", 2, 64, True), ("sru", 1, 32, True)])
+def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, fp8):
+    """d = 4096, narrow weight types, packed, 17 <= T <= 64 and two stages per launch: the matrix-core kernel
+    gives a workgroup 32 features (half the input-block traffic).  Per feature the arithmetic and its order
+    are those of the one-tile kernel, so the bits must agree; both are also held to the oracle."""
+    import workloads as wl
+    import paper_1803_11389_amd as ss
+    d, n_layers = 4096, 2
+    L = 2 * T + 3
+    print(f"two tiles {cell} k={k} T={T} fp8={fp8}", flush=True)
+    rng = np.random.default_rng(4200 + T + k)
+    ncol = k * d
+    Wf = [(rng.uniform(-1, 1, (3 * d, ncol)) * 2.0 / np.sqrt(ncol)).astype(np.float32) for _ in range(n_layers)]
+    W = [wl.quantize_fp8(w) for w in Wf] if fp8 else [wl.to_bf16_bits(w) for w in Wf]
+    x = rng.standard_normal((L, d)).astype(np.float32)
+    if cell == "sru":
+        run = lambda: gpu_sru(W, None, x, None, T=T, packed=True)
+        ref = oracle.sru_forward(W, None, x, T=T)
+    else:
+        run = lambda: gpu_qrnn(W, None, x, None, None, T=T, k=k, packed=True)
+        ref = oracle.qrnn_forward(W, None, x, T=T, k=k)
+    two = run()
+    ss.tune("feature_tiles", 1)
+    try:
+        one = run()
+    finally:
+        ss.tune("feature_tiles", 0)
+    for u, v in zip(two, one):
+        np.testing.assert_array_equal(u, v)
+    for u, r in zip(two, ref):
+        if np.asarray(r).size:
+            assert _rel_err(u, r) <= BF16_TOL, _rel_err(u, r)
