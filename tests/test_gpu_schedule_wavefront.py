@@ -83,27 +83,34 @@ def test_fewer_blocks_than_layers_and_single_block():
             assert max_abs(u, r) <= TOL, max_abs(u, r)
 
 
-@pytest.mark.parametrize("cell,k,T,fp8", [("sru", 1, 64, False), ("qrnn", 2, 32, False), ("qrnn", 2, 64, True), ("sru", 1, 32, True)])
-def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, fp8):
-    """d = 4096, narrow weight types, packed, 17 <= T <= 64 and two stages per launch: the matrix-core kernel
-    gives a workgroup 32 features (half the input-block traffic).  Per feature the arithmetic and its order
-    are those of the one-tile kernel, so the bits must agree; both are also held to the oracle."""
+@pytest.mark.parametrize("cell,k,T,mode,d,n_layers", [
+    ("sru", 1, 64, "bf16", 4096, 2), ("qrnn", 2, 32, "bf16", 4096, 2), ("qrnn", 2, 64, "fp8", 4096, 2), ("sru", 1, 32, "fp8", 4096, 2),
+    ("qrnn", 3, 33, "bf16", 2048, 5), ("sru", 1, 20, "f32", 2048, 6), ("qrnn", 2, 48, "fp8", 2048, 4),
+])
+def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, mode, d, n_layers):
+    """Packed weights, 17 <= T <= 64 and launches wide enough to fill the chip with d/32 workgroups per
+    stage: the matrix-core kernel gives a workgroup 32 features (half the input-block traffic).  Per
+    feature the arithmetic and its order are those of the one-tile kernel, so the bits must agree; the
+    result is also held to the oracle.  Biases, initial state and a ragged last block included."""
     import workloads as wl
     import paper_1803_11389_amd as ss
-    d, n_layers = 4096, 2
     L = 2 * T + 3
-    print(f"two tiles {cell} k={k} T={T} fp8={fp8}", flush=True)
-    rng = np.random.default_rng(4200 + T + k)
+    print(f"two tiles {cell} k={k} T={T} {mode} d={d} layers={n_layers}", flush=True)
+    rng = np.random.default_rng(4200 + T + k + d)
     ncol = k * d
     Wf = [(rng.uniform(-1, 1, (3 * d, ncol)) * 2.0 / np.sqrt(ncol)).astype(np.float32) for _ in range(n_layers)]
-    W = [wl.quantize_fp8(w) for w in Wf] if fp8 else [wl.to_bf16_bits(w) for w in Wf]
+    W = [wl.quantize_fp8(w) for w in Wf] if mode == "fp8" else [wl.to_bf16_bits(w) for w in Wf] if mode == "bf16" else Wf
+    nb = 2 if cell == "sru" else 3
+    b = [rng.uniform(-1, 1, nb * d).astype(np.float32) for _ in range(n_layers)]
     x = rng.standard_normal((L, d)).astype(np.float32)
+    c0 = rng.standard_normal((n_layers, d)).astype(np.float32)
+    xh0 = rng.standard_normal((n_layers, k - 1, d)).astype(np.float32) if k > 1 else None
     if cell == "sru":
-        run = lambda: gpu_sru(W, None, x, None, T=T, packed=True)
-        ref = oracle.sru_forward(W, None, x, T=T)
+        run = lambda: gpu_sru(W, b, x, c0, T=T, packed=True)
+        ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
     else:
-        run = lambda: gpu_qrnn(W, None, x, None, None, T=T, k=k, packed=True)
-        ref = oracle.qrnn_forward(W, None, x, T=T, k=k)
+        run = lambda: gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, packed=True)
+        ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
     two = run()
     ss.tune("feature_tiles", 1)
     try:
@@ -114,4 +121,7 @@ def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, fp8):
         np.testing.assert_array_equal(u, v)
     for u, r in zip(two, ref):
         if np.asarray(r).size:
-            assert _rel_err(u, r) <= BF16_TOL, _rel_err(u, r)
+            if mode == "f32":
+                assert max_abs(u, r) <= TOL, max_abs(u, r)
+            else:
+                assert _rel_err(u, r) <= BF16_TOL, _rel_err(u, r)
