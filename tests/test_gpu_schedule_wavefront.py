@@ -94,7 +94,7 @@ def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, mode, d,
     result is also held to the oracle.  Biases, initial state and a ragged last block included."""
     import workloads as wl
     import paper_1803_11389_amd as ss
-    L = 2 * T + 3
+    L = (2 if d >= 4096 else 5) * T + 3        # enough blocks in flight that d/32 workgroups per stage fill the chip
     print(f"two tiles {cell} k={k} T={T} {mode} d={d} layers={n_layers}", flush=True)
     rng = np.random.default_rng(4200 + T + k + d)
     ncol = k * d
