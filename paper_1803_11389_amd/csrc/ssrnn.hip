@@ -479,11 +479,14 @@ int launch_persistent(const Plan& p, const void* const* W, const float* const* b
 
 template <int CELL>
 int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
-  const dim3 grid(p.d / (MFMA_F * (p.packed ? p.ft : 1)) * p.ksplit, nstage);
+  // two feature tiles per workgroup only for launches that fill the chip that way (the first and last
+  // steps of a wavefront hold fewer stages); both instances give the same bits
+  const int ft = (p.packed && p.ft == 2 && static_cast<long>(p.d) / (2 * MFMA_F) * nstage >= 256) ? 2 : 1;
+  const dim3 grid(p.d / (MFMA_F * ft) * p.ksplit, nstage);
   const dim3 block(p.mfma_nw * 64);
 #define SSRNN_MFMA_CASE(NT_)                                                                              \
   if (p.nt_tiles == NT_) {                                                                                \
-    if (p.packed && p.ft == 2 && (NT_ == 2 || NT_ == 4)) {                                                \
+    if (ft == 2 && (NT_ == 2 || NT_ == 4)) {                                                              \
       constexpr int NTF = (NT_ == 2 || NT_ == 4) ? NT_ : 2;                                               \
       if (p.wdt == SSRNN_FP8)                                                                             \
         hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_FP8, NTF, 2>), grid, block, 0, st, s, p.d, p.k); \
