@@ -184,7 +184,9 @@ int ssrnn_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
  * narrow layer's columns over several workgroups; 2, 4, 8: at most that many
  * parts), "feature_tiles" (1: the packed matrix-core kernel always gives a workgroup one
  * tile of 16 features; by default it gives two where a launch holds enough
- * stages), "spin_limit" (ticks of the 100 MHz wall clock that one grid-barrier
+ * stages), "wide" (1: never the kernel that gives a workgroup 64 features, which
+ * long blocks of packed bf16 weights take by default when launches are wide
+ * enough), "spin_limit" (ticks of the 100 MHz wall clock that one grid-barrier
  * wait of the persistent schedule may take before the kernel gives up; default
  * one second).  A value the shape does not allow is ignored.  Results are
  * unaffected beyond fp32 re-association.  Host.  Returns SSRNN_EINVAL for an

@@ -116,6 +116,10 @@ __device__ __forceinline__ void store_operand(void* op, int ldt, int op_bf16, in
   else static_cast<float*>(op)[(static_cast<long>(i >> 2) * ldt + r) * 4 + (i & 3)] = v;
 }
 
+// Workgroup barrier that orders LDS traffic only: vector-memory requests of the
+// waves (the weight prefetch) stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Logistic function and tanh from the hardware exp2; absolute error a few
 // 1e-7, both saturate cleanly (exp -> inf gives 0 / -1, exp -> 0 gives 1 / 1).
 __device__ __forceinline__ float sigmoidf_fast(float z) {

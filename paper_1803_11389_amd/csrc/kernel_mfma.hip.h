@@ -98,13 +98,14 @@ struct MfmaEpilogueOperands {
   float xh[EPT];        // SRU: x_t of this thread's (feature, step) pairs of chunk 0
 };
 
+// tid: the thread's index among the NW * 64 threads that share the feature tile (threadIdx.x when the
+// whole workgroup does; the lane when every wave has a tile of its own, NW = 1).
 template <int CELL, int NT, int NW>
-__device__ __forceinline__ MfmaEpilogueOperands<NT, NW> mfma_epilogue_fetch(const Stage& s, int d, int f0) {
+__device__ __forceinline__ MfmaEpilogueOperands<NT, NW> mfma_epilogue_fetch(const Stage& s, int d, int f0, int tid) {
   constexpr int NTH = NW * 64;
   constexpr int CT = MfmaCfg<NT>::NTC * 16;
   constexpr int CHUNK = MfmaCfg<NT>::NTC * 256;
   MfmaEpilogueOperands<NT, NW> o;
-  const int tid = threadIdx.x;
   o.b0 = o.b1 = o.b2 = 0.0f;
   if (s.bias) {
     const int i = f0 + (tid & 15);
@@ -128,14 +129,20 @@ __device__ __forceinline__ MfmaEpilogueOperands<NT, NW> mfma_epilogue_fetch(cons
 }
 
 template <int CELL, int NT, int NW>
+__device__ __forceinline__ MfmaEpilogueOperands<NT, NW> mfma_epilogue_fetch(const Stage& s, int d, int f0) {
+  return mfma_epilogue_fetch<CELL, NT, NW>(s, d, f0, static_cast<int>(threadIdx.x));
+}
+
+// The LDS arrays belong to the NW * 64 threads that share the tile; the barriers inside are workgroup
+// barriers, so every wave of the workgroup must make the call (the stage's step count is uniform).
+template <int CELL, int NT, int NW>
 __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, floatx4_t (&acc)[3][NT],
                                               const MfmaEpilogueOperands<NT, NW>& ops, float* part,
-                                              float* g_a, float* g_b, float* g_o, float* c_carry) {
+                                              float* g_a, float* g_b, float* g_o, float* c_carry, int tid) {
   constexpr int NTH = NW * 64;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int CHUNK = NTC * 256;              // (step, feature) pairs per chunk
   constexpr int EPT = (CHUNK + NTH - 1) / NTH;  // pairs per thread
-  const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int li = lane & 15;
@@ -224,6 +231,13 @@ __device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, flo
       // reading; its first barrier orders this phase's reads before the next phase B
     }
   }
+}
+
+template <int CELL, int NT, int NW>
+__device__ __forceinline__ void mfma_epilogue(const Stage& s, int d, int f0, floatx4_t (&acc)[3][NT],
+                                              const MfmaEpilogueOperands<NT, NW>& ops, float* part,
+                                              float* g_a, float* g_b, float* g_o, float* c_carry) {
+  mfma_epilogue<CELL, NT, NW>(s, d, f0, acc, ops, part, g_a, g_b, g_o, c_carry, static_cast<int>(threadIdx.x));
 }
 
 // Split-K over workgroups (narrow layers): instead of the epilogue, a workgroup

@@ -51,10 +51,6 @@ struct PersistArgs {
 __device__ __forceinline__ void store_agent(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float load_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// Workgroup barrier that orders LDS traffic only: vector-memory requests of the
-// waves (the weight prefetch) stay in flight across it.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
 // Requirements (checked by the host): k = 1, fp32, one pass covers all columns
 // (NW * NV * 256 == d), F / FG even and >= 2, F * TT <= blockDim.x,
 // n_layers <= PERSIST_MAX_LAYERS, gridDim.x * F == d, all workgroups resident

@@ -29,6 +29,7 @@
 #include "kernel_mfma.hip.h"
 #include "kernel_mfma_lds.hip.h"
 #include "kernel_mfma_packed.hip.h"
+#include "kernel_mfma_wide.hip.h"
 #include "kernel_valu_persistent.hip.h"
 
 using namespace ssrnn;
@@ -277,6 +278,7 @@ struct Plan {
   bool packed;         // weights are in the matrix-core fragment order (ssrnn_pack_weights)
   bool lds_four_waves; // LDS-staged kernel, one or two time tiles: the four-wave instance (short rows)
   int ft;              // packed kernel: feature tiles (of 16) per workgroup, 1 or 2
+  bool wide;           // long blocks of packed bf16 weights: the 64-features-per-workgroup kernel
   bool one_wg_per_cu;  // vector-ALU geometry for a launch whose workgroups must all be resident
   int concurrent;      // stages per launch in the steady state of the schedule (1: one launch per stage)
 };
@@ -285,6 +287,7 @@ int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
 long long g_tune_spin_limit = 0;   // 0 = default (one second); otherwise wall-clock ticks a grid-barrier wait may take
 int g_tune_ksplit = 0;     // 0 = default, 1 = never split, 2/4/8 = at most that many parts
 int g_tune_ft = 0;         // 0 = default, 1 = always one feature tile per workgroup
+int g_tune_wide = 0;       // 0 = default, 1 = never the 64-features-per-workgroup kernel
 
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
   // a wave-wide 16-byte load covers 256 fp32, 512 bf16 or 1024 8-bit columns; the narrow types are taken up to T = 8
@@ -421,6 +424,12 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   // where those bytes weigh against the weights' (17..64 steps; measured at d = 4096, us per stage:
   // bf16 k = 2, T = 64: 43.4 -> 38.6; 8-bit: 29.7 -> 25.5; fp32 T = 32: 38.1 -> 37.0, T = 64 unchanged and
   // left alone) and needs a launch with enough stages to fill the chip with d/32 workgroups each.
+  // Long blocks of packed bf16 weights: 64 features per workgroup (the input block crosses a CU's memory
+  // path once for four feature tiles), when the launches hold enough stages to fill the chip with d/64
+  // workgroups each and a wave's walk over all columns is whole ring iterations.
+  p.wide = p.packed && p.wdt == SSRNN_BF16 && (p.nt_tiles == 8 || p.nt_tiles == 16) && p.ksplit == 1 &&
+           p.d % WIDE_F == 0 && ncol % (4 * WIDE_KSTEP) == 0 && static_cast<long>(p.d) / WIDE_F * conc >= 256 &&
+           g_tune_wide != 1;
   p.ft = 1;
   if (p.packed && (p.nt_tiles == 2 || (p.nt_tiles == 4 && p.wdt != SSRNN_F32)) && p.ksplit == 1 && ntile % 2 == 0 &&
       conc >= 2 && ntile / 2 * conc >= 256 && g_tune_ft != 1)
@@ -479,6 +488,14 @@ int launch_persistent(const Plan& p, const void* const* W, const float* const* b
 
 template <int CELL>
 int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
+  if (p.wide) {
+    const dim3 wgrid(p.d / WIDE_F, nstage), wblock(WIDE_TILES * 64);
+    if (p.nt_tiles == 8)
+      hipLaunchKernelGGL((stage_mfma_wide_kernel<CELL, 8>), wgrid, wblock, 0, st, s, p.d, p.k);
+    else
+      hipLaunchKernelGGL((stage_mfma_wide_kernel<CELL, 16>), wgrid, wblock, 0, st, s, p.d, p.k);
+    return SSRNN_OK;
+  }
   // two feature tiles per workgroup only for launches that fill the chip that way (the first and last
   // steps of a wavefront hold fewer stages); both instances give the same bits
   const int ft = (p.packed && p.ft == 2 && static_cast<long>(p.d) / (2 * MFMA_F) * nstage >= 256) ? 2 : 1;
@@ -867,6 +884,7 @@ int ssrnn_tune(const char* key, int value) {
   else if (!strcmp(key, "valu_nv")) g_tune_valu_nv = value;
   else if (!strcmp(key, "ksplit")) g_tune_ksplit = value;
   else if (!strcmp(key, "feature_tiles")) g_tune_ft = value;
+  else if (!strcmp(key, "wide")) g_tune_wide = value;
   else if (!strcmp(key, "spin_limit")) g_tune_spin_limit = value;
   else return fail(SSRNN_EINVAL, "ssrnn_tune: unknown key %s", key);
   return SSRNN_OK;

@@ -125,3 +125,45 @@ def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, mode, d,
                 assert max_abs(u, r) <= TOL, max_abs(u, r)
             else:
                 assert _rel_err(u, r) <= BF16_TOL, _rel_err(u, r)
+
+
+@pytest.mark.parametrize("cell,k,T,d,n_layers,nblocks", [
+    ("sru", 1, 100, 4096, 4, 4), ("qrnn", 2, 70, 2048, 8, 8), ("sru", 1, 256, 4096, 4, 4), ("qrnn", 3, 130, 2048, 8, 9),
+])
+def test_long_blocks_of_packed_bf16_weights_on_the_64_feature_kernel(cell, k, T, d, n_layers, nblocks):
+    """65 <= T <= 256, packed bf16 weights and launches wide enough for d/64 workgroups per stage to fill the
+    chip: the kernel whose waves own a feature tile each and share the input block through LDS.  Against the
+    oracle (bf16 bar), against the oracle that rounds the same operand, and against the 16-feature kernel on
+    the same inputs (the two sum a row's products in different orders, so not bit for bit)."""
+    import workloads as wl
+    import paper_1803_11389_amd as ss
+    from test_gpu_parity import _check_against_rounding_oracle
+    L = (nblocks - 1) * T + max(1, T // 3)           # a ragged last block
+    print(f"64-feature kernel {cell} k={k} T={T} d={d} layers={n_layers} L={L}", flush=True)
+    rng = np.random.default_rng(4300 + T + k + d)
+    ncol = k * d
+    W = [wl.to_bf16_bits((rng.uniform(-1, 1, (3 * d, ncol)) * 2.0 / np.sqrt(ncol)).astype(np.float32)) for _ in range(n_layers)]
+    nb = 2 if cell == "sru" else 3
+    b = [rng.uniform(-1, 1, nb * d).astype(np.float32) for _ in range(n_layers)]
+    x = rng.standard_normal((L, d)).astype(np.float32)
+    c0 = rng.standard_normal((n_layers, d)).astype(np.float32)
+    xh0 = rng.standard_normal((n_layers, k - 1, d)).astype(np.float32) if k > 1 else None
+    if cell == "sru":
+        run = lambda: gpu_sru(W, b, x, c0, T=T, packed=True)
+        ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
+    else:
+        run = lambda: gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, packed=True)
+        ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
+    wide = run()
+    ss.tune("wide", 1)
+    try:
+        narrow = run()
+    finally:
+        ss.tune("wide", 0)
+    for u, v, r in zip(wide, narrow, ref):
+        if np.asarray(r).size:
+            assert np.all(np.isfinite(u))
+            assert _rel_err(u, r) <= BF16_TOL, _rel_err(u, r)
+            assert _rel_err(u, v) <= 1e-3, _rel_err(u, v)
+    assert not all(np.array_equal(u, v) for u, v in zip(wide, narrow)), "the 64-feature kernel was not taken"
+    _check_against_rounding_oracle(cell, W, b, x, c0, xh0, T, k, wide[0], wide[1])
