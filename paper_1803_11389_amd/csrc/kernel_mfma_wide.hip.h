@@ -7,8 +7,9 @@
 // per stage, 27 us at 64 bytes per clock, more than the MFMAs take.  Here the
 // four waves of a workgroup own one feature tile each and walk ALL columns in
 // step; the k-step of X they all need (64 columns x NT*16 steps, bf16: 32 KiB at
-// 256 steps) is fetched once per workgroup into LDS, double-buffered, and read
-// by the four waves from there.  A CU then pulls X once for four tiles, and a
+// 256 steps) is fetched once per workgroup into LDS -- straight from memory
+// (global_load_lds, 16 bytes per lane, no staging registers), three buffers, two
+// k-steps ahead of its use -- and read by the four waves from there.  A CU then pulls X once for four tiles, and a
 // wave's accumulators hold complete sums, so the epilogue needs no sum across
 // waves.  A stage is d/64 workgroups: the chip is filled only by launches that
 // hold several stages (the wavefront schedule), which is when the host picks
@@ -16,8 +17,11 @@
 //
 // Weights: the packed layout of kernel_mfma_packed.hip.h; a wave streams the
 // fragments of its own tile, 6 KiB per k-step, through a ring of 4 k-steps.
-// One workgroup barrier per k-step orders the LDS buffers; it waits for LDS
-// traffic only, so the weight prefetch stays in flight across it.
+// One workgroup barrier per k-step orders the LDS buffers.  Before it a wave
+// waits until its own pieces of the next tile have landed (vmcnt counts loads in
+// issue order, so "all but the N youngest" names exactly them) and for its LDS
+// reads; the younger requests -- weight fragments and the tile after next --
+// stay in flight across the barrier.
 #pragma once
 
 #include "kernel_mfma.hip.h"
@@ -42,7 +46,8 @@ __global__ __launch_bounds__(WIDE_TILES * 64) void stage_mfma_wide_kernel(const 
   constexpr int EPI_PART = 3 * NTC * 256;
   constexpr int EPI_G = MFMA_F * (NTC * 16 + 1);
   constexpr int EPI_FLOATS = EPI_PART + 3 * EPI_G + MFMA_F;
-  constexpr int SMEM = (2 * BTILE > WIDE_TILES * EPI_FLOATS * 4) ? 2 * BTILE : WIDE_TILES * EPI_FLOATS * 4;
+  constexpr int NBUF = 3;                            // LDS buffers of X tiles
+  constexpr int SMEM = (NBUF * BTILE > WIDE_TILES * EPI_FLOATS * 4) ? NBUF * BTILE : WIDE_TILES * EPI_FLOATS * 4;
   __shared__ __attribute__((aligned(16))) char smem[SMEM];
 
   const int tid = threadIdx.x;
@@ -77,21 +82,19 @@ __global__ __launch_bounds__(WIDE_TILES * 64) void stage_mfma_wide_kernel(const 
     const int cc = e / R, r = e - cc * R;
     cp_src[i] = static_cast<int>(cc * ldtb) + min(r, s.nt - 1) * 16;
   }
-  ssrnn_f32x4 stage_regs[NCOPY];
   // k-step ks covers columns [ks*64, ks*64+64) of lag block j = ks*64 / d: chunk columns (m/8 .. m/8+7) of the
-  // operand copy, rows shifted back by the lag
-  auto fetch_b = [&](int ks) {
+  // operand copy, rows shifted back by the lag.  A wave's 64 lanes deliver 1 KiB that lies contiguous in the
+  // LDS tile (lane l at byte l*16 of it), which is what the load-to-LDS instruction writes.
+  auto fetch_b = [&](int ks, int buf) {
     const int col = ks * WIDE_KSTEP;
     const int j = col / d;
     const int m = col - j * d;
     const char* src = xop + static_cast<long>(m / 8) * ldtb - j * 16;
+    char* dst = smem + buf * BTILE + wave * 1024;
 #pragma unroll
-    for (int i = 0; i < NCOPY; ++i) stage_regs[i] = *reinterpret_cast<const ssrnn_f32x4*>(src + cp_src[i]);
-  };
-  auto store_b = [&](int buf) {
-    char* dst = smem + buf * BTILE + tid * 16;
-#pragma unroll
-    for (int i = 0; i < NCOPY; ++i) *reinterpret_cast<ssrnn_f32x4*>(dst + i * (WIDE_TILES * 64 * 16)) = stage_regs[i];
+    for (int i = 0; i < NCOPY; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + cp_src[i]),
+                                       (__attribute__((address_space(3))) void*)(dst + i * (WIDE_TILES * 64 * 16)), 16, 0, 0);
   };
 
   // ---- A side: ring of SA k-steps of this wave's fragments
@@ -125,26 +128,32 @@ __global__ __launch_bounds__(WIDE_TILES * 64) void stage_mfma_wide_kernel(const 
     }
   };
 
-  // ---- prologue: fragments of k-steps 0 .. SA-2, X tile of k-step 0 in buffer 0, tile 1 on its way
+  // ---- prologue: X tiles of k-steps 0 and 1 and the fragments of k-steps 0 .. SA-2 requested; tile 0 landed
+  fetch_b(0, 0);
+  fetch_b(1, 1);
 #pragma unroll
   for (int p = 0; p < SA - 1; ++p) load_a(p, p);     // nks >= SA (host)
-  fetch_b(0);
-  store_b(0);
-  fetch_b(1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   lds_barrier();
 
-  // ---- main loop, SA k-steps per iteration so that ring slots are compile-time.  In k-step ks the X tile
-  // of k-step ks+1, requested one step earlier, goes from registers to the other LDS buffer (which every
-  // wave stopped reading before the barrier that ended k-step ks-1), and the tile of k-step ks+2 is
-  // requested: a request has a whole k-step to arrive.
+  // ---- main loop, SA k-steps per iteration so that ring slots are compile-time.  K-step ks requests the X
+  // tile of k-step ks+2 into the buffer that held tile ks-1 (every wave stopped reading it before the barrier
+  // that ended k-step ks-1) and the fragments of k-step ks+3, multiplies, then waits for its pieces of tile
+  // ks+1: issued in k-step ks-1, with the fragments of ks+2, tile ks+2 and the fragments of ks+3 behind them.
+  constexpr int YOUNGER = 6 + NCOPY + 6;
   for (int ks0 = 0; ks0 < nks; ks0 += SA) {
 #pragma unroll
     for (int p = 0; p < SA; ++p) {
       const int ks = ks0 + p;
-      if (ks + 1 < nks) store_b((ks + 1) & 1);
-      if (ks + 2 < nks) fetch_b(ks + 2);
-      if (ks + SA - 1 < nks) load_a((p + SA - 1) % SA, ks + SA - 1);   // the slot k-step ks-1 has left
-      multiply(p, ks & 1);
+      const bool steady = ks + SA - 1 < nks;                          // all three kinds of request are made
+      // the count below relies on the order of issue: tile requests, then fragment requests, then the multiply
+      if (ks + 2 < nks) fetch_b(ks + 2, (ks + 2) % NBUF);
+      __builtin_amdgcn_sched_barrier(0);
+      if (steady) load_a((p + SA - 1) % SA, ks + SA - 1);             // the slot k-step ks-1 has left
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(p, ks % NBUF);
+      if (steady) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(YOUNGER) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // the last k-steps: fewer requests behind
       lds_barrier();                                                  // tile ks+1 is in place, tile ks is free
     }
   }
