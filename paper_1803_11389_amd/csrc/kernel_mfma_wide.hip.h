@@ -31,9 +31,11 @@ namespace ssrnn {
 constexpr int WIDE_TILES = 4;                 // feature tiles (of 16) per workgroup = waves
 constexpr int WIDE_F = WIDE_TILES * MFMA_F;   // features per workgroup
 constexpr int WIDE_KSTEP = 64;                // bf16 columns per k-step (128 bytes of a weight row)
+// weight fragment ring: 8 k-steps where the registers allow it (8 time tiles), else 4
+constexpr int wide_ring_slots(int nt) { return nt == 8 ? 8 : 4; }
 
-// Requirements (checked by the host): bf16 packed weights, d % 64 == 0, (k*d) % 256 == 0 (whole ring
-// iterations of 4 k-steps), NT * 16 >= nt, an operand copy of the input block, no split of the columns.
+// Requirements (checked by the host): bf16 packed weights, d % 64 == 0, k*d a multiple of
+// wide_ring_slots(NT) * 64 (whole ring iterations), NT * 16 >= nt, an operand copy of the input block, no split of the columns.
 template <int CELL, int NT>
 __global__ __launch_bounds__(WIDE_TILES * 64) void stage_mfma_wide_kernel(const StageBatch batch, int d, int k) {
   const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(WIDE_TILES * 64) void stage_mfma_wide_kernel(const 
   constexpr int R = NT * 16;                         // time rows of a B tile
   constexpr int BTILE = 8 * R * 16;                  // bytes of one k-step of X in LDS: 8 chunk columns x R rows x 16 B
   constexpr int NCOPY = BTILE / (WIDE_TILES * 64 * 16);   // 16-byte pieces each thread moves per k-step
-  constexpr int SA = 4;                              // weight fragment ring slots (k-steps)
+  constexpr int SA = wide_ring_slots(NT);            // weight fragment ring slots (k-steps)
   // epilogue arrays of one wave (the one-wave form of mfma_epilogue)
   constexpr int EPI_PART = 3 * NTC * 256;
   constexpr int EPI_G = MFMA_F * (NTC * 16 + 1);

@@ -428,7 +428,8 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   // path once for four feature tiles), when the launches hold enough stages to fill the chip with d/64
   // workgroups each and a wave's walk over all columns is whole ring iterations.
   p.wide = p.packed && p.wdt == SSRNN_BF16 && (p.nt_tiles == 8 || p.nt_tiles == 16) && p.ksplit == 1 &&
-           p.d % WIDE_F == 0 && ncol % (4 * WIDE_KSTEP) == 0 && static_cast<long>(p.d) / WIDE_F * conc >= 256 &&
+           p.d % WIDE_F == 0 && ncol % (wide_ring_slots(p.nt_tiles) * WIDE_KSTEP) == 0 &&
+           static_cast<long>(p.d) / WIDE_F * conc >= 256 &&
            g_tune_wide != 1;
   p.ft = 1;
   if (p.packed && (p.nt_tiles == 2 || (p.nt_tiles == 4 && p.wdt != SSRNN_F32)) && p.ksplit == 1 && ntile % 2 == 0 &&
