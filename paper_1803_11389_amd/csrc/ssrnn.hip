@@ -489,7 +489,9 @@ int launch_persistent(const Plan& p, const void* const* W, const float* const* b
 
 template <int CELL>
 int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
-  if (p.wide) {
+  // the first and last launches of a wavefront hold one or two stages: too few 64-feature workgroups to
+  // occupy the chip, so those go to the 16-feature kernel (another summation order, same tolerances)
+  if (p.wide && static_cast<long>(p.d) / WIDE_F * nstage > 128) {
     const dim3 wgrid(p.d / WIDE_F, nstage), wblock(WIDE_TILES * 64);
     if (p.nt_tiles == 8)
       hipLaunchKernelGGL((stage_mfma_wide_kernel<CELL, 8>), wgrid, wblock, 0, st, s, p.d, p.k);
