@@ -127,6 +127,27 @@ int sru_forward(const void* const* W, const float* const* bias, const float* x,
                 int d, long L, int T, int wdtype, int flags, void* workspace,
                 size_t workspace_bytes, void* stream);
 
+/* sru_forward for callers that cannot allocate device memory and so have no
+ * workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * sru_forward (SSRNN_SCHED_PERSISTENT excepted: SSRNN_EUNSUPPORTED); the scratch is
+ * a static array of SSRNN_NOALLOC_SCRATCH_BYTES in device memory that is part
+ * of the library's code object: every GPU the library runs on holds its own copy
+ * from the first call there until the process ends.  The call allocates and
+ * frees nothing.  The first call on a device looks the array's address up
+ * (make it outside any stream capture); later calls only launch kernels.
+ * A shape whose ssrnn_workspace_bytes(n_layers, d, 1, min(T, L), wdtype)
+ * exceeds SSRNN_NOALLOC_SCRATCH_BYTES fails with SSRNN_EWORKSPACE before any
+ * work is queued.  All calls on one GPU share that GPU's array, whatever their
+ * stream or thread: calls that overlap in time there race; queue them on one
+ * stream or order the streams.  Nothing in the array needs to start at zero
+ * and nothing is kept in it between calls. */
+#define SSRNN_NOALLOC_SCRATCH_BYTES (32u << 20)
+int sru_forward_noalloc(const void* const* W, const float* const* bias,
+                        const float* x, const float* c_init, float* h,
+                        float* c_final, int n_layers, int d, long L, int T,
+                        int wdtype, int flags, void* stream);
+
 /* Stacked QRNN forward with fo-pooling, Eq. 3 per layer generalised from the
  * printed window of 2 to a causal window of k inputs:
  *   u_g = sum_{j<k} W_g^j x_{t-j} (+ b_g);  xh = tanh(u_0); f = sigma(u_1); o = sigma(u_2);

@@ -22,7 +22,9 @@ WEIGHTS_PACKED = 1 << 8
 # every symbol include/ssrnn.h declares
 EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",
            "qrnn_forward", "ssrnn_linear_forward", "ssrnn_packed_weight_bytes", "ssrnn_pack_weights",
-           "ssrnn_read_probe", "ssrnn_workspace_status", "ssrnn_tune", "ssrnn_weight_bytes")
+           "ssrnn_read_probe", "ssrnn_workspace_status", "ssrnn_tune", "ssrnn_weight_bytes",
+           "sru_forward_noalloc")
+NOALLOC_SCRATCH_BYTES = 32 << 20   # SSRNN_NOALLOC_SCRATCH_BYTES of include/ssrnn.h
 
 _lib = None
 
@@ -50,6 +52,8 @@ def load_library():
     lib.ssrnn_workspace_bytes.argtypes = [ip] * 5
     lib.sru_forward.restype = ip
     lib.sru_forward.argtypes = [vp] * 6 + [ip, ip, lp, ip, ip, ip, vp, sz, vp]
+    lib.sru_forward_noalloc.restype = ip
+    lib.sru_forward_noalloc.argtypes = [vp] * 6 + [ip, ip, lp, ip, ip, ip, vp]
     lib.qrnn_forward.restype = ip
     lib.qrnn_forward.argtypes = [vp] * 8 + [ip, ip, lp, ip, ip, ip, ip, vp, sz, vp]
     lib.ssrnn_linear_forward.restype = ip
@@ -236,6 +240,35 @@ def sru_forward(W: List, bias: Optional[List], x, c_init=None, *, T: int, flags:
     rc = lib.sru_forward(wt, bt, _p(x), _p(c_init), _p(h), _p(c_final), n_layers, d, L, int(T), wdt,
                          int(flags), workspace.buf.data_ptr(), workspace.nbytes, _stream_handle(stream))
     _check(rc)
+    return h, c_final
+
+
+def sru_forward_noalloc(W: List, bias: Optional[List], x, c_init, h, c_final, *, T: int, flags: int = 0, stream=None):
+    """sru_forward_noalloc of include/ssrnn.h: sru_forward on the library's static
+    device scratch.  Every buffer, outputs included, is the caller's; nothing is
+    allocated here or in the library.  Returns (h, c_final)."""
+    import torch
+    lib = load_library()
+    n_layers = len(W)
+    d = W[0].shape[1]
+    wdt = _wdtype(W[0])
+    for w in W:
+        _req(w, "W[l]", (3 * d, d))
+    _req(x, "x", None, torch.float32)
+    L = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != d:
+        raise ValueError("x must be [L, d]")
+    _req(c_init, "c_init", (n_layers, d), torch.float32)
+    if bias is not None:
+        for b in bias:
+            _req(b, "bias[l]", (2 * d,), torch.float32)
+    if h is None or c_final is None:
+        raise ValueError("h and c_final must be given: this entry point allocates nothing")
+    _req(h, "h", (L, d), torch.float32)
+    _req(c_final, "c_final", (n_layers, d), torch.float32)
+    wt, bt = _ptr_table(W), _ptr_table(bias)
+    _check(lib.sru_forward_noalloc(wt, bt, _p(x), _p(c_init), _p(h), _p(c_final), n_layers, d, L, int(T), wdt,
+                                   int(flags), _stream_handle(stream)))
     return h, c_final
 
 

@@ -21,6 +21,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 
 #include "common.hip.h"
@@ -788,11 +789,44 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   return SSRNN_OK;
 }
 
+// ---- static device scratch of sru_forward_noalloc ---------------------------------
+// The array lives in every device's copy of the code object; host code never uses its name as an address,
+// only the per-device pointer hipGetSymbolAddress returns (looked up once per device, with that device
+// current).
+__device__ __align__(256) unsigned char scratch[SSRNN_NOALLOC_SCRATCH_BYTES];
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[NOALLOC_MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device, or null with the error recorded.
+void* static_scratch(int* status) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { *status = fail(SSRNN_EDEVICE, "hipGetDevice: %s", hipGetErrorString(e)); return nullptr; }
+  if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) {
+    *status = fail(SSRNN_EUNSUPPORTED, "sru_forward_noalloc: device ordinal %d is beyond the %d this library keeps scratch addresses for", dev, NOALLOC_MAX_DEVICES);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      *status = fail(SSRNN_EDEVICE, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *status = SSRNN_OK;
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
 
-int ssrnn_version(void) { return 200; }   // 0.2.0: 8-bit weights, wavefront schedule
+int ssrnn_version(void) { return 300; }   // 0.3.0: allocation-free entry point
 
 const char* ssrnn_last_error(void) { return g_last_error.c_str(); }
 
@@ -806,6 +840,27 @@ int sru_forward(const void* const* W, const float* const* bias, const float* x, 
                 void* workspace, size_t workspace_bytes, void* stream) {
   return forward(CELL_SRU, W, bias, x, c_init, nullptr, h, c_final, nullptr, n_layers, d, L, T, 1, wdtype,
                  flags, workspace, workspace_bytes, stream);
+}
+
+int sru_forward_noalloc(const void* const* W, const float* const* bias, const float* x, const float* c_init,
+                        float* h, float* c_final, int n_layers, int d, long L, int T, int wdtype, int flags,
+                        void* stream) {
+  if ((flags & SSRNN_SCHED_MASK) == SSRNN_SCHED_PERSISTENT)
+    return fail(SSRNN_EUNSUPPORTED, "sru_forward_noalloc: the persistent schedule reports through the caller's workspace and is not offered here");
+  if (n_layers < 1 || d < 1 || L < 0 || T < 1)
+    return fail(SSRNN_EINVAL, "sru_forward_noalloc: need n_layers >= 1, d >= 1, L >= 0, T >= 1 (got %d, %d, %ld, %d)", n_layers, d, L, T);
+  if (!shape_ok(n_layers, d, 1, T, wdtype)) return fail(SSRNN_EUNSUPPORTED, "sru_forward_noalloc: unknown weight type or shape too large");
+  // the block actually processed is at most L steps long, and the scratch is laid out for that
+  const int t_eff = (L > 0 && T > L) ? static_cast<int>(L) : T;
+  const size_t need = workspace_layout(n_layers, d, 1, t_eff, wdtype).total;
+  if (need > SSRNN_NOALLOC_SCRATCH_BYTES)
+    return fail(SSRNN_EWORKSPACE, "sru_forward_noalloc: this shape needs %zu bytes of scratch, the static array holds %zu; use sru_forward with a workspace",
+                need, static_cast<size_t>(SSRNN_NOALLOC_SCRATCH_BYTES));
+  int status = SSRNN_OK;
+  void* ptr = static_scratch(&status);
+  if (!ptr) return status;
+  return forward(CELL_SRU, W, bias, x, c_init, nullptr, h, c_final, nullptr, n_layers, d, L, T, 1, wdtype,
+                 flags, ptr, SSRNN_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int qrnn_forward(const void* const* W, const float* const* bias, const float* x, const float* c_init,
