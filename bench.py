@@ -4,22 +4,34 @@ size T, and achieved HBM bandwidth against the 8 TB/s peak.
 
 A "step" of this benchmark (--steps K) is one pass of the whole hot path over
 one batch of synthetic input: the full L-step sequence through the whole layer
-stack with one block size T, every layer's weights read once per block, in the
-library's default schedule (independent (block, layer) stages share a launch;
---flags 1 times the one-launch-per-stage schedule in streaming order).  The headline workload is the benchmark's HBM-roofline
-configuration (8-layer SRU, d = 4096, fp32 weights, 1.6 GB, L = 2048) at T = 4.
-Inputs and weights are resident in HBM before the timed region starts.
+stack with one block size T, every layer's weights read once per block.  The
+headline workload is the benchmark's HBM-roofline configuration (8-layer SRU,
+d = 4096, fp32 weights, 1.6 GB, L = 2048) at T = 4.  Inputs and weights are
+resident in HBM before the timed region starts.
 
-Prints ONE JSON line.  `value` = time steps per second of the headline (T given
-by --T); `sweep` lists the other block sizes of the same workload; `roofline`
-prices the dominant kernel against the HBM peak; `cpu_baseline` is the CPU
-oracle timed on this machine's host cores on a bounded sample.
+Two schedules are timed.  `value` / `roofline`: the library's default for a call
+that holds the whole sequence, in which the independent (block, layer) stages of
+an anti-diagonal share a launch -- block b+1 enters layer 0 while block b is in
+layer 1, so a block's output exists only once n_layers - 1 further blocks of
+input have been taken in (`config.lookahead_blocks`).  `roofline_streaming`:
+one launch per stage in streaming order, block b through all layers before block
+b+1 starts (no look-ahead: the T-step latency of Section 3 of the paper).
+
+Prints ONE JSON line.  `sweep` lists the other block sizes of the headline
+workload, `c5_sweep` the bf16 matrix-core configuration (8-layer QRNN, d = 4096,
+T = 16, 64, 256), `cache_resident_configs` the two configurations whose weights
+fit the Infinity Cache, priced against a read probe on resident data;
+`cpu_baseline` is the CPU oracle timed on this machine's host cores on a bounded
+sample.  Counter figures (`traffic`, `mfma_busy_pct`) are read from the rocprofv3
+summaries under profiles/ (profiles/INDEX.md), which were made with this file.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -30,29 +42,40 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
 FP32_PEAK_TFLOPS = 157.3    # MI355X published fp32 (vector / matrix) peak
 BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 MFMA peak (8-bit weights are multiplied as bf16)
+SWEEP_PASSES = 5            # sweep rows: median of this many timed passes after one warm-up
 
-# HBM bytes per launch of the stage kernel (read + written) measured with rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE and scaled by the copy probe; recorded from the summaries under profiles/ (same commands, same
-# workloads, default schedule: a launch holds up to n_layers stages).
-MEASURED_TRAFFIC_BYTES = {
-    ("C4", 1, "row-major"): 1_608_320_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T1.txt
-    ("C4", 4, "row-major"): 1_594_350_000,    # profiles/stage_valu_kernel_C4_sru8_d4096_T4.txt
-    ("C4", 16, "row-major"): 1_555_170_000,    # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T16.txt
-    ("C4", 16, "packed"): 1_555_160_000,    # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T16.txt
-    ("C4", 64, "row-major"): 1_407_210_000,    # profiles/stage_mfma_lds_kernel_f32_C4_sru8_d4096_T64.txt
-    ("C4", 64, "packed"): 1_407_300_000,    # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T64.txt
-    ("C4", 128, "packed"): 1_262_680_000,    # profiles/stage_mfma_packed_kernel_f32_C4_sru8_d4096_T128.txt
-    ("C5", 16, "packed"): 1_583_890_000,    # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T16.txt
-    ("C5", 64, "packed"): 1_497_710_000,    # profiles/stage_mfma_packed_kernel_bf16_C5_qrnn8_d4096_T64.txt
-    # ("C5", 256, "packed"): two kernels share that pass (profiles/stage_mfma_wide_kernel_bf16_C5_qrnn8_d4096_T256.txt)
-    ("C5", 256, "row-major"): 1_251_490_000,    # profiles/stage_mfma_lds_kernel_bf16_C5_qrnn8_d4096_T256.txt
-    ("X1", 1, "row-major"): 805_270_000,    # profiles/stage_valu_kernel_bf16_X1_sru8_d4096_T1.txt
-    ("X2", 1, "row-major"): 404_830_000,    # profiles/stage_valu_kernel_fp8_X2_sru8_d4096_T1.txt
-    ("X2", 16, "packed"): 399_850_000,    # profiles/stage_mfma_packed_kernel_fp8_X2_sru8_d4096_T16.txt
-    ("X3", 64, "packed"): 772_610_000,    # profiles/stage_mfma_packed_kernel_fp8_X3_qrnn8_d4096_T64.txt
-    ("X3", 256, "packed"): 732_460_000,    # profiles/stage_mfma_packed_kernel_fp8_X3_qrnn8_d4096_T256.txt
-    ("C2", 4, "row-major"): 50_660_000,    # profiles/stage_valu_kernel_C2_sru4_d1024_T4.txt
-}
+
+def profile_index(path=None):
+    """Rows of profiles/INDEX.md as dicts (column header -> cell text)."""
+    path = path or os.path.join(ROOT, "profiles", "INDEX.md")
+    rows, header = [], None
+    if not os.path.exists(path):
+        return rows
+    for line in open(path):
+        if not line.startswith("|"):
+            continue
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if header is None:
+            header = cells
+        elif not set(cells[0]) <= set("-: "):
+            rows.append(dict(zip(header, cells)))
+    return rows
+
+
+def profile_row(workload: str, T: int, weights: str, schedule: str, rows=None):
+    """The INDEX.md row of (workload name prefix, T, weight layout, schedule), or None."""
+    for r in (profile_index() if rows is None else rows):
+        if r.get("workload", "").startswith(workload) and r.get("T") == str(T) and r.get("weights") == weights \
+                and r.get("schedule") == schedule:
+            return r
+    return None
+
+
+def _num(cell):
+    try:
+        return float(cell)
+    except (TypeError, ValueError):
+        return None
 
 
 def parse_args():
@@ -62,7 +85,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C4", help="workload name prefix (C1..C5, X1..X3)")
     ap.add_argument("--T", type=int, default=4, help="block size of the headline number")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the other block sizes")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the other block sizes and the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--flags", type=int, default=0, help="ssrnn flags (schedule / kernel override)")
     ap.add_argument("--packed", action="store_true",
@@ -72,6 +95,155 @@ def parse_args():
                     help="only run a plain device copy of this many MiB three times and exit: the reference "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     return ap.parse_args()
+
+
+class Stack:
+    """One workload on the device: weights (row-major and, where a packed form exists, packed), input,
+    output buffers and a workspace for its largest block."""
+
+    def __init__(self, ss, wl, torch, cfg, dev, want_packed=True, tmax=0):
+        self.ss, self.cfg, self.torch = ss, cfg, torch
+        inp = wl.make_inputs(cfg)
+        self.W_host = inp["W"]
+        self.wdt = {"f32": ss.F32, "bf16": ss.BF16, "fp8": ss.FP8}[cfg.wdtype]
+        if self.wdt == ss.FP8:
+            self.W = [ss.Fp8Weights(torch.from_numpy(w.blob()).to(dev), cfg.d, cfg.k) for w in self.W_host]
+        else:
+            self.W = [torch.from_numpy(w).to(dev) for w in self.W_host]
+        # second copy of the weights in the matrix-core kernel's order: a model-load-time step, outside every timed region
+        self.W_packed = [ss.pack_weights(w) for w in self.W] if want_packed and ss.packed_weight_bytes(cfg.d, cfg.k, self.wdt) > 0 else None
+        if cfg.d_feat:
+            self.x = ss.linear_forward(torch.from_numpy(inp["P"]).to(dev), torch.from_numpy(inp["feat"]).to(dev))
+        else:
+            self.x = torch.from_numpy(inp["x"]).to(dev)
+        self.h = torch.empty((cfg.L, cfg.d), dtype=torch.float32, device=dev)
+        self.c_final = torch.empty((cfg.n_layers, cfg.d), dtype=torch.float32, device=dev)
+        self.ws = ss.Workspace.for_shape(cfg.n_layers, cfg.d, cfg.k, max(max(cfg.Ts), tmax), self.wdt, dev)
+        torch.cuda.synchronize()
+
+    def one_pass(self, T, flags=0, packed=False):
+        ss, cfg = self.ss, self.cfg
+        Wl = self.W_packed if packed else self.W
+        fl = flags | (ss.WEIGHTS_PACKED if packed else 0)
+        if cfg.cell == "sru":
+            ss.sru_forward(Wl, None, self.x, None, T=T, flags=fl, h=self.h, c_final=self.c_final, workspace=self.ws)
+        else:
+            ss.qrnn_forward(Wl, None, self.x, None, None, T=T, k=cfg.k, flags=fl, h=self.h, c_final=self.c_final, workspace=self.ws)
+
+    def time_block(self, T, steps, warmup, flags=0, packed=False):
+        """`steps` passes timed as one region: (seconds per pass by the host clock, ms per pass by HIP
+        events recorded on the stream the kernels are launched on)."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.one_pass(T, flags, packed)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            self.one_pass(T, flags, packed)
+        e1.record()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps, e0.elapsed_time(e1) / steps
+
+    def time_median(self, T, flags=0, packed=False, passes=SWEEP_PASSES):
+        """One warm-up, then `passes` passes timed one by one with HIP events: the median, in ms."""
+        torch = self.torch
+        self.one_pass(T, flags, packed)
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(passes):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            self.one_pass(T, flags, packed)
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return statistics.median(ms)
+
+    def launches(self, T, flags=0):
+        """(stages, launches of the stage kernel) of one pass at block size T."""
+        cfg, ss = self.cfg, self.ss
+        nblocks = (cfg.L + T - 1) // T
+        nstage = cfg.n_layers * nblocks
+        if (flags & 3) == ss.SCHED_STAGES or cfg.n_layers == 1 or nblocks == 1:
+            return nstage, nstage
+        # wavefront: one launch per anti-diagonal of the (block, layer) grid, at most 8 stages per launch
+        n = 0
+        for step in range(nblocks + cfg.n_layers - 1):
+            active = min(step, cfg.n_layers - 1) - max(0, step - (nblocks - 1)) + 1
+            n += (active + 7) // 8
+        return nstage, n
+
+    def row(self, T, ms):
+        cfg = self.cfg
+        nstage = cfg.n_layers * ((cfg.L + T - 1) // T)
+        steps_s = cfg.L / (ms * 1e-3)
+        gbs = cfg.algorithmic_bytes_per_step(T) * steps_s / 1e9
+        return {"T": T, "steps_per_s": round(steps_s, 1), "ms_per_pass": round(ms, 3),
+                "us_per_stage": round(ms * 1e3 / nstage, 2), "algorithmic_GBps": round(gbs, 1),
+                "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "TFLOPps": round(cfg.flops_per_step() * steps_s / 1e12, 2)}
+
+
+def roofline_block(stack, T, ev_ms, flags, packed, index_rows):
+    """Prices the stage kernel of one timed configuration: algorithmic bytes (or flops) of a launch over its
+    average duration (HIP events over the timed region / launches in it)."""
+    cfg, ss = stack.cfg, stack.ss
+    nstage, nlaunch = stack.launches(T, flags)
+    per_launch = nstage / nlaunch
+    stage_bytes = (cfg.weight_bytes_per_layer() + 2 * cfg.d * 4 * T) * per_launch
+    stage_flops = 2.0 * 3 * cfg.d * cfg.ncol * T * per_launch
+    launch_s = ev_ms * 1e-3 / nlaunch
+    schedule = "per-stage" if nlaunch == nstage else "wavefront"
+    prow = profile_row(cfg.name[:2], T, "packed" if packed else "row-major", schedule, index_rows) \
+        if (flags & ~(3 | ss.WEIGHTS_PACKED)) == 0 else None
+    common = {"traffic": int(_num(prow["traffic bytes per launch"])) if prow and _num(prow.get("traffic bytes per launch")) else None,
+              "traffic_source": ("profiles/" + prow["file"]) if prow else None,
+              "kernel": (prow["kernel"] if prow and prow.get("kernel") else "stage kernel"),
+              "schedule": schedule, "lookahead_blocks": (cfg.n_layers - 1) if schedule == "wavefront" else 0,
+              "launches_per_pass": nlaunch, "stages_per_launch": round(per_launch, 3),
+              "avg_launch_us": round(launch_s * 1e6, 2), "us_per_stage": round(ev_ms * 1e3 / nstage, 2),
+              "steps_per_s": round(cfg.L / (ev_ms * 1e-3), 1),
+              "algorithmic_bytes_per_launch": round(stage_bytes), "flops_per_launch": stage_flops,
+              "weights_vs_infinity_cache": round(cfg.n_layers * cfg.weight_bytes_per_layer() / 256e6, 2)}
+    # fp32 weights cross the ridge (157.3 TFLOP/s against 8 TB/s) near T = 39; bf16 weights stay HBM-bound up to
+    # T = 256 (ridge near T = 310 against 2.5 PFLOP/s); 8-bit weights (multiplied as bf16) cross near T = 156
+    if (cfg.wdtype == "f32" and T >= 64) or (cfg.wdtype == "fp8" and T >= 160):
+        peak = FP32_PEAK_TFLOPS if cfg.wdtype == "f32" else BF16_PEAK_TFLOPS
+        achieved = stage_flops / launch_s / 1e12
+        return {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), **common}
+    achieved = stage_bytes / launch_s / 1e9
+    return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), **common}
+
+
+def read_probe_rate(ss, torch, bufs, per_launch, reps_bytes=8e9):
+    """GB/s of ssrnn_read_probe launches that hold `per_launch` of the equally long buffers each (the
+    shape of a stage launch with that many stages), the best of a few workgroup counts."""
+    dev = bufs[0].device
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    nbytes = bufs[0].numel() * bufs[0].element_size()
+    groups_of = [bufs[i:i + per_launch] for i in range(0, len(bufs) - per_launch + 1, per_launch)]
+    reps = max(1, int(reps_bytes / (nbytes * per_launch * len(groups_of))))
+    best = None
+    for groups in (64, 128, 256, 512, 1024, 2048):
+        for g in groups_of:
+            ss.read_probe(g, sink, groups=groups)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            for g in groups_of:
+                ss.read_probe(g, sink, groups=groups)
+        e1.record()
+        torch.cuda.synchronize()
+        sec = e0.elapsed_time(e1) * 1e-3 / (reps * len(groups_of))
+        cand = {"GBps": round(nbytes * per_launch / sec / 1e9, 1), "us_per_launch": round(sec * 1e6, 2),
+                "bytes_per_launch": nbytes * per_launch, "workgroups_per_buffer": groups}
+        if best is None or cand["GBps"] > best["GBps"]:
+            best = cand
+    return best
 
 
 def main():
@@ -100,206 +272,99 @@ def main():
         print(json.dumps({"copy_probe_MiB": args.copy_probe, "bytes_read_per_copy": n * 4, "bytes_written_per_copy": n * 4}))
         return
     ss.load_library()
+    index_rows = profile_index()
 
     t_gen = time.perf_counter()
-    inp = wl.make_inputs(cfg)
-    W_host = inp["W"]
-    wdt = {"f32": ss.F32, "bf16": ss.BF16, "fp8": ss.FP8}[cfg.wdtype]
-    if wdt == ss.FP8:
-        W = [ss.Fp8Weights(torch.from_numpy(w.blob()).to(dev), cfg.d, cfg.k) for w in W_host]
-        if args.T > 8:
-            args.packed = True      # 8-bit weights reach the matrix cores in packed form only
-    else:
-        W = [torch.from_numpy(w).to(dev) for w in W_host]
-    # second copy of the weights in the matrix-core kernel's order (a model-load-time step, outside
-    # every timed region); the sweep times both layouts
-    W_packed = None
-    if ss.packed_weight_bytes(cfg.d, cfg.k, wdt) > 0 and (args.packed or (not args.no_sweep and args.flags == 0)):
-        W_packed = [ss.pack_weights(w) for w in W]
+    wdt_is_fp8 = cfg.wdtype == "fp8"
+    if wdt_is_fp8 and args.T > 8:
+        args.packed = True      # 8-bit weights reach the matrix cores in packed form only
+    sched = args.flags & 3
+    stack = Stack(ss, wl, torch, cfg, dev, want_packed=args.packed or not args.no_sweep, tmax=args.T)
     if args.packed:
-        assert W_packed is not None, "this workload's weights cannot be packed"
-        W = W_packed
-        args.flags |= ss.WEIGHTS_PACKED
-    if cfg.d_feat:
-        feat = torch.from_numpy(inp["feat"]).to(dev)
-        P = torch.from_numpy(inp["P"]).to(dev)
-        x = ss.linear_forward(P, feat)
-    else:
-        x = torch.from_numpy(inp["x"]).to(dev)
-    torch.cuda.synchronize()
+        assert stack.W_packed is not None, "this workload's weights cannot be packed"
     t_gen = time.perf_counter() - t_gen
 
-    h = torch.empty((cfg.L, cfg.d), dtype=torch.float32, device=dev)
-    c_final = torch.empty((cfg.n_layers, cfg.d), dtype=torch.float32, device=dev)
-    Tmax = max(max(cfg.Ts), args.T)
-    ws = ss.Workspace.for_shape(cfg.n_layers, cfg.d, cfg.k, Tmax, wdt, dev)
-
-    def one_pass(T, packed=False):
-        Wl = W_packed if packed else W
-        fl = args.flags | (ss.WEIGHTS_PACKED if packed else 0)
-        if cfg.cell == "sru":
-            ss.sru_forward(Wl, None, x, None, T=T, flags=fl, h=h, c_final=c_final, workspace=ws)
-        else:
-            ss.qrnn_forward(Wl, None, x, None, None, T=T, k=cfg.k, flags=fl, h=h, c_final=c_final, workspace=ws)
-
-    def measure(T, steps, warmup, packed=False):
-        """Returns (seconds per pass by the host clock, ms per pass by HIP events
-        recorded on the stream the kernels are launched on)."""
-        for _ in range(warmup):
-            one_pass(T, packed)
-        torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        for _ in range(steps):
-            one_pass(T, packed)
-        e1.record()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        return dt / steps, e0.elapsed_time(e1) / steps
-
-    def launches(T):
-        """(stages, launches of the stage kernel) of one pass at block size T under args.flags."""
-        nblocks = (cfg.L + T - 1) // T
-        nstage = cfg.n_layers * nblocks
-        sched = args.flags & 3
-        if sched == ss.SCHED_PERSISTENT:
-            return nstage, 1
-        if sched == ss.SCHED_STAGES or cfg.n_layers == 1 or nblocks == 1:
-            return nstage, nstage
-        # wavefront: one launch per anti-diagonal of the (block, layer) grid, at most 8 stages per launch
-        n = 0
-        for step in range(nblocks + cfg.n_layers - 1):
-            active = min(step, cfg.n_layers - 1) - max(0, step - (nblocks - 1)) + 1
-            n += (active + 7) // 8
-        return nstage, n
-
-    def row(T, sec, ev_ms):
-        nstage = cfg.n_layers * ((cfg.L + T - 1) // T)
-        steps_s = cfg.L / sec
-        gbs = cfg.algorithmic_bytes_per_step(T) * steps_s / 1e9
-        tf = cfg.flops_per_step() * steps_s / 1e12
-        return {"T": T, "steps_per_s": round(steps_s, 1), "ms_per_pass": round(sec * 1e3, 3),
-                "us_per_stage": round(ev_ms * 1e3 / nstage, 2), "algorithmic_GBps": round(gbs, 1),
-                "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "TFLOPps": round(tf, 2)}
-
-    sec, ev_ms = measure(args.T, args.steps, args.warmup)
-    head = row(args.T, sec, ev_ms)
-    h_head = h[: min(cfg.L, 1024)].clone()
-
+    # ---- headline: exactly --steps passes timed as one region
+    sec, ev_ms = stack.time_block(args.T, args.steps, args.warmup, args.flags, args.packed)
+    head = stack.row(args.T, sec * 1e3)
     head["weights"] = "packed" if args.packed else "row-major"
+    h_head = stack.h[: min(cfg.L, 1024)].clone()
+    roofline = roofline_block(stack, args.T, ev_ms, args.flags, args.packed, index_rows)
+
+    # ---- the same block size with one launch per stage in streaming order (no look-ahead)
+    roofline_streaming = None
+    if sched == 0 and roofline["schedule"] == "wavefront":
+        _, ev_s = stack.time_block(args.T, max(2, args.steps // 2), 1, args.flags | ss.SCHED_STAGES, args.packed)
+        roofline_streaming = roofline_block(stack, args.T, ev_s, args.flags | ss.SCHED_STAGES, args.packed, index_rows)
+
     sweep = []
     if not args.no_sweep:
         for T in cfg.Ts:
-            if T == args.T:
-                r = dict(head)
-            elif wdt == ss.FP8 and T > 8 and not args.packed:
-                r = {"T": T, "weights": "row-major", "note": "row-major 8-bit weights run 8 steps per weight pass beyond T = 8 (the T = 8 row); see packed"}
-            else:
-                s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
-                r = row(T, s_, e_)
-                r["weights"] = head["weights"]
-            if (args.flags & 3) == 0 and launches(T)[0] != launches(T)[1] and "steps_per_s" in r:
-                # the same block size with one launch per stage in streaming (block-major) order
-                keep = args.flags
-                args.flags |= ss.SCHED_STAGES
-                s_, e_ = measure(T, max(1, min(args.steps, 2)), 1)
-                args.flags = keep
-                ps = row(T, s_, e_)
+            if wdt_is_fp8 and T > 8 and not args.packed:
+                sweep.append({"T": T, "weights": "row-major", "note": "row-major 8-bit weights run 8 steps per weight pass beyond T = 8 (the T = 8 row); see packed"})
+                continue
+            r = stack.row(T, stack.time_median(T, args.flags, args.packed))
+            r["weights"] = head["weights"]
+            r["passes"] = f"median of {SWEEP_PASSES}"
+            nstage, nlaunch = stack.launches(T, args.flags)
+            if sched == 0 and nstage != nlaunch:
+                ps = stack.row(T, stack.time_median(T, args.flags | ss.SCHED_STAGES, args.packed))
                 r["per_stage_schedule"] = {key: ps[key] for key in ("steps_per_s", "us_per_stage", "frac_hbm_peak")}
-            if W_packed is not None and not args.packed:
-                # the same block size with pre-packed weights (matrix-core kernel at every T)
-                s_, e_ = measure(T, max(1, min(args.steps, 2)), 1, packed=True)
-                pk = row(T, s_, e_)
+            if stack.W_packed is not None and not args.packed:
+                pk = stack.row(T, stack.time_median(T, args.flags, True))
                 r["packed"] = {key: pk[key] for key in ("steps_per_s", "us_per_stage", "algorithmic_GBps", "frac_hbm_peak", "TFLOPps")}
             sweep.append(r)
 
-    # dominant kernel: the stage kernel.  Algorithmic bytes of one (block, layer)
-    # stage = the layer's weights once + the input block read + the output block
-    # written (fp32); a launch holds nstage / nlaunch stages on average.
-    # Duration = event time of the timed region / launches in it.
-    T = args.T
-    nstage, nlaunch = launches(T)
-    per_launch = nstage / nlaunch
-    stage_bytes = (cfg.weight_bytes_per_layer() + 2 * cfg.d * 4 * T) * per_launch
-    stage_flops = 2.0 * 3 * cfg.d * cfg.ncol * T * per_launch
-    stage_s = ev_ms * 1e-3 / nlaunch
-    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name[:2], T, "packed" if args.packed else "row-major")) \
-        if (args.flags & ~ss.WEIGHTS_PACKED) == 0 else None
-    per_stage_schedule = next((r_.get("per_stage_schedule") for r_ in sweep if r_["T"] == T), None)
-    common = {"traffic": traffic, "kernel": "stage kernel (a launch holds the independent (block, layer) stages of one step)",
-              "launches_per_pass": nlaunch, "stages_per_launch": round(per_launch, 3),
-              "avg_launch_us": round(stage_s * 1e6, 2), "us_per_stage": head["us_per_stage"],
-              "algorithmic_bytes_per_launch": round(stage_bytes),
-              "flops_per_launch": stage_flops,
-              "weights_vs_infinity_cache": round(cfg.n_layers * cfg.weight_bytes_per_layer() / 256e6, 2)}
-    # fp32 weights cross the ridge (157.3 TFLOP/s against 8 TB/s) near T = 39; bf16 weights stay
-    # HBM-bound up to T = 256 (ridge near T = 310 against 2.5 PFLOP/s)
-    # 8-bit weights (multiplied as bf16) cross near T = 156
-    if (cfg.wdtype == "f32" and T >= 64) or (cfg.wdtype == "fp8" and T >= 160):
-        peak = FP32_PEAK_TFLOPS if cfg.wdtype == "f32" else BF16_PEAK_TFLOPS
-        achieved = stage_flops / stage_s / 1e12
-        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                    "frac": round(achieved / peak, 4), **common}
-    else:
-        achieved = stage_bytes / stage_s / 1e9
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), **common}
-
-    # What a kernel that only reads reaches on this device, at the stage kernels' launch size: one probe
-    # launch per layer's weight matrix, layers in turn so that nothing stays in cache between launches.
-    sink = torch.zeros(4, dtype=torch.int32, device=dev)
-    probe_bufs = [w.buf if wdt == ss.FP8 else w for w in W]
-    for w in probe_bufs:
-        ss.read_probe(w, sink)
-    torch.cuda.synchronize()
-    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = max(1, 64 // len(W))
-    p0.record()
-    for _ in range(reps):
-        for w in probe_bufs:
-            ss.read_probe(w, sink)
-    p1.record()
-    torch.cuda.synchronize()
-    probe_s = p0.elapsed_time(p1) * 1e-3 / (reps * len(W))
-    probe_gbs = cfg.weight_bytes_per_layer() / probe_s / 1e9
-    roofline["read_probe_GBps"] = round(probe_gbs, 1)
-    roofline["read_probe_us_per_layer"] = round(probe_s * 1e6, 2)
+    # ---- what a kernel that only reads reaches, in launches of the stage launches' shape and size: eight
+    # layers per launch (the wavefront schedule's launches) and one layer per launch (the per-stage schedule's)
+    probe_bufs = [w.buf if wdt_is_fp8 else w for w in stack.W]
+    probe = {"wavefront_shaped": read_probe_rate(ss, torch, probe_bufs, min(8, len(probe_bufs))),
+             "per_stage_shaped": read_probe_rate(ss, torch, probe_bufs, 1)}
     if roofline["bound"] == "hbm":
-        roofline["frac_of_read_probe"] = round(roofline["achieved"] / probe_gbs, 4)
+        key = "wavefront_shaped" if roofline["schedule"] == "wavefront" else "per_stage_shaped"
+        roofline["read_probe_GBps"] = probe[key]["GBps"]
+        roofline["frac_of_read_probe"] = round(roofline["achieved"] / probe[key]["GBps"], 4)
+    if roofline_streaming and roofline_streaming["bound"] == "hbm":
+        roofline_streaming["read_probe_GBps"] = probe["per_stage_shaped"]["GBps"]
+        roofline_streaming["frac_of_read_probe"] = round(roofline_streaming["achieved"] / probe["per_stage_shaped"]["GBps"], 4)
 
-    # The two cache-resident configurations of the benchmark (4 layers of d = 1024, 50 / 101 MB of weights), every
-    # block size of theirs in the default schedule: a few milliseconds each, reported next to the headline workload.
-    others = []
-    if not args.no_sweep and cfg.name.startswith("C4") and args.flags == 0:
+    # ---- configuration 5 (bf16 weights on the matrix cores) and the two cache-resident configurations
+    c5_sweep, others = [], []
+    if not args.no_sweep and cfg.name.startswith("C4") and args.flags == 0 and not args.packed:
+        del stack.W_packed
+        stack.W_packed = None
+        torch.cuda.empty_cache()
+        c5 = wl.by_name("C5")
+        s5 = Stack(ss, wl, torch, c5, dev)
+        for T in c5.Ts:
+            r = s5.row(T, s5.time_median(T, 0, True))
+            r["weights"] = "packed"
+            r["frac_bf16_mfma_peak"] = round(r["TFLOPps"] / BF16_PEAK_TFLOPS, 4)
+            ps = s5.row(T, s5.time_median(T, ss.SCHED_STAGES, True))
+            r["per_stage_schedule"] = {key: ps[key] for key in ("steps_per_s", "us_per_stage", "frac_hbm_peak", "TFLOPps")}
+            rm = s5.row(T, s5.time_median(T, 0, False))
+            r["row_major"] = {key: rm[key] for key in ("steps_per_s", "us_per_stage", "frac_hbm_peak", "TFLOPps")}
+            prow = profile_row("C5", T, "packed", "wavefront", index_rows)
+            r["mfma_busy_pct"] = _num(prow.get("MFMA busy %")) if prow else None
+            r["traffic"] = int(_num(prow["traffic bytes per launch"])) if prow and _num(prow.get("traffic bytes per launch")) else None
+            r["profile"] = ("profiles/" + prow["file"]) if prow else None
+            c5_sweep.append(r)
+        del s5
+        torch.cuda.empty_cache()
         for name in ("C2", "C3"):
             oc = wl.by_name(name)
-            oi = wl.make_inputs(oc)
-            oW = [torch.from_numpy(w).to(dev) for w in oi["W"]]
-            ox = ss.linear_forward(torch.from_numpy(oi["P"]).to(dev), torch.from_numpy(oi["feat"]).to(dev)) if oc.d_feat \
-                else torch.from_numpy(oi["x"]).to(dev)
-            oh = torch.empty((oc.L, oc.d), dtype=torch.float32, device=dev)
-            occ = torch.empty((oc.n_layers, oc.d), dtype=torch.float32, device=dev)
-            ows = ss.Workspace.for_shape(oc.n_layers, oc.d, oc.k, max(oc.Ts), ss.F32, dev)
+            so = Stack(ss, wl, torch, oc, dev, want_packed=False)
+            # the weights of the whole stack, read again and again: they stay in the Infinity Cache
+            cache_probe = read_probe_rate(ss, torch, so.W, len(so.W), reps_bytes=2e9)
             for T_ in oc.Ts:
-                def go():
-                    if oc.cell == "sru":
-                        ss.sru_forward(oW, None, ox, None, T=T_, h=oh, c_final=occ, workspace=ows)
-                    else:
-                        ss.qrnn_forward(oW, None, ox, None, None, T=T_, k=oc.k, h=oh, c_final=occ, workspace=ows)
-                go()
-                torch.cuda.synchronize()
-                q0, q1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                q0.record()
-                for _ in range(5):
-                    go()
-                q1.record()
-                torch.cuda.synchronize()
-                sec_ = q0.elapsed_time(q1) * 1e-3 / 5
-                others.append({"workload": oc.name, "T": T_, "steps_per_s": round(oc.L / sec_, 1),
-                               "us_per_stage": round(sec_ * 1e6 / (oc.n_layers * ((oc.L + T_ - 1) // T_)), 2),
-                               "note": "weights fit the 256 MB Infinity Cache: not priced against the HBM peak"})
+                r = so.row(T_, so.time_median(T_))
+                others.append({"workload": oc.name, "T": T_, "steps_per_s": r["steps_per_s"], "us_per_stage": r["us_per_stage"],
+                               "algorithmic_GBps": r["algorithmic_GBps"],
+                               "cache_read_probe_GBps": cache_probe["GBps"],
+                               "frac_of_cache_read_probe": round(r["algorithmic_GBps"] / cache_probe["GBps"], 4),
+                               "note": "weights fit the 256 MB Infinity Cache: priced against a read probe on the resident weights, not against the HBM peak"})
+            del so
+            torch.cuda.empty_cache()
 
     cpu = None
     if not args.no_cpu:
@@ -307,12 +372,12 @@ def main():
         cores = oracle.num_threads()
         n = args.cpu_sample_steps or (1024 if cfg.d >= 4096 else 1000)   # about 15 s of CPU time on 16 cores at d = 4096
         n = min(n, cfg.L)
-        xs = x[:n].cpu().numpy()
+        xs = stack.x[:n].cpu().numpy()
         t0 = time.perf_counter()
         if cfg.cell == "sru":
-            h_ref, _ = oracle.sru_forward(W_host, None, xs, T=args.T)
+            h_ref, _ = oracle.sru_forward(stack.W_host, None, xs, T=args.T)
         else:
-            h_ref, _, _ = oracle.qrnn_forward(W_host, None, xs, T=args.T, k=cfg.k)
+            h_ref, _, _ = oracle.qrnn_forward(stack.W_host, None, xs, T=args.T, k=cfg.k)
         dt = time.perf_counter() - t0
         m = min(n, h_head.shape[0])
         err = float(np.abs(h_head[:m].cpu().numpy().astype(np.float64) - h_ref[:m]).max())
@@ -322,9 +387,9 @@ def main():
         try:
             t1 = time.perf_counter()
             if cfg.cell == "sru":
-                oracle.sru_forward(W_host, None, xs[:n1], T=args.T)
+                oracle.sru_forward(stack.W_host, None, xs[:n1], T=args.T)
             else:
-                oracle.qrnn_forward(W_host, None, xs[:n1], T=args.T, k=cfg.k)
+                oracle.qrnn_forward(stack.W_host, None, xs[:n1], T=args.T, k=cfg.k)
             dt1 = time.perf_counter() - t1
         finally:
             oracle.set_num_threads(cores)
@@ -334,23 +399,26 @@ def main():
                          f"{dt:.1f} s of CPU time",
                "gpu_vs_oracle_max_abs_err_on_sample": err}
 
+    lookahead = roofline["lookahead_blocks"]
+    schedule_text = (f"wavefront: the independent (block, layer) stages of an anti-diagonal share a launch; a block's output "
+                     f"needs {lookahead} further blocks ({lookahead * args.T} time steps) of input" if roofline["schedule"] == "wavefront"
+                     else "one launch per stage, streaming order (no look-ahead)")
     out = {
         "metric": "single-stream time steps/sec vs block T; achieved HBM GB/s (% of peak)",
         "value": head["steps_per_s"], "unit": "time steps/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": head["ms_per_pass"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": {"f32": "f32", "bf16": "bf16 weights, f32 accumulate", "fp8": "fp8 (E4M3, row-scaled) weights, f32 accumulate"}[cfg.wdtype],
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f32": "f32", "bf16": "bf16 weights, f32 accumulate", "fp8": "fp8 (E4M3, row-scaled) weights, f32 accumulate"}[cfg.wdtype],
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_layers}-layer {cfg.cell.upper()}, d={cfg.d}, k={cfg.k}, "
                                f"L={cfg.L}, batch 1, {cfg.wdtype} weights "
                                f"({cfg.n_layers * cfg.weight_bytes_per_layer() / 1e9:.2f} GB), block T={args.T}",
-                   "T": args.T, "schedule": {0: "wavefront (independent stages share a launch)" if nlaunch != nstage else "one launch per stage",
-                                             1: "one launch per stage, streaming order", 2: "persistent", 3: "wavefront"}[args.flags & 3],
+                   "T": args.T, "schedule": schedule_text, "lookahead_blocks": lookahead,
                    "weights": head["weights"], "flags": args.flags},
         "achieved_hbm_GBps": head["algorithmic_GBps"], "frac_hbm_peak": head["frac_hbm_peak"],
-        "per_stage_schedule": per_stage_schedule,
-        "sweep": sweep, "roofline": roofline, "cpu_baseline": cpu,
-        "cache_resident_configs": others,
-        "setup_s": round(t_gen, 1),
+        "roofline": roofline, "roofline_streaming": roofline_streaming, "read_probe": probe,
+        "sweep": sweep, "c5_sweep": c5_sweep, "cache_resident_configs": others,
+        "cpu_baseline": cpu, "setup_s": round(t_gen, 1),
     }
     print(json.dumps(out))
 

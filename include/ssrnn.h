@@ -13,7 +13,10 @@
  * b + l (the wavefront schedule: block b+1 enters the first layer while block b
  * is in the second); a call of one block, or SSRNN_SCHED_STAGES, takes the
  * stages one by one in streaming order (block b through every layer before
- * block b+1 starts).  The results are the same bits either way.
+ * block b+1 starts).  The two schedules give the same results up to fp32
+ * re-association, and the same bits where one kernel instance with one launch
+ * geometry serves both (the geometry may depend on how many stages a launch
+ * holds: see the SSRNN_OPT_* flags).
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless it says "host".  W[] and bias[]
@@ -23,7 +26,7 @@
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *     Buffers must stay valid until that work has finished.  The work is
  *     kernel launches only, so a call on a capturing stream records into a HIP
- *     graph (the persistent schedule, a cooperative launch, excepted).
+ *     graph.
  *   - x, h: time-major [L x d] fp32, row t = time step t.  State c: fp32.
  *   - Weights: row-major, fp32 (SSRNN_F32), bfloat16 bit patterns (SSRNN_BF16)
  *     or 8-bit floats with one fp32 scale per row (SSRNN_FP8, see
@@ -52,7 +55,7 @@ typedef enum {
   SSRNN_EINVAL = 1,       /* NULL required pointer, size out of range              */
   SSRNN_EUNSUPPORTED = 2, /* shape or option no kernel here can take               */
   SSRNN_EWORKSPACE = 3,   /* workspace NULL, misaligned or too small               */
-  SSRNN_EDEVICE = 4       /* a HIP call failed, or a kernel reported a failed wait */
+  SSRNN_EDEVICE = 4       /* a HIP call failed                                     */
 } ssrnn_status;
 
 typedef enum { SSRNN_F32 = 0, SSRNN_BF16 = 1, SSRNN_FP8 = 2 } ssrnn_wdtype;
@@ -63,12 +66,6 @@ typedef enum { SSRNN_F32 = 0, SSRNN_BF16 = 1, SSRNN_FP8 = 2 } ssrnn_wdtype;
 enum {
   SSRNN_SCHED_AUTO = 0,
   SSRNN_SCHED_STAGES = 1,     /* one kernel launch per (block, layer) stage, streaming order */
-  SSRNN_SCHED_PERSISTENT = 2, /* one cooperative launch for the whole call; stages are
-                                 separated by a grid barrier and the next stage's first
-                                 weights are requested across it.  Stacked SRU with fp32
-                                 row-major weights, T <= 8, d a multiple of 256 with at
-                                 most one workgroup per compute unit.  Its waits are bounded:
-                                 see ssrnn_workspace_status.                                 */
   SSRNN_SCHED_WAVEFRONT = 3,  /* one launch per anti-diagonal b + l of the (block, layer)
                                  grid: up to n_layers independent stages side by side       */
   SSRNN_SCHED_MASK = 3,
@@ -77,7 +74,15 @@ enum {
   SSRNN_KERNEL_VALU = 2 << 4,    /* bandwidth kernel, FMA on the vector ALU (short blocks)   */
   SSRNN_KERNEL_MFMA = 3 << 4,    /* matrix-core kernel                                       */
   SSRNN_KERNEL_MASK = 7 << 4,
-  SSRNN_WEIGHTS_PACKED = 1 << 8  /* every W[l] was written by ssrnn_pack_weights                */
+  SSRNN_WEIGHTS_PACKED = 1 << 8, /* every W[l] was written by ssrnn_pack_weights                */
+  /* Per-call limits on the launch geometry (tests and measurements; results change by fp32
+     re-association at most).  By default the matrix-core kernels adapt to the number of
+     stages a launch holds: a narrow layer's columns are split over several workgroups when
+     the launch would not fill the chip otherwise, and a workgroup owns 32 or 64 features
+     instead of 16 when the launch is wide enough. */
+  SSRNN_OPT_NO_SPLIT = 1 << 9,   /* never split a layer's columns over workgroups               */
+  SSRNN_OPT_ONE_TILE = 1 << 10,  /* always 16 features per workgroup                            */
+  SSRNN_OPT_MASK = 3 << 9
 };
 
 /* Library version, major*10000 + minor*100 + patch.  Host; never fails. */
@@ -89,7 +94,7 @@ const char* ssrnn_last_error(void);
 
 /* Bytes of device scratch *_forward needs for this shape (inter-layer
  * activations for two blocks in flight, their operand copies for the
- * matrix-core kernels, control words).  Host.  Returns 0 for arguments *_forward would
+ * matrix-core kernels, partial sums of split stages).  Host.  Returns 0 for arguments *_forward would
  * reject.  The workspace must be 256-byte aligned; its contents need not be
  * initialised and are not preserved.  Calls that share a workspace must not
  * overlap in time (queue them on one stream, or order the streams). */
@@ -105,12 +110,6 @@ size_t ssrnn_workspace_bytes(int n_layers, int d, int k, int T, int wdtype);
  * codes exactly (to fp32 on the vector ALU, to bf16 on the matrix cores) and
  * apply the scale to the finished fp32 sum of a row. */
 size_t ssrnn_weight_bytes(int d, int k, int wdtype);
-
-/* After a *_forward call that ran the persistent schedule: synchronizes the
- * stream and reports whether one of the kernel's bounded waits ran out
- * (SSRNN_EDEVICE; the outputs of that call are then incomplete) or not
- * (SSRNN_OK).  workspace: the one given to that call. */
-int ssrnn_workspace_status(const void* workspace, void* stream);
 
 /* Stacked SRU forward, Eq. 2 per layer, T steps per weight pass (Section 3).
  *   xh = W x_t;  f = sigma(W_f x_t + b_f);  r = sigma(W_r x_t + b_r);
@@ -130,7 +129,7 @@ int sru_forward(const void* const* W, const float* const* bias, const float* x,
 /* sru_forward for callers that cannot allocate device memory and so have no
  * workspace to pass: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, kernels and results as
- * sru_forward (SSRNN_SCHED_PERSISTENT excepted: SSRNN_EUNSUPPORTED); the scratch is
+ * sru_forward; the scratch is
  * a static array of SSRNN_NOALLOC_SCRATCH_BYTES in device memory that is part
  * of the library's code object: every GPU the library runs on holds its own copy
  * from the first call there until the process ends.  The call allocates and
@@ -190,29 +189,6 @@ int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out,
 size_t ssrnn_packed_weight_bytes(int d, int k, int wdtype);
 int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype,
                        void* stream);
-
-/* Measurement aid: one kernel that reads buf[0, bytes) once with streaming
- * 16-byte loads and keeps nothing: the rate a pure read reaches on this device,
- * against which bench.py quotes the stage kernels next to the published HBM
- * peak.  buf: device, 16-byte aligned, bytes a multiple of 16; sink: 4 bytes of
- * device memory the kernel may write; enqueued on stream. */
-int ssrnn_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
-
-/* Measurement aid: override one launch-geometry choice of the kernels for the
- * calls that follow, process-wide (not thread-safe; 0 restores the default).
- * Keys: "valu_F" (features per workgroup), "valu_nw" (wavefronts per
- * workgroup), "valu_nv" (column chunks per lane), "ksplit" (1: never split a
- * narrow layer's columns over several workgroups; 2, 4, 8: at most that many
- * parts), "feature_tiles" (1: the packed matrix-core kernel always gives a workgroup one
- * tile of 16 features; by default it gives two where a launch holds enough
- * stages), "wide" (1: never the kernel that gives a workgroup 64 features, which
- * long blocks of packed bf16 weights take by default when launches are wide
- * enough), "spin_limit" (ticks of the 100 MHz wall clock that one grid-barrier
- * wait of the persistent schedule may take before the kernel gives up; default
- * one second).  A value the shape does not allow is ignored.  Results are
- * unaffected beyond fp32 re-association.  Host.  Returns SSRNN_EINVAL for an
- * unknown key. */
-int ssrnn_tune(const char* key, int value);
 
 #ifdef __cplusplus
 }

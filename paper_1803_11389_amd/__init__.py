@@ -15,15 +15,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssrnn.so")
 
 F32, BF16, FP8 = 0, 1, 2
-SCHED_AUTO, SCHED_STAGES, SCHED_PERSISTENT, SCHED_WAVEFRONT = 0, 1, 2, 3
+SCHED_AUTO, SCHED_STAGES, SCHED_WAVEFRONT = 0, 1, 3
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_VALU, KERNEL_MFMA = 0, 1 << 4, 2 << 4, 3 << 4
 WEIGHTS_PACKED = 1 << 8
+OPT_NO_SPLIT, OPT_ONE_TILE = 1 << 9, 1 << 10
 
-# every symbol include/ssrnn.h declares
+# every symbol include/ssrnn.h declares, then those of include/ssrnn_probe.h (measurement aids)
 EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",
            "qrnn_forward", "ssrnn_linear_forward", "ssrnn_packed_weight_bytes", "ssrnn_pack_weights",
-           "ssrnn_read_probe", "ssrnn_workspace_status", "ssrnn_tune", "ssrnn_weight_bytes",
-           "sru_forward_noalloc")
+           "ssrnn_weight_bytes", "sru_forward_noalloc")
+PROBE_EXPORTS = ("ssrnn_read_probe",)
 NOALLOC_SCRATCH_BYTES = 32 << 20   # SSRNN_NOALLOC_SCRATCH_BYTES of include/ssrnn.h
 
 _lib = None
@@ -65,11 +66,7 @@ def load_library():
     lib.ssrnn_pack_weights.restype = ip
     lib.ssrnn_pack_weights.argtypes = [vp, vp, ip, ip, ip, vp]
     lib.ssrnn_read_probe.restype = ip
-    lib.ssrnn_read_probe.argtypes = [vp, sz, vp, vp]
-    lib.ssrnn_workspace_status.restype = ip
-    lib.ssrnn_workspace_status.argtypes = [vp, vp]
-    lib.ssrnn_tune.restype = ip
-    lib.ssrnn_tune.argtypes = [ctypes.c_char_p, ip]
+    lib.ssrnn_read_probe.argtypes = [vp, ip, sz, ip, vp, vp]
     _lib = lib
     return lib
 
@@ -81,10 +78,6 @@ def _check(rc: int):
 
 def version() -> int:
     return load_library().ssrnn_version()
-
-
-def tune(key: str, value: int) -> None:
-    _check(load_library().ssrnn_tune(key.encode(), int(value)))
 
 
 def workspace_bytes(n_layers: int, d: int, k: int, T: int, wdtype: int) -> int:
@@ -138,17 +131,17 @@ def pack_weights(W, stream=None):
     return out
 
 
-def workspace_status(workspace: "Workspace", stream=None) -> None:
-    """ssrnn_workspace_status: synchronizes the stream; raises SsrnnError if a
-    bounded wait of the persistent schedule ran out in the last call."""
-    _check(load_library().ssrnn_workspace_status(workspace.buf.data_ptr(), _stream_handle(stream)))
-
-
-def read_probe(buf, sink, stream=None) -> None:
-    """ssrnn_read_probe over a contiguous device tensor; sink: a device tensor of at least 4 bytes."""
-    _req(buf, "buf")
+def read_probe(bufs, sink, groups: int = 0, stream=None) -> None:
+    """ssrnn_read_probe (include/ssrnn_probe.h): one launch that reads up to eight
+    equally long contiguous device tensors once; sink: a device tensor of at least 4 bytes."""
+    bufs = list(bufs) if isinstance(bufs, (list, tuple)) else [bufs]
+    for b in bufs:
+        _req(b, "buf")
     _req(sink, "sink")
-    _check(load_library().ssrnn_read_probe(_p(buf), buf.numel() * buf.element_size(), _p(sink), _stream_handle(stream)))
+    nbytes = bufs[0].numel() * bufs[0].element_size()
+    if any(b.numel() * b.element_size() != nbytes for b in bufs):
+        raise ValueError("the buffers of one probe launch must be equally long")
+    _check(load_library().ssrnn_read_probe(_ptr_table(bufs), len(bufs), nbytes, int(groups), _p(sink), _stream_handle(stream)))
 
 
 def _wdtype(w) -> int:

@@ -2,7 +2,7 @@
 //
 // Same decomposition and epilogue as the other matrix-core kernels; the weight
 // matrix has been re-tiled once, at model-load time, into the order the MFMA
-// fragments are consumed (pack_weights_kernel below): for feature tile ft and
+// fragments are consumed (ssrnn_pack_weights): for feature tile ft and
 // k-step s the six 1 KiB fragments (gate 0..2 x half 0..1) lie back to back,
 //
 //   chunk index = (((ft * nks_total + s) * 3 + gate) * 2 + half) * 64 + lane,   16 bytes per chunk,
@@ -47,22 +47,6 @@ struct MfmaPkCfg {
   static constexpr int SB = (FT > 1) ? 2 : (WT == W_FP8) ? ((NT <= 1) ? 4 : 2) : ((NT <= 4) ? 4 : 2);   // B fragment ring slots (sub-steps)
   static constexpr int NBT = (WT == W_FP8) ? ((NT > 8) ? 2 : (NT > 4) ? 4 : NT) : ((NT > 8) ? 8 : NT);   // time tiles per B fetch
 };
-
-// One thread per 16-byte chunk of the packed matrix (see the layout above).
-__global__ void pack_weights_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int d, long row_chunks,
-                                    int nks_total, long nchunks) {
-  const long o = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (o >= nchunks) return;
-  const int lane = static_cast<int>(o & 63);
-  const int half = static_cast<int>((o >> 6) & 1);
-  const long r = o >> 7;
-  const int gate = static_cast<int>(r % 3);
-  const long r2 = r / 3;
-  const int s = static_cast<int>(r2 % nks_total);
-  const long ft = r2 / nks_total;
-  const long row = static_cast<long>(gate) * d + ft * 16 + (lane & 15);
-  dst[o] = src[row * row_chunks + static_cast<long>(s) * 8 + (lane >> 4) * 2 + half];
-}
 
 // Eight E4M3 codes (two 32-bit words, lowest address first) as eight bf16 values.
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));

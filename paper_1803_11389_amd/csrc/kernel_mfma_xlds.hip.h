@@ -1,0 +1,326 @@
+// Matrix-core kernel for pre-packed weights with the input block staged in LDS:
+// 64 features per workgroup.
+//
+// In the 16-feature matrix-core kernels every workgroup pulls the whole input
+// block X (Eq. 4 of arXiv 1803.11389: the T columns all rows of W are
+// multiplied with) through its compute unit's vector memory path, 256 times per
+// stage at d = 4096.  Here a workgroup owns 64 features; its four waves own one
+// 16-feature tile each (three 16-row M tiles: candidate, forget, reset/output)
+// and walk ALL k*d columns in step, so a piece of X is needed by all four at the
+// same time and is fetched ONCE per workgroup, straight from memory into LDS
+// (global_load_lds, 16 bytes per lane, no staging registers), and read from
+// there as MFMA B fragments.  A wave's accumulators then hold complete sums, so
+// the gates and the recurrence of Eq. 2 / Eq. 3 are applied to them in
+// registers: no sum across waves, no LDS round trip and no barrier in the
+// epilogue.  A stage is d/64 workgroups; the host picks this kernel when a launch
+// holds enough independent stages to fill the chip.
+//
+// Weights: the packed layout of kernel_mfma_packed.hip.h.  A wave streams the
+// fragments of its own tile, 6 KiB per k-step (128 bytes of each of its 48
+// rows), non-temporal, through a register ring.
+//
+// Pipeline.  The unit is a "B-step": NSUB k-steps whose X columns form one LDS
+// tile of at most 32 KiB; there are four LDS buffers and four ring slots of
+// weight fragments.  The MFMAs of consecutive steps form one uninterrupted
+// stream: every B fragment is read from LDS three fragments ahead of its use,
+// across step boundaries.  In the middle of B-step s a wave waits until its own
+// pieces of the X tile of step s+1 have landed and meets the other waves at a
+// barrier (after it, tile s+1 is complete and every wave has long finished
+// reading tile s-1), then requests its share of the X tile of step s+3 into the
+// buffer that held tile s-1 and its weight fragments of step s+3 into the ring
+// slot step s-1 has left.  Vector memory operations of a wave complete in issue
+// order, so "all but the N youngest have completed" (s_waitcnt vmcnt(N)) names
+// exactly the pieces of tile s+1: what was requested after them -- two steps of
+// weight fragments and one X tile -- stays in flight across the barrier.  The
+// X tiles are moved by buffer loads with the LDS bit (buffer_load_dwordx4 ... lds):
+// the compiler counts those like any other load, so the waits it inserts for
+// the weight fragments are exact as well.  The loop body is four B-steps (ring
+// slots and LDS buffers are compile-time) and free of branches; the last four
+// steps are a second instance that requests nothing past the end.
+#pragma once
+
+#include <type_traits>
+
+#include "kernel_mfma.hip.h"
+
+namespace ssrnn {
+
+constexpr int XLDS_TILES = 4;                 // feature tiles (of 16) per workgroup = waves
+constexpr int XLDS_F = XLDS_TILES * MFMA_F;   // features per workgroup
+constexpr int XLDS_DEPTH = 3;                 // B-steps between a request and its use
+constexpr int XLDS_NBUF = XLDS_DEPTH + 1;     // LDS buffers = weight ring slots (in B-steps)
+
+// A read-only window on device memory (buffer descriptor) and the 16-bytes-per-lane load through it that
+// writes LDS instead of registers: lane l's bytes land at lds + l*16, lds being the same for the whole wave.
+// Requests outside the window return zeros.  The descriptor type exists in the device compilation only; the
+// host compilation, which needs the kernel's signature and nothing of its body, sees an empty stand-in.
+#if defined(__HIP_DEVICE_COMPILE__)
+struct LdsLoadWindow { __amdgpu_buffer_rsrc_t rsrc; };
+__device__ __forceinline__ LdsLoadWindow make_lds_load_window(const void* base, int bytes) {
+  return LdsLoadWindow{__builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000)};
+}
+__device__ __forceinline__ void load_to_lds16(const LdsLoadWindow& w, char* lds, int byte_offset) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(w.rsrc, (__attribute__((address_space(3))) void*)lds, 16, byte_offset, 0, 0, 0);
+}
+#else
+struct LdsLoadWindow {};
+__device__ __forceinline__ LdsLoadWindow make_lds_load_window(const void*, int) { return LdsLoadWindow{}; }
+__device__ __forceinline__ void load_to_lds16(const LdsLoadWindow&, char*, int) {}
+#endif
+
+template <int WT, int NT>
+struct XldsCfg {
+  static constexpr int R = NT * 16;                       // time rows of an X tile
+  static_assert(R >= 32, "at least two time tiles");
+  static constexpr int NSUB = (R >= 256) ? 1 : 2;         // k-steps per B-step
+  static constexpr int KCOLS = (WT == W_BF16) ? 64 : 32;  // weight columns per k-step (128 bytes of a row)
+  static constexpr int VEC = (WT == W_BF16) ? 8 : 4;      // X elements per 16-byte chunk of the operand copy
+  static constexpr int KSTEP_BYTES = 8 * R * 16;          // one k-step of X in LDS: 8 chunk columns x R rows x 16 B
+  static constexpr int BSTEP_BYTES = NSUB * KSTEP_BYTES;
+  static constexpr int NTHREADS = XLDS_TILES * 64;
+  static_assert(BSTEP_BYTES % (NTHREADS * 16) == 0, "every thread moves whole 16-byte pieces");
+  static constexpr int NCOPY = BSTEP_BYTES / (NTHREADS * 16);   // X pieces a thread requests per B-step
+  static constexpr int PER_KSTEP = NCOPY / NSUB;                 // of which per k-step
+  static constexpr int NA = 6 * NSUB;                            // weight fragments a wave requests per B-step
+  static constexpr int NFRAG = NSUB * 2 * NT;                    // B fragments (k-step, half, time tile) per B-step
+  static constexpr int KSTEPS_PER_ITER = XLDS_NBUF * NSUB;       // k-steps of one loop body
+};
+
+// Columns (k*d) the kernel takes: whole loop bodies.
+template <int WT, int NT>
+constexpr int xlds_col_multiple() { return XldsCfg<WT, NT>::KSTEPS_PER_ITER * XldsCfg<WT, NT>::KCOLS; }
+
+// Requirements (checked by the host): packed fp32 or bf16 weights, d % 64 == 0, k*d a multiple of
+// xlds_col_multiple(), 1 <= nt <= NT*16, an operand copy of the input block smaller than 2 GiB, no
+// split of the columns.
+template <int CELL, int WT, int NT>
+__global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const StageBatch batch, int d, int k) {
+  static_assert(WT == W_F32 || WT == W_BF16, "fp32 or bf16 weights");
+  using Cfg = XldsCfg<WT, NT>;
+  constexpr int R = Cfg::R, NSUB = Cfg::NSUB, NCOPY = Cfg::NCOPY, KCOLS = Cfg::KCOLS, VEC = Cfg::VEC;
+  constexpr int NFRAG = Cfg::NFRAG, NA = Cfg::NA;
+  constexpr int NBUF = XLDS_NBUF, DEPTH = XLDS_DEPTH;
+  const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
+  __shared__ __attribute__((aligned(16))) char smem[NBUF * Cfg::BSTEP_BYTES];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // a scalar: LDS addresses derived from it stay scalar
+  const int li = lane & 15;
+  const int kg = lane >> 4;
+  const int ncol = k * d;
+  const int nks = ncol / KCOLS;                      // every wave walks all k-steps
+  const int nsteps = nks / NSUB;
+  const int ft = blockIdx.x * XLDS_TILES + wave;     // this wave's feature tile
+  const int f0 = ft * MFMA_F;
+
+  if (CELL == CELL_QRNN && tid < XLDS_F) refresh_history(s, d, k, blockIdx.x * XLDS_F + tid);
+
+  // ---- epilogue operands that live in memory, requested before the main loop.  In the MFMA result
+  // layout lane (tl = lane % 16, fg = lane / 16) holds time step tl of a tile for features 4*fg .. 4*fg+3.
+  const int fl = f0 + 4 * kg;                        // first of this lane's four features
+  float4 bias0 = make_float4(0.f, 0.f, 0.f, 0.f), bias1 = bias0, bias2 = bias0;
+  if (s.bias) {
+    if (CELL == CELL_SRU) {
+      bias1 = *reinterpret_cast<const float4*>(s.bias + fl);
+      bias2 = *reinterpret_cast<const float4*>(s.bias + d + fl);
+    } else {
+      bias0 = *reinterpret_cast<const float4*>(s.bias + fl);
+      bias1 = *reinterpret_cast<const float4*>(s.bias + d + fl);
+      bias2 = *reinterpret_cast<const float4*>(s.bias + 2 * d + fl);
+    }
+  }
+  const float4 cst = *reinterpret_cast<const float4*>(s.c + fl);      // running cell state of the four features
+
+  floatx4_t acc[3][NT];
+#pragma unroll
+  for (int g = 0; g < 3; ++g)
+#pragma unroll
+    for (int n = 0; n < NT; ++n) acc[g][n] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  // ---- X side.  Piece e = i * 256 + tid of a B-step's tile is row e % R of chunk column e / R (chunk
+  // columns 0..7 belong to the first k-step of the B-step, 8..15 to the second); the tile is stored in
+  // that order, so the 64 pieces of a wave's request are 1 KiB contiguous in LDS, which is what a load
+  // with the LDS bit writes (lane l at byte l*16 behind the address in M0).  Rows past the end of a
+  // short block repeat its last row; the columns they produce are never read out.  The operand copy is
+  // addressed through a window that starts at its first byte (row -(k-1) of chunk column 0) and ends
+  // with it, so that a request outside of it could only return zeros.
+  const int ldtb = s.ldt * 16;                       // bytes per chunk column of the operand copy
+  const LdsLoadWindow xwin = make_lds_load_window(static_cast<const char*>(s.xop) - (k - 1) * 16, (d / VEC) * ldtb);
+  int cp_off[NCOPY];                                 // byte offset of the piece behind (row 0 of) its k-step's first chunk column
+#pragma unroll
+  for (int i = 0; i < NCOPY; ++i) {
+    const int e = i * Cfg::NTHREADS + tid;
+    const int c = e / R, r = e - c * R;
+    cp_off[i] = (c & 7) * ldtb + (k - 1 + min(r, s.nt - 1)) * 16;
+  }
+  // cursor of the next k-step whose X columns are requested: lag block x_j, first column x_m within it
+  int x_j = 0, x_m = 0;
+  int xbase[NSUB];                                   // byte offset of (row 0 of) the first chunk column of each k-step of the tile on request
+  auto advance_x = [&]() {                           // moves the cursor one B-step on
+#pragma unroll
+    for (int u = 0; u < NSUB; ++u) {
+      xbase[u] = (x_m / VEC) * ldtb - x_j * 16;      // rows shifted back by the lag
+      x_m += KCOLS;
+      if (x_m >= d) { x_m -= d; ++x_j; }
+    }
+  };
+  auto request_x_piece = [&](int buf, int i) {       // piece i lies in k-step (i*256 + tid) / (8*R) = i / PER_KSTEP of the B-step
+    load_to_lds16(xwin, smem + buf * Cfg::BSTEP_BYTES + wave * 1024 + i * (Cfg::NTHREADS * 16), xbase[i / Cfg::PER_KSTEP] + cp_off[i]);
+  };
+
+  // ---- weight side: ring of NBUF B-steps of this wave's fragments
+  const char* aptr = static_cast<const char*>(s.W) + static_cast<size_t>(ft) * nks * 6144 + lane * 16;
+  floatx4_t aring[NBUF][NSUB][6];
+  int a_ks = 0;                                      // first k-step of the B-step whose fragments are requested
+  auto request_a_piece = [&](int slot, int i) {      // fragment i % 6 of k-step i / 6 of the B-step
+    aring[slot][i / 6][i % 6] = load_stream16(aptr + static_cast<size_t>(a_ks + i / 6) * 6144 + (i % 6) * 1024);
+  };
+
+  // ---- B fragments: fragment q of a B-step is (k-step q / 2NT, half (q / NT) % 2, time tile q % NT); lane
+  // (li, kg) reads time row li of the tile from chunk column 2*kg + half.  They pass through a ring of BQ
+  // register sets, BQ-1 reads ahead of the MFMAs that use them.
+  constexpr int BQ = 4;
+  static_assert(NFRAG % BQ == 0 && NFRAG >= 2 * BQ, "the fragment ring repeats with the B-step");
+  using bfrag_t = std::conditional_t<WT == W_BF16, bf16x8_t, floatx4_t>;
+  bfrag_t bq[BQ];
+  const char* bt = smem + kg * 2 * (R * 16) + li * 16;
+  auto read_b = [&](int buf, int q) {
+    const int u = q / (2 * NT), h = (q / NT) & 1, n = q % NT;
+    bq[q % BQ] = *reinterpret_cast<const bfrag_t*>(bt + buf * Cfg::BSTEP_BYTES + u * Cfg::KSTEP_BYTES + h * (R * 16) + n * 256);
+  };
+  auto mfma_b = [&](int slot, int q) {
+    const int u = q / (2 * NT), h = (q / NT) & 1, n = q % NT;
+#pragma unroll
+    for (int g = 0; g < 3; ++g) {
+      if constexpr (WT == W_BF16) {
+        bf16x8_t a;
+        __builtin_memcpy(&a, &aring[slot][u][g * 2 + h], sizeof a);
+        acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[q % BQ], acc[g][n], 0, 0, 0);
+      } else {
+        const floatx4_t av = aring[slot][u][g * 2 + h];
+        const floatx4_t bv = bq[q % BQ];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[e], bv[e], acc[g][n], 0, 0, 0);
+      }
+    }
+  };
+
+  // B-step at ring position P.  LAST: the final loop body, whose steps P >= 1 have nothing left to request
+  // and whose last step has no successor.
+  constexpr int QSYNC = NFRAG / 2;                   // fragment index in front of which the waves meet
+  auto bstep = [&](auto last_tag, auto p_tag) {
+    constexpr bool LAST = decltype(last_tag)::value;
+    constexpr int P = decltype(p_tag)::value;
+    constexpr bool has_next = !LAST || P < NBUF - 1;         // step s+1 exists
+    constexpr bool req = !LAST || P == 0;                    // step s+DEPTH exists
+    constexpr int nxt = (P + DEPTH) % NBUF;                  // buffer / slot of step s-1 = of step s+DEPTH
+    // requests younger than this wave's pieces of tile s+1 at the meeting point: the weight fragments of
+    // steps s+1 and s+2 and the X tile of step s+2, as far as those steps exist
+    constexpr int exist2 = (!LAST || P + 2 <= NBUF - 1) ? 1 : 0;
+    constexpr int younger = NA + exist2 * (NA + NCOPY);
+    // the requests of step s+DEPTH (X pieces first, then weight fragments: the wait above counts on that
+    // order) are spread over the fragment groups behind the meeting point, a few per group
+    constexpr int NREQ = NCOPY + NA;
+    constexpr int NGRP = NFRAG - QSYNC;                      // groups they are spread over
+#pragma unroll
+    for (int q = 0; q < NFRAG; ++q) {
+      if (q == QSYNC && has_next) {
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(younger) : "memory");   // tile s+1 is in place, tile s-1 is free
+        if constexpr (req) advance_x();
+      }
+      // read ahead: the last BQ-1 fragments' successors are the first fragments of the next step
+      if (q + BQ - 1 < NFRAG) read_b(P, q + BQ - 1);
+      else if (has_next) read_b((P + 1) % NBUF, q + BQ - 1 - NFRAG);
+      if (req && q >= QSYNC) {
+#pragma unroll
+        for (int i = ((q - QSYNC) * NREQ) / NGRP; i < ((q - QSYNC + 1) * NREQ) / NGRP; ++i) {
+          if (i < NCOPY) request_x_piece(nxt, i);
+          else request_a_piece(nxt, i - NCOPY);
+        }
+      }
+      mfma_b(P, q);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (req) a_ks += NSUB;
+  };
+  auto body = [&](auto last_tag) {
+    static_assert(NBUF == 4, "ring positions are spelled out below");
+    bstep(last_tag, std::integral_constant<int, 0>{});
+    bstep(last_tag, std::integral_constant<int, 1>{});
+    bstep(last_tag, std::integral_constant<int, 2>{});
+    bstep(last_tag, std::integral_constant<int, 3>{});
+  };
+
+  // ---- prologue: steps 0 .. DEPTH-1 requested (tile before fragments, the order of the loop), tile 0
+  // landed, its first fragments on their way.  Behind the pieces of tile 0 lie the fragments of steps 0, 1, 2
+  // and the tiles of steps 1, 2.
+#pragma unroll
+  for (int p = 0; p < DEPTH; ++p) {
+    advance_x();
+#pragma unroll
+    for (int i = 0; i < NCOPY; ++i) request_x_piece(p, i);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) request_a_piece(p, i);
+    a_ks += NSUB;
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(DEPTH * NA + (DEPTH - 1) * NCOPY) : "memory");
+#pragma unroll
+  for (int q = 0; q < BQ - 1; ++q) read_b(0, q);
+  for (int s0 = 0; s0 < nsteps - NBUF; s0 += NBUF) body(std::false_type{});
+  body(std::true_type{});
+
+  // ---- epilogue in registers.  Lane (tl, fg) holds, for each time tile n, step n*16 + tl of features
+  // fl .. fl+3 in all three gates, so the gate non-linearities need no exchange; the recurrence
+  // c_t = f_t c_{t-1} + (1 - f_t) cand_t is a prefix scan of affine maps over the 16 lanes of a row,
+  // carried from tile to tile by a broadcast of the row's last valid lane.
+  const float b0[4] = {bias0.x, bias0.y, bias0.z, bias0.w};
+  const float b1[4] = {bias1.x, bias1.y, bias1.z, bias1.w};
+  const float b2[4] = {bias2.x, bias2.y, bias2.z, bias2.w};
+  float cin[4] = {cst.x, cst.y, cst.z, cst.w};
+  const int rowbase = lane & 48;
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    if (n * 16 < s.nt) {                                     // uniform over the workgroup
+      const int t = n * 16 + li;
+      const int tlast = min(16, s.nt - n * 16) - 1;          // last valid step of this tile
+      const bool valid = li <= tlast;
+      float4 xt = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (CELL == CELL_SRU && valid) xt = *reinterpret_cast<const float4*>(s.xcur + static_cast<long>(t) * s.ldx + fl);
+      const float xv[4] = {xt.x, xt.y, xt.z, xt.w};
+      float hv[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float u0 = acc[0][n][r] + b0[r], u1 = acc[1][n][r] + b1[r], u2 = acc[2][n][r] + b2[r];
+        const float f = sigmoidf_fast(u1);
+        const float o = sigmoidf_fast(u2);
+        const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);
+        float a = f, b = (1.0f - f) * cand;
+        affine_scan<16>(a, b);
+        const float c = fmaf(a, cin[r], b);                  // state after step t
+        hv[r] = o * tanhf_fast(c);
+        if (CELL == CELL_SRU) hv[r] += (1.0f - o) * xv[r];
+        cin[r] = __shfl(c, rowbase + tlast);                 // state after the tile's last valid step
+      }
+      if (valid) {
+        *reinterpret_cast<float4*>(s.hout + static_cast<long>(t) * s.ldh + fl) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+        if (s.hop) {
+          if (s.op_bf16) {
+            uint2 pk;
+            pk.x = f32_to_bf16_rne(hv[0]) | (static_cast<uint32_t>(f32_to_bf16_rne(hv[1])) << 16);
+            pk.y = f32_to_bf16_rne(hv[2]) | (static_cast<uint32_t>(f32_to_bf16_rne(hv[3])) << 16);
+            *reinterpret_cast<uint2*>(static_cast<char*>(s.hop) + (static_cast<long>(fl >> 3) * s.ldt + t) * 16 + (fl & 7) * 2) = pk;
+          } else {
+            *reinterpret_cast<float4*>(static_cast<char*>(s.hop) + (static_cast<long>(fl >> 2) * s.ldt + t) * 16) =
+                make_float4(hv[0], hv[1], hv[2], hv[3]);
+          }
+        }
+      }
+    }
+  }
+  if (li == 0) *reinterpret_cast<float4*>(s.c + fl) = make_float4(cin[0], cin[1], cin[2], cin[3]);
+}
+
+}  // namespace ssrnn

@@ -24,21 +24,17 @@
 #include <mutex>
 #include <string>
 
-#include "common.hip.h"
+#include "host.hip.h"
+#include "../../include/ssrnn_probe.h"
 #include "kernel_generic.hip.h"
-#include "kernel_valu.hip.h"
-#include "kernel_mfma.hip.h"
-#include "kernel_mfma_lds.hip.h"
-#include "kernel_mfma_packed.hip.h"
-#include "kernel_mfma_wide.hip.h"
-#include "kernel_valu_persistent.hip.h"
 
 using namespace ssrnn;
 
 namespace {
-
 thread_local std::string g_last_error;
+}
 
+namespace ssrnn {
 int fail(int code, const char* fmt, ...) {
   char buf[512];
   va_list ap;
@@ -48,12 +44,27 @@ int fail(int code, const char* fmt, ...) {
   g_last_error = buf;
   return code;
 }
+}  // namespace ssrnn
 
-#define HIP_TRY(expr)                                                                   \
-  do {                                                                                  \
-    hipError_t e_ = (expr);                                                             \
-    if (e_ != hipSuccess) return fail(SSRNN_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
-  } while (0)
+namespace ssrnn {
+int launch_generic(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
+  const int grid = (p.d + GENERIC_WAVES - 1) / GENERIC_WAVES;
+  const dim3 g(grid < 4096 ? grid : 4096, nstage), b(GENERIC_WAVES * 64);
+#define SSRNN_GENERIC_CASE(CELL_)                                                          \
+  if (p.wdt == SSRNN_FP8) hipLaunchKernelGGL((stage_generic_kernel<CELL_, W_FP8>), g, b, 0, st, s, p.d, p.k);   \
+  else if (p.wdt == SSRNN_BF16) hipLaunchKernelGGL((stage_generic_kernel<CELL_, W_BF16>), g, b, 0, st, s, p.d, p.k); \
+  else hipLaunchKernelGGL((stage_generic_kernel<CELL_, W_F32>), g, b, 0, st, s, p.d, p.k);
+  if (p.cell == CELL_SRU) { SSRNN_GENERIC_CASE(CELL_SRU) } else { SSRNN_GENERIC_CASE(CELL_QRNN) }
+#undef SSRNN_GENERIC_CASE
+  return SSRNN_OK;
+}
+}  // namespace ssrnn
+
+namespace {
+
+constexpr int MFMA_F = 16;          // features per tile of the matrix-core kernels
+constexpr int MFMA_MAX_T = 256;     // longest block one launch of theirs accumulates
+constexpr int XLDS_F = 64;          // features per workgroup of the 64-feature kernel
 
 constexpr size_t WS_ALIGN = 256;
 constexpr size_t WS_CONTROL_BYTES = 256;
@@ -75,8 +86,6 @@ struct WorkspaceLayout {
   int upart_rows;       // rows per (part, gate) plane
   size_t total;
 };
-
-constexpr int KSPLIT_MAX = 8;
 
 // Buffer (l, parity) (0 <= l < n_layers) holds the input rows of layer l for a
 // block of that parity, preceded by the k-1 rows before it.  Buffers (0, .) are
@@ -213,6 +222,23 @@ __global__ void stage_input_vec_kernel(const float* x, const float* xhist_init, 
   }
 }
 
+// One thread per 16-byte chunk of the packed matrix: chunk (((ft * nks_total + s) * 3 + gate) * 2 + half) * 64 + lane
+// holds bytes [s*128 + (lane/16)*32 + half*16, +16) of row gate*d + ft*16 + lane%16 (kernel_mfma_packed.hip.h).
+__global__ void pack_weights_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int d, long row_chunks,
+                                    int nks_total, long nchunks) {
+  const long o = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (o >= nchunks) return;
+  const int lane = static_cast<int>(o & 63);
+  const int half = static_cast<int>((o >> 6) & 1);
+  const long r = o >> 7;
+  const int gate = static_cast<int>(r % 3);
+  const long r2 = r / 3;
+  const int s = static_cast<int>(r2 % nks_total);
+  const long ft = r2 / nks_total;
+  const long row = static_cast<long>(gate) * d + ft * 16 + (lane & 15);
+  dst[o] = src[row * row_chunks + static_cast<long>(s) * 8 + (lane >> 4) * 2 + half];
+}
+
 __global__ void copy_scales_kernel(const float* src, float* dst, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = src[i];
@@ -223,28 +249,32 @@ __global__ void copy_history_kernel(const float* src, float* dst, long n) {
   if (i < n) dst[i] = src ? src[i] : 0.0f;
 }
 
-// Measurement aid: every 16-byte chunk of a buffer is read once with streaming loads, four in flight per
-// thread, and folded into a word that is stored only if it takes one particular value (so the loads cannot
-// be dropped).  Its rate is what a kernel that does nothing but read reaches on the device at hand.
+// Measurement aid (include/ssrnn_probe.h): blockIdx.y picks one of up to eight buffers; the gridDim.x
+// workgroups of a buffer read one contiguous slab each, their waves 1 KiB pieces in turn, sixteen loads
+// (16 KiB) in flight per wave, streaming like the stage kernels' weight loads.  What is read is folded into
+// a word that is stored only if it takes one particular value, so the loads cannot be dropped.
 typedef unsigned ssrnn_u32x4 __attribute__((ext_vector_type(4)));
-__global__ __launch_bounds__(512) void read_probe_kernel(const ssrnn_u32x4* __restrict__ p, size_t n16, unsigned* sink) {
-  // every wave streams its own contiguous piece, 16 KiB (sixteen 1 KiB loads) in flight at a time
-  const size_t nwave = static_cast<size_t>(gridDim.x) * (blockDim.x >> 6);
-  const size_t wave = static_cast<size_t>(blockIdx.x) * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  const size_t per_wave = (n16 + nwave - 1) / nwave;               // chunks per wave
-  const size_t begin = wave * per_wave;
-  const size_t end = begin + per_wave < n16 ? begin + per_wave : n16;
-  const unsigned lane = threadIdx.x & 63;
+struct ProbeBufs { const ssrnn_u32x4* p[MAX_BATCH_STAGES]; };
+__global__ __launch_bounds__(512) void read_probe_kernel(const ProbeBufs bufs, size_t n16, unsigned* sink) {
+  const ssrnn_u32x4* __restrict__ p = bufs.p[blockIdx.y];
+  const size_t per_wg = (n16 + gridDim.x - 1) / gridDim.x;          // chunks per workgroup
+  const size_t begin = static_cast<size_t>(blockIdx.x) * per_wg;
+  const size_t end = begin + per_wg < n16 ? begin + per_wg : n16;
+  const unsigned lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   ssrnn_u32x4 acc = {0u, 0u, 0u, 0u};
-  size_t i = begin + lane;
-  for (; i + 15 * 64 < end; i += 16 * 64) {
+  const size_t stride = static_cast<size_t>(nw) * 64;
+  // sixteen requests per lane at a time; those past the end of a short slab are left out, the others
+  // go out together all the same
+  for (size_t i = begin + static_cast<size_t>(wave) * 64 + lane; i < end; i += 16 * stride) {
     ssrnn_u32x4 v[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) v[j] = __builtin_nontemporal_load(p + i + j * 64);
+    for (int j = 0; j < 16; ++j) {
+      v[j] = ssrnn_u32x4{0u, 0u, 0u, 0u};
+      if (i + j * stride < end) v[j] = __builtin_nontemporal_load(p + i + j * stride);
+    }
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc ^= v[j];
   }
-  for (; i < end; i += 64) acc ^= __builtin_nontemporal_load(p + i);
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u) *sink = acc[0];
 }
 
@@ -264,36 +294,10 @@ __global__ void linear_kernel(const float* __restrict__ P, const float* __restri
 
 // --------------------------------------------------------------- the plan
 
-enum KernelKind { K_GENERIC = 1, K_VALU = 2, K_MFMA = 3 };
-
-struct Plan {
-  int cell, n_layers, d, k, T, wdt;
-  long L;
-  KernelKind kind;
-  // VALU kernel geometry
-  int tt, nv, nw, npass, F, grid;
-  // MFMA kernel geometry
-  int nt_tiles;
-  int ksplit;          // workgroups per feature tile (columns split), 1 unless the layer is narrow
-  int mfma_nw;         // waves per workgroup of the matrix-core kernel
-  bool packed;         // weights are in the matrix-core fragment order (ssrnn_pack_weights)
-  bool lds_four_waves; // LDS-staged kernel, one or two time tiles: the four-wave instance (short rows)
-  int ft;              // packed kernel: feature tiles (of 16) per workgroup, 1 or 2
-  bool wide;           // long blocks of packed bf16 weights: the 64-features-per-workgroup kernel
-  bool one_wg_per_cu;  // vector-ALU geometry for a launch whose workgroups must all be resident
-  int concurrent;      // stages per launch in the steady state of the schedule (1: one launch per stage)
-};
-
-int g_tune_valu_F = 0, g_tune_valu_nw = 0, g_tune_valu_nv = 0;
-long long g_tune_spin_limit = 0;   // 0 = default (one second); otherwise wall-clock ticks a grid-barrier wait may take
-int g_tune_ksplit = 0;     // 0 = default, 1 = never split, 2/4/8 = at most that many parts
-int g_tune_ft = 0;         // 0 = default, 1 = always one feature tile per workgroup
-int g_tune_wide = 0;       // 0 = default, 1 = never the 64-features-per-workgroup kernel
-
 bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
   // a wave-wide 16-byte load covers 256 fp32, 512 bf16 or 1024 8-bit columns; the narrow types are taken up to T = 8
   const int chw = 1024 / static_cast<int>(weight_esize(p.wdt));
-  if (p.T > (p.wdt == SSRNN_F32 ? VALU_MAX_T : 8) || p.d % chw != 0) return false;
+  if (p.T > (p.wdt == SSRNN_F32 ? valu_max_t() : 8) || p.d % chw != 0) return false;
   if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
   for (int l = 0; l < p.n_layers; ++l)
     if (!aligned16(W[l])) return false;
@@ -301,67 +305,28 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
   const int fg = 2;   // F is kept even for every T so that one workgroup shape serves all block sizes
   const int q = p.k * p.d / chw;
   p.nv = (q % 2 == 0 && q >= 16) ? 2 : 1;
-  if (g_tune_valu_nv == 1 || (g_tune_valu_nv == 2 && q % 2 == 0)) p.nv = g_tune_valu_nv;
   if (p.wdt == SSRNN_FP8) p.nv = 1;   // 16 columns per lane and chunk already: one chunk per lane
   const int qq = q / p.nv;
   p.nw = 1;
-  for (int w = 1; w <= VALU_MAX_WAVES; ++w)
+  for (int w = 1; w <= valu_max_waves(); ++w)
     if (qq % w == 0) p.nw = w;
-  if (g_tune_valu_nw >= 1 && g_tune_valu_nw <= VALU_MAX_WAVES && qq % g_tune_valu_nw == 0) p.nw = g_tune_valu_nw;
   p.npass = qq / p.nw;
   // Features per workgroup: the smallest even count that gives at most one workgroup per CU; wide layers
   // (d >= 4096) with short blocks take more, smaller workgroups instead, which lets the hardware's
   // dispatcher even out the workgroups' unequal memory rates (measured at d = 4096, us per stage: T = 4,
   // 512 workgroups 32.8 against 33.5 with 256; T = 1, 2048 workgroups of one work item 31.5 against 32.5
   // with 512; from T = 3 on the single-item workgroups lose, 39 us).
-  int wg_target = (p.d < 4096 || p.tt > 8 || p.one_wg_per_cu) ? 256 : (p.tt <= 2 ? 2048 : 512);
+  int wg_target = (p.d < 4096 || p.tt > 8) ? 256 : (p.tt <= 2 ? 2048 : 512);
   if (p.wdt == SSRNN_BF16 && wg_target > 256) wg_target /= 2;   // half the bytes per feature: twice the features
   if (p.wdt == SSRNN_FP8 && wg_target > 256) wg_target = wg_target / 4 > 256 ? wg_target / 4 : 256;
   int F = 0;
   for (int f = fg; f <= 64; f += fg)
     if (p.d % f == 0 && f * wg_target >= p.d) { F = f; break; }
   if (F == 0) F = fg;
-  if (g_tune_valu_F > 0 && g_tune_valu_F % fg == 0 && g_tune_valu_F <= 64 && p.d % g_tune_valu_F == 0) F = g_tune_valu_F;
   if (p.d % F != 0) return false;
   p.F = F;
   p.grid = p.d / F;
   return true;
-}
-
-template <int CELL>
-int launch_valu(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
-  const dim3 grid(p.grid, nstage), block(p.nw * 64);
-  const size_t lds = static_cast<size_t>(p.nw) * 3 * p.F * p.tt * sizeof(float);
-#define SSRNN_VALU_CASE(TT_, NV_)                                                          \
-  if (p.tt == TT_ && p.nv == NV_) {                                                        \
-    if (p.wdt == SSRNN_BF16) {                                                             \
-      if constexpr (TT_ <= 8) {                                                            \
-        if (p.npass == 1)                                                                  \
-          hipLaunchKernelGGL((stage_valu_kernel<CELL, W_BF16, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
-        else                                                                               \
-          hipLaunchKernelGGL((stage_valu_kernel<CELL, W_BF16, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
-        return SSRNN_OK;                                                                   \
-      }                                                                                    \
-    } else if (p.wdt == SSRNN_FP8) {                                                       \
-      if constexpr (TT_ <= 8 && NV_ == 1) {                                                \
-        if (p.npass == 1)                                                                  \
-          hipLaunchKernelGGL((stage_valu_kernel<CELL, W_FP8, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
-        else                                                                               \
-          hipLaunchKernelGGL((stage_valu_kernel<CELL, W_FP8, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
-        return SSRNN_OK;                                                                   \
-      }                                                                                    \
-    } else {                                                                               \
-      if (p.npass == 1)                                                                    \
-        hipLaunchKernelGGL((stage_valu_kernel<CELL, W_F32, TT_, NV_, false>), grid, block, lds, st, s, p.d, p.k, p.F, 1); \
-      else                                                                                 \
-        hipLaunchKernelGGL((stage_valu_kernel<CELL, W_F32, TT_, NV_, true>), grid, block, lds, st, s, p.d, p.k, p.F, p.npass); \
-      return SSRNN_OK;                                                                     \
-    }                                                                                      \
-  }
-  SSRNN_VALU_CASE(1, 1) SSRNN_VALU_CASE(2, 1) SSRNN_VALU_CASE(4, 1) SSRNN_VALU_CASE(8, 1) SSRNN_VALU_CASE(16, 1)
-  SSRNN_VALU_CASE(1, 2) SSRNN_VALU_CASE(2, 2) SSRNN_VALU_CASE(4, 2) SSRNN_VALU_CASE(8, 2) SSRNN_VALU_CASE(16, 2)
-#undef SSRNN_VALU_CASE
-  return fail(SSRNN_EUNSUPPORTED, "no vector-ALU kernel for T tile %d, NV %d", p.tt, p.nv);
 }
 
 // Longest block the matrix-core kernels accumulate in one weight pass.  The LDS-staged kernel's
@@ -371,24 +336,13 @@ int mfma_block_cap(int wdt, bool packed) { return (wdt == SSRNN_F32 && !packed) 
 // Columns per k-step of the matrix-core kernels: 128 bytes of a weight row.
 int mfma_kstep(int wdt) { return 128 / static_cast<int>(weight_esize(wdt)); }
 
-// Waves per workgroup of the matrix-core kernel that takes this block length and weight layout.
-int mfma_waves(int nt_tiles, bool packed) {
-  switch (nt_tiles) {
-    case 1: return packed ? MfmaPkCfg<1>::NW : MfmaCfg<1>::NW;
-    case 2: return packed ? MfmaPkCfg<2>::NW : MfmaCfg<2>::NW;
-    case 4: return packed ? MfmaPkCfg<4>::NW : MfmaCfg<4>::NW;
-    case 8: return packed ? MfmaPkCfg<8>::NW : MfmaCfg<8>::NW;
-    default: return packed ? MfmaPkCfg<16>::NW : MfmaCfg<16>::NW;
-  }
-}
-
 // Shapes ssrnn_pack_weights takes: whole 16-feature tiles, and k-steps of 128 bytes that never straddle lag blocks.
 bool pack_shape_ok(int d, int k, int wdt) {
   if (d < 1 || k < 1 || !shape_ok(1, d, k, 1, wdt)) return false;
   return d % MFMA_F == 0 && d % mfma_kstep(wdt) == 0;
 }
 
-bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws) {
+bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist_init, const void* ws, size_t op_stride) {
   if (p.d % MFMA_F != 0 || p.T > mfma_block_cap(p.wdt, p.packed)) return false;
   if (p.wdt == SSRNN_FP8 && !p.packed) return false;   // 8-bit weights reach the matrix cores in packed form only
   if (!aligned16(x) || !aligned16(xhist_init) || !aligned16(ws)) return false;
@@ -396,7 +350,7 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
     if (!aligned16(W[l])) return false;
   const int tiles = (p.T + 15) / 16;
   p.nt_tiles = tiles <= 1 ? 1 : tiles <= 2 ? 2 : tiles <= 4 ? 4 : tiles <= 8 ? 8 : 16;
-  int nw = mfma_waves(p.nt_tiles, p.packed);
+  int nw = p.packed ? mfma_packed_waves(p.nt_tiles) : mfma_lds_waves(p.nt_tiles);
   const int kstep = mfma_kstep(p.wdt);
   const long ncol = static_cast<long>(p.k) * p.d;
   // short rows: eight waves would get at most four k-steps each, too few for their pipelines
@@ -411,159 +365,52 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   p.ksplit = 1;
   const int ntile = p.d / MFMA_F;
   const int conc = p.concurrent > 1 ? p.concurrent : 1;
-  if (ntile < 128 && p.nt_tiles <= 8 && g_tune_ksplit != 1) {
+  if (ntile < 128 && p.nt_tiles <= 8 && !(p.opts & SSRNN_OPT_NO_SPLIT)) {
     int ks = 1;
     while (ks < KSPLIT_MAX && ntile * conc * ks * 2 <= 256 && ncol % (static_cast<long>(nw) * kstep * ks * 2) == 0) ks *= 2;
-    if (g_tune_ksplit > 1 && g_tune_ksplit <= ks) ks = g_tune_ksplit;
     p.ksplit = ks;
   }
   // waves per workgroup: the kernel's maximum, halved (not below one per SIMD) while a wave would get a single k-step
   p.mfma_nw = nw;
   if (p.ksplit > 1)
     while (p.mfma_nw > 4 && ncol / (static_cast<long>(p.mfma_nw) * p.ksplit * kstep) < 2) p.mfma_nw /= 2;
-  // Two feature tiles per workgroup halve the input-block bytes every CU pulls through the L2; that pays
-  // where those bytes weigh against the weights' (17..64 steps; measured at d = 4096, us per stage:
-  // bf16 k = 2, T = 64: 43.4 -> 38.6; 8-bit: 29.7 -> 25.5; fp32 T = 32: 38.1 -> 37.0, T = 64 unchanged and
-  // left alone) and needs a launch with enough stages to fill the chip with d/32 workgroups each.
-  // Long blocks of packed bf16 weights: 64 features per workgroup (the input block crosses a CU's memory
-  // path once for four feature tiles), when the launches hold enough stages to fill the chip with d/64
-  // workgroups each and a wave's walk over all columns is whole ring iterations.
-  p.wide = p.packed && p.wdt == SSRNN_BF16 && (p.nt_tiles == 8 || p.nt_tiles == 16) && p.ksplit == 1 &&
-           p.d % WIDE_F == 0 && ncol % (wide_ring_slots(p.nt_tiles) * WIDE_KSTEP) == 0 &&
-           static_cast<long>(p.d) / WIDE_F * conc >= 256 &&
-           g_tune_wide != 1;
+  // Every 16-feature workgroup pulls the whole input block through its CU's memory path.  Where those bytes
+  // weigh against the weights' (blocks of 17 steps and more) and the launches hold enough stages to fill
+  // the chip with larger workgroups, a workgroup owns 64 features and shares the input block through LDS
+  // (packed fp32 and bf16 weights), or 32 features in the packed kernel itself (8-bit weights).
+  p.xlds = p.packed && p.nt_tiles >= 2 && p.ksplit == 1 && p.d % XLDS_F == 0 && xlds_takes(p.wdt, p.nt_tiles, ncol) &&
+           static_cast<long>(p.d) / XLDS_F * conc >= 256 && op_stride < (1ull << 31) && !(p.opts & SSRNN_OPT_ONE_TILE);
   p.ft = 1;
   if (p.packed && (p.nt_tiles == 2 || (p.nt_tiles == 4 && p.wdt != SSRNN_F32)) && p.ksplit == 1 && ntile % 2 == 0 &&
-      conc >= 2 && ntile / 2 * conc >= 256 && g_tune_ft != 1)
+      conc >= 2 && ntile / 2 * conc >= 256 && !(p.opts & SSRNN_OPT_ONE_TILE))
     p.ft = 2;
   return true;
 }
 
-// ---- persistent schedule (vector-ALU kernel, stacked SRU) -----------------------
-constexpr size_t WS_CTR_OFFSET = 0, WS_ABORT_OFFSET = 64;   // control words at the start of the workspace
-
-__global__ void zero_control_kernel(unsigned* ctr, unsigned* abort_flag) {
-  if (threadIdx.x == 0) { *ctr = 0u; *abort_flag = 0u; }
-}
-
-// The whole call as one cooperative launch.  Returns SSRNN_EUNSUPPORTED (without launching) when the
-// shape or the device does not allow it, so that the caller can take the per-stage schedule instead.
-int launch_persistent(const Plan& p, const void* const* W, const float* const* bias, const float* x, const float* c_init,
-                      float* h, float* c_final, void* workspace, const WorkspaceLayout& wl, hipStream_t st) {
-  const int fg = p.tt >= 16 ? 1 : 2;
-  const int nitems = p.F / fg;
-  if (p.cell != CELL_SRU || p.wdt != SSRNN_F32 || p.k != 1 || p.npass != 1 || p.tt > 8 || p.n_layers > PERSIST_MAX_LAYERS || nitems < 2 || nitems % 2 != 0 ||
-      p.F * p.tt > p.nw * 64)
-    return fail(SSRNN_EUNSUPPORTED, "persistent schedule: stacked SRU with fp32 weights, T <= 8, one column pass and an even number of feature groups per workgroup");
-  PersistArgs a{};
-  for (int l = 0; l < p.n_layers; ++l) {
-    a.W[l] = static_cast<const float*>(W[l]);
-    a.bias[l] = (bias && bias[l]) ? bias[l] : nullptr;
-  }
-  a.x = x; a.c_init = c_init; a.h = h; a.c_final = c_final;
-  a.act = reinterpret_cast<float*>(static_cast<char*>(workspace) + wl.act_offset);
-  a.act_stride = 2 * wl.act_stride / sizeof(float);   // the even-block buffer of every layer
-  a.ctr = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + WS_CTR_OFFSET);
-  a.abort_flag = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + WS_ABORT_OFFSET);
-  a.spin_limit = g_tune_spin_limit > 0 ? g_tune_spin_limit : 100000000LL;   // default: one second of the 100 MHz wall clock
-  a.L = p.L; a.n_layers = p.n_layers; a.d = p.d; a.T = p.T; a.F = p.F; a.ld = wl.ld;
-  const size_t lds = (static_cast<size_t>(p.nw) * 3 * p.F * p.tt + static_cast<size_t>(p.n_layers) * p.F + 1) * sizeof(float);
-  const void* fn = nullptr;
-#define SSRNN_PERSIST_CASE(TT_, NV_) \
-  if (p.tt == TT_ && p.nv == NV_) fn = reinterpret_cast<const void*>(&persistent_sru_kernel<TT_, NV_>);
-  SSRNN_PERSIST_CASE(1, 1) SSRNN_PERSIST_CASE(2, 1) SSRNN_PERSIST_CASE(4, 1) SSRNN_PERSIST_CASE(8, 1)
-  SSRNN_PERSIST_CASE(1, 2) SSRNN_PERSIST_CASE(2, 2) SSRNN_PERSIST_CASE(4, 2) SSRNN_PERSIST_CASE(8, 2)
-#undef SSRNN_PERSIST_CASE
-  if (!fn) return fail(SSRNN_EUNSUPPORTED, "persistent schedule: no kernel for T tile %d, NV %d", p.tt, p.nv);
-  // every workgroup must be resident at once: ask the runtime how many fit
-  int dev = 0, ncu = 0, per_cu = 0;
-  HIP_TRY(hipGetDevice(&dev));
-  HIP_TRY(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
-  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, p.nw * 64, lds));
-  if (static_cast<long>(per_cu) * ncu < p.grid)
-    return fail(SSRNN_EUNSUPPORTED, "persistent schedule: %d workgroups do not fit the device at once", p.grid);
-  hipLaunchKernelGGL(zero_control_kernel, dim3(1), dim3(64), 0, st, a.ctr, a.abort_flag);
-  void* args[] = {&a};
-  HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(p.grid), dim3(p.nw * 64), args, static_cast<unsigned>(lds), st));
-  return SSRNN_OK;
-}
-
-template <int CELL>
 int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
-  // the first and last launches of a wavefront hold one or two stages: too few 64-feature workgroups to
-  // occupy the chip, so those go to the 16-feature kernel (another summation order, same tolerances)
-  if (p.wide && static_cast<long>(p.d) / WIDE_F * nstage > 128) {
-    const dim3 wgrid(p.d / WIDE_F, nstage), wblock(WIDE_TILES * 64);
-    if (p.nt_tiles == 8)
-      hipLaunchKernelGGL((stage_mfma_wide_kernel<CELL, 8>), wgrid, wblock, 0, st, s, p.d, p.k);
-    else
-      hipLaunchKernelGGL((stage_mfma_wide_kernel<CELL, 16>), wgrid, wblock, 0, st, s, p.d, p.k);
-    return SSRNN_OK;
-  }
-  // two feature tiles per workgroup only for launches that fill the chip that way (the first and last
-  // steps of a wavefront hold fewer stages); both instances give the same bits
+  // the first and last launch of a wavefront hold one stage: too few 64-feature workgroups to occupy the
+  // chip, so those go to the 16-feature kernel (another summation order, same tolerances)
+  if (p.xlds && static_cast<long>(p.d) / XLDS_F * nstage >= 128)
+    return p.wdt == SSRNN_BF16 ? launch_mfma_xlds_bf16(p, s, nstage, st) : launch_mfma_xlds_f32(p, s, nstage, st);
+  // two feature tiles per workgroup only for launches that fill the chip that way; both instances give the same bits
   const int ft = (p.packed && p.ft == 2 && static_cast<long>(p.d) / (2 * MFMA_F) * nstage >= 256) ? 2 : 1;
   const dim3 grid(p.d / (MFMA_F * ft) * p.ksplit, nstage);
   const dim3 block(p.mfma_nw * 64);
-#define SSRNN_MFMA_CASE(NT_)                                                                              \
-  if (p.nt_tiles == NT_) {                                                                                \
-    if (ft == 2 && (NT_ == 2 || NT_ == 4)) {                                                              \
-      constexpr int NTF = (NT_ == 2 || NT_ == 4) ? NT_ : 2;                                               \
-      if (p.wdt == SSRNN_FP8)                                                                             \
-        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_FP8, NTF, 2>), grid, block, 0, st, s, p.d, p.k); \
-      else if (p.wdt == SSRNN_BF16)                                                                       \
-        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_BF16, NTF, 2>), grid, block, 0, st, s, p.d, p.k); \
-      else                                                                                                \
-        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_F32, NTF, 2>), grid, block, 0, st, s, p.d, p.k); \
-    } else if (p.packed) {                                                                                \
-      if (p.wdt == SSRNN_FP8)                                                                             \
-        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_FP8, NT_>), grid, block, 0, st, s, p.d, p.k); \
-      else if (p.wdt == SSRNN_BF16)                                                                       \
-        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k); \
-      else                                                                                                \
-        hipLaunchKernelGGL((stage_mfma_packed_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k); \
-    } else if (NT_ <= 2 && p.lds_four_waves) {                                                            \
-      constexpr int NTL = NT_ <= 2 ? NT_ : 1;                                                             \
-      if (p.wdt == SSRNN_BF16)                                                                            \
-        hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_BF16, NTL, 4>), grid, block, 0, st, s, p.d, p.k); \
-      else                                                                                                \
-        hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_F32, NTL, 4>), grid, block, 0, st, s, p.d, p.k); \
-    } else if (p.wdt == SSRNN_BF16) {                                                                     \
-      hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_BF16, NT_>), grid, block, 0, st, s, p.d, p.k);    \
-    } else if constexpr (NT_ < 16) {                                                                      \
-      hipLaunchKernelGGL((stage_mfma_lds_kernel<CELL, W_F32, NT_>), grid, block, 0, st, s, p.d, p.k);     \
-    } else {                                                                                              \
-      return fail(SSRNN_EUNSUPPORTED, "no matrix-core kernel for %d time tiles of row-major fp32 weights", p.nt_tiles); \
-    }                                                                                                     \
-    if (p.ksplit > 1)                                                                                     \
-      hipLaunchKernelGGL((split_epilogue_kernel<CELL>), dim3(p.d / MFMA_F, nstage), dim3(512), 0, st, s, p.d, p.k); \
-    return SSRNN_OK;                                                                                      \
-  }
-  SSRNN_MFMA_CASE(1) SSRNN_MFMA_CASE(2) SSRNN_MFMA_CASE(4) SSRNN_MFMA_CASE(8) SSRNN_MFMA_CASE(16)
-#undef SSRNN_MFMA_CASE
-  return fail(SSRNN_EUNSUPPORTED, "no matrix-core kernel for %d time tiles", p.nt_tiles);
-}
-
-template <int CELL>
-int launch_generic(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
-  const int grid = (p.d + GENERIC_WAVES - 1) / GENERIC_WAVES;
-  const dim3 g(grid < 4096 ? grid : 4096, nstage), b(GENERIC_WAVES * 64);
-  if (p.wdt == SSRNN_FP8)
-    hipLaunchKernelGGL((stage_generic_kernel<CELL, W_FP8>), g, b, 0, st, s, p.d, p.k);
-  else if (p.wdt == SSRNN_BF16)
-    hipLaunchKernelGGL((stage_generic_kernel<CELL, W_BF16>), g, b, 0, st, s, p.d, p.k);
-  else
-    hipLaunchKernelGGL((stage_generic_kernel<CELL, W_F32>), g, b, 0, st, s, p.d, p.k);
-  return SSRNN_OK;
+  int rc;
+  if (!p.packed) rc = launch_mfma_lds(p, s, nstage, grid, block, st);
+  else if (p.wdt == SSRNN_FP8) rc = launch_mfma_packed_fp8(p, s, nstage, ft, grid, block, st);
+  else if (p.wdt == SSRNN_BF16) rc = launch_mfma_packed_bf16(p, s, nstage, ft, grid, block, st);
+  else rc = launch_mfma_packed_f32(p, s, nstage, ft, grid, block, st);
+  if (rc == SSRNN_OK && p.ksplit > 1) rc = launch_split_epilogue(p, s, nstage, st);
+  return rc;
 }
 
 // One launch (two for split stages) for nstage <= MAX_BATCH_STAGES stages that do not depend on each other.
-template <int CELL>
 int launch_stages(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
   switch (p.kind) {
-    case K_VALU: return launch_valu<CELL>(p, s, nstage, st);
-    case K_MFMA: return launch_mfma<CELL>(p, s, nstage, st);
-    default: return launch_generic<CELL>(p, s, nstage, st);
+    case K_VALU: return launch_valu(p, s, nstage, st);
+    case K_MFMA: return launch_mfma(p, s, nstage, st);
+    default: return launch_generic(p, s, nstage, st);
   }
 }
 
@@ -585,7 +432,9 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   const int sched = flags & SSRNN_SCHED_MASK;
   const int kforce = flags & SSRNN_KERNEL_MASK;
   const bool packed = (flags & SSRNN_WEIGHTS_PACKED) != 0;
-  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED)) != 0 || sched > SSRNN_SCHED_WAVEFRONT)
+  const int opts = flags & SSRNN_OPT_MASK;
+  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED | SSRNN_OPT_MASK)) != 0 ||
+      (sched != SSRNN_SCHED_AUTO && sched != SSRNN_SCHED_STAGES && sched != SSRNN_SCHED_WAVEFRONT))
     return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
   if (packed && kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_MFMA)
     return fail(SSRNN_EINVAL, "%s: packed weights are read by the matrix-core kernel only", name);
@@ -618,20 +467,11 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   p.cell = cell; p.n_layers = n_layers; p.d = d; p.k = k; p.T = T; p.wdt = wdt; p.L = L;
   p.kind = K_GENERIC;
   p.packed = packed;
+  p.opts = opts;
   // Kernel choice.  Forced: that kernel or an error.  Otherwise: the vector-ALU kernel where it applies
   // (fp32, T <= 16), except that from T = 5 on a layer wide enough to give the matrix-core kernel one
   // workgroup per CU (d >= 4096) goes there (measured at d = 4096: 34.8 us per stage against 36.3 at
   // T = 8 and 40.0 at T = 16); the matrix-core kernel for everything else it takes; the generic kernel last.
-  if (sched == SSRNN_SCHED_PERSISTENT) {
-    if (packed || (kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_VALU))
-      return fail(SSRNN_EUNSUPPORTED, "%s: the persistent schedule runs the vector-ALU kernel on row-major weights", name);
-    p.one_wg_per_cu = true;
-    if (!plan_valu(p, W, x, xhist_init, workspace))
-      return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs T <= 16 and d %% 256 == 0 (fp32 weights) or T <= 8 and d %% 512 == 0 (bf16) or d %% 1024 == 0 (8-bit), and 16-byte aligned buffers", name);
-    p.kind = K_VALU;
-    // c_final already holds the initial state (init_state_kernel above)
-    return launch_persistent(p, W, bias, x, c_final, h, c_final, workspace, wl, st);
-  }
   bool valu_ok = false;
   if (!packed && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU)) {
     valu_ok = plan_valu(p, W, x, xhist_init, workspace);
@@ -658,7 +498,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     const int cap = mfma_block_cap(wdt, packed);
     p.T = T < cap ? T : cap;
     p.concurrent = stages_per_launch(p.T);
-    if (plan_mfma(p, W, x, xhist_init, workspace)) { p.kind = K_MFMA; T = p.T; }
+    if (plan_mfma(p, W, x, xhist_init, workspace, workspace_layout(n_layers, d, k, p.T, wdt).op_stride)) { p.kind = K_MFMA; T = p.T; }
     else {
       p.T = T;
       if (kforce == SSRNN_KERNEL_MFMA || packed)
@@ -670,7 +510,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   // 8-bit weights beyond T = 8, which have no matrix-core kernel): cut the block to that kernel's longest.
   // Results do not depend on the block size; the weights are then fetched once per 8 (16) steps.
   if (p.kind == K_GENERIC && kforce == SSRNN_KERNEL_AUTO && !packed) {
-    const int cap = (wdt == SSRNN_F32) ? VALU_MAX_T : 8;
+    const int cap = (wdt == SSRNN_F32) ? valu_max_t() : 8;
     if (T > cap) {
       p.T = cap;
       if (plan_valu(p, W, x, xhist_init, workspace)) { p.kind = K_VALU; T = cap; }
@@ -751,7 +591,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     return s;
   };
   auto launch = [&](const StageBatch& sb, int n) {
-    return (cell == CELL_SRU) ? launch_stages<CELL_SRU>(p, sb, n, st) : launch_stages<CELL_QRNN>(p, sb, n, st);
+    return launch_stages(p, sb, n, st);
   };
 
   const bool wavefront = sched == SSRNN_SCHED_WAVEFRONT || (sched == SSRNN_SCHED_AUTO && n_layers > 1 && nblocks > 1);
@@ -826,7 +666,7 @@ void* static_scratch(int* status) {
 
 extern "C" {
 
-int ssrnn_version(void) { return 300; }   // 0.3.0: allocation-free entry point
+int ssrnn_version(void) { return 400; }   // 0.4.0: 64-feature matrix-core kernel, per-call geometry options
 
 const char* ssrnn_last_error(void) { return g_last_error.c_str(); }
 
@@ -845,8 +685,6 @@ int sru_forward(const void* const* W, const float* const* bias, const float* x, 
 int sru_forward_noalloc(const void* const* W, const float* const* bias, const float* x, const float* c_init,
                         float* h, float* c_final, int n_layers, int d, long L, int T, int wdtype, int flags,
                         void* stream) {
-  if ((flags & SSRNN_SCHED_MASK) == SSRNN_SCHED_PERSISTENT)
-    return fail(SSRNN_EUNSUPPORTED, "sru_forward_noalloc: the persistent schedule reports through the caller's workspace and is not offered here");
   if (n_layers < 1 || d < 1 || L < 0 || T < 1)
     return fail(SSRNN_EINVAL, "sru_forward_noalloc: need n_layers >= 1, d >= 1, L >= 0, T >= 1 (got %d, %d, %ld, %d)", n_layers, d, L, T);
   if (!shape_ok(n_layers, d, 1, T, wdtype)) return fail(SSRNN_EUNSUPPORTED, "sru_forward_noalloc: unknown weight type or shape too large");
@@ -915,36 +753,20 @@ int ssrnn_pack_weights(const void* W, void* W_packed, int d, int k, int wdtype, 
   return SSRNN_OK;
 }
 
-int ssrnn_workspace_status(const void* workspace, void* stream) {
-  if (!workspace) return fail(SSRNN_EINVAL, "ssrnn_workspace_status: workspace is NULL");
-  unsigned flag = 0;
-  HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
-  HIP_TRY(hipMemcpy(&flag, static_cast<const char*>(workspace) + WS_ABORT_OFFSET, sizeof flag, hipMemcpyDeviceToHost));
-  if (flag != 0) return fail(SSRNN_EDEVICE, "a grid barrier of the persistent schedule timed out; the outputs of that call are incomplete");
-  return SSRNN_OK;
-}
-
-int ssrnn_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
-  if (!buf || !sink) return fail(SSRNN_EINVAL, "ssrnn_read_probe: NULL pointer");
-  if (!aligned16(buf) || bytes % 16 != 0) return fail(SSRNN_EINVAL, "ssrnn_read_probe: buffer must be 16-byte aligned and a multiple of 16 bytes long");
+int ssrnn_read_probe(const void* const* bufs, int n, size_t bytes, int groups, void* sink, void* stream) {
+  if (!bufs || !sink) return fail(SSRNN_EINVAL, "ssrnn_read_probe: NULL pointer");
+  if (n < 1 || n > MAX_BATCH_STAGES) return fail(SSRNN_EINVAL, "ssrnn_read_probe: 1 to %d buffers per launch", MAX_BATCH_STAGES);
+  if (groups < 0 || groups > 65535) return fail(SSRNN_EINVAL, "ssrnn_read_probe: 0 to 65535 workgroups per buffer");
+  if (bytes % 16 != 0) return fail(SSRNN_EINVAL, "ssrnn_read_probe: buffers must be a multiple of 16 bytes long");
+  ProbeBufs pb{};
+  for (int i = 0; i < n; ++i) {
+    if (!bufs[i] || !aligned16(bufs[i])) return fail(SSRNN_EINVAL, "ssrnn_read_probe: buffer %d is NULL or not 16-byte aligned", i);
+    pb.p[i] = static_cast<const ssrnn_u32x4*>(bufs[i]);
+  }
   if (bytes == 0) return SSRNN_OK;
-  const size_t n16 = bytes / 16;
-  hipLaunchKernelGGL(read_probe_kernel, dim3(256), dim3(512), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const ssrnn_u32x4*>(buf), n16, static_cast<unsigned*>(sink));
+  hipLaunchKernelGGL(read_probe_kernel, dim3(groups ? groups : 256, n), dim3(512), 0, static_cast<hipStream_t>(stream),
+                     pb, bytes / 16, static_cast<unsigned*>(sink));
   HIP_TRY(hipGetLastError());
-  return SSRNN_OK;
-}
-
-int ssrnn_tune(const char* key, int value) {
-  if (!key) return fail(SSRNN_EINVAL, "ssrnn_tune: key is NULL");
-  if (!strcmp(key, "valu_F")) g_tune_valu_F = value;
-  else if (!strcmp(key, "valu_nw")) g_tune_valu_nw = value;
-  else if (!strcmp(key, "valu_nv")) g_tune_valu_nv = value;
-  else if (!strcmp(key, "ksplit")) g_tune_ksplit = value;
-  else if (!strcmp(key, "feature_tiles")) g_tune_ft = value;
-  else if (!strcmp(key, "wide")) g_tune_wide = value;
-  else if (!strcmp(key, "spin_limit")) g_tune_spin_limit = value;
-  else return fail(SSRNN_EINVAL, "ssrnn_tune: unknown key %s", key);
   return SSRNN_OK;
 }
 

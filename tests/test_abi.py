@@ -19,17 +19,21 @@ def lib():
     return ss.load_library()
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ssrnn.h")).read()
+def _declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"}
 
 
 def test_every_declared_symbol_is_exported(lib):
-    names = _declared_symbols()
-    assert names == set(ss.EXPORTS)
-    for n in names:
-        assert getattr(lib, n) is not None
+    """The method's interface (ssrnn.h) and the measurement aids (ssrnn_probe.h) are separate headers; the
+    product header holds no process-wide setting."""
+    for header, table in (("ssrnn.h", ss.EXPORTS), ("ssrnn_probe.h", ss.PROBE_EXPORTS)):
+        names = _declared_symbols(header)
+        assert names == set(table), header
+        for n in names:
+            assert getattr(lib, n) is not None
+    assert "tune" not in open(os.path.join(ROOT, "include", "ssrnn.h")).read()
 
 
 def test_version_and_workspace_query(lib):
@@ -88,11 +92,12 @@ def test_bad_arguments_fail_on_the_host(lib):
     assert ss.packed_weight_bytes(64, 1, ss.FP8) == 0                        # rows shorter than a 128-byte k-step
     assert ss.workspace_bytes(2, 1024, 2, 64, ss.FP8) == ss.workspace_bytes(2, 1024, 2, 64, ss.BF16)
     assert call(wdt=2, flags=3 << 4) == 2                                    # row-major 8-bit weights + matrix-core kernel
-    assert lib.ssrnn_read_probe(None, 1024, fake, None) == 1
-    assert lib.ssrnn_read_probe(fake, 1000, fake, None) == 1                 # not a multiple of 16 bytes
-    assert lib.ssrnn_read_probe(ctypes.c_void_p(0x1004), 1024, fake, None) == 1
-    assert lib.ssrnn_tune(b"no_such_key", 1) == 1
-    assert lib.ssrnn_tune(None, 1) == 1
+    assert call(flags=2) == 1                                                # no such schedule
+    assert lib.ssrnn_read_probe(None, 1, 1024, 0, fake, None) == 1
+    assert lib.ssrnn_read_probe(tab, 1, 1000, 0, fake, None) == 1            # not a multiple of 16 bytes
+    assert lib.ssrnn_read_probe((ctypes.c_void_p * 1)(0x1004), 1, 1024, 0, fake, None) == 1
+    assert lib.ssrnn_read_probe(tab, 9, 1024, 0, fake, None) == 1            # more buffers than a launch holds
+    assert lib.ssrnn_read_probe(tab, 1, 1024, 0, None, None) == 1
 
 
 def test_binding_refuses_to_run_without_the_library(monkeypatch):

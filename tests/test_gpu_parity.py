@@ -389,6 +389,7 @@ def test_read_probe_runs_and_leaves_its_input_alone():
     keep = buf.clone()
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     ss.read_probe(buf, sink)
+    ss.read_probe([buf, keep, buf], sink, groups=7)
     ss.read_probe(buf[:4], sink)
     torch.cuda.synchronize()
     assert torch.equal(buf, keep)

@@ -40,11 +40,8 @@ def test_wavefront_equals_stage_by_stage_bitwise(cell, d, n_layers, L, T, k, bf1
     # Narrow layers: the library splits a stage's columns over fewer workgroups when a launch holds several
     # stages, which re-associates the fp32 sums.  With the split switched off both schedules add in the same
     # order and must give the same bits; the library's own choice is then checked against the oracle.
-    ss.tune("ksplit", 1)
-    try:
-        a, w, auto = run(STAGES), run(WAVEFRONT), run(0)
-    finally:
-        ss.tune("ksplit", 0)
+    ns = ss.OPT_NO_SPLIT
+    a, w, auto = run(STAGES | ns), run(WAVEFRONT | ns), run(ns)
     for u, v, z in zip(a, w, auto):
         np.testing.assert_array_equal(u, v)
         np.testing.assert_array_equal(u, z)      # the default of a call with several blocks and layers is the wavefront
@@ -106,17 +103,13 @@ def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, mode, d,
     c0 = rng.standard_normal((n_layers, d)).astype(np.float32)
     xh0 = rng.standard_normal((n_layers, k - 1, d)).astype(np.float32) if k > 1 else None
     if cell == "sru":
-        run = lambda: gpu_sru(W, b, x, c0, T=T, packed=True)
+        run = lambda flags=0: gpu_sru(W, b, x, c0, T=T, flags=flags, packed=True)
         ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
     else:
-        run = lambda: gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, packed=True)
+        run = lambda flags=0: gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, flags=flags, packed=True)
         ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
     two = run()
-    ss.tune("feature_tiles", 1)
-    try:
-        one = run()
-    finally:
-        ss.tune("feature_tiles", 0)
+    one = run(ss.OPT_ONE_TILE)
     for u, v in zip(two, one):
         np.testing.assert_array_equal(u, v)
     for u, r in zip(two, ref):
@@ -149,17 +142,13 @@ def test_long_blocks_of_packed_bf16_weights_on_the_64_feature_kernel(cell, k, T,
     c0 = rng.standard_normal((n_layers, d)).astype(np.float32)
     xh0 = rng.standard_normal((n_layers, k - 1, d)).astype(np.float32) if k > 1 else None
     if cell == "sru":
-        run = lambda: gpu_sru(W, b, x, c0, T=T, packed=True)
+        run = lambda flags=0: gpu_sru(W, b, x, c0, T=T, flags=flags, packed=True)
         ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
     else:
-        run = lambda: gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, packed=True)
+        run = lambda flags=0: gpu_qrnn(W, b, x, c0, xh0, T=T, k=k, flags=flags, packed=True)
         ref = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
     wide = run()
-    ss.tune("wide", 1)
-    try:
-        narrow = run()
-    finally:
-        ss.tune("wide", 0)
+    narrow = run(ss.OPT_ONE_TILE)
     for u, v, r in zip(wide, narrow, ref):
         if np.asarray(r).size:
             assert np.all(np.isfinite(u))

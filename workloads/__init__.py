@@ -213,15 +213,22 @@ def layer_weight(wl: Workload, layer: int) -> np.ndarray:
     return to_bf16_bits(w) if wl.wdtype == "bf16" else w
 
 
-def make_inputs(wl: Workload, L: Optional[int] = None, n_layers: Optional[int] = None):
+def make_inputs(wl: Workload, L: Optional[int] = None, n_layers: Optional[int] = None, threads: int = 8):
     """Returns a dict: W (list), x [L, d] float32 or feat/P for projected
     inputs.  Biases are zero and c_init is zero in every configuration, so
     they are not generated.  L / n_layers may be cut down for prefix tests;
-    the draws of a prefix equal the leading draws of the full tensors."""
+    the draws of a prefix equal the leading draws of the full tensors.  The
+    layers of a wide stack are drawn side by side on `threads` threads (every
+    value is a function of its counter, so the result does not depend on it)."""
     L_full = wl.L
     L = L_full if L is None else L
     n_layers = wl.n_layers if n_layers is None else n_layers
-    out = {"W": [layer_weight(wl, l) for l in range(n_layers)]}
+    if threads > 1 and n_layers > 1 and wl.d >= 2048:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(threads, n_layers)) as ex:
+            out = {"W": list(ex.map(lambda l: layer_weight(wl, l), range(n_layers)))}
+    else:
+        out = {"W": [layer_weight(wl, l) for l in range(n_layers)]}
     if wl.d_feat:
         out["feat"] = normal(wl.seed, TID_FEAT, (L_full, wl.d_feat))[:L].copy()
         out["P"] = uniform(wl.seed, TID_PROJ, (wl.d, wl.d_feat), 1.0 / math.sqrt(wl.d_feat))
