@@ -30,8 +30,9 @@ namespace ssrnn {
 
 constexpr int VALU_MAX_WAVES = 8;
 constexpr int VALU_MAX_T = 16;    // longest block this kernel takes
-// features per accumulation group: two, or one when 16 steps fill the registers
-constexpr int valu_fg(int tt) { return tt >= 16 ? 1 : 2; }
+// features per accumulation group: two; one where that keeps the kernel within 128 registers (4 steps: two workgroups
+// per compute unit instead of one) or fits at all (16 steps)
+constexpr int valu_fg(int tt) { return (tt >= 16 || tt == 4) ? 1 : 2; }
 
 __device__ __forceinline__ float dot4(const float4& w, const float4& x, float acc) {
   acc = fmaf(w.x, x.x, acc);

@@ -313,10 +313,10 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
   p.npass = qq / p.nw;
   // Features per workgroup: the smallest even count that gives at most one workgroup per CU; wide layers
   // (d >= 4096) with short blocks take more, smaller workgroups instead, which lets the hardware's
-  // dispatcher even out the workgroups' unequal memory rates (measured at d = 4096, us per stage: T = 4,
-  // 512 workgroups 32.8 against 33.5 with 256; T = 1, 2048 workgroups of one work item 31.5 against 32.5
-  // with 512; from T = 3 on the single-item workgroups lose, 39 us).
-  int wg_target = (p.d < 4096 || p.tt > 8) ? 256 : (p.tt <= 2 ? 2048 : 512);
+  // dispatcher even out the workgroups' unequal memory rates (measured at d = 4096, us per stage, one launch
+  // per stage: T = 4, 1024 workgroups 32.1, 512 32.3, 256 32.8, 2048 33.7; T = 1, 2048 workgroups of one work
+  // item 31.4 against 32.5 with 512).
+  int wg_target = (p.d < 4096 || p.tt > 8) ? 256 : (p.tt <= 2 ? 2048 : p.tt <= 4 ? 1024 : 512);
   if (p.wdt == SSRNN_BF16 && wg_target > 256) wg_target /= 2;   // half the bytes per feature: twice the features
   if (p.wdt == SSRNN_FP8 && wg_target > 256) wg_target = wg_target / 4 > 256 ? wg_target / 4 : 256;
   int F = 0;
