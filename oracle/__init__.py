@@ -44,10 +44,8 @@ def load_library(path: str):
     vp, ip, lp = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
     lib.oracle_num_threads.restype = ip
     lib.oracle_set_num_threads.argtypes = [ip]
-    lib.oracle_set_operand_rounding.argtypes = [ip]
-    lib.oracle_set_operand_rounding.restype = None
-    lib.oracle_sru_forward.argtypes = [vp] * 7 + [ip, ip, lp, ip, ip]
-    lib.oracle_qrnn_forward.argtypes = [vp] * 9 + [ip, ip, lp, ip, ip, ip]
+    lib.oracle_sru_forward.argtypes = [vp] * 7 + [ip, ip, lp, ip, ip, ip, ip]
+    lib.oracle_qrnn_forward.argtypes = [vp] * 9 + [ip, ip, lp, ip, ip, ip, ip, ip]
     lib.oracle_sru_step.argtypes = [vp] * 5 + [ip, ip]
     lib.oracle_qrnn_step.argtypes = [vp] * 5 + [ip, ip, ip]
     lib.oracle_linear_forward.argtypes = [vp] * 3 + [ip, ip, lp]
@@ -72,13 +70,6 @@ def _load():
 
 def num_threads() -> int:
     return _load().oracle_num_threads()
-
-
-def set_operand_rounding(mode: int) -> None:
-    """0 (default): exact arithmetic.  1: the block X of Eq. 4 enters the matrix
-    product rounded to bfloat16 (what a bf16 matrix-core kernel does); all else
-    stays double.  Callers restore 0 when done."""
-    _load().oracle_set_operand_rounding(int(mode))
 
 
 def set_num_threads(n: int) -> None:
@@ -132,9 +123,11 @@ def _as(a, dtype, shape=None):
     return a
 
 
-def sru_forward(W, bias, x, c_init=None, T=1, return_all=False):
+def sru_forward(W, bias, x, c_init=None, T=1, return_all=False, round_operand=False, reverse=False):
     """W: list of [3d, d] float32 / uint16 arrays or 8-bit weight objects; bias: None or list of
-    None / [2d] float32; x: [L, d].  Returns (h, c_final[, h_all]) as float64."""
+    None / [2d] float32; x: [L, d].  round_operand: the block X of Eq. 4 enters the products rounded to
+    bfloat16; reverse: every layer walks the sequence from its last step to its first.
+    Returns (h, c_final[, h_all]) as float64."""
     lib = _load()
     n_layers = len(W)
     wdt = _wdt_of(W[0])
@@ -156,14 +149,15 @@ def sru_forward(W, bias, x, c_init=None, T=1, return_all=False):
     wp, _k1 = _ptr_array(W)
     bp, _k2 = _ptr_array(bias)
     rc = lib.oracle_sru_forward(wp, bp, _ptr(x), _ptr(c_init), _ptr(h), _ptr(c_final),
-                                _ptr(h_all), n_layers, d, L, int(T), wdt)
+                                _ptr(h_all), n_layers, d, L, int(T), wdt, int(bool(round_operand)), int(bool(reverse)))
     if rc != 0:
         raise ValueError("oracle_sru_forward rejected its arguments")
     return (h, c_final, h_all) if return_all else (h, c_final)
 
 
-def qrnn_forward(W, bias, x, c_init=None, xhist_init=None, T=1, k=2, return_all=False):
-    """W: list of [3d, k*d]; bias: None or list of None / [3d]; x: [L, d].
+def qrnn_forward(W, bias, x, c_init=None, xhist_init=None, T=1, k=2, return_all=False, round_operand=False, reverse=False):
+    """W: list of [3d, k*d]; bias: None or list of None / [3d]; x: [L, d].  round_operand, reverse: as
+    for sru_forward (in reverse the window of step t holds x_t, x_{t+1}, ...).
     Returns (h, c_final, xhist_final[, h_all]) as float64."""
     lib = _load()
     n_layers = len(W)
@@ -189,7 +183,7 @@ def qrnn_forward(W, bias, x, c_init=None, xhist_init=None, T=1, k=2, return_all=
     bp, _k2 = _ptr_array(bias)
     rc = lib.oracle_qrnn_forward(wp, bp, _ptr(x), _ptr(c_init), _ptr(xhist_init), _ptr(h),
                                  _ptr(c_final), _ptr(xhist_final) if k > 1 else None,
-                                 _ptr(h_all), n_layers, d, L, int(T), int(k), wdt)
+                                 _ptr(h_all), n_layers, d, L, int(T), int(k), wdt, int(bool(round_operand)), int(bool(reverse)))
     if rc != 0:
         raise ValueError("oracle_qrnn_forward rejected its arguments")
     return (h, c_final, xhist_final, h_all) if return_all else (h, c_final, xhist_final)

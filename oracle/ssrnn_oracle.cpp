@@ -25,11 +25,22 @@
 // order whatever T is, so the result is bit-identical for every block size.
 // Nothing is rounded between layers.  The paper does not state the precision
 // of its runs (Section 4).  For kernels that hand the block X of Eq. 4 to the
-// matrix product in bfloat16, oracle_set_operand_rounding(1) makes this
-// oracle round exactly that operand the same way (double -> float ->
-// bfloat16, both round-to-nearest-even) and nothing else: the highway term,
-// the state and the sums stay double.  The default, 0, rounds nothing, and
-// every pin below is stated for it.
+// matrix product in bfloat16, the argument round_operand = 1 of
+// oracle_*_forward makes this oracle round exactly that operand the same way
+// (double -> float -> bfloat16, both round-to-nearest-even) and nothing else:
+// the highway term, the state and the sums stay double.  With 0 nothing is
+// rounded, and every pin below is stated for it.
+//
+// Direction.  The paper notes that a bidirectional network is two independent
+// passes over the sequence, one in each direction (Section 2.1).  With
+// reverse = 1 every layer walks the sequence from its last step to its first:
+// step number tau = 0 .. L-1 of the walk is time L-1-tau, "the previous step"
+// is the later time (c_{t+1} in place of c_{t-1}; the QRNN window holds x_t,
+// x_{t+1}, ...), c_init is the state before time L-1 is taken in, c_final the
+// state after time 0, and xhist entry (l, j) is layer l's input j+1 steps before
+// the walk starts (and, on return, the last k-1 inputs it took in).  h stays
+// indexed by time.  Nothing else differs, so the reverse pass over x equals the
+// forward pass over the time-reversed x, read backwards (a pin).
 //
 // Pins (tests/test_oracle_*.py): hand-worked d=2 examples for both cells,
 // step-by-step brute force (oracle_*_step below, written separately),
@@ -100,8 +111,6 @@ inline double weight_at(const void* W, int wdt, size_t rows, size_t ncol, size_t
 
 inline double sigma(double z) { return 1.0 / (1.0 + std::exp(-z)); }
 
-int g_round_operand = 0;   // 0: X of Eq. 4 enters the product as it is; 1: rounded to bfloat16
-
 // Nearest bfloat16 (ties to even) of the nearest float of v, as a double.
 inline double to_bf16_value(double v) {
   const float f = static_cast<float>(v);
@@ -114,7 +123,11 @@ inline double to_bf16_value(double v) {
   return static_cast<double>(r);
 }
 
-inline double operand(double v) { return g_round_operand ? to_bf16_value(v) : v; }
+// X of Eq. 4 as it enters the product: as it is, or rounded to bfloat16.
+inline double operand(double v, int round_operand) { return round_operand ? to_bf16_value(v) : v; }
+
+// Row of the time-major arrays that step tau of a layer's walk over L steps reads and writes.
+inline long time_of(long tau, long L, int reverse) { return reverse ? L - 1 - tau : tau; }
 
 // U[g][i][t] = sum_col W[g*d+i][col] * X[col][t]   (Eq. 4 for all three gates)
 // X is the [ncol x nt] block, column t contiguous in t for a fixed col.
@@ -136,15 +149,15 @@ void gate_block(const void* W, int wdt, int d, int ncol, const double* X,
 // One SRU layer over the whole sequence, T steps per block.
 // xin/hout: double [L x d]; c: double [d] in/out.
 void sru_layer(const void* W, int wdt, const float* bias, const double* xin,
-               double* hout, double* c, int d, long L, int T) {
+               double* hout, double* c, int d, long L, int T, int round_operand, int reverse) {
   std::vector<double> X(static_cast<size_t>(d) * T);
   std::vector<double> U(static_cast<size_t>(3) * d * T);
   for (long t0 = 0; t0 < L; t0 += T) {
     const int nt = static_cast<int>(L - t0 < T ? L - t0 : T);
-    // X = [x_{t0} ... x_{t0+nt-1}] as columns
+    // X = [x_{t0} ... x_{t0+nt-1}] as columns (t0, t count steps of the walk)
     for (int j = 0; j < d; ++j)
       for (int t = 0; t < nt; ++t)
-        X[static_cast<size_t>(j) * nt + t] = operand(xin[(t0 + t) * d + j]);
+        X[static_cast<size_t>(j) * nt + t] = operand(xin[time_of(t0 + t, L, reverse) * d + j], round_operand);
     gate_block(W, wdt, d, d, X.data(), nt, U.data());
     const double* Ux = U.data();
     const double* Uf = U.data() + static_cast<size_t>(d) * nt;
@@ -159,8 +172,8 @@ void sru_layer(const void* W, int wdt, const float* bias, const double* xin,
         const double f = sigma(Uf[static_cast<size_t>(i) * nt + t] + bf);
         const double r = sigma(Ur[static_cast<size_t>(i) * nt + t] + br);
         ci = f * ci + (1.0 - f) * xh;
-        const double xt = xin[(t0 + t) * d + i];
-        hout[(t0 + t) * d + i] = r * std::tanh(ci) + (1.0 - r) * xt;
+        const double xt = xin[time_of(t0 + t, L, reverse) * d + i];
+        hout[time_of(t0 + t, L, reverse) * d + i] = r * std::tanh(ci) + (1.0 - r) * xt;
       }
       c[i] = ci;
     }
@@ -170,13 +183,13 @@ void sru_layer(const void* W, int wdt, const float* bias, const double* xin,
 // One QRNN layer.  hist: double [(k-1) x d] in/out (lag j+1 at row j).
 void qrnn_layer(const void* W, int wdt, const float* bias, const double* xin,
                 double* hout, double* c, double* hist, int d, long L, int T,
-                int k) {
+                int k, int round_operand, int reverse) {
   const int ncol = k * d;
   std::vector<double> X(static_cast<size_t>(ncol) * T);
   std::vector<double> U(static_cast<size_t>(3) * d * T);
-  // input at absolute time s (s may be negative: taken from hist)
+  // input at step s of the walk (s may be negative: taken from hist)
   auto x_at = [&](long s, int m) -> double {
-    if (s >= 0) return xin[s * d + m];
+    if (s >= 0) return xin[time_of(s, L, reverse) * d + m];
     return hist[static_cast<size_t>(-s - 1) * d + m];
   };
   for (long t0 = 0; t0 < L; t0 += T) {
@@ -185,7 +198,7 @@ void qrnn_layer(const void* W, int wdt, const float* bias, const double* xin,
     for (int j = 0; j < k; ++j)
       for (int m = 0; m < d; ++m)
         for (int t = 0; t < nt; ++t)
-          X[(static_cast<size_t>(j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m));
+          X[(static_cast<size_t>(j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m), round_operand);
     gate_block(W, wdt, d, ncol, X.data(), nt, U.data());
     const double* Uz = U.data();
     const double* Uf = U.data() + static_cast<size_t>(d) * nt;
@@ -201,7 +214,7 @@ void qrnn_layer(const void* W, int wdt, const float* bias, const double* xin,
         const double f = sigma(Uf[static_cast<size_t>(i) * nt + t] + bf);
         const double o = sigma(Uo[static_cast<size_t>(i) * nt + t] + bo);
         ci = f * ci + (1.0 - f) * z;
-        hout[(t0 + t) * d + i] = o * std::tanh(ci);
+        hout[time_of(t0 + t, L, reverse) * d + i] = o * std::tanh(ci);
       }
       c[i] = ci;
     }
@@ -227,9 +240,6 @@ int oracle_num_threads(void) {
 #endif
 }
 
-// mode 0 (default): exact operands; 1: the block X of Eq. 4 is rounded to bfloat16 before the product.
-void oracle_set_operand_rounding(int mode) { g_round_operand = mode ? 1 : 0; }
-
 void oracle_set_num_threads(int n) {
 #ifdef _OPENMP
   if (n > 0) omp_set_num_threads(n);
@@ -243,11 +253,12 @@ void oracle_set_num_threads(int n) {
 // NULL; x: double [L x d] (fp32 inputs are widened exactly by the caller);
 // c_init: double [n_layers x d] or NULL; outputs double:
 // h [L x d] (top layer), c_final [n_layers x d], h_all optional
-// [n_layers x L x d] (every layer's output).  Returns 0, or 1 on bad arguments.
+// [n_layers x L x d] (every layer's output).  round_operand, reverse: see the
+// header of this file.  Returns 0, or 1 on bad arguments.
 int oracle_sru_forward(const void* const* W, const float* const* bias,
                        const double* x, const double* c_init, double* h,
                        double* c_final, double* h_all, int n_layers, int d,
-                       long L, int T, int wdt) {
+                       long L, int T, int wdt, int round_operand, int reverse) {
   if (!W || !c_final || n_layers < 1 || d < 1 || L < 0 || T < 1) return 1;
   if (L > 0 && (!x || !h)) return 1;
   if (wdt != WDT_F32 && wdt != WDT_BF16 && wdt != WDT_FP8) return 1;
@@ -259,7 +270,7 @@ int oracle_sru_forward(const void* const* W, const float* const* bias,
     for (int i = 0; i < d; ++i)
       c[i] = c_init ? c_init[static_cast<size_t>(l) * d + i] : 0.0;
     sru_layer(W[l], wdt, bias ? bias[l] : nullptr, cur.data(), nxt.data(),
-              c.data(), d, L, T);
+              c.data(), d, L, T, round_operand, reverse);
     std::memcpy(c_final + static_cast<size_t>(l) * d, c.data(), d * sizeof(double));
     if (h_all && n) std::memcpy(h_all + static_cast<size_t>(l) * n, nxt.data(), n * sizeof(double));
     cur.swap(nxt);
@@ -275,7 +286,7 @@ int oracle_qrnn_forward(const void* const* W, const float* const* bias,
                         const double* x, const double* c_init,
                         const double* xhist_init, double* h, double* c_final,
                         double* xhist_final, double* h_all, int n_layers,
-                        int d, long L, int T, int k, int wdt) {
+                        int d, long L, int T, int k, int wdt, int round_operand, int reverse) {
   if (!W || !c_final || n_layers < 1 || d < 1 || L < 0 || T < 1 || k < 1) return 1;
   if (L > 0 && (!x || !h)) return 1;
   if (wdt != WDT_F32 && wdt != WDT_BF16 && wdt != WDT_FP8) return 1;
@@ -290,7 +301,7 @@ int oracle_qrnn_forward(const void* const* W, const float* const* bias,
     if (xhist_init)
       for (size_t i = 0; i < nh; ++i) hist[i] = xhist_init[l * nh + i];
     qrnn_layer(W[l], wdt, bias ? bias[l] : nullptr, cur.data(), nxt.data(),
-               c.data(), hist.data(), d, L, T, k);
+               c.data(), hist.data(), d, L, T, k, round_operand, reverse);
     std::memcpy(c_final + static_cast<size_t>(l) * d, c.data(), d * sizeof(double));
     if (xhist_final && nh) std::memcpy(xhist_final + l * nh, hist.data(), nh * sizeof(double));
     if (h_all && n) std::memcpy(h_all + static_cast<size_t>(l) * n, nxt.data(), n * sizeof(double));

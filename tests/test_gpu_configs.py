@@ -117,11 +117,7 @@ def test_config5_first_layer_against_the_operand_rounding_oracle():
     W_dev = [to_dev(inp["W"][0])]
     W_packed = [ss.pack_weights(W_dev[0])]
     x_dev = to_dev(inp["x"])
-    oracle.set_operand_rounding(1)
-    try:
-        h_ref, c_ref, _ = oracle.qrnn_forward(inp["W"][:1], None, inp["x"], T=64, k=cfg.k)
-    finally:
-        oracle.set_operand_rounding(0)
+    h_ref, c_ref, _ = oracle.qrnn_forward(inp["W"][:1], None, inp["x"], T=64, k=cfg.k, round_operand=True)
     sh, sc = float(np.abs(h_ref).max()), float(np.abs(c_ref).max())
     for T in cfg.Ts:
         for layout, Wl, flags in (("row-major", W_dev, 0), ("packed", W_packed, ss.WEIGHTS_PACKED)):

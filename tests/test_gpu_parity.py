@@ -322,14 +322,10 @@ def _check_against_rounding_oracle(cell, W, b, x, c0, xh0, T, k, h, c):
     the fast exp/rcp, and the rare input that rounds to the neighbouring
     bfloat16 because the two sides' fp32 activations differ in the last place
     (each such flip moves a pre-activation by about |w||x| 2^-8, a few 1e-5)."""
-    oracle.set_operand_rounding(1)
-    try:
-        if cell == "sru":
-            h_ref, c_ref = oracle.sru_forward(W, b, x, c_init=c0, T=T)
-        else:
-            h_ref, c_ref, _ = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k)
-    finally:
-        oracle.set_operand_rounding(0)
+    if cell == "sru":
+        h_ref, c_ref = oracle.sru_forward(W, b, x, c_init=c0, T=T, round_operand=True)
+    else:
+        h_ref, c_ref, _ = oracle.qrnn_forward(W, b, x, c_init=c0, xhist_init=xh0, T=T, k=k, round_operand=True)
     assert _rel_err(h, h_ref) <= BF16_MATCHED_TOL, _rel_err(h, h_ref)
     assert _rel_err(c, c_ref) <= BF16_MATCHED_TOL, _rel_err(c, c_ref)
 

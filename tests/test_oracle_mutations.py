@@ -26,16 +26,23 @@ MUTATIONS = [
     ("sigmoid sign", "return 1.0 / (1.0 + std::exp(-z));", "return 1.0 / (1.0 + std::exp(z));"),
     ("weights read transposed (square case)", "const double w = weight_at(W, wdt, static_cast<size_t>(3) * d, ncol, row, col);",
      "const double w = ncol == d ? weight_at(W, wdt, static_cast<size_t>(3) * d, ncol, (row / d) * d + col, row % d) : weight_at(W, wdt, static_cast<size_t>(3) * d, ncol, row, col);"),
-    ("qrnn: lag blocks reversed", "X[(static_cast<size_t>(j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m));",
-     "X[(static_cast<size_t>(k - 1 - j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m));"),
-    ("qrnn: looks ahead instead of back", "= operand(x_at(t0 + t - j, m));", "= operand(x_at(t0 + t + j < L ? t0 + t + j : L - 1, m));"),
-    ("rounding mode: default rounds", "int g_round_operand = 0;", "int g_round_operand = 1;"),
+    ("qrnn: lag blocks reversed", "X[(static_cast<size_t>(j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m), round_operand);",
+     "X[(static_cast<size_t>(k - 1 - j) * d + m) * nt + t] = operand(x_at(t0 + t - j, m), round_operand);"),
+    ("qrnn: looks ahead instead of back", "= operand(x_at(t0 + t - j, m), round_operand);", "= operand(x_at(t0 + t + j < L ? t0 + t + j : L - 1, m), round_operand);"),
+    ("rounding mode: rounds when not asked to", "return round_operand ? to_bf16_value(v) : v;", "return to_bf16_value(v);"),
+    ("rounding mode: argument ignored", "return round_operand ? to_bf16_value(v) : v;", "return v;"),
+    ("reverse: direction ignored", "return reverse ? L - 1 - tau : tau;", "return tau;"),
+    ("reverse: off by one", "return reverse ? L - 1 - tau : tau;", "return reverse ? (tau == 0 ? L - 1 : L - tau) % L : tau;"),
+    ("reverse: sru output written in walk order", "hout[time_of(t0 + t, L, reverse) * d + i] = r * std::tanh(ci) + (1.0 - r) * xt;", "hout[(t0 + t) * d + i] = r * std::tanh(ci) + (1.0 - r) * xt;"),
+    ("reverse: sru highway term taken in walk order", "const double xt = xin[time_of(t0 + t, L, reverse) * d + i];", "const double xt = xin[(t0 + t) * d + i];"),
+    ("reverse: qrnn output written in walk order", "hout[time_of(t0 + t, L, reverse) * d + i] = o * std::tanh(ci);", "hout[(t0 + t) * d + i] = o * std::tanh(ci);"),
+    ("reverse: qrnn window read in time order", "if (s >= 0) return xin[time_of(s, L, reverse) * d + m];", "if (s >= 0) return xin[s * d + m];"),
     ("rounding mode: truncates instead of rounding to nearest even", "u = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;", "u = u & 0xFFFF0000u;"),
-    ("rounding mode: highway term rounded too", "const double xt = xin[(t0 + t) * d + i];", "const double xt = operand(xin[(t0 + t) * d + i]);"),
-    ("rounding mode: qrnn window not rounded", "= operand(x_at(t0 + t - j, m));", "= x_at(t0 + t - j, m);"),
+    ("rounding mode: highway term rounded too", "const double xt = xin[time_of(t0 + t, L, reverse) * d + i];", "const double xt = operand(xin[time_of(t0 + t, L, reverse) * d + i], round_operand);"),
+    ("rounding mode: qrnn window not rounded", "= operand(x_at(t0 + t - j, m), round_operand);", "= x_at(t0 + t - j, m);"),
     ("qrnn: candidate not squashed", "const double z = std::tanh(Uz[static_cast<size_t>(i) * nt + t] + bz);",
      "const double z = Uz[static_cast<size_t>(i) * nt + t] + bz;"),
-    ("qrnn: output without tanh", "hout[(t0 + t) * d + i] = o * std::tanh(ci);", "hout[(t0 + t) * d + i] = o * ci;"),
+    ("qrnn: output without tanh", "hout[time_of(t0 + t, L, reverse) * d + i] = o * std::tanh(ci);", "hout[time_of(t0 + t, L, reverse) * d + i] = o * ci;"),
     ("qrnn: history order reversed", "nh[static_cast<size_t>(j) * d + m] = x_at(L - 1 - j, m);",
      "nh[static_cast<size_t>(k - 2 - j) * d + m] = x_at(L - 1 - j, m);"),
     ("state not carried across blocks", "      c[i] = ci;\n    }\n  }\n}\n\n// One QRNN layer.", "    }\n  }\n}\n\n// One QRNN layer."),
@@ -73,6 +80,7 @@ BATTERY = [
     pins.test_linear_projection_against_numpy,
     pins.test_future_inputs_do_not_change_past_outputs,
     pins.test_operand_rounding_mode_rounds_only_the_matrix_operand,
+    pins.test_reverse_direction_is_the_forward_pass_over_the_reversed_sequence,
     pins.test_fp8_code_values_follow_the_format,
     pins.test_fp8_weights_equal_their_fp32_values_bitwise,
     pins.test_fp8_row_scales_are_applied_per_row,

@@ -517,59 +517,106 @@ def _bf16_round_numpy(a):
 
 
 def test_operand_rounding_mode_rounds_only_the_matrix_operand():
-    """oracle.set_operand_rounding(1): the block X of Eq. (4) enters the products
-    as bfloat16; the SRU highway term still uses the exact x_t.  Pinned by
+    """round_operand=True: the block X of Eq. (4) enters the products as
+    bfloat16; the SRU highway term still uses the exact x_t.  Pinned by
     (i) inputs that bfloat16 holds exactly: nothing changes, bit for bit;
     (ii) 1 + 2^-9, a quarter of a bfloat16 step above 1: the gates are those of
     x = 1 while the highway term keeps 1 + 2^-9; (iii) a random layer against
-    numpy products of explicitly rounded inputs."""
+    numpy products of explicitly rounded inputs.  The mode is an argument of
+    the call: a call without it rounds nothing, whatever ran before."""
     rng = _rng(77)
     d, L = 6, 9
     W, b = _rand_sru(rng, 1, d, 2.0)
-    try:
-        # (i)
-        x_exact = _bf16_round_numpy(rng.standard_normal((L, d)).astype(np.float32))
-        ref = oracle.sru_forward(W, b, x_exact, T=4)
-        oracle.set_operand_rounding(1)
-        got = oracle.sru_forward(W, b, x_exact, T=4)
-        np.testing.assert_array_equal(got[0], ref[0])
-        np.testing.assert_array_equal(got[1], ref[1])
-        # (ii) r = 1/2 exactly (W_r = 0, b_r = 0): h = tanh(c)/2 + x/2
-        W1 = [np.zeros((3, 1), np.float32)]
-        W1[0][0, 0] = 1.0                                   # candidate = x
-        xq = np.array([[1.0 + 2.0 ** -9]], np.float32)
-        h, c = oracle.sru_forward(W1, None, xq, T=1)        # f = 1/2: c = (rounded x) / 2
-        assert c[0, 0] == 0.5
-        assert h[0, 0] == 0.5 * math.tanh(0.5) + 0.5 * float(xq[0, 0])
-        oracle.set_operand_rounding(0)
-        h0, c0 = oracle.sru_forward(W1, None, xq, T=1)
-        assert c0[0, 0] == 0.5 * float(xq[0, 0])
-        # (iii)
-        x = rng.standard_normal((L, d)).astype(np.float32)
-        Xr = _bf16_round_numpy(x).astype(np.float64)
-        U = Xr @ W[0].astype(np.float64).T
-        f = _sigmoid(U[:, d:2 * d] + b[0][:d])
-        r = _sigmoid(U[:, 2 * d:] + b[0][d:])
-        cc = _recurrence_closed_form(f, U[:, :d], np.zeros(d))
-        h_expect = r * np.tanh(cc) + (1.0 - r) * x.astype(np.float64)
-        oracle.set_operand_rounding(1)
-        h, _ = oracle.sru_forward(W, b, x, T=3)
-        np.testing.assert_allclose(h, h_expect, rtol=1e-11, atol=1e-12)
-        # QRNN: window rows are rounded too
-        k = 2
-        Wq, bq = _rand_qrnn(rng, 1, d, k, 2.0)
-        xh0 = rng.standard_normal((1, k - 1, d)).astype(np.float32)
-        padded = np.concatenate([_bf16_round_numpy(xh0[0][::-1]).astype(np.float64), Xr], 0)
-        Wd = Wq[0].astype(np.float64)
-        U = np.zeros((L, 3 * d))
-        for j in range(k):
-            U += padded[k - 1 - j: k - 1 - j + L] @ Wd[:, j * d:(j + 1) * d].T
-        U += bq[0]
-        cc = _recurrence_closed_form(_sigmoid(U[:, d:2 * d]), np.tanh(U[:, :d]), np.zeros(d))
-        hq, _, _ = oracle.qrnn_forward(Wq, bq, x, xhist_init=xh0, T=4, k=k)
-        np.testing.assert_allclose(hq, _sigmoid(U[:, 2 * d:]) * np.tanh(cc), rtol=1e-11, atol=1e-12)
-    finally:
-        oracle.set_operand_rounding(0)
+    # (i)
+    x_exact = _bf16_round_numpy(rng.standard_normal((L, d)).astype(np.float32))
+    ref = oracle.sru_forward(W, b, x_exact, T=4)
+    got = oracle.sru_forward(W, b, x_exact, T=4, round_operand=True)
+    np.testing.assert_array_equal(got[0], ref[0])
+    np.testing.assert_array_equal(got[1], ref[1])
+    # (ii) r = 1/2 exactly (W_r = 0, b_r = 0): h = tanh(c)/2 + x/2
+    W1 = [np.zeros((3, 1), np.float32)]
+    W1[0][0, 0] = 1.0                                   # candidate = x
+    xq = np.array([[1.0 + 2.0 ** -9]], np.float32)
+    h, c = oracle.sru_forward(W1, None, xq, T=1, round_operand=True)        # f = 1/2: c = (rounded x) / 2
+    assert c[0, 0] == 0.5
+    assert h[0, 0] == 0.5 * math.tanh(0.5) + 0.5 * float(xq[0, 0])
+    h0, c0 = oracle.sru_forward(W1, None, xq, T=1)
+    assert c0[0, 0] == 0.5 * float(xq[0, 0])
+    # (iii)
+    x = rng.standard_normal((L, d)).astype(np.float32)
+    Xr = _bf16_round_numpy(x).astype(np.float64)
+    U = Xr @ W[0].astype(np.float64).T
+    f = _sigmoid(U[:, d:2 * d] + b[0][:d])
+    r = _sigmoid(U[:, 2 * d:] + b[0][d:])
+    cc = _recurrence_closed_form(f, U[:, :d], np.zeros(d))
+    h_expect = r * np.tanh(cc) + (1.0 - r) * x.astype(np.float64)
+    h, _ = oracle.sru_forward(W, b, x, T=3, round_operand=True)
+    np.testing.assert_allclose(h, h_expect, rtol=1e-11, atol=1e-12)
+    # QRNN: window rows are rounded too
+    k = 2
+    Wq, bq = _rand_qrnn(rng, 1, d, k, 2.0)
+    xh0 = rng.standard_normal((1, k - 1, d)).astype(np.float32)
+    padded = np.concatenate([_bf16_round_numpy(xh0[0][::-1]).astype(np.float64), Xr], 0)
+    Wd = Wq[0].astype(np.float64)
+    U = np.zeros((L, 3 * d))
+    for j in range(k):
+        U += padded[k - 1 - j: k - 1 - j + L] @ Wd[:, j * d:(j + 1) * d].T
+    U += bq[0]
+    cc = _recurrence_closed_form(_sigmoid(U[:, d:2 * d]), np.tanh(U[:, :d]), np.zeros(d))
+    hq, _, _ = oracle.qrnn_forward(Wq, bq, x, xhist_init=xh0, T=4, k=k, round_operand=True)
+    np.testing.assert_allclose(hq, _sigmoid(U[:, 2 * d:]) * np.tanh(cc), rtol=1e-11, atol=1e-12)
+
+
+def test_reverse_direction_is_the_forward_pass_over_the_reversed_sequence():
+    """reverse=True walks every layer from the last step to the first (Section 2.1:
+    the second direction of a bidirectional network is an independent pass).  Pins:
+    (i) bit for bit, reverse(x) = flip(forward(flip(x))), final state and window
+    included, for stacks, ragged blocks and given initial state / window;
+    (ii) against the step functions walked backwards by hand (they know nothing of
+    direction); (iii) h at the last time step depends on x at that step only."""
+    rng = _rng(91)
+    d, L, n_layers = 5, 11, 3
+    W, b = _rand_sru(rng, n_layers, d, 2.0)
+    x = rng.standard_normal((L, d)).astype(np.float32)
+    c0 = rng.standard_normal((n_layers, d)).astype(np.float32)
+    for T in (1, 4, 16):
+        h_r, c_r = oracle.sru_forward(W, b, x, c_init=c0, T=T, reverse=True)
+        h_f, c_f = oracle.sru_forward(W, b, x[::-1].copy(), c_init=c0, T=T)
+        np.testing.assert_array_equal(h_r, h_f[::-1])
+        np.testing.assert_array_equal(c_r, c_f)
+    # (ii) one SRU layer by hand, from the last step to the first
+    c = c0[0].astype(np.float64).copy()
+    h_hand = np.zeros((L, d))
+    for t in range(L - 1, -1, -1):
+        h_hand[t], c = oracle.sru_step(W[0], b[0], x[t], c)
+    h1, c1 = oracle.sru_forward(W[:1], b[:1], x, c_init=c0[:1], T=4, reverse=True)
+    np.testing.assert_array_equal(h1, h_hand)
+    np.testing.assert_array_equal(c1[0], c)
+    # (iii)
+    x2 = x.copy()
+    x2[:-1] += 1.0
+    h2, _ = oracle.sru_forward(W[:1], b[:1], x2, c_init=c0[:1], T=4, reverse=True)
+    np.testing.assert_array_equal(h2[-1], h1[-1])
+    assert not np.array_equal(h2[0], h1[0])
+    # QRNN, window of 3: the window of step t holds x_t, x_{t+1}, x_{t+2}; xhist_init are the inputs beyond the end
+    k = 3
+    Wq, bq = _rand_qrnn(rng, 2, d, k, 2.0)
+    xh0 = rng.standard_normal((2, k - 1, d)).astype(np.float32)
+    for T in (1, 3, 16):
+        h_r, c_r, xh_r = oracle.qrnn_forward(Wq, bq, x, c_init=c0[:2], xhist_init=xh0, T=T, k=k, reverse=True)
+        h_f, c_f, xh_f = oracle.qrnn_forward(Wq, bq, x[::-1].copy(), c_init=c0[:2], xhist_init=xh0, T=T, k=k)
+        np.testing.assert_array_equal(h_r, h_f[::-1])
+        np.testing.assert_array_equal(c_r, c_f)
+        np.testing.assert_array_equal(xh_r, xh_f)
+    c = c0[0].astype(np.float64).copy()
+    h_hand = np.zeros((L, d))
+    ext = np.concatenate([x.astype(np.float64), xh0[0].astype(np.float64)], 0)      # row L + j: the input j+1 steps beyond the end
+    for t in range(L - 1, -1, -1):
+        h_hand[t], c = oracle.qrnn_step(Wq[0], bq[0], ext[t:t + k], c, k)
+    h1, c1, xh1 = oracle.qrnn_forward(Wq[:1], bq[:1], x, c_init=c0[:1], xhist_init=xh0[:1], T=4, k=k, reverse=True)
+    np.testing.assert_array_equal(h1, h_hand)
+    np.testing.assert_array_equal(c1[0], c)
+    np.testing.assert_array_equal(xh1[0], x[:k - 1].astype(np.float64))              # lag j+1 of the walk's end = time j
 
 
 def test_edge_cases():
