@@ -82,7 +82,15 @@ enum {
      instead of 16 when the launch is wide enough. */
   SSRNN_OPT_NO_SPLIT = 1 << 9,   /* never split a layer's columns over workgroups               */
   SSRNN_OPT_ONE_TILE = 1 << 10,  /* always 16 features per workgroup                            */
-  SSRNN_OPT_MASK = 3 << 9
+  SSRNN_OPT_MASK = 3 << 9,
+  /* Direction (Section 2.1: a bidirectional network is two independent passes, one in each
+     direction; joining their outputs is the caller's).  Every layer walks the sequence from
+     its last step to its first: c_{t+1} takes the place of c_{t-1}, the QRNN window of step t
+     holds x_t, x_{t+1}, ..., c_init is the state before time L-1 is taken in, c_final the state
+     after time 0, xhist_init entry (l, j) layer l's input j+1 steps beyond time L-1, xhist_final
+     its inputs at times j.  x and h stay indexed by time.  The result equals the forward pass
+     over the time-reversed x, read backwards. */
+  SSRNN_REVERSE = 1 << 11
 };
 
 /* Library version, major*10000 + minor*100 + patch.  Host; never fails. */

@@ -19,6 +19,7 @@ SCHED_AUTO, SCHED_STAGES, SCHED_WAVEFRONT = 0, 1, 3
 KERNEL_AUTO, KERNEL_GENERIC, KERNEL_VALU, KERNEL_MFMA = 0, 1 << 4, 2 << 4, 3 << 4
 WEIGHTS_PACKED = 1 << 8
 OPT_NO_SPLIT, OPT_ONE_TILE = 1 << 9, 1 << 10
+REVERSE = 1 << 11
 
 # every symbol include/ssrnn.h declares, then those of include/ssrnn_probe.h (measurement aids)
 EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",

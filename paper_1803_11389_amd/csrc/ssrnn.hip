@@ -144,14 +144,14 @@ __global__ void init_state_kernel(const float* c_init, float* c, long n) {
   if (i < n) c[i] = c_init ? c_init[i] : 0.0f;
 }
 
-// xhist_final[l][j][m] = layer l's input at time L-1-j.  Layer 0 reads x (and
+// xhist_final[l][j][m] = layer l's input at step L-1-j of the walk over the sequence.  Layer 0 reads x (and
 // xhist_init for times before 0); layer l > 0 reads the hand-off buffer behind
 // layer l-1, whose rows end with the last block.  One thread per (l, m), lags
 // in descending order so that an aliased xhist_init is read before it is
 // overwritten.
 __global__ void gather_history_kernel(const float* x, const float* xhist_init, float* xhist_final,
                                       const char* act0, size_t act_stride, int ld, int n_layers, int d,
-                                      int k, long L, int nt_last) {
+                                      int k, long L, int nt_last, int reverse) {
   const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
   if (id >= static_cast<long>(n_layers) * d) return;
   const int l = static_cast<int>(id / d);
@@ -160,8 +160,8 @@ __global__ void gather_history_kernel(const float* x, const float* xhist_init, f
   for (int j = k - 2; j >= 0; --j) {
     float v;
     if (l == 0) {
-      const long s = L - 1 - j;
-      if (s >= 0) v = x[s * d + m];
+      const long s = L - 1 - j;                            // step of the walk; its row of x depends on the direction
+      if (s >= 0) v = x[(reverse ? L - 1 - s : s) * d + m];
       else v = xhist_init ? xhist_init[(-s - 1) * d + m] : 0.0f;
     } else {
       const float* a = reinterpret_cast<const float*>(act0 + static_cast<size_t>(2 * l) * act_stride);   // act0: parity of the last block
@@ -171,19 +171,20 @@ __global__ void gather_history_kernel(const float* x, const float* xhist_init, f
   }
 }
 
-// Rows -(k-1) .. nt-1 of layer 0's input for the block that starts at time t0,
-// gathered from x (times >= 0) and xhist_init / zeros (times < 0), as fp32 rows
+// Rows -(k-1) .. nt-1 of layer 0's input for the block that starts at step t0 of
+// the walk over the sequence (step s is time s, or time L-1-s in reverse),
+// gathered from x (steps >= 0) and xhist_init / zeros (steps < 0), as fp32 rows
 // and optionally as an operand copy.  dst / dst_op point at row 0 of their buffers.
 __global__ void stage_input_kernel(const float* x, const float* xhist_init, float* dst, void* dst_op, int ldt,
-                                   int op_bf16, int ld, int d, int k, long t0, int nt) {
+                                   int op_bf16, int ld, int d, int k, long t0, int nt, long L, int reverse) {
   const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
   const long n = static_cast<long>(k - 1 + nt) * d;
   if (id >= n) return;
   const long r = id / d - (k - 1);
   const int m = static_cast<int>(id % d);
-  const long sabs = t0 + r;
+  const long sabs = t0 + r;                                // step of the walk
   float v;
-  if (sabs >= 0) v = x[sabs * d + m];
+  if (sabs >= 0) v = x[(reverse ? L - 1 - sabs : sabs) * d + m];
   else v = xhist_init ? xhist_init[(-sabs - 1) * d + m] : 0.0f;
   dst[r * ld + m] = v;
   if (dst_op) store_operand(dst_op, ldt, op_bf16, static_cast<int>(r), m, v);
@@ -193,13 +194,13 @@ __global__ void stage_input_kernel(const float* x, const float* xhist_init, floa
 // thread moves 8 consecutive columns of one row (blockIdx.y = row + k-1) with
 // 16-byte accesses: two row-major stores and one (bf16) or two (fp32) operand chunks.
 __global__ void stage_input_vec_kernel(const float* x, const float* xhist_init, float* dst, void* dst_op, int ldt,
-                                       int op_bf16, int ld, int d, int k, long t0) {
+                                       int op_bf16, int ld, int d, int k, long t0, long L, int reverse) {
   const int m = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
   if (m >= d) return;
   const int r = static_cast<int>(blockIdx.y) - (k - 1);
   const long sabs = t0 + r;
   float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
-  const float* src = sabs >= 0 ? x + sabs * d + m : (xhist_init ? xhist_init + (-sabs - 1) * d + m : nullptr);
+  const float* src = sabs >= 0 ? x + (reverse ? L - 1 - sabs : sabs) * d + m : (xhist_init ? xhist_init + (-sabs - 1) * d + m : nullptr);
   if (src) {
     v0 = *reinterpret_cast<const float4*>(src);
     v1 = *reinterpret_cast<const float4*>(src + 4);
@@ -433,7 +434,8 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   const int kforce = flags & SSRNN_KERNEL_MASK;
   const bool packed = (flags & SSRNN_WEIGHTS_PACKED) != 0;
   const int opts = flags & SSRNN_OPT_MASK;
-  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED | SSRNN_OPT_MASK)) != 0 ||
+  const int reverse = (flags & SSRNN_REVERSE) ? 1 : 0;
+  if ((flags & ~(SSRNN_SCHED_MASK | SSRNN_KERNEL_MASK | SSRNN_WEIGHTS_PACKED | SSRNN_OPT_MASK | SSRNN_REVERSE)) != 0 ||
       (sched != SSRNN_SCHED_AUTO && sched != SSRNN_SCHED_STAGES && sched != SSRNN_SCHED_WAVEFRONT))
     return fail(SSRNN_EINVAL, "%s: unknown flags 0x%x", name, flags);
   if (packed && kforce != SSRNN_KERNEL_AUTO && kforce != SSRNN_KERNEL_MFMA)
@@ -542,11 +544,11 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
       const int per_row = d / 8;
       const int bx = per_row < 256 ? (per_row + 63) / 64 * 64 : 256;
       hipLaunchKernelGGL(stage_input_vec_kernel, dim3((per_row + bx - 1) / bx, k - 1 + nt), dim3(bx), 0, st, x,
-                         xhist_init, act(0, b), use_op ? opbuf(0, b) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0);
+                         xhist_init, act(0, b), use_op ? opbuf(0, b) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, L, reverse);
     } else {
       const long n = static_cast<long>(k - 1 + nt) * d;
       hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0, b),
-                         use_op ? opbuf(0, b) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, nt);
+                         use_op ? opbuf(0, b) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, nt, L, reverse);
     }
   };
 
@@ -557,19 +559,20 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
     s.W = W[l];
     s.wscale = (wdt == SSRNN_FP8) ? reinterpret_cast<const float*>(static_cast<const char*>(W[l]) + fp8_scale_offset(d, k)) : nullptr;
     s.bias = (bias && bias[l]) ? bias[l] : nullptr;
+    // rows of x and h are times; a stage's rows are steps of the walk, which in reverse run against time
     if (l == 0 && !stage_in) {
-      s.xcur = x + t0 * d;
+      s.xcur = x + (reverse ? L - 1 - t0 : t0) * d;
       s.xop = nullptr;
-      s.ldx = d;
+      s.ldx = reverse ? -d : d;
     } else {
       s.xcur = act(l, b);
       s.xop = use_op ? opbuf(l, b) : nullptr;
       s.ldx = wl.ld;
     }
     if (l == n_layers - 1) {
-      s.hout = h + t0 * d;
+      s.hout = h + (reverse ? L - 1 - t0 : t0) * d;
       s.hop = nullptr;
-      s.ldh = d;
+      s.ldh = reverse ? -d : d;
       s.hist_mode = 0;
     } else {
       s.hout = act(l + 1, b);
@@ -624,7 +627,7 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   }
   if (xhist_final && k > 1)
     hipLaunchKernelGGL(gather_history_kernel, dim3((nstate + 255) / 256), dim3(256), 0, st, x, xhist_init, xhist_final,
-                       act0 + static_cast<size_t>((nblocks - 1) & 1) * wl.act_stride, wl.act_stride, wl.ld, n_layers, d, k, L, nt_last);
+                       act0 + static_cast<size_t>((nblocks - 1) & 1) * wl.act_stride, wl.act_stride, wl.ld, n_layers, d, k, L, nt_last, reverse);
   HIP_TRY(hipGetLastError());
   return SSRNN_OK;
 }

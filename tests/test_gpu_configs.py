@@ -191,3 +191,58 @@ def test_config5_full_length_properties():
     cfg = wl.CONFIGS[4]
     h = _full_length(cfg, [64, 16, 256, -16, -64, -256], 80, 2e-2, True)
     assert float(h.abs().max()) < 1.0        # QRNN: h = o * tanh(c), 0 < o < 1
+
+
+# ---- the whole sequence of the two wide configurations against the oracle, at one block size each, in the
+# launch configuration bench.py times (default schedule).  The oracle takes the sequence in chunks (its
+# result does not depend on the chunking: a pin) so that progress is reported while it runs.
+
+def _full_length_against_oracle(cfg, T, packed, tol, relative, capsys, chunk=256):
+    import time
+    import torch
+    import paper_1803_11389_amd as ss
+    inp = wl.make_inputs(cfg)
+    W_dev = [to_dev(w) for w in inp["W"]]
+    if packed:
+        W_dev = [ss.pack_weights(w) for w in W_dev]
+    x_dev = to_dev(inp["x"])
+    flags = ss.WEIGHTS_PACKED if packed else 0
+    if cfg.cell == "sru":
+        h, c = ss.sru_forward(W_dev, None, x_dev, None, T=T, flags=flags)
+    else:
+        h, c, _ = ss.qrnn_forward(W_dev, None, x_dev, None, None, T=T, k=cfg.k, flags=flags)
+    torch.cuda.synchronize()
+    h, c = h.cpu().numpy(), c.cpu().numpy()
+    assert np.all(np.isfinite(h)) and np.all(np.isfinite(c))
+    del W_dev, x_dev
+    c_ref, xh_ref = None, None
+    err_h, max_h, t0 = 0.0, 0.0, time.time()
+    for s in range(0, cfg.L, chunk):
+        e = min(cfg.L, s + chunk)
+        if cfg.cell == "sru":
+            h_ref, c_ref = oracle.sru_forward(inp["W"], None, inp["x"][s:e], c_init=c_ref, T=64)
+        else:
+            h_ref, c_ref, xh_ref = oracle.qrnn_forward(inp["W"], None, inp["x"][s:e], c_init=c_ref, xhist_init=xh_ref, T=64, k=cfg.k)
+        err_h = max(err_h, max_abs(h[s:e], h_ref))
+        max_h = max(max_h, float(np.abs(h_ref).max()))
+        with capsys.disabled():
+            print(f"  {cfg.name} T={T}: oracle through step {e} of {cfg.L}, {time.time() - t0:.0f} s, max |delta h| so far {err_h:.3e}", flush=True)
+    err_c = max_abs(c, c_ref)
+    if relative:
+        err_h, err_c = err_h / max(max_h, 1e-6), err_c / max(float(np.abs(c_ref).max()), 1e-6)
+    with capsys.disabled():
+        print(f"  {cfg.name} full L={cfg.L} T={T} {'packed' if packed else 'row-major'}: err h {err_h:.3e} c_final {err_c:.3e}", flush=True)
+    assert err_h <= tol and err_c <= tol, (err_h, err_c)
+
+
+@pytest.mark.timeout(900)
+def test_config4_whole_sequence_against_the_oracle(capsys):
+    """C4, all 2048 steps and the final state at the headline block size, fp32 bar."""
+    _full_length_against_oracle(wl.CONFIGS[3], 4, False, 1e-4, False, capsys)
+
+
+@pytest.mark.timeout(1500)
+def test_config5_whole_sequence_against_the_oracle(capsys):
+    """C5, all 4096 steps and the final state at T = 64 with packed weights (the 64-features-per-workgroup
+    matrix-core kernel in every full launch), bf16 bar."""
+    _full_length_against_oracle(wl.CONFIGS[4], 64, True, 2e-2, True, capsys)
