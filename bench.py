@@ -87,6 +87,10 @@ def parse_args():
     ap.add_argument("--T", type=int, default=4, help="block size of the headline number")
     ap.add_argument("--no-sweep", action="store_true", help="skip the other block sizes and the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time nothing but the headline configuration (no sweep, no second schedule, no read probe, no CPU "
+                         "baseline): the form the rocprofv3 summaries under profiles/ are made with, so that the kernel "
+                         "statistics hold launches of one kind")
     ap.add_argument("--flags", type=int, default=0, help="ssrnn flags (schedule / kernel override)")
     ap.add_argument("--packed", action="store_true",
                     help="pre-pack the weights (ssrnn_pack_weights, outside the timed region) and run every block size on the matrix-core kernel")
@@ -273,6 +277,8 @@ def main():
         return
     ss.load_library()
     index_rows = profile_index()
+    if args.headline_only:
+        args.no_sweep = args.no_cpu = True
 
     t_gen = time.perf_counter()
     wdt_is_fp8 = cfg.wdtype == "fp8"
@@ -293,7 +299,7 @@ def main():
 
     # ---- the same block size with one launch per stage in streaming order (no look-ahead)
     roofline_streaming = None
-    if sched == 0 and roofline["schedule"] == "wavefront":
+    if sched == 0 and roofline["schedule"] == "wavefront" and not args.headline_only:
         _, ev_s = stack.time_block(args.T, max(2, args.steps // 2), 1, args.flags | ss.SCHED_STAGES, args.packed)
         roofline_streaming = roofline_block(stack, args.T, ev_s, args.flags | ss.SCHED_STAGES, args.packed, index_rows)
 
@@ -318,9 +324,10 @@ def main():
     # ---- what a kernel that only reads reaches, in launches of the stage launches' shape and size: eight
     # layers per launch (the wavefront schedule's launches) and one layer per launch (the per-stage schedule's)
     probe_bufs = [w.buf if wdt_is_fp8 else w for w in stack.W]
-    probe = {"wavefront_shaped": read_probe_rate(ss, torch, probe_bufs, min(8, len(probe_bufs))),
-             "per_stage_shaped": read_probe_rate(ss, torch, probe_bufs, 1)}
-    if roofline["bound"] == "hbm":
+    probe = None if args.headline_only else {
+        "wavefront_shaped": read_probe_rate(ss, torch, probe_bufs, min(8, len(probe_bufs))),
+        "per_stage_shaped": read_probe_rate(ss, torch, probe_bufs, 1)}
+    if probe and roofline["bound"] == "hbm":
         key = "wavefront_shaped" if roofline["schedule"] == "wavefront" else "per_stage_shaped"
         roofline["read_probe_GBps"] = probe[key]["GBps"]
         roofline["frac_of_read_probe"] = round(roofline["achieved"] / probe[key]["GBps"], 4)

@@ -316,8 +316,9 @@ bool plan_valu(Plan& p, const void* const* W, const float* x, const float* xhist
   // (d >= 4096) with short blocks take more, smaller workgroups instead, which lets the hardware's
   // dispatcher even out the workgroups' unequal memory rates (measured at d = 4096, us per stage, one launch
   // per stage: T = 4, 1024 workgroups 32.1, 512 32.3, 256 32.8, 2048 33.7; T = 1, 2048 workgroups of one work
-  // item 31.4 against 32.5 with 512).
-  int wg_target = (p.d < 4096 || p.tt > 8) ? 256 : (p.tt <= 2 ? 2048 : p.tt <= 4 ? 1024 : 512);
+  // item 31.4 against 32.5 with 512; launches that hold eight stages: T = 4, 512 workgroups per stage 29.0,
+  // 1024 30.2).
+  int wg_target = (p.d < 4096 || p.tt > 8) ? 256 : (p.tt <= 2 ? 2048 : (p.tt <= 4 && p.concurrent <= 1) ? 1024 : 512);
   if (p.wdt == SSRNN_BF16 && wg_target > 256) wg_target /= 2;   // half the bytes per feature: twice the features
   if (p.wdt == SSRNN_FP8 && wg_target > 256) wg_target = wg_target / 4 > 256 ? wg_target / 4 : 256;
   int F = 0;
@@ -474,8 +475,15 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   // (fp32, T <= 16), except that from T = 5 on a layer wide enough to give the matrix-core kernel one
   // workgroup per CU (d >= 4096) goes there (measured at d = 4096: 34.8 us per stage against 36.3 at
   // T = 8 and 40.0 at T = 16); the matrix-core kernel for everything else it takes; the generic kernel last.
+  auto stages_per_launch = [&](int t) {
+    const long nb = (L + t - 1) / t;
+    const bool wf = sched == SSRNN_SCHED_WAVEFRONT || (sched == SSRNN_SCHED_AUTO && n_layers > 1 && nb > 1);
+    const long width = nb < n_layers ? nb : n_layers;
+    return wf ? static_cast<int>(width < MAX_BATCH_STAGES ? width : MAX_BATCH_STAGES) : 1;
+  };
   bool valu_ok = false;
   if (!packed && (kforce == SSRNN_KERNEL_AUTO || kforce == SSRNN_KERNEL_VALU)) {
+    p.concurrent = stages_per_launch(T);
     valu_ok = plan_valu(p, W, x, xhist_init, workspace);
     if (!valu_ok && kforce == SSRNN_KERNEL_VALU)
       return fail(SSRNN_EUNSUPPORTED, "%s: vector-ALU kernel needs T <= 16 and d %% 256 == 0 (fp32 weights) or T <= 8 and d %% 512 == 0 (bf16) or d %% 1024 == 0 (8-bit), and 16-byte aligned buffers", name);
@@ -484,12 +492,6 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   // (17.1 against 18.4 us per stage at d = 4096, T = 1); beyond that its conversions and FMAs no longer hide
   // fp32, narrow layers: when a launch holds enough stages to give every CU an unsplit matrix-core
   // workgroup, that kernel wins from T = 9 on (d = 1024, k = 2, T = 16: 5.6 against 6.8 us per stage)
-  auto stages_per_launch = [&](int t) {
-    const long nb = (L + t - 1) / t;
-    const bool wf = sched == SSRNN_SCHED_WAVEFRONT || (sched == SSRNN_SCHED_AUTO && n_layers > 1 && nb > 1);
-    const long width = nb < n_layers ? nb : n_layers;
-    return wf ? static_cast<int>(width < MAX_BATCH_STAGES ? width : MAX_BATCH_STAGES) : 1;
-  };
   const bool prefer_mfma = kforce == SSRNN_KERNEL_AUTO &&
                            (wdt != SSRNN_F32 ? T > 2
                                              : (T > 4 && d / MFMA_F >= 256) ||
