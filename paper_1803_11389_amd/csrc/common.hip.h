@@ -58,11 +58,39 @@ struct Stage {
   int tp;                  // steps per feature row of upart
 };
 
+// Layer 0's input rows -(k-1) .. nt-1 of the block that starts at step t0 of the
+// walk over the sequence (step s is time s, or time L-1-s in reverse), gathered
+// from x (steps >= 0) and xhist_init / zeros (steps < 0) into the block's fp32
+// hand-off rows and, when dst_op is set, its operand copy.  dst / dst_op point
+// at row 0 of their buffers.  dst null: nothing to stage.
+struct StageIn {
+  const float* x;
+  const float* xhist_init;
+  float* dst;
+  void* dst_op;
+  long t0;
+  long L;
+  int nt;
+  int ldt;
+  int op_bf16;
+  int ld;
+  int d;
+  int k;
+  int reverse;
+  int vec;                 // d % 8 == 0 and 16-byte aligned buffers: 8 columns per thread with 16-byte accesses
+};
+
 // Stages that do not depend on each other -- (block b, layer l) pairs with the
-// same b + l -- go into one launch: blockIdx.y picks the stage.
+// same b + l -- go into one launch: blockIdx.y picks the stage.  A launch may
+// carry one more row of workgroups in front of them (in.dst set: blockIdx.y == 0
+// stages, blockIdx.y - 1 picks the stage) that copies layer 0's input of a later
+// block, which nothing in the launch reads or writes, so that the copy costs no
+// launch of its own; it goes first so that it is not the launch's tail.
 constexpr int MAX_BATCH_STAGES = 8;
 struct StageBatch {
   Stage s[MAX_BATCH_STAGES];
+  StageIn in;
+  int n;
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
@@ -114,6 +142,56 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 __device__ __forceinline__ void store_operand(void* op, int ldt, int op_bf16, int r, int i, float v) {
   if (op_bf16) static_cast<uint16_t*>(op)[(static_cast<long>(i >> 3) * ldt + r) * 8 + (i & 7)] = f32_to_bf16_rne(v);
   else static_cast<float*>(op)[(static_cast<long>(i >> 2) * ldt + r) * 4 + (i & 3)] = v;
+}
+
+// The rows of a StageIn, spread over the gridDim.x workgroups of one row of a launch.
+__device__ __forceinline__ void stage_input_rows(const StageIn& in) {
+  const long nthreads = static_cast<long>(gridDim.x) * blockDim.x;
+  const long tid = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (in.vec) {
+    const int per_row = in.d >> 3;
+    const long n = static_cast<long>(in.k - 1 + in.nt) * per_row;
+    for (long id = tid; id < n; id += nthreads) {
+      const int r = static_cast<int>(id / per_row) - (in.k - 1);
+      const int m = static_cast<int>(id % per_row) * 8;
+      const long sabs = in.t0 + r;                           // step of the walk
+      float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+      const float* src = sabs >= 0 ? in.x + (in.reverse ? in.L - 1 - sabs : sabs) * in.d + m
+                                   : (in.xhist_init ? in.xhist_init + (-sabs - 1) * in.d + m : nullptr);
+      if (src) {
+        v0 = *reinterpret_cast<const float4*>(src);
+        v1 = *reinterpret_cast<const float4*>(src + 4);
+      }
+      float* out = in.dst + static_cast<long>(r) * in.ld + m;
+      *reinterpret_cast<float4*>(out) = v0;
+      *reinterpret_cast<float4*>(out + 4) = v1;
+      if (!in.dst_op) continue;
+      if (in.op_bf16) {
+        uint4 pk;
+        pk.x = f32_to_bf16_rne(v0.x) | (static_cast<uint32_t>(f32_to_bf16_rne(v0.y)) << 16);
+        pk.y = f32_to_bf16_rne(v0.z) | (static_cast<uint32_t>(f32_to_bf16_rne(v0.w)) << 16);
+        pk.z = f32_to_bf16_rne(v1.x) | (static_cast<uint32_t>(f32_to_bf16_rne(v1.y)) << 16);
+        pk.w = f32_to_bf16_rne(v1.z) | (static_cast<uint32_t>(f32_to_bf16_rne(v1.w)) << 16);
+        *reinterpret_cast<uint4*>(static_cast<char*>(in.dst_op) + (static_cast<long>(m >> 3) * in.ldt + r) * 16) = pk;
+      } else {
+        char* o = static_cast<char*>(in.dst_op) + (static_cast<long>(m >> 2) * in.ldt + r) * 16;
+        *reinterpret_cast<float4*>(o) = v0;
+        *reinterpret_cast<float4*>(o + static_cast<long>(in.ldt) * 16) = v1;
+      }
+    }
+  } else {
+    const long n = static_cast<long>(in.k - 1 + in.nt) * in.d;
+    for (long id = tid; id < n; id += nthreads) {
+      const long r = id / in.d - (in.k - 1);
+      const int m = static_cast<int>(id % in.d);
+      const long sabs = in.t0 + r;
+      float v;
+      if (sabs >= 0) v = in.x[(in.reverse ? in.L - 1 - sabs : sabs) * in.d + m];
+      else v = in.xhist_init ? in.xhist_init[(-sabs - 1) * in.d + m] : 0.0f;
+      in.dst[r * in.ld + m] = v;
+      if (in.dst_op) store_operand(in.dst_op, in.ldt, in.op_bf16, static_cast<int>(r), m, v);
+    }
+  }
 }
 
 // Workgroup barrier that orders LDS traffic only: vector-memory requests of the

@@ -43,6 +43,9 @@ struct Plan {
 
 constexpr int KSPLIT_MAX = 8;
 
+// Rows of workgroups of a stage launch: one per stage, and one more when the batch carries input rows to stage.
+inline unsigned launch_rows(const StageBatch& s, int nstage) { return static_cast<unsigned>(nstage) + (s.in.dst ? 1u : 0u); }
+
 // One launch for nstage <= MAX_BATCH_STAGES stages that do not depend on each other (blockIdx.y = stage).
 int launch_valu(const Plan& p, const StageBatch& s, int nstage, hipStream_t st);
 int launch_generic(const Plan& p, const StageBatch& s, int nstage, hipStream_t st);

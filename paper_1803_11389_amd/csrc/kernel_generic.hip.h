@@ -22,7 +22,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 template <int CELL, int WT>
 __global__ __launch_bounds__(GENERIC_WAVES * 64) void stage_generic_kernel(const StageBatch batch, int d, int k) {
-  const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
+  if (batch.in.dst && blockIdx.y == 0) { stage_input_rows(batch.in); return; }   // the launch's staging row
+  const Stage s = batch.s[blockIdx.y - (batch.in.dst ? 1 : 0)];   // independent stages share a launch
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int ncol = k * d;

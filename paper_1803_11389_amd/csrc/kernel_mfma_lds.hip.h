@@ -37,7 +37,8 @@ struct MfmaLdsCfg {
 // to overlap (d = 1024, T = 16, four stages per launch: 3.5 against 3.8 us per stage).
 template <int CELL, int WT, int NT, int NW_ = MfmaCfg<NT>::NW>
 __global__ __launch_bounds__(NW_ * 64) void stage_mfma_lds_kernel(const StageBatch batch, int d, int k) {
-  const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
+  if (batch.in.dst && blockIdx.y == 0) { stage_input_rows(batch.in); return; }   // the launch's staging row
+  const Stage s = batch.s[blockIdx.y - (batch.in.dst ? 1 : 0)];   // independent stages share a launch
   constexpr int NW = NW_;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int KSTEP = (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row

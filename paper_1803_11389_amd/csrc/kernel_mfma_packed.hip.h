@@ -61,7 +61,8 @@ __device__ __forceinline__ bf16x8_t fp8x8_to_bf16(uint32_t w0, uint32_t w1) {
 template <int CELL, int WT, int NT, int FT = 1>
 __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kernel(const StageBatch batch, int d, int k) {
   static_assert(FT == 1 || FT == 2, "one or two feature tiles per workgroup");
-  const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
+  if (batch.in.dst && blockIdx.y == 0) { stage_input_rows(batch.in); return; }   // the launch's staging row
+  const Stage s = batch.s[blockIdx.y - (batch.in.dst ? 1 : 0)];   // independent stages share a launch
   constexpr int NW = MfmaPkCfg<NT, WT>::NW;
   constexpr int NTC = MfmaCfg<NT>::NTC;
   constexpr int KSTEP = (WT == W_FP8) ? 128 : (WT == W_BF16) ? 64 : 32;    // columns per k-step: 128 bytes of every row

@@ -110,11 +110,12 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
   // (d = 4096, k = 2, us per stage, plain against by die: T = 64 32.5 / 33.2, T = 128 36.6 / 37.1, T = 256
   // 55.2 / 54.2; fp32, T = 32: 33.8 / 33.5).
   constexpr bool BY_DIE = NT >= 16 || WT == W_F32;
-  int stage_no = blockIdx.y, group_no = blockIdx.x;
+  if (batch.in.dst && blockIdx.y == 0) { stage_input_rows(batch.in); return; }   // the launch's staging row
+  int stage_no = blockIdx.y - (batch.in.dst ? 1 : 0), group_no = blockIdx.x;
   if constexpr (BY_DIE) {
-    const int total = gridDim.x * gridDim.y;
+    const int total = gridDim.x * batch.n;
     if (total % 8 == 0) {
-      const int p = blockIdx.y * gridDim.x + blockIdx.x;   // launch order
+      const int p = stage_no * gridDim.x + blockIdx.x;     // launch order among the stage workgroups
       const int q = (p % 8) * (total / 8) + p / 8;
       stage_no = q / gridDim.x;
       group_no = q - stage_no * gridDim.x;

@@ -128,7 +128,8 @@ __device__ __forceinline__ int butterfly_index(int lane) {
 // block and every product stay fp32.
 template <int CELL, int WT, int TT, int NV, bool MP>
 __global__ __launch_bounds__(VALU_MAX_WAVES * 64) void stage_valu_kernel(const StageBatch batch, int d, int k, int F, int npass_arg) {
-  const Stage s = batch.s[blockIdx.y];   // independent stages share a launch
+  if (batch.in.dst && blockIdx.y == 0) { stage_input_rows(batch.in); return; }   // the launch's staging row
+  const Stage s = batch.s[blockIdx.y - (batch.in.dst ? 1 : 0)];   // independent stages share a launch
   const int npass = MP ? npass_arg : 1;
   constexpr int CPL = (WT == W_FP8) ? 16 : (WT == W_BF16) ? 8 : 4;     // columns per lane per 16-byte load
   constexpr int CHW = 64 * CPL;                   // columns per wave-wide load

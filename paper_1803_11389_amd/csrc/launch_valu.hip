@@ -9,7 +9,7 @@ int valu_max_t() { return VALU_MAX_T; }
 
 template <int CELL>
 static int launch_valu_cell(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
-  const dim3 grid(p.grid, nstage), block(p.nw * 64);
+  const dim3 grid(p.grid, launch_rows(s, nstage)), block(p.nw * 64);
   const size_t lds = static_cast<size_t>(p.nw) * 3 * p.F * p.tt * sizeof(float);
 #define SSRNN_VALU_CASE(TT_, NV_)                                                          \
   if (p.tt == TT_ && p.nv == NV_) {                                                        \

@@ -49,7 +49,7 @@ int fail(int code, const char* fmt, ...) {
 namespace ssrnn {
 int launch_generic(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
   const int grid = (p.d + GENERIC_WAVES - 1) / GENERIC_WAVES;
-  const dim3 g(grid < 4096 ? grid : 4096, nstage), b(GENERIC_WAVES * 64);
+  const dim3 g(grid < 4096 ? grid : 4096, launch_rows(s, nstage)), b(GENERIC_WAVES * 64);
 #define SSRNN_GENERIC_CASE(CELL_)                                                          \
   if (p.wdt == SSRNN_FP8) hipLaunchKernelGGL((stage_generic_kernel<CELL_, W_FP8>), g, b, 0, st, s, p.d, p.k);   \
   else if (p.wdt == SSRNN_BF16) hipLaunchKernelGGL((stage_generic_kernel<CELL_, W_BF16>), g, b, 0, st, s, p.d, p.k); \
@@ -171,57 +171,9 @@ __global__ void gather_history_kernel(const float* x, const float* xhist_init, f
   }
 }
 
-// Rows -(k-1) .. nt-1 of layer 0's input for the block that starts at step t0 of
-// the walk over the sequence (step s is time s, or time L-1-s in reverse),
-// gathered from x (steps >= 0) and xhist_init / zeros (steps < 0), as fp32 rows
-// and optionally as an operand copy.  dst / dst_op point at row 0 of their buffers.
-__global__ void stage_input_kernel(const float* x, const float* xhist_init, float* dst, void* dst_op, int ldt,
-                                   int op_bf16, int ld, int d, int k, long t0, int nt, long L, int reverse) {
-  const long id = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
-  const long n = static_cast<long>(k - 1 + nt) * d;
-  if (id >= n) return;
-  const long r = id / d - (k - 1);
-  const int m = static_cast<int>(id % d);
-  const long sabs = t0 + r;                                // step of the walk
-  float v;
-  if (sabs >= 0) v = x[(reverse ? L - 1 - sabs : sabs) * d + m];
-  else v = xhist_init ? xhist_init[(-sabs - 1) * d + m] : 0.0f;
-  dst[r * ld + m] = v;
-  if (dst_op) store_operand(dst_op, ldt, op_bf16, static_cast<int>(r), m, v);
-}
-
-// Same rows for widths that are multiples of 8 and 16-byte aligned buffers: a
-// thread moves 8 consecutive columns of one row (blockIdx.y = row + k-1) with
-// 16-byte accesses: two row-major stores and one (bf16) or two (fp32) operand chunks.
-__global__ void stage_input_vec_kernel(const float* x, const float* xhist_init, float* dst, void* dst_op, int ldt,
-                                       int op_bf16, int ld, int d, int k, long t0, long L, int reverse) {
-  const int m = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
-  if (m >= d) return;
-  const int r = static_cast<int>(blockIdx.y) - (k - 1);
-  const long sabs = t0 + r;
-  float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
-  const float* src = sabs >= 0 ? x + (reverse ? L - 1 - sabs : sabs) * d + m : (xhist_init ? xhist_init + (-sabs - 1) * d + m : nullptr);
-  if (src) {
-    v0 = *reinterpret_cast<const float4*>(src);
-    v1 = *reinterpret_cast<const float4*>(src + 4);
-  }
-  float* out = dst + static_cast<long>(r) * ld + m;
-  *reinterpret_cast<float4*>(out) = v0;
-  *reinterpret_cast<float4*>(out + 4) = v1;
-  if (!dst_op) return;
-  if (op_bf16) {
-    uint4 pk;
-    pk.x = f32_to_bf16_rne(v0.x) | (static_cast<uint32_t>(f32_to_bf16_rne(v0.y)) << 16);
-    pk.y = f32_to_bf16_rne(v0.z) | (static_cast<uint32_t>(f32_to_bf16_rne(v0.w)) << 16);
-    pk.z = f32_to_bf16_rne(v1.x) | (static_cast<uint32_t>(f32_to_bf16_rne(v1.y)) << 16);
-    pk.w = f32_to_bf16_rne(v1.z) | (static_cast<uint32_t>(f32_to_bf16_rne(v1.w)) << 16);
-    *reinterpret_cast<uint4*>(static_cast<char*>(dst_op) + (static_cast<long>(m >> 3) * ldt + r) * 16) = pk;
-  } else {
-    char* o = static_cast<char*>(dst_op) + (static_cast<long>(m >> 2) * ldt + r) * 16;
-    *reinterpret_cast<float4*>(o) = v0;
-    *reinterpret_cast<float4*>(o + static_cast<long>(ldt) * 16) = v1;
-  }
-}
+// Layer 0's input rows of one block in a launch of their own (the first block of a call; later blocks
+// ride in the stage launches, see StageBatch).
+__global__ void stage_input_kernel(const StageIn in) { stage_input_rows(in); }
 
 // One thread per 16-byte chunk of the packed matrix: chunk (((ft * nks_total + s) * 3 + gate) * 2 + half) * 64 + lane
 // holds bytes [s*128 + (lane/16)*32 + half*16, +16) of row gate*d + ft*16 + lane%16 (kernel_mfma_packed.hip.h).
@@ -396,7 +348,7 @@ int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) 
     return p.wdt == SSRNN_BF16 ? launch_mfma_xlds_bf16(p, s, nstage, st) : launch_mfma_xlds_f32(p, s, nstage, st);
   // two feature tiles per workgroup only for launches that fill the chip that way; both instances give the same bits
   const int ft = (p.packed && p.ft == 2 && static_cast<long>(p.d) / (2 * MFMA_F) * nstage >= 256) ? 2 : 1;
-  const dim3 grid(p.d / (MFMA_F * ft) * p.ksplit, nstage);
+  const dim3 grid(p.d / (MFMA_F * ft) * p.ksplit, launch_rows(s, nstage));
   const dim3 block(p.mfma_nw * 64);
   int rc;
   if (!p.packed) rc = launch_mfma_lds(p, s, nstage, grid, block, st);
@@ -538,20 +490,22 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   auto block_len = [&](long b) { return static_cast<int>(L - b * T < T ? L - b * T : T); };
   const int nt_last = block_len(nblocks - 1);
 
-  // layer 0's input rows of block b into its hand-off buffer
+  // layer 0's input rows of block b into its hand-off buffer: what to copy, and the copy as a launch of its own
+  auto input_rows = [&](long b) {
+    StageIn in{};
+    in.x = x; in.xhist_init = xhist_init;
+    in.dst = act(0, b);
+    in.dst_op = use_op ? opbuf(0, b) : nullptr;
+    in.t0 = b * T; in.L = L; in.nt = block_len(b);
+    in.ldt = wl.ldt; in.op_bf16 = op_bf16; in.ld = wl.ld; in.d = d; in.k = k; in.reverse = reverse;
+    in.vec = (d % 8 == 0 && aligned16(x) && aligned16(xhist_init)) ? 1 : 0;
+    return in;
+  };
   auto stage_input = [&](long b) {
-    const long t0 = b * T;
-    const int nt = block_len(b);
-    if (d % 8 == 0 && aligned16(x) && aligned16(xhist_init) && k - 1 + nt <= 65535) {
-      const int per_row = d / 8;
-      const int bx = per_row < 256 ? (per_row + 63) / 64 * 64 : 256;
-      hipLaunchKernelGGL(stage_input_vec_kernel, dim3((per_row + bx - 1) / bx, k - 1 + nt), dim3(bx), 0, st, x,
-                         xhist_init, act(0, b), use_op ? opbuf(0, b) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, L, reverse);
-    } else {
-      const long n = static_cast<long>(k - 1 + nt) * d;
-      hipLaunchKernelGGL(stage_input_kernel, dim3((n + 255) / 256), dim3(256), 0, st, x, xhist_init, act(0, b),
-                         use_op ? opbuf(0, b) : nullptr, wl.ldt, op_bf16, wl.ld, d, k, t0, nt, L, reverse);
-    }
+    const StageIn in = input_rows(b);
+    const long n = static_cast<long>(k - 1 + in.nt) * (in.vec ? d / 8 : d);
+    const long groups = (n + 255) / 256;
+    hipLaunchKernelGGL(stage_input_kernel, dim3(static_cast<unsigned>(groups < 4096 ? groups : 4096)), dim3(256), 0, st, in);
   };
 
   // stage (block b, layer l); slot: its position in the launch (picks the split-K scratch area)
@@ -602,11 +556,14 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   const bool wavefront = sched == SSRNN_SCHED_WAVEFRONT || (sched == SSRNN_SCHED_AUTO && n_layers > 1 && nblocks > 1);
   if (!wavefront) {
     // streaming order, one launch per stage
+    // (the next block's input rows are staged by the launch of layer 0, which does not touch their buffer)
+    if (stage_in) stage_input(0);
     for (long b = 0; b < nblocks; ++b) {
-      if (stage_in) stage_input(b);
       for (int l = 0; l < n_layers; ++l) {
         StageBatch sb{};
         sb.s[0] = make_stage(b, l, 0);
+        sb.n = 1;
+        if (stage_in && l == 0 && b + 1 < nblocks) sb.in = input_rows(b + 1);
         const int rc = launch(sb, 1);
         if (rc != SSRNN_OK) return rc;
       }
@@ -614,14 +571,18 @@ int forward(int cell, const void* const* W, const float* const* bias, const floa
   } else {
     // step s runs the stages (b, l) with b + l = s: their inputs were written in step s-1 (or staged from x),
     // their states were left by step s-1, and no two of them touch the same buffer
+    // (layer 0's input of block step + 1 is staged by the first launch of step `step`: the stages of that
+    // step read and write the other buffer of layer 0's pair, or none)
+    if (stage_in) stage_input(0);
     for (long step = 0; step < nblocks + n_layers - 1; ++step) {
-      if (stage_in && step < nblocks) stage_input(step);
       const int l_lo = step >= nblocks ? static_cast<int>(step - (nblocks - 1)) : 0;
       const int l_hi = step < n_layers ? static_cast<int>(step) : n_layers - 1;
       for (int l0 = l_lo; l0 <= l_hi; l0 += MAX_BATCH_STAGES) {
         StageBatch sb{};
         int n = 0;
         for (int l = l0; l <= l_hi && n < MAX_BATCH_STAGES; ++l, ++n) sb.s[n] = make_stage(step - l, l, n);
+        sb.n = n;
+        if (stage_in && l0 == l_lo && step + 1 < nblocks) sb.in = input_rows(step + 1);
         const int rc = launch(sb, n);
         if (rc != SSRNN_OK) return rc;
       }

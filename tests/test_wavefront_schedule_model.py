@@ -4,8 +4,9 @@ A launch holds the stages (block b, layer l) with the same b + l.  Stage (b, l)
 reads layer l's input buffer of parity b % 2 and the state c[l]; for the QRNN it
 also reads the end of block b-1 in layer l+1's other buffer (the window rows it
 copies in front of its output); it writes layer l+1's input buffer of parity
-b % 2 (or h for the top layer) and c[l].  Layer 0's buffers are filled from x by
-a staging launch right before the step that needs them.  The model replays that
+b % 2 (or h for the top layer) and c[l].  Layer 0's buffers are filled from x:
+block 0 by a launch of its own, block s+1 by an extra row of workgroups in the
+first launch of step s.  The model replays that
 with a tag per buffer (the block whose rows it holds) and checks what the
 kernels rely on: inside a launch nothing written by one stage is touched by
 another, and every read finds the block it expects.  A schedule with a single
@@ -22,9 +23,9 @@ def run_schedule(n_layers, nblocks, qrnn, stage_in, buffers_per_layer=2):
     h = set()
     par = (lambda b: b % 2) if buffers_per_layer == 2 else (lambda b: 0)
     launches = 0
+    if stage_in:
+        act[(0, par(0))] = 0                  # staging launch of block 0, ahead of everything in stream order
     for step in range(nblocks + n_layers - 1):
-        if stage_in and step < nblocks:
-            act[(0, par(step))] = step        # staging launch, ahead of the step's compute launch in stream order
         l_lo = step - (nblocks - 1) if step >= nblocks else 0
         l_hi = min(step, n_layers - 1)
         for l0 in range(l_lo, l_hi + 1, MAX_BATCH):
@@ -46,10 +47,17 @@ def run_schedule(n_layers, nblocks, qrnn, stage_in, buffers_per_layer=2):
                         r.add(("act", l + 1, par(b - 1)))
                         assert act.get((l + 1, par(b - 1))) == b - 1, ("window rows come from the wrong block", b, l)
                 reads.append(r); writes.append(w)
+            staged = stage_in and l0 == l_lo and step + 1 < nblocks
+            if staged:                                   # the launch's staging row: block step + 1 into layer 0's buffer
+                stages = stages + [("stage-in", step + 1)]
+                reads.append(set()); writes.append({("act", 0, par(step + 1))})
             for i in range(len(stages)):
                 for j in range(len(stages)):
                     if i != j:
                         assert not (writes[i] & (reads[j] | writes[j])), ("two stages of a launch share a buffer", stages[i], stages[j])
+            if staged:
+                act[(0, par(step + 1))] = step + 1
+                stages = stages[:-1]
             for (b, l), w in zip(stages, writes):       # apply the launch's writes
                 c[l] = b
                 if l == n_layers - 1:
