@@ -55,6 +55,7 @@ int launch_mfma_packed_bf16(const Plan& p, const StageBatch& s, int nstage, int 
 int launch_mfma_packed_fp8(const Plan& p, const StageBatch& s, int nstage, int ft, dim3 grid, dim3 block, hipStream_t st);
 int launch_mfma_xlds_f32(const Plan& p, const StageBatch& s, int nstage, hipStream_t st);
 int launch_mfma_xlds_bf16(const Plan& p, const StageBatch& s, int nstage, hipStream_t st);
+int launch_mfma_xlds_fp8(const Plan& p, const StageBatch& s, int nstage, hipStream_t st);
 int launch_split_epilogue(const Plan& p, const StageBatch& s, int nstage, hipStream_t st);
 
 // Geometry the planner needs from the kernel headers without including them.

@@ -32,6 +32,16 @@
 namespace ssrnn {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+// Eight E4M3 codes (two 32-bit words, lowest address first) as eight bf16 values (exact: 3 mantissa bits into 7).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x8_t fp8x8_to_bf16(uint32_t w0, uint32_t w1) {
+  const bf16x2_t a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, false);
+  const bf16x2_t b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, true);
+  const bf16x2_t c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, false);
+  const bf16x2_t e = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, true);
+  return bf16x8_t{a[0], a[1], b[0], b[1], c[0], c[1], e[0], e[1]};
+}
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 constexpr int MFMA_F = 16;          // features per workgroup

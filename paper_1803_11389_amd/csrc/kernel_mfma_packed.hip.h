@@ -48,16 +48,6 @@ struct MfmaPkCfg {
   static constexpr int NBT = (WT == W_FP8) ? ((NT > 8) ? 2 : (NT > 4) ? 4 : NT) : ((NT > 8) ? 8 : NT);   // time tiles per B fetch
 };
 
-// Eight E4M3 codes (two 32-bit words, lowest address first) as eight bf16 values.
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ bf16x8_t fp8x8_to_bf16(uint32_t w0, uint32_t w1) {
-  const bf16x2_t a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, false);
-  const bf16x2_t b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, true);
-  const bf16x2_t c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, false);
-  const bf16x2_t e = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, true);
-  return bf16x8_t{a[0], a[1], b[0], b[1], c[0], c[1], e[0], e[1]};
-}
-
 template <int CELL, int WT, int NT, int FT = 1>
 __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kernel(const StageBatch batch, int d, int k) {
   static_assert(FT == 1 || FT == 2, "one or two feature tiles per workgroup");

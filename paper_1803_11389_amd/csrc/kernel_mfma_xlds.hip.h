@@ -8,8 +8,8 @@
 // 16-feature tile each (three 16-row M tiles: candidate, forget, reset/output)
 // and walk ALL k*d columns in step, so a piece of X is needed by all four at the
 // same time and is fetched ONCE per workgroup, straight from memory into LDS
-// (global_load_lds, 16 bytes per lane, no staging registers), and read from
-// there as MFMA B fragments.  A wave's accumulators then hold complete sums, so
+// (buffer loads with the LDS bit, 16 bytes per lane, no staging registers), and
+// read from there as MFMA B fragments.  A wave's accumulators then hold complete sums, so
 // the gates and the recurrence of Eq. 2 / Eq. 3 are applied to them in
 // registers: no sum across waves, no LDS round trip and no barrier in the
 // epilogue.  A stage is d/64 workgroups; the host picks this kernel when a launch
@@ -18,6 +18,14 @@
 // Weights: the packed layout of kernel_mfma_packed.hip.h.  A wave streams the
 // fragments of its own tile, 6 KiB per k-step (128 bytes of each of its 48
 // rows), non-temporal, through a register ring.
+//
+// 8-bit weights (E4M3 codes, widened to bf16 right before the multiply; the row
+// scales multiply the finished sums).  128 bytes of a row are 128 columns, twice
+// what one LDS tile of bf16 inputs holds, so the kernel's "k-step" is HALF a
+// packed k-step: the three fragments (one per gate) with the packed layout's
+// half index h, whose 16 bytes per lane are columns (lane/16)*32 + h*16 .. +16
+// of the packed k-step, i.e. two MFMA K-slices of 8, and the eight 8-column
+// chunk columns (lane/16)*4 + h*2 + {0, 1} of the input block that they multiply.
 //
 // Pipeline.  The unit is a "B-step": NSUB k-steps whose X columns form one LDS
 // tile of at most 32 KiB; there are four LDS buffers and four ring slots of
@@ -73,15 +81,16 @@ struct XldsCfg {
   static constexpr int R = NT * 16;                       // time rows of an X tile
   static_assert(R >= 32, "at least two time tiles");
   static constexpr int NSUB = (R >= 256) ? 1 : 2;         // k-steps per B-step
-  static constexpr int KCOLS = (WT == W_BF16) ? 64 : 32;  // weight columns per k-step (128 bytes of a row)
-  static constexpr int VEC = (WT == W_BF16) ? 8 : 4;      // X elements per 16-byte chunk of the operand copy
+  static constexpr int KCOLS = (WT == W_F32) ? 32 : 64;   // weight columns per k-step (fp32, bf16: 128 bytes of a row; 8-bit: 64)
+  static constexpr int VEC = (WT == W_F32) ? 4 : 8;       // X elements per 16-byte chunk of the operand copy
+  static constexpr int AFR = (WT == W_FP8) ? 3 : 6;       // weight fragments (1 KiB each) of a wave per k-step
   static constexpr int KSTEP_BYTES = 8 * R * 16;          // one k-step of X in LDS: 8 chunk columns x R rows x 16 B
   static constexpr int BSTEP_BYTES = NSUB * KSTEP_BYTES;
   static constexpr int NTHREADS = XLDS_TILES * 64;
   static_assert(BSTEP_BYTES % (NTHREADS * 16) == 0, "every thread moves whole 16-byte pieces");
   static constexpr int NCOPY = BSTEP_BYTES / (NTHREADS * 16);   // X pieces a thread requests per B-step
   static constexpr int PER_KSTEP = NCOPY / NSUB;                 // of which per k-step
-  static constexpr int NA = 6 * NSUB;                            // weight fragments a wave requests per B-step
+  static constexpr int NA = AFR * NSUB;                          // weight fragments a wave requests per B-step
   static constexpr int NFRAG = NSUB * 2 * NT;                    // B fragments (k-step, half, time tile) per B-step
   static constexpr int KSTEPS_PER_ITER = XLDS_NBUF * NSUB;       // k-steps of one loop body
 };
@@ -90,15 +99,14 @@ struct XldsCfg {
 template <int WT, int NT>
 constexpr int xlds_col_multiple() { return XldsCfg<WT, NT>::KSTEPS_PER_ITER * XldsCfg<WT, NT>::KCOLS; }
 
-// Requirements (checked by the host): packed fp32 or bf16 weights, d % 64 == 0, k*d a multiple of
+// Requirements (checked by the host): packed weights, d % 64 == 0 (8-bit: d % 128 == 0), k*d a multiple of
 // xlds_col_multiple(), 1 <= nt <= NT*16, an operand copy of the input block smaller than 2 GiB, no
 // split of the columns.
 template <int CELL, int WT, int NT>
 __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const StageBatch batch, int d, int k) {
-  static_assert(WT == W_F32 || WT == W_BF16, "fp32 or bf16 weights");
   using Cfg = XldsCfg<WT, NT>;
   constexpr int R = Cfg::R, NSUB = Cfg::NSUB, NCOPY = Cfg::NCOPY, KCOLS = Cfg::KCOLS, VEC = Cfg::VEC;
-  constexpr int NFRAG = Cfg::NFRAG, NA = Cfg::NA;
+  constexpr int NFRAG = Cfg::NFRAG, NA = Cfg::NA, AFR = Cfg::AFR;
   constexpr int NBUF = XLDS_NBUF, DEPTH = XLDS_DEPTH;
   // Which (stage, feature group) this workgroup takes.  The hardware hands consecutive workgroups to the
   // eight compute dies in turn, each with an L2 of its own, and every workgroup of a stage reads that
@@ -152,6 +160,12 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
     }
   }
   const float4 cst = *reinterpret_cast<const float4*>(s.c + fl);      // running cell state of the four features
+  float4 sc0 = make_float4(1.f, 1.f, 1.f, 1.f), sc1 = sc0, sc2 = sc0;  // 8-bit weights: the rows' scales
+  if constexpr (WT == W_FP8) {
+    sc0 = *reinterpret_cast<const float4*>(s.wscale + fl);
+    sc1 = *reinterpret_cast<const float4*>(s.wscale + d + fl);
+    sc2 = *reinterpret_cast<const float4*>(s.wscale + 2 * d + fl);
+  }
 
   floatx4_t acc[3][NT];
 #pragma unroll
@@ -173,7 +187,10 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
   for (int i = 0; i < NCOPY; ++i) {
     const int e = i * Cfg::NTHREADS + tid;
     const int c = e / R, r = e - c * R;
-    cp_off[i] = (c & 7) * ldtb + (k - 1 + min(r, s.nt - 1)) * 16;
+    // LDS chunk column c & 7 = 2 * (K group of 16 lanes) + K-slice; with 8-bit weights a K group's 32
+    // columns of the packed k-step are four chunk columns, of which a half takes two
+    const int csrc = (WT == W_FP8) ? ((c & 7) >> 1) * 4 + (c & 1) : (c & 7);
+    cp_off[i] = csrc * ldtb + (k - 1 + min(r, s.nt - 1)) * 16;
   }
   // cursor of the next k-step whose X columns are requested: lag block x_j, first column x_m within it
   int x_j = 0, x_m = 0;
@@ -181,7 +198,8 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
   auto advance_x = [&]() {                           // moves the cursor one B-step on
 #pragma unroll
     for (int u = 0; u < NSUB; ++u) {
-      xbase[u] = (x_m / VEC) * ldtb - x_j * 16;      // rows shifted back by the lag
+      if constexpr (WT == W_FP8) xbase[u] = ((x_m & ~127) / VEC + ((x_m >> 6) & 1) * 2) * ldtb - x_j * 16;   // packed k-step, half
+      else xbase[u] = (x_m / VEC) * ldtb - x_j * 16;  // rows shifted back by the lag
       x_m += KCOLS;
       if (x_m >= d) { x_m -= d; ++x_j; }
     }
@@ -191,11 +209,15 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
   };
 
   // ---- weight side: ring of NBUF B-steps of this wave's fragments
-  const char* aptr = static_cast<const char*>(s.W) + static_cast<size_t>(ft) * nks * 6144 + lane * 16;
-  floatx4_t aring[NBUF][NSUB][6];
+  const char* aptr = static_cast<const char*>(s.W) + static_cast<size_t>(ft) * nks * (AFR * 1024) + lane * 16;
+  floatx4_t aring[NBUF][NSUB][AFR];
   int a_ks = 0;                                      // first k-step of the B-step whose fragments are requested
-  auto request_a_piece = [&](int slot, int i) {      // fragment i % 6 of k-step i / 6 of the B-step
-    aring[slot][i / 6][i % 6] = load_stream16(aptr + static_cast<size_t>(a_ks + i / 6) * 6144 + (i % 6) * 1024);
+  auto request_a_piece = [&](int slot, int i) {      // fragment i % AFR of k-step i / AFR of the B-step
+    const int ks = a_ks + i / AFR;
+    if constexpr (WT == W_FP8)                       // gate i % 3, half ks % 2 of packed k-step ks / 2
+      aring[slot][i / AFR][i % AFR] = load_stream16(aptr + static_cast<size_t>(ks >> 1) * 6144 + ((i % AFR) * 2 + (ks & 1)) * 1024);
+    else
+      aring[slot][i / AFR][i % AFR] = load_stream16(aptr + static_cast<size_t>(ks) * 6144 + (i % AFR) * 1024);
   };
 
   // ---- B fragments: fragment q of a B-step is (k-step q / 2NT, half (q / NT) % 2, time tile q % NT); lane
@@ -203,18 +225,30 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
   // register sets, BQ-1 reads ahead of the MFMAs that use them.
   constexpr int BQ = 4;
   static_assert(NFRAG % BQ == 0 && NFRAG >= 2 * BQ, "the fragment ring repeats with the B-step");
-  using bfrag_t = std::conditional_t<WT == W_BF16, bf16x8_t, floatx4_t>;
+  using bfrag_t = std::conditional_t<WT == W_F32, floatx4_t, bf16x8_t>;
   bfrag_t bq[BQ];
   const char* bt = smem + kg * 2 * (R * 16) + li * 16;
   auto read_b = [&](int buf, int q) {
     const int u = q / (2 * NT), h = (q / NT) & 1, n = q % NT;
     bq[q % BQ] = *reinterpret_cast<const bfrag_t*>(bt + buf * Cfg::BSTEP_BYTES + u * Cfg::KSTEP_BYTES + h * (R * 16) + n * 256);
   };
+  bf16x8_t awide[3];                                  // 8-bit weights: the K-slice in use, widened, one per gate
   auto mfma_b = [&](int slot, int q) {
     const int u = q / (2 * NT), h = (q / NT) & 1, n = q % NT;
+    if constexpr (WT == W_FP8) {
+      if (n == 0) {                                   // a new K-slice: words 2h, 2h+1 of the lane's 16 codes
+#pragma unroll
+        for (int g = 0; g < 3; ++g) {
+          const floatx4_t a4 = aring[slot][u][g];
+          awide[g] = fp8x8_to_bf16(__float_as_uint(a4[h * 2]), __float_as_uint(a4[h * 2 + 1]));
+        }
+      }
+    }
 #pragma unroll
     for (int g = 0; g < 3; ++g) {
-      if constexpr (WT == W_BF16) {
+      if constexpr (WT == W_FP8) {
+        acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(awide[g], bq[q % BQ], acc[g][n], 0, 0, 0);
+      } else if constexpr (WT == W_BF16) {
         bf16x8_t a;
         __builtin_memcpy(&a, &aring[slot][u][g * 2 + h], sizeof a);
         acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[q % BQ], acc[g][n], 0, 0, 0);
@@ -300,6 +334,9 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
   const float b0[4] = {bias0.x, bias0.y, bias0.z, bias0.w};
   const float b1[4] = {bias1.x, bias1.y, bias1.z, bias1.w};
   const float b2[4] = {bias2.x, bias2.y, bias2.z, bias2.w};
+  const float w0[4] = {sc0.x, sc0.y, sc0.z, sc0.w};
+  const float w1[4] = {sc1.x, sc1.y, sc1.z, sc1.w};
+  const float w2[4] = {sc2.x, sc2.y, sc2.z, sc2.w};
   float cin[4] = {cst.x, cst.y, cst.z, cst.w};
   const int rowbase = lane & 48;
 #pragma unroll
@@ -314,7 +351,12 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
       float hv[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float u0 = acc[0][n][r] + b0[r], u1 = acc[1][n][r] + b1[r], u2 = acc[2][n][r] + b2[r];
+        float u0, u1, u2;
+        if constexpr (WT == W_FP8) {
+          u0 = fmaf(w0[r], acc[0][n][r], b0[r]); u1 = fmaf(w1[r], acc[1][n][r], b1[r]); u2 = fmaf(w2[r], acc[2][n][r], b2[r]);
+        } else {
+          u0 = acc[0][n][r] + b0[r]; u1 = acc[1][n][r] + b1[r]; u2 = acc[2][n][r] + b2[r];
+        }
         const float f = sigmoidf_fast(u1);
         const float o = sigmoidf_fast(u2);
         const float cand = (CELL == CELL_SRU) ? u0 : tanhf_fast(u0);

@@ -1,6 +1,6 @@
 // Body of the launcher of the 64-features-per-workgroup matrix-core kernel
 // (kernel_mfma_xlds.hip.h) for one weight type: the including translation unit
-// defines SSRNN_XL_WT (W_F32 or W_BF16) and SSRNN_XL_NAME.
+// defines SSRNN_XL_WT (W_F32, W_BF16 or W_FP8) and SSRNN_XL_NAME.
 #include "host.hip.h"
 #include "kernel_mfma_xlds.hip.h"
 
@@ -18,7 +18,7 @@ static int launch_cell(const Plan& p, const StageBatch& s, int nstage, hipStream
   // fp32 weights: from four time tiles on the stage is bound by the matrix cores, where the 16-feature
   // kernel (no barrier, no LDS reads) measured faster (d = 4096, T = 64: 57.3 against 60.0 us per stage)
   SSRNN_XL_CASE(2)
-  if constexpr (WT == W_BF16) { SSRNN_XL_CASE(4) SSRNN_XL_CASE(8) SSRNN_XL_CASE(16) }
+  if constexpr (WT != W_F32) { SSRNN_XL_CASE(4) SSRNN_XL_CASE(8) SSRNN_XL_CASE(16) }
 #undef SSRNN_XL_CASE
   return fail(SSRNN_EUNSUPPORTED, "no 64-feature matrix-core kernel for %d time tiles", p.nt_tiles);
 }
@@ -36,6 +36,15 @@ bool xlds_takes(int wdt, int nt_tiles, long ncol) {
       case 4: return whole(xlds_col_multiple<W_BF16, 4>());
       case 8: return whole(xlds_col_multiple<W_BF16, 8>());
       case 16: return whole(xlds_col_multiple<W_BF16, 16>());
+      default: return false;
+    }
+  }
+  if (wdt == SSRNN_FP8) {
+    switch (nt_tiles) {
+      case 2: return whole(xlds_col_multiple<W_FP8, 2>());
+      case 4: return whole(xlds_col_multiple<W_FP8, 4>());
+      case 8: return whole(xlds_col_multiple<W_FP8, 8>());
+      case 16: return whole(xlds_col_multiple<W_FP8, 16>());
       default: return false;
     }
   }

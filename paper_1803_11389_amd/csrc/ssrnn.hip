@@ -331,7 +331,8 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   // Every 16-feature workgroup pulls the whole input block through its CU's memory path.  Where those bytes
   // weigh against the weights' (blocks of 17 steps and more) and the launches hold enough stages to fill
   // the chip with larger workgroups, a workgroup owns 64 features and shares the input block through LDS
-  // (packed fp32 and bf16 weights), or 32 features in the packed kernel itself (8-bit weights).
+  // (packed weights of any type); launches that kernel does not take may still put 32 features into a
+  // workgroup of the packed kernel itself.
   p.xlds = p.packed && p.nt_tiles >= 2 && p.ksplit == 1 && p.d % XLDS_F == 0 && xlds_takes(p.wdt, p.nt_tiles, ncol) &&
            static_cast<long>(p.d) / XLDS_F * conc >= 256 && op_stride < (1ull << 31) && !(p.opts & SSRNN_OPT_ONE_TILE);
   p.ft = 1;
@@ -345,7 +346,9 @@ int launch_mfma(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) 
   // the first and last launch of a wavefront hold one stage: too few 64-feature workgroups to occupy the
   // chip, so those go to the 16-feature kernel (another summation order, same tolerances)
   if (p.xlds && static_cast<long>(p.d) / XLDS_F * nstage >= 128)
-    return p.wdt == SSRNN_BF16 ? launch_mfma_xlds_bf16(p, s, nstage, st) : launch_mfma_xlds_f32(p, s, nstage, st);
+    return p.wdt == SSRNN_BF16 ? launch_mfma_xlds_bf16(p, s, nstage, st)
+         : p.wdt == SSRNN_FP8  ? launch_mfma_xlds_fp8(p, s, nstage, st)
+                               : launch_mfma_xlds_f32(p, s, nstage, st);
   // two feature tiles per workgroup only for launches that fill the chip that way; both instances give the same bits
   const int ft = (p.packed && p.ft == 2 && static_cast<long>(p.d) / (2 * MFMA_F) * nstage >= 256) ? 2 : 1;
   const dim3 grid(p.d / (MFMA_F * ft) * p.ksplit, launch_rows(s, nstage));

@@ -120,22 +120,26 @@ def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, mode, d,
                 assert _rel_err(u, r) <= BF16_TOL, _rel_err(u, r)
 
 
-@pytest.mark.parametrize("cell,k,T,d,n_layers,nblocks", [
-    ("sru", 1, 100, 4096, 4, 4), ("qrnn", 2, 70, 2048, 8, 8), ("sru", 1, 256, 4096, 4, 4), ("qrnn", 3, 130, 2048, 8, 9),
+@pytest.mark.parametrize("cell,k,T,d,n_layers,nblocks,mode", [
+    ("sru", 1, 100, 4096, 4, 4, "bf16"), ("qrnn", 2, 70, 2048, 8, 8, "bf16"), ("sru", 1, 256, 4096, 4, 4, "bf16"),
+    ("qrnn", 3, 130, 2048, 8, 9, "bf16"),
+    ("sru", 1, 24, 4096, 4, 6, "fp8"), ("qrnn", 2, 70, 2048, 8, 8, "fp8"), ("sru", 1, 256, 4096, 4, 4, "fp8"),
+    ("qrnn", 3, 130, 2048, 8, 9, "fp8"), ("qrnn", 2, 50, 4096, 4, 5, "fp8"),
 ])
-def test_long_blocks_of_packed_bf16_weights_on_the_64_feature_kernel(cell, k, T, d, n_layers, nblocks):
-    """65 <= T <= 256, packed bf16 weights and launches wide enough for d/64 workgroups per stage to fill the
-    chip: the kernel whose waves own a feature tile each and share the input block through LDS.  Against the
-    oracle (bf16 bar), against the oracle that rounds the same operand, and against the 16-feature kernel on
-    the same inputs (the two sum a row's products in different orders, so not bit for bit)."""
+def test_long_blocks_of_packed_bf16_weights_on_the_64_feature_kernel(cell, k, T, d, n_layers, nblocks, mode):
+    """17 <= T <= 256, packed bf16 or 8-bit weights and launches wide enough for d/64 workgroups per stage to
+    fill the chip: the kernel whose waves own a feature tile each and share the input block through LDS.
+    Against the oracle (bf16 bar), against the oracle that rounds the same operand, and against the 16-feature
+    kernel on the same inputs (the two sum a row's products in different orders, so not bit for bit)."""
     import workloads as wl
     import paper_1803_11389_amd as ss
     from test_gpu_parity import _check_against_rounding_oracle
     L = (nblocks - 1) * T + max(1, T // 3)           # a ragged last block
-    print(f"64-feature kernel {cell} k={k} T={T} d={d} layers={n_layers} L={L}", flush=True)
+    print(f"64-feature kernel {cell} k={k} T={T} d={d} layers={n_layers} L={L} {mode}", flush=True)
     rng = np.random.default_rng(4300 + T + k + d)
     ncol = k * d
-    W = [wl.to_bf16_bits((rng.uniform(-1, 1, (3 * d, ncol)) * 2.0 / np.sqrt(ncol)).astype(np.float32)) for _ in range(n_layers)]
+    Wf = [(rng.uniform(-1, 1, (3 * d, ncol)) * 2.0 / np.sqrt(ncol)).astype(np.float32) for _ in range(n_layers)]
+    W = [wl.quantize_fp8(w) for w in Wf] if mode == "fp8" else [wl.to_bf16_bits(w) for w in Wf]
     nb = 2 if cell == "sru" else 3
     b = [rng.uniform(-1, 1, nb * d).astype(np.float32) for _ in range(n_layers)]
     x = rng.standard_normal((L, d)).astype(np.float32)
