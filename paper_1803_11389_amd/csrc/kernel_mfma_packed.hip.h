@@ -45,7 +45,7 @@ struct MfmaPkCfg {
   static constexpr int NW = 4;                            // waves per workgroup
   static constexpr int SA = 4;                            // weight fragment ring slots (k-steps)
   static constexpr int SB = (FT > 1) ? 2 : (WT == W_FP8) ? ((NT <= 1) ? 4 : 2) : ((NT <= 4) ? 4 : 2);   // B fragment ring slots (sub-steps)
-  static constexpr int NBT = (WT == W_FP8) ? ((NT > 8) ? 2 : (NT > 4) ? 4 : NT) : ((NT > 8) ? 8 : NT);   // time tiles per B fetch
+  static constexpr int NBT = (WT == W_FP8) ? ((NT > 8) ? 2 : (NT > 4) ? 4 : NT) : ((NT > 8) ? 4 : NT);   // time tiles per B fetch
 };
 
 template <int CELL, int WT, int NT, int FT = 1>
@@ -117,9 +117,22 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   // read out.
   constexpr int VEC = (WT == W_F32) ? 4 : 8;         // elements per 16-byte chunk of the operand copy
   constexpr int NPC = CW / VEC;                      // B pieces per lane, k-step and time tile (2; 4 for 8-bit weights)
-  int brow[NT];
+  // (kept in registers except in the 16-tile instances, which have none to spare and recompute it per load)
+  constexpr bool BROW_REGS = NT < 16;
+  int brow[BROW_REGS ? NT : 1];
+  if constexpr (BROW_REGS) {
 #pragma unroll
-  for (int n = 0; n < NT; ++n) brow[n] = min(n * 16 + li, s.nt - 1) * 16;
+    for (int n = 0; n < NT; ++n) brow[n] = min(n * 16 + li, s.nt - 1) * 16;
+  }
+  const int nt_last = s.nt - 1;
+  auto b_row = [&](int n) {
+    if constexpr (BROW_REGS) return brow[n];
+    else {
+      int r = min(n * 16 + li, nt_last) * 16;
+      asm volatile("" : "+v"(r));                    // computed where it is used: hoisted out of the loop, the 64 sums of row and chunk-column offsets would spill
+      return r;
+    }
+  };
   const long ldtb = static_cast<long>(s.ldt) * 16;  // bytes per chunk column
   const char* xop = static_cast<const char*>(s.xop);
 
@@ -136,7 +149,7 @@ __global__ __launch_bounds__(MfmaPkCfg<NT>::NW * 64) void stage_mfma_packed_kern
   };
   auto load_b_piece = [&](int slot, int tile0, int i) {      // i = (tile - tile0) * NPC + piece
     const int n = i / NPC, h = i % NPC;
-    const char* src = xop + b_off + h * ldtb + brow[tile0 + n];
+    const char* src = xop + b_off + h * ldtb + b_row(tile0 + n);
     if constexpr (WT == W_F32) bring[slot][n].v[h] = *reinterpret_cast<const float4*>(src);
     else bring[slot][n].v[h] = *reinterpret_cast<const bf16x8_t*>(src);
   };

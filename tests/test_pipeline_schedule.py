@@ -147,7 +147,7 @@ def replay_packed(SA, SB, U, nks, NBH=1):
 
 # (SA, SB, NBH) per number of time tiles as in MfmaPkCfg: NT <= 4 -> (4, 4, 1); NT = 8 -> (4, 2, 1); NT = 16 -> (4, 2, 2);
 # 8-bit weights: NT = 1 -> (4, 4, 1); NT = 2, 4 -> (4, 2, 1); NT = 8 -> (4, 2, 2); NT = 16 -> (4, 2, 8)
-@pytest.mark.parametrize("SA,SB,NBH", [(4, 4, 1), (4, 2, 1), (4, 2, 2), (4, 2, 8)])
+@pytest.mark.parametrize("SA,SB,NBH", [(4, 4, 1), (4, 2, 1), (4, 2, 2), (4, 2, 4), (4, 2, 8)])
 @pytest.mark.parametrize("nks", [4, 8, 16, 32, 64])
 def test_packed_schedule_is_in_range_and_complete(SA, SB, NBH, nks):
     replay_packed(SA, SB, max(SA, SB), nks, NBH)
