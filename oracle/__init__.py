@@ -49,6 +49,8 @@ def load_library(path: str):
     lib.oracle_sru_step.argtypes = [vp] * 5 + [ip, ip]
     lib.oracle_qrnn_step.argtypes = [vp] * 5 + [ip, ip, ip]
     lib.oracle_linear_forward.argtypes = [vp] * 3 + [ip, ip, lp]
+    lib.oracle_lstm_forward.argtypes = [vp] * 10 + [ip, ip, lp, ip]
+    lib.oracle_lstm_step.argtypes = [vp] * 7 + [ip]
     return lib
 
 
@@ -230,3 +232,54 @@ def linear_forward(P, feat):
     rc = lib.oracle_linear_forward(_ptr(P), _ptr(feat), _ptr(y), d_out, d_in, L)
     assert rc == 0
     return y
+
+
+def lstm_forward(W, U, bias, x, h_init=None, c_init=None, T=1, return_all=False):
+    """Stacked LSTM (Eq. 1), the paper's comparison network; the input products of T steps are formed
+    together (Section 3.1).  W, U: lists of [4d, d] float32 (rows f | i | o | c-hat); bias: None or list of
+    None / [4d] float32; x: [L, d].  Returns (h, h_final, c_final[, h_all]) as float64."""
+    lib = _load()
+    n_layers = len(W)
+    assert len(U) == n_layers
+    W = [_as(w, np.float32) for w in W]
+    U = [_as(u, np.float32) for u in U]
+    d = W[0].shape[1]
+    for w, u in zip(W, U):
+        assert w.shape == (4 * d, d) and u.shape == (4 * d, d)
+    x = _as(x, np.float64)
+    L = x.shape[0]
+    assert x.shape == (L, d)
+    h_init = _as(h_init, np.float64, (n_layers, d))
+    c_init = _as(c_init, np.float64, (n_layers, d))
+    if bias is not None:
+        bias = [None if b is None else _as(b, np.float32, (4 * d,)) for b in bias]
+    h = np.empty((L, d), np.float64)
+    h_final = np.empty((n_layers, d), np.float64)
+    c_final = np.empty((n_layers, d), np.float64)
+    h_all = np.empty((n_layers, L, d), np.float64) if return_all else None
+    wp, _k1 = _ptr_array(W)
+    up, _k2 = _ptr_array(U)
+    bp, _k3 = _ptr_array(bias)
+    rc = lib.oracle_lstm_forward(wp, up, bp, _ptr(x), _ptr(h_init), _ptr(c_init), _ptr(h), _ptr(h_final),
+                                 _ptr(c_final), _ptr(h_all), n_layers, d, L, int(T))
+    if rc != 0:
+        raise ValueError("oracle_lstm_forward rejected its arguments")
+    return (h, h_final, c_final, h_all) if return_all else (h, h_final, c_final)
+
+
+def lstm_step(W, U, bias, x_t, h_prev, c):
+    """One layer, one step of Eq. 1, brute force.  Returns (h_t, c_new) as float64."""
+    lib = _load()
+    W = _as(W, np.float32)
+    U = _as(U, np.float32)
+    d = W.shape[1]
+    assert W.shape == (4 * d, d) and U.shape == (4 * d, d)
+    bias = _as(bias, np.float32, (4 * d,))
+    x_t = _as(x_t, np.float64, (d,))
+    h_prev = _as(h_prev, np.float64, (d,))
+    c = _as(c, np.float64, (d,)).copy()
+    h_t = np.empty(d, np.float64)
+    rc = lib.oracle_lstm_step(_ptr(W), _ptr(U), _ptr(bias), _ptr(x_t), _ptr(h_prev), _ptr(c), _ptr(h_t), d)
+    if rc != 0:
+        raise ValueError("oracle_lstm_step rejected its arguments")
+    return h_t, c

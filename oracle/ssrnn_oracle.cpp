@@ -1,4 +1,5 @@
-// CPU oracle for single-stream SRU / QRNN inference (arXiv 1803.11389).
+// CPU oracle for single-stream SRU / QRNN inference (arXiv 1803.11389), and for
+// the LSTM the paper compares them with.
 //
 // TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
 // GPU library is checked against.  It shares no code with the GPU path, is not
@@ -42,7 +43,8 @@
 // indexed by time.  Nothing else differs, so the reverse pass over x equals the
 // forward pass over the time-reversed x, read backwards (a pin).
 //
-// Pins (tests/test_oracle_*.py): hand-worked d=2 examples for both cells,
+// Pins (tests/test_oracle_*.py; the LSTM's are in tests/test_oracle_lstm_pins.py):
+// hand-worked d=2 examples for both cells,
 // step-by-step brute force (oracle_*_step below, written separately),
 // closed forms (f==0, f==1/2, f==1, r==0, W==0), the non-iterative solution of
 // the linear recurrence, an independent library matrix product for the weight
@@ -55,7 +57,19 @@
 // a multiple of 256 bytes, followed by one fp32 scale per row;
 // W[row][col] = scale[row] * value(q[row][col]).
 //
+// LSTM (paper Eq. (1)), the network the method is compared with (Sections 2.2
+// and 3.1):  f = sigma(W_f x + U_f h_{t-1} + b_f), i and o likewise,
+// c-hat = tanh(W_c x + U_c h_{t-1} + b_c), c_t = f*c_{t-1} + i*c-hat,
+// h_t = o*tanh(c_t).  Section 3.1: the products with the input, W x_t, do not
+// depend on the feedback and are formed for T steps together (a weight row
+// applied to all T columns, as in Eq. 4); the products with h_{t-1} follow step
+// by step.  oracle_lstm_forward takes its steps in that order; every
+// pre-activation is (W-row . x) + (U-row . h_{t-1}) + b with both dot products
+// in ascending column order, so the result is bit-identical for every T.
+//
 // Storage conventions
+//   LSTM W,U: row-major [4d x d] fp32, rows [0,d) = f, [d,2d) = i, [2d,3d) = o,
+//             [3d,4d) = c-hat (the order Eq. 1 lists them);  b : [4d] or NULL
 //   SRU  W  : row-major [3d x d],   rows [0,d) = W, [d,2d) = W_f, [2d,3d) = W_r
 //   SRU  b  : [2d] = b_f | b_r  (no bias on xh, Eq. 2);  NULL means zero
 //   QRNN W  : row-major [3d x k*d], column block j multiplies x_{t-j};
@@ -228,6 +242,50 @@ void qrnn_layer(const void* W, int wdt, const float* bias, const double* xin,
   }
 }
 
+// One LSTM layer (Eq. 1) over the whole sequence, the input products of T steps at a time (Section 3.1).
+// xin/hout: double [L x d]; hprev, c: double [d] in/out (h_{t-1} and c_{t-1} of the next step to come).
+void lstm_layer(const float* W, const float* U, const float* bias, const double* xin, double* hout,
+                double* hprev, double* c, int d, long L, int T) {
+  std::vector<double> A(static_cast<size_t>(4) * d * T);   // A[row][t] = W[row] . x_{t0+t}
+  std::vector<double> hnew(d);
+  for (long t0 = 0; t0 < L; t0 += T) {
+    const int nt = static_cast<int>(L - t0 < T ? L - t0 : T);
+    // the part without feedback, all nt steps of the block: one weight fetched once and used nt times
+#pragma omp parallel for schedule(static)
+    for (int row = 0; row < 4 * d; ++row) {
+      double* acc = A.data() + static_cast<size_t>(row) * nt;
+      for (int t = 0; t < nt; ++t) acc[t] = 0.0;
+      for (int col = 0; col < d; ++col) {
+        const double w = static_cast<double>(W[static_cast<size_t>(row) * d + col]);
+        for (int t = 0; t < nt; ++t) acc[t] += w * xin[(t0 + t) * d + col];
+      }
+    }
+    // the part with feedback, one step after the other
+    for (int t = 0; t < nt; ++t) {
+#pragma omp parallel for schedule(static)
+      for (int i = 0; i < d; ++i) {
+        double pre[4];
+        for (int g = 0; g < 4; ++g) {
+          const size_t row = static_cast<size_t>(g) * d + i;
+          double u = 0.0;
+          for (int col = 0; col < d; ++col) u += static_cast<double>(U[row * d + col]) * hprev[col];
+          pre[g] = A[row * nt + t] + u + (bias ? static_cast<double>(bias[row]) : 0.0);
+        }
+        const double f = sigma(pre[0]);
+        const double in = sigma(pre[1]);
+        const double o = sigma(pre[2]);
+        const double chat = std::tanh(pre[3]);
+        c[i] = f * c[i] + in * chat;
+        hnew[i] = o * std::tanh(c[i]);
+      }
+      for (int i = 0; i < d; ++i) {
+        hprev[i] = hnew[i];
+        hout[(t0 + t) * d + i] = hnew[i];
+      }
+    }
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -352,6 +410,64 @@ int oracle_qrnn_step(const void* W, const float* bias, const double* xwin,
     const double f = 1.0 / (1.0 + std::exp(-u[1]));
     const double o = 1.0 / (1.0 + std::exp(-u[2]));
     c[i] = f * c[i] + (1.0 - f) * z;
+    h_t[i] = o * std::tanh(c[i]);
+  }
+  return 0;
+}
+
+// Stacked LSTM forward (Eq. 1 per layer; the input products blocked by T as Section 3.1 describes).
+// W[l], U[l]: fp32 [4d x d]; bias: NULL, or array whose entries may be NULL ([4d]); x: double [L x d];
+// h_init, c_init: double [n_layers x d] or NULL (zeros); outputs double: h [L x d] (top layer),
+// h_final, c_final [n_layers x d] (every layer's h and c after the last step), h_all optional
+// [n_layers x L x d].  Returns 0, or 1 on bad arguments.
+int oracle_lstm_forward(const float* const* W, const float* const* U, const float* const* bias,
+                        const double* x, const double* h_init, const double* c_init, double* h,
+                        double* h_final, double* c_final, double* h_all, int n_layers, int d, long L, int T) {
+  if (!W || !U || !h_final || !c_final || n_layers < 1 || d < 1 || L < 0 || T < 1) return 1;
+  if (L > 0 && (!x || !h)) return 1;
+  const size_t n = static_cast<size_t>(L) * d;
+  std::vector<double> cur(n), nxt(n);
+  for (size_t i = 0; i < n; ++i) cur[i] = x[i];
+  for (int l = 0; l < n_layers; ++l) {
+    std::vector<double> c(d), hp(d);
+    for (int i = 0; i < d; ++i) {
+      c[i] = c_init ? c_init[static_cast<size_t>(l) * d + i] : 0.0;
+      hp[i] = h_init ? h_init[static_cast<size_t>(l) * d + i] : 0.0;
+    }
+    lstm_layer(W[l], U[l], bias ? bias[l] : nullptr, cur.data(), nxt.data(), hp.data(), c.data(), d, L, T);
+    std::memcpy(c_final + static_cast<size_t>(l) * d, c.data(), d * sizeof(double));
+    std::memcpy(h_final + static_cast<size_t>(l) * d, hp.data(), d * sizeof(double));
+    if (h_all && n) std::memcpy(h_all + static_cast<size_t>(l) * n, nxt.data(), n * sizeof(double));
+    cur.swap(nxt);
+  }
+  if (n) std::memcpy(h, cur.data(), n * sizeof(double));
+  return 0;
+}
+
+// Brute force: one LSTM layer, one time step, the eight matrix-vector products of Eq. 1 written out
+// gate by gate.  x_t, h_prev: double [d]; c: in/out; h_t: out (may not alias h_prev).
+int oracle_lstm_step(const float* W, const float* U, const float* bias, const double* x_t,
+                     const double* h_prev, double* c, double* h_t, int d) {
+  if (!W || !U || !x_t || !h_prev || !c || !h_t || d < 1 || h_t == h_prev) return 1;
+  const size_t dd = static_cast<size_t>(d);
+  for (int i = 0; i < d; ++i) {
+    double zf = 0.0, zi = 0.0, zo = 0.0, zc = 0.0;
+    for (int j = 0; j < d; ++j) zf += static_cast<double>(W[(0 * dd + i) * dd + j]) * x_t[j];
+    for (int j = 0; j < d; ++j) zi += static_cast<double>(W[(1 * dd + i) * dd + j]) * x_t[j];
+    for (int j = 0; j < d; ++j) zo += static_cast<double>(W[(2 * dd + i) * dd + j]) * x_t[j];
+    for (int j = 0; j < d; ++j) zc += static_cast<double>(W[(3 * dd + i) * dd + j]) * x_t[j];
+    double yf = 0.0, yi = 0.0, yo = 0.0, yc = 0.0;
+    for (int j = 0; j < d; ++j) yf += static_cast<double>(U[(0 * dd + i) * dd + j]) * h_prev[j];
+    for (int j = 0; j < d; ++j) yi += static_cast<double>(U[(1 * dd + i) * dd + j]) * h_prev[j];
+    for (int j = 0; j < d; ++j) yo += static_cast<double>(U[(2 * dd + i) * dd + j]) * h_prev[j];
+    for (int j = 0; j < d; ++j) yc += static_cast<double>(U[(3 * dd + i) * dd + j]) * h_prev[j];
+    const double bf = bias ? bias[i] : 0.0, bi = bias ? bias[dd + i] : 0.0;
+    const double bo = bias ? bias[2 * dd + i] : 0.0, bc = bias ? bias[3 * dd + i] : 0.0;
+    const double f = 1.0 / (1.0 + std::exp(-(zf + yf + bf)));
+    const double in = 1.0 / (1.0 + std::exp(-(zi + yi + bi)));
+    const double o = 1.0 / (1.0 + std::exp(-(zo + yo + bo)));
+    const double chat = std::tanh(zc + yc + bc);
+    c[i] = f * c[i] + in * chat;
     h_t[i] = o * std::tanh(c[i]);
   }
   return 0;

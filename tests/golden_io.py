@@ -16,7 +16,7 @@ def _num(tok: str) -> float:
 
 def load_example(name: str) -> dict:
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
-    rows = {"W": [], "x": [], "c": [], "h": []}
+    rows = {"W": [], "U": [], "x": [], "c": [], "h": []}
     ex = {"bias": None}
     with open(path) as fh:
         for line in fh:
@@ -30,13 +30,17 @@ def load_example(name: str) -> dict:
                 ex[key] = int(toks[0])
             elif key in rows:
                 rows[key].append([_num(t) for t in toks])
-            elif key in ("bias", "c_init"):
+            elif key in ("bias", "c_init", "h_init"):
                 ex[key] = np.array([_num(t) for t in toks], np.float64)
             else:
                 raise ValueError(f"{name}: unknown key {key}")
-    d, k = ex["d"], ex["k"]
+    d, k = ex["d"], ex.get("k", 1)
     ex["W"] = np.array(rows["W"], np.float64).astype(np.float32)
-    assert ex["W"].shape == (3 * d, k * d)
+    if ex["cell"] == "lstm":
+        ex["U"] = np.array(rows["U"], np.float64).astype(np.float32)
+        assert ex["W"].shape == (4 * d, d) and ex["U"].shape == (4 * d, d)
+    else:
+        assert ex["W"].shape == (3 * d, k * d)
     ex["x"] = np.array(rows["x"], np.float32)
     ex["c"] = np.array(rows["c"], np.float64)
     ex["h"] = np.array(rows["h"], np.float64)

@@ -7,6 +7,7 @@ import os
 import pytest
 
 import oracle
+import test_oracle_lstm_pins as lpins
 import test_oracle_pins as pins
 
 SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "ssrnn_oracle.cpp")
@@ -59,6 +60,27 @@ MUTATIONS = [
     ("stack: every layer reads the external input", "    cur.swap(nxt);\n  }\n  if (n) std::memcpy(h, cur.data(), n * sizeof(double));\n  return 0;\n}\n\n// Stacked QRNN",
      "    if (l == n_layers - 1) cur.swap(nxt);\n  }\n  if (n) std::memcpy(h, cur.data(), n * sizeof(double));\n  return 0;\n}\n\n// Stacked QRNN"),
     ("step function: bias dropped", "if (bias) { uf += bias[i]; ur += bias[d + i]; }", ""),
+    ("lstm: input gate replaced by 1 - f", "c[i] = f * c[i] + in * chat;\n        hnew[i]", "c[i] = f * c[i] + (1.0 - f) * chat;\n        hnew[i]"),
+    ("lstm: forget gate not applied", "c[i] = f * c[i] + in * chat;\n        hnew[i]", "c[i] = c[i] + in * chat;\n        hnew[i]"),
+    ("lstm: candidate not squashed", "const double chat = std::tanh(pre[3]);", "const double chat = pre[3];"),
+    ("lstm: output without tanh of the cell", "hnew[i] = o * std::tanh(c[i]);", "hnew[i] = o * c[i];"),
+    ("lstm: input and output gate rows swapped", "const double in = sigma(pre[1]);\n        const double o = sigma(pre[2]);", "const double in = sigma(pre[2]);\n        const double o = sigma(pre[1]);"),
+    ("lstm: forget and candidate rows swapped", "const double f = sigma(pre[0]);\n        const double in = sigma(pre[1]);\n        const double o = sigma(pre[2]);\n        const double chat = std::tanh(pre[3]);",
+     "const double f = sigma(pre[3]);\n        const double in = sigma(pre[1]);\n        const double o = sigma(pre[2]);\n        const double chat = std::tanh(pre[0]);"),
+    ("lstm: feedback term dropped", "pre[g] = A[row * nt + t] + u + (bias", "pre[g] = A[row * nt + t] + (bias"),
+    ("lstm: feedback matrix read transposed", "u += static_cast<double>(U[row * d + col]) * hprev[col];", "u += static_cast<double>(U[(static_cast<size_t>(g) * d + col) * d + i]) * hprev[col];"),
+    ("lstm: feedback uses the step's own partial output", "        hnew[i] = o * std::tanh(c[i]);\n      }", "        hnew[i] = o * std::tanh(c[i]);\n        hprev[i] = hnew[i];\n      }"),
+    ("lstm: feedback frozen at the start of the block", "        hprev[i] = hnew[i];\n        hout[(t0 + t) * d + i] = hnew[i];", "        if (t == nt - 1) hprev[i] = hnew[i];\n        hout[(t0 + t) * d + i] = hnew[i];"),
+    ("lstm: bias dropped", "+ u + (bias ? static_cast<double>(bias[row]) : 0.0);", "+ u;"),
+    ("lstm: bias added twice", "+ u + (bias ? static_cast<double>(bias[row]) : 0.0);", "+ u + 2.0 * (bias ? static_cast<double>(bias[row]) : 0.0);"),
+    ("lstm: input products of a block use the block's first input", "for (int t = 0; t < nt; ++t) acc[t] += w * xin[(t0 + t) * d + col];", "for (int t = 0; t < nt; ++t) acc[t] += w * xin[t0 * d + col];"),
+    ("lstm: input matrix read transposed", "const double w = static_cast<double>(W[static_cast<size_t>(row) * d + col]);", "const double w = static_cast<double>(W[(static_cast<size_t>(row / d) * d + col) * d + row % d]);"),
+    ("lstm: initial h ignored", "hp[i] = h_init ? h_init[static_cast<size_t>(l) * d + i] : 0.0;", "hp[i] = 0.0;"),
+    ("lstm: initial c ignored", "c[i] = c_init ? c_init[static_cast<size_t>(l) * d + i] : 0.0;\n      hp[i]", "c[i] = 0.0;\n      hp[i]"),
+    ("lstm: every layer reads the external input", "    cur.swap(nxt);\n  }\n  if (n) std::memcpy(h, cur.data(), n * sizeof(double));\n  return 0;\n}\n\n// Brute force: one LSTM layer",
+     "    if (l == n_layers - 1) cur.swap(nxt);\n  }\n  if (n) std::memcpy(h, cur.data(), n * sizeof(double));\n  return 0;\n}\n\n// Brute force: one LSTM layer"),
+    ("lstm step function: feedback of the forget gate dropped", "1.0 / (1.0 + std::exp(-(zf + yf + bf)));", "1.0 / (1.0 + std::exp(-(zf + bf)));"),
+    ("lstm step function: input gate bias from the output gate", "1.0 / (1.0 + std::exp(-(zi + yi + bi)));", "1.0 / (1.0 + std::exp(-(zi + yi + bo)));"),
     ("projection transposed", "static_cast<double>(P[static_cast<size_t>(i) * d_in + j])", "static_cast<double>(P[(static_cast<size_t>(j) * d_out + i) % (static_cast<size_t>(d_in) * d_out)])"),
 ]
 
@@ -84,6 +106,18 @@ BATTERY = [
     pins.test_fp8_code_values_follow_the_format,
     pins.test_fp8_weights_equal_their_fp32_values_bitwise,
     pins.test_fp8_row_scales_are_applied_per_row,
+    lambda: [lpins.test_lstm_hand_example(T) for T in (1, 2, 4)],
+    lpins.test_lstm_step_hand_example,
+    lambda: lpins.test_lstm_blocked_equals_bruteforce_bitwise(2, 2, 5, 11, 4, False),
+    lambda: lpins.test_lstm_blocked_equals_bruteforce_bitwise(3, 3, 4, 20, 16, True),
+    lpins.test_lstm_all_zero_weights_halve_the_cell,
+    lpins.test_lstm_closed_input_gate_and_open_forget_gate_keep_the_cell,
+    lpins.test_lstm_closed_forget_gate_and_open_input_gate_give_the_candidate,
+    lpins.test_scalar_lstm_iterated_with_math_functions,
+    lpins.test_lstm_without_feedback_against_library_product_and_solved_recurrence,
+    lpins.test_lstm_feedback_products_against_library_product,
+    lpins.test_lstm_stack_feeds_h_to_the_next_layer,
+    lpins.test_lstm_chunk_chaining_equals_one_call,
 ]
 
 
