@@ -20,7 +20,9 @@ b+1 starts (no look-ahead: the T-step latency of Section 3 of the paper).
 Prints ONE JSON line.  `sweep` lists the other block sizes of the headline
 workload, `c5_sweep` the bf16 matrix-core configuration (8-layer QRNN, d = 4096,
 T = 16, 64, 256), `cache_resident_configs` the two configurations whose weights
-fit the Infinity Cache, priced against a read probe on resident data;
+fit the Infinity Cache, priced against a read probe on resident data,
+`lstm_comparator` the paper's comparison network (Eq. 1, Section 3.1) on the same
+harness: its speed-up with T levels off below 2;
 `cpu_baseline` is the CPU oracle timed on this machine's host cores on a bounded
 sample.  Counter figures (`traffic`, `mfma_busy_pct`) are read from the rocprofv3
 summaries under profiles/ (profiles/INDEX.md), which were made with this file.
@@ -373,6 +375,42 @@ def main():
             del so
             torch.cuda.empty_cache()
 
+    # ---- the paper's comparison network (Eq. 1) on the same harness: an LSTM's feedback products cannot be
+    # blocked, so processing T steps at a time saves at most the input products' half of the weight traffic
+    # (Section 3.1) -- its speed-up over T = 1 levels off below 2 where the SRU's keeps growing
+    lstm_rows = []
+    if not args.no_sweep and cfg.name.startswith("C4") and args.flags == 0 and not args.packed:
+        for lc in wl.LSTM_CONFIGS:
+            inp = wl.make_lstm_inputs(lc)
+            Wd = [torch.from_numpy(w).to(dev) for w in inp["W"]]
+            Ud = [torch.from_numpy(u).to(dev) for u in inp["U"]]
+            xd = torch.from_numpy(inp["x"]).to(dev)
+            del inp
+            base = None
+            for T_ in lc.Ts:
+                ws = ss.Workspace(ss.load_library().lstm_workspace_bytes(lc.n_layers, lc.d, T_), dev)
+                times = []
+                for i in range(1 + 3):
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    ss.lstm_forward(Wd, Ud, None, xd, T=T_, workspace=ws)
+                    torch.cuda.synchronize()
+                    if i:
+                        times.append(time.perf_counter() - t0)
+                sec = sorted(times)[len(times) // 2]
+                sps = lc.L / sec
+                base = base or sps
+                gbps = lc.algorithmic_bytes_per_step(T_) * sps / 1e9
+                resident = lc.n_layers * lc.weight_bytes_per_layer() < 256e6
+                lstm_rows.append({"workload": lc.name, "T": T_, "steps_per_s": round(sps, 1), "ms_per_pass": round(sec * 1e3, 3),
+                                  "speedup_vs_T1": round(sps / base, 3),
+                                  "us_per_step_and_layer": round(sec * 1e6 / lc.L / lc.n_layers, 2),
+                                  "algorithmic_GBps": round(gbps, 1),
+                                  "frac_hbm_peak": None if resident else round(gbps / HBM_PEAK_GBS, 4),
+                                  "passes": "median of 3"})
+            del Wd, Ud, xd
+            torch.cuda.empty_cache()
+
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -424,7 +462,7 @@ def main():
                    "weights": head["weights"], "flags": args.flags},
         "achieved_hbm_GBps": head["algorithmic_GBps"], "frac_hbm_peak": head["frac_hbm_peak"],
         "roofline": roofline, "roofline_streaming": roofline_streaming, "read_probe": probe,
-        "sweep": sweep, "c5_sweep": c5_sweep, "cache_resident_configs": others,
+        "sweep": sweep, "c5_sweep": c5_sweep, "cache_resident_configs": others, "lstm_comparator": lstm_rows,
         "cpu_baseline": cpu, "setup_s": round(t_gen, 1),
     }
     print(json.dumps(out))

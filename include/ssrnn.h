@@ -172,6 +172,35 @@ int qrnn_forward(const void* const* W, const float* const* bias, const float* x,
                  long L, int T, int k, int wdtype, int flags, void* workspace,
                  size_t workspace_bytes, void* stream);
 
+/* Stacked LSTM forward, Eq. 1 per layer: the network the paper compares SRU and
+ * QRNN with, run as its Section 3.1 describes.
+ *   f = sigma(W_f x_t + U_f h_{t-1} + b_f);  i, o likewise;
+ *   chat = tanh(W_c x_t + U_c h_{t-1} + b_c);
+ *   c_t = f*c_{t-1} + i*chat;  h_t = o*tanh(c_t).
+ * The products with the input are formed for min(T, 16) steps in one pass over
+ * W; the products with h_{t-1} take one pass over U per time step, whatever T
+ * is -- which is the paper's point: blocking can at best halve an LSTM's weight
+ * traffic.  fp32 only.
+ * W[l], U[l] [4d x d] row-major, rows [0,d) = f, [d,2d) = i, [2d,3d) = o,
+ *            [3d,4d) = chat (the order of Eq. 1).
+ * bias       NULL (all zero), or host array whose entry l is NULL or [4d].
+ * x          [L x d] input of layer 0;  h  out [L x d], the top layer's output
+ *            (must not overlap x).
+ * h_init, c_init  [n_layers x d], or NULL for zeros.
+ * h_final, c_final  out [n_layers x d]: every layer's h and c after the last
+ *            step; may alias h_init / c_init.
+ * flags      0.  workspace: lstm_workspace_bytes(n_layers, d, T) bytes, 256-byte
+ *            aligned, contents neither expected nor preserved.
+ * d >= 1 (any width; rows that are a multiple of 4 values in 16-byte aligned
+ * buffers take the fast path), n_layers >= 1, L >= 0, T >= 1.  Errors as for
+ * sru_forward.  Asynchronous on `stream`; kernel launches only. */
+size_t lstm_workspace_bytes(int n_layers, int d, int T);
+int lstm_forward(const float* const* W, const float* const* U,
+                 const float* const* bias, const float* x, const float* h_init,
+                 const float* c_init, float* h, float* h_final, float* c_final,
+                 int n_layers, int d, long L, int T, int flags, void* workspace,
+                 size_t workspace_bytes, void* stream);
+
 /* y[L x d_out] = feat[L x d_in] * P^T, P row-major [d_out x d_in]; no bias, no
  * activation.  The input projection of the ASR-shaped benchmark workload
  * (40-dim features -> d); not part of the paper's method. */

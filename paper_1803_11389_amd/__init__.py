@@ -24,7 +24,7 @@ REVERSE = 1 << 11
 # every symbol include/ssrnn.h declares, then those of include/ssrnn_probe.h (measurement aids)
 EXPORTS = ("ssrnn_version", "ssrnn_last_error", "ssrnn_workspace_bytes", "sru_forward",
            "qrnn_forward", "ssrnn_linear_forward", "ssrnn_packed_weight_bytes", "ssrnn_pack_weights",
-           "ssrnn_weight_bytes", "sru_forward_noalloc")
+           "ssrnn_weight_bytes", "sru_forward_noalloc", "lstm_workspace_bytes", "lstm_forward")
 PROBE_EXPORTS = ("ssrnn_read_probe",)
 NOALLOC_SCRATCH_BYTES = 32 << 20   # SSRNN_NOALLOC_SCRATCH_BYTES of include/ssrnn.h
 
@@ -66,6 +66,10 @@ def load_library():
     lib.ssrnn_packed_weight_bytes.argtypes = [ip] * 3
     lib.ssrnn_pack_weights.restype = ip
     lib.ssrnn_pack_weights.argtypes = [vp, vp, ip, ip, ip, vp]
+    lib.lstm_workspace_bytes.restype = sz
+    lib.lstm_workspace_bytes.argtypes = [ip] * 3
+    lib.lstm_forward.restype = ip
+    lib.lstm_forward.argtypes = [vp] * 9 + [ip, ip, lp, ip, ip, vp, sz, vp]
     lib.ssrnn_read_probe.restype = ip
     lib.ssrnn_read_probe.argtypes = [vp, ip, sz, ip, vp, vp]
     _lib = lib
@@ -235,6 +239,40 @@ def sru_forward(W: List, bias: Optional[List], x, c_init=None, *, T: int, flags:
                          int(flags), workspace.buf.data_ptr(), workspace.nbytes, _stream_handle(stream))
     _check(rc)
     return h, c_final
+
+
+def lstm_forward(W: List, U: List, bias: Optional[List], x, h_init=None, c_init=None, *, T: int, flags: int = 0,
+                 workspace: Optional[Workspace] = None, stream=None):
+    """lstm_forward of include/ssrnn.h (the paper's comparison network, Eq. 1).  W, U: lists of [4d, d] fp32
+    device tensors; bias: None or list of None / [4d]; x: [L, d] fp32.  Returns (h, h_final, c_final)."""
+    import torch
+    lib = load_library()
+    n_layers = len(W)
+    if len(U) != n_layers:
+        raise ValueError("W and U must have one matrix per layer each")
+    d = W[0].shape[1]
+    for w, u in zip(W, U):
+        _req(w, "W[l]", (4 * d, d), torch.float32)
+        _req(u, "U[l]", (4 * d, d), torch.float32)
+    _req(x, "x", None, torch.float32)
+    L = x.shape[0]
+    if x.dim() != 2 or x.shape[1] != d:
+        raise ValueError("x must be [L, d]")
+    _req(h_init, "h_init", (n_layers, d), torch.float32)
+    _req(c_init, "c_init", (n_layers, d), torch.float32)
+    if bias is not None:
+        for b in bias:
+            _req(b, "bias[l]", (4 * d,), torch.float32)
+    h = torch.empty((L, d), dtype=torch.float32, device=x.device)
+    h_final = torch.empty((n_layers, d), dtype=torch.float32, device=x.device)
+    c_final = torch.empty((n_layers, d), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = Workspace(lib.lstm_workspace_bytes(n_layers, d, int(T)), x.device)
+    wt, ut, bt = _ptr_table(W), _ptr_table(U), _ptr_table(bias)
+    rc = lib.lstm_forward(wt, ut, bt, _p(x), _p(h_init), _p(c_init), _p(h), _p(h_final), _p(c_final), n_layers, d, L,
+                          int(T), int(flags), workspace.buf.data_ptr(), workspace.nbytes, _stream_handle(stream))
+    _check(rc)
+    return h, h_final, c_final
 
 
 def sru_forward_noalloc(W: List, bias: Optional[List], x, c_init, h, c_final, *, T: int, flags: int = 0, stream=None):

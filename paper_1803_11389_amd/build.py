@@ -19,7 +19,7 @@ LIB = os.path.join(HERE, "libssrnn.so")
 SOURCES = [
     "ssrnn.hip", "launch_valu.hip", "launch_mfma_lds.hip",
     "launch_mfma_packed_f32.hip", "launch_mfma_packed_bf16.hip", "launch_mfma_packed_fp8.hip",
-    "launch_mfma_xlds_f32.hip", "launch_mfma_xlds_bf16.hip", "launch_mfma_xlds_fp8.hip",
+    "launch_mfma_xlds_f32.hip", "launch_mfma_xlds_bf16.hip", "launch_mfma_xlds_fp8.hip", "launch_lstm.hip",
 ]
 
 HIPCC_FLAGS = [

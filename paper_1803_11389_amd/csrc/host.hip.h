@@ -58,6 +58,13 @@ int launch_mfma_xlds_bf16(const Plan& p, const StageBatch& s, int nstage, hipStr
 int launch_mfma_xlds_fp8(const Plan& p, const StageBatch& s, int nstage, hipStream_t st);
 int launch_split_epilogue(const Plan& p, const StageBatch& s, int nstage, hipStream_t st);
 
+// LSTM comparator (launch_lstm.hip): what lstm_workspace_bytes and lstm_forward of the C ABI forward to.
+size_t lstm_workspace_bytes_impl(int n_layers, int d, int T);
+int lstm_forward_impl(const float* const* W, const float* const* U, const float* const* bias, const float* x,
+                      const float* h_init, const float* c_init, float* h, float* h_final, float* c_final,
+                      int n_layers, int d, long L, int T, int flags, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
 // Geometry the planner needs from the kernel headers without including them.
 int valu_max_waves();
 int valu_max_t();

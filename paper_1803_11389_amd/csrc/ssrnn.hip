@@ -635,7 +635,7 @@ void* static_scratch(int* status) {
 
 extern "C" {
 
-int ssrnn_version(void) { return 400; }   // 0.4.0: 64-feature matrix-core kernel, per-call geometry options
+int ssrnn_version(void) { return 410; }   // 0.4.1: 8-bit weights in the 64-feature kernel, input staging inside the stage launches, LSTM comparator
 
 const char* ssrnn_last_error(void) { return g_last_error.c_str(); }
 
@@ -676,6 +676,16 @@ int qrnn_forward(const void* const* W, const float* const* bias, const float* x,
                  size_t workspace_bytes, void* stream) {
   return forward(CELL_QRNN, W, bias, x, c_init, xhist_init, h, c_final, xhist_final, n_layers, d, L, T, k,
                  wdtype, flags, workspace, workspace_bytes, stream);
+}
+
+size_t lstm_workspace_bytes(int n_layers, int d, int T) { return lstm_workspace_bytes_impl(n_layers, d, T); }
+
+int lstm_forward(const float* const* W, const float* const* U, const float* const* bias, const float* x,
+                 const float* h_init, const float* c_init, float* h, float* h_final, float* c_final,
+                 int n_layers, int d, long L, int T, int flags, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  return lstm_forward_impl(W, U, bias, x, h_init, c_init, h, h_final, c_final, n_layers, d, L, T, flags,
+                           workspace, workspace_bytes, stream);
 }
 
 int ssrnn_linear_forward(const float* P, const float* feat, float* y, int d_out, int d_in, long L,

@@ -59,3 +59,13 @@ def max_abs(a, b):
     a = np.asarray(a, np.float64)
     b = np.asarray(b, np.float64)
     return float(np.max(np.abs(a - b))) if a.size else 0.0
+
+
+def gpu_lstm(W, U, bias, x, h_init=None, c_init=None, T=1):
+    import torch
+    import paper_1803_11389_amd as ss
+    f32 = lambda a: None if a is None else to_dev(np.asarray(a, np.float32))
+    bd = None if bias is None else [f32(b) for b in bias]
+    h, hf, cf = ss.lstm_forward([f32(w) for w in W], [f32(u) for u in U], bd, f32(x), f32(h_init), f32(c_init), T=T)
+    torch.cuda.synchronize()
+    return h.cpu().numpy(), hf.cpu().numpy(), cf.cpu().numpy()

@@ -100,6 +100,36 @@ def test_bad_arguments_fail_on_the_host(lib):
     assert lib.ssrnn_read_probe(tab, 1, 1024, 0, None, None) == 1
 
 
+def test_lstm_bad_arguments_fail_on_the_host(lib):
+    fake = ctypes.c_void_p(0x1000)     # never dereferenced: every call below fails validation first
+    tab = (ctypes.c_void_p * 1)(0x1000)
+    args = dict(W=tab, U=tab, bias=None, x=fake, h_init=None, c_init=None, h=fake, h_final=fake, c_final=fake,
+                n_layers=1, d=128, L=8, T=4, flags=0, ws=fake, ws_bytes=1 << 20, stream=None)
+
+    def call(**kw):
+        a = dict(args, **kw)
+        return lib.lstm_forward(a["W"], a["U"], a["bias"], a["x"], a["h_init"], a["c_init"], a["h"], a["h_final"],
+                                a["c_final"], a["n_layers"], a["d"], a["L"], a["T"], a["flags"], a["ws"], a["ws_bytes"],
+                                a["stream"])
+
+    assert call(W=None) == 1 and b"NULL" in lib.ssrnn_last_error()
+    assert call(U=None) == 1
+    assert call(U=(ctypes.c_void_p * 1)(None)) == 1
+    assert call(h_final=None) == 1 and call(c_final=None) == 1
+    assert call(x=None) == 1 and call(h=None) == 1
+    assert call(n_layers=0) == 1 and call(d=0) == 1 and call(L=-1) == 1 and call(T=0) == 1
+    assert call(flags=1) == 1
+    assert call(d=1 << 17) == 2
+    assert call(ws=None) == 1
+    assert call(ws=ctypes.c_void_p(0x1010)) == 1                 # misaligned
+    assert call(ws_bytes=512) == 3 and b"needed" in lib.ssrnn_last_error()
+    need = lib.lstm_workspace_bytes(2, 1024, 64)
+    # two copies of the layers' h, the input products of 16 steps, two hand-off blocks of 16 steps
+    assert need >= 2 * 2 * 1024 * 4 + 16 * 4 * 1024 * 4 + 2 * 16 * 1024 * 4
+    assert lib.lstm_workspace_bytes(2, 1024, 64) == lib.lstm_workspace_bytes(2, 1024, 16)
+    assert lib.lstm_workspace_bytes(0, 1024, 4) == 0 and lib.lstm_workspace_bytes(1, 0, 4) == 0 and lib.lstm_workspace_bytes(1, 8, 0) == 0
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch):
     monkeypatch.setattr(ss, "_lib", None)
     monkeypatch.setattr(ss, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libssrnn.so"))

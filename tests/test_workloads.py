@@ -96,3 +96,23 @@ def test_fp8_quantizer_scales_rows_to_the_format_maximum():
     blob = q.blob()
     assert blob.size == 512 + 48 and np.array_equal(blob[:480], q.q.reshape(-1)) and not blob[480:512].any()
     np.testing.assert_array_equal(blob[512:].view(np.float32), q.scale)
+
+
+def test_lstm_comparator_inputs():
+    """The comparison network's inputs: shapes, bounds, determinism, distinct draws for W and U, and the
+    byte count per step that the bench prices it with (U every step, W once per block of up to 16 steps)."""
+    lc = wl.LSTM_CONFIGS[1]                     # the paper's large LSTM: one layer of width 700
+    a, b = wl.make_lstm_inputs(lc, L=5), wl.make_lstm_inputs(lc, L=5)
+    assert len(a["W"]) == len(a["U"]) == lc.n_layers
+    assert a["W"][0].shape == a["U"][0].shape == (4 * lc.d, lc.d) and a["x"].shape == (5, lc.d)
+    assert a["W"][0].dtype == a["x"].dtype == np.float32
+    np.testing.assert_array_equal(a["W"][0], b["W"][0])
+    np.testing.assert_array_equal(a["x"], b["x"])
+    assert not np.array_equal(a["W"][0], a["U"][0])
+    assert np.abs(a["W"][0]).max() <= 1.0 / np.sqrt(lc.d) and np.abs(a["U"][0]).max() <= 1.0 / np.sqrt(lc.d)
+    big = wl.LSTM_CONFIGS[0]
+    per_matrix = 4 * big.d * big.d * 4
+    assert big.weight_bytes_per_layer() == 2 * per_matrix
+    small = 14 * big.d * 4 * big.n_layers
+    assert big.algorithmic_bytes_per_step(1) == big.n_layers * 2 * per_matrix + small
+    assert big.algorithmic_bytes_per_step(64) == big.algorithmic_bytes_per_step(16) == big.n_layers * per_matrix * 17 / 16 + small

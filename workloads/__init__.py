@@ -197,6 +197,49 @@ EXTRA: Tuple[Workload, ...] = (
 )
 
 
+# The paper's comparison network (Eq. 1, Section 3.1), for the comparator rows of the bench: an LSTM stack
+# with as many layers as configuration 4 and about its weight bytes (8 d^2 values per layer at d = 2560
+# against 3 d^2 at d = 4096), and the paper's own "large" LSTM (one layer of width 700, 1,024 steps,
+# Section 4).  W and U ~ U(+-1/sqrt(d)), biases zero, x ~ N(0, 1).
+@dataclass(frozen=True)
+class LstmWorkload:
+    name: str
+    n_layers: int
+    d: int
+    L: int
+    Ts: Tuple[int, ...]
+    index: int
+
+    @property
+    def seed(self) -> int:
+        return BASE_SEED + self.index
+
+    def weight_bytes_per_layer(self) -> int:
+        return 2 * 4 * self.d * self.d * 4
+
+    def algorithmic_bytes_per_step(self, T: int, input_block: int = 16) -> float:
+        """Per time step and stack: U once per step, W once per min(T, input_block) steps (the steps one
+        pass over W serves), and per layer the input row read, the output row written, the 4d input
+        products written and read, h_{t-1} and c read and written."""
+        per_layer = 4 * self.d * self.d * 4 * (1.0 + 1.0 / min(T, input_block)) + (2 + 8 + 4) * self.d * 4
+        return self.n_layers * per_layer
+
+
+LSTM_CONFIGS: Tuple[LstmWorkload, ...] = (
+    LstmWorkload("L1_lstm8_d2560", 8, 2560, 256, (1, 2, 4, 16, 64), index=8),
+    LstmWorkload("L2_lstm1_d700_paper_large", 1, 700, 1024, (1, 4, 16, 64), index=9),
+)
+
+
+def make_lstm_inputs(wl: LstmWorkload, L: Optional[int] = None):
+    """Returns a dict: W, U (lists of [4d, d] float32, rows f | i | o | c-hat), x [L, d] float32."""
+    L = wl.L if L is None else L
+    bound = 1.0 / math.sqrt(wl.d)
+    return {"W": [uniform(wl.seed, TID_W0 + 2 * l, (4 * wl.d, wl.d), bound) for l in range(wl.n_layers)],
+            "U": [uniform(wl.seed, TID_W0 + 2 * l + 1, (4 * wl.d, wl.d), bound) for l in range(wl.n_layers)],
+            "x": normal(wl.seed, TID_X, (L * wl.d,)).reshape(L, wl.d)}
+
+
 def by_name(prefix: str) -> Workload:
     for c in CONFIGS + EXTRA:
         if c.name.startswith(prefix):
