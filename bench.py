@@ -97,6 +97,8 @@ def parse_args():
     ap.add_argument("--packed", action="store_true",
                     help="pre-pack the weights (ssrnn_pack_weights, outside the timed region) and run every block size on the matrix-core kernel")
     ap.add_argument("--cpu-sample-steps", type=int, default=0, help="time steps of the CPU sample (0 = auto)")
+    ap.add_argument("--lstm-only", default="", metavar="NAME",
+                    help="time only the comparison network NAME (L1, L2) at block size --T (for profiling)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB three times and exit: the reference "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -252,6 +254,46 @@ def read_probe_rate(ss, torch, bufs, per_launch, reps_bytes=8e9):
     return best
 
 
+def lstm_comparator_rows(ss, wl, torch, dev, configs, only_T=None):
+    """The paper's comparison network (Eq. 1) timed like the stacks above.  An LSTM's feedback products
+    cannot be blocked, so processing T steps at a time saves at most the input products' half of the weight
+    traffic (Section 3.1): its speed-up over T = 1 levels off below 2 where the SRU's keeps growing."""
+    rows = []
+    lib = ss.load_library()
+    for lc in configs:
+        inp = wl.make_lstm_inputs(lc)
+        Wd = [torch.from_numpy(w).to(dev) for w in inp["W"]]
+        Ud = [torch.from_numpy(u).to(dev) for u in inp["U"]]
+        xd = torch.from_numpy(inp["x"]).to(dev)
+        del inp
+        base = None
+        for T_ in (lc.Ts if only_T is None else (only_T,)):
+            ws = ss.Workspace(lib.lstm_workspace_bytes(lc.n_layers, lc.d, T_), dev)
+            times = []
+            for i in range(1 + 3):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ss.lstm_forward(Wd, Ud, None, xd, T=T_, workspace=ws)
+                torch.cuda.synchronize()
+                if i:
+                    times.append(time.perf_counter() - t0)
+            sec = sorted(times)[len(times) // 2]
+            sps = lc.L / sec
+            base = base or sps
+            gbps = lc.algorithmic_bytes_per_step(T_) * sps / 1e9
+            resident = lc.n_layers * lc.weight_bytes_per_layer() < 256e6
+            rows.append({"workload": lc.name, "T": T_, "steps_per_s": round(sps, 1), "ms_per_pass": round(sec * 1e3, 3),
+                         "speedup_vs_T1": round(sps / base, 3) if only_T is None else None,
+                         "us_per_step_and_layer": round(sec * 1e6 / lc.L / lc.n_layers, 2),
+                         "algorithmic_bytes_per_step": int(lc.algorithmic_bytes_per_step(T_)),
+                         "algorithmic_GBps": round(gbps, 1),
+                         "frac_hbm_peak": None if resident else round(gbps / HBM_PEAK_GBS, 4),
+                         "passes": "median of 3"})
+        del Wd, Ud, xd
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -278,6 +320,11 @@ def main():
         print(json.dumps({"copy_probe_MiB": args.copy_probe, "bytes_read_per_copy": n * 4, "bytes_written_per_copy": n * 4}))
         return
     ss.load_library()
+    if args.lstm_only:
+        lc = [c for c in wl.LSTM_CONFIGS if c.name.startswith(args.lstm_only)]
+        assert lc, f"no LSTM workload named {args.lstm_only}"
+        print(json.dumps({"lstm_comparator": lstm_comparator_rows(ss, wl, torch, dev, lc[:1], only_T=args.T)}))
+        return
     index_rows = profile_index()
     if args.headline_only:
         args.no_sweep = args.no_cpu = True
@@ -375,41 +422,10 @@ def main():
             del so
             torch.cuda.empty_cache()
 
-    # ---- the paper's comparison network (Eq. 1) on the same harness: an LSTM's feedback products cannot be
-    # blocked, so processing T steps at a time saves at most the input products' half of the weight traffic
-    # (Section 3.1) -- its speed-up over T = 1 levels off below 2 where the SRU's keeps growing
+    # ---- the paper's comparison network (Eq. 1) on the same harness
     lstm_rows = []
     if not args.no_sweep and cfg.name.startswith("C4") and args.flags == 0 and not args.packed:
-        for lc in wl.LSTM_CONFIGS:
-            inp = wl.make_lstm_inputs(lc)
-            Wd = [torch.from_numpy(w).to(dev) for w in inp["W"]]
-            Ud = [torch.from_numpy(u).to(dev) for u in inp["U"]]
-            xd = torch.from_numpy(inp["x"]).to(dev)
-            del inp
-            base = None
-            for T_ in lc.Ts:
-                ws = ss.Workspace(ss.load_library().lstm_workspace_bytes(lc.n_layers, lc.d, T_), dev)
-                times = []
-                for i in range(1 + 3):
-                    torch.cuda.synchronize()
-                    t0 = time.perf_counter()
-                    ss.lstm_forward(Wd, Ud, None, xd, T=T_, workspace=ws)
-                    torch.cuda.synchronize()
-                    if i:
-                        times.append(time.perf_counter() - t0)
-                sec = sorted(times)[len(times) // 2]
-                sps = lc.L / sec
-                base = base or sps
-                gbps = lc.algorithmic_bytes_per_step(T_) * sps / 1e9
-                resident = lc.n_layers * lc.weight_bytes_per_layer() < 256e6
-                lstm_rows.append({"workload": lc.name, "T": T_, "steps_per_s": round(sps, 1), "ms_per_pass": round(sec * 1e3, 3),
-                                  "speedup_vs_T1": round(sps / base, 3),
-                                  "us_per_step_and_layer": round(sec * 1e6 / lc.L / lc.n_layers, 2),
-                                  "algorithmic_GBps": round(gbps, 1),
-                                  "frac_hbm_peak": None if resident else round(gbps / HBM_PEAK_GBS, 4),
-                                  "passes": "median of 3"})
-            del Wd, Ud, xd
-            torch.cuda.empty_cache()
+        lstm_rows = lstm_comparator_rows(ss, wl, torch, dev, wl.LSTM_CONFIGS)
 
     cpu = None
     if not args.no_cpu:
