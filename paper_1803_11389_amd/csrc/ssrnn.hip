@@ -8,8 +8,10 @@
 // independent of each other: the wavefront schedule runs them as one launch
 // (step s = b + l, at most n_layers stages wide), the per-stage schedule runs
 // them one launch each in streaming order (block b through all layers before
-// block b+1 starts).  Both read every layer's weights once per block and give
-// the same bits.  Layer l's output block is handed to layer l+1 through a
+// block b+1 starts).  Both read every layer's weights once per block; their
+// results are equal up to fp32 re-association, and bit for bit wherever the same
+// kernel instance serves both (the number of stages in a launch can decide the
+// instance).  Layer l's output block is handed to layer l+1 through a
 // [(k-1)+T] x d buffer in the workspace whose first k-1 rows hold the tail of
 // the previous block (the QRNN's causal window, Eq. 3); there are two such
 // buffers per layer, used by even and odd blocks, because block b+1 is written
