@@ -242,7 +242,7 @@ def sru_forward(W: List, bias: Optional[List], x, c_init=None, *, T: int, flags:
 
 
 def lstm_forward(W: List, U: List, bias: Optional[List], x, h_init=None, c_init=None, *, T: int, flags: int = 0,
-                 workspace: Optional[Workspace] = None, stream=None):
+                 h=None, h_final=None, c_final=None, workspace: Optional[Workspace] = None, stream=None):
     """lstm_forward of include/ssrnn.h (the paper's comparison network, Eq. 1).  W, U: lists of [4d, d] fp32
     device tensors; bias: None or list of None / [4d]; x: [L, d] fp32.  Returns (h, h_final, c_final)."""
     import torch
@@ -263,9 +263,15 @@ def lstm_forward(W: List, U: List, bias: Optional[List], x, h_init=None, c_init=
     if bias is not None:
         for b in bias:
             _req(b, "bias[l]", (4 * d,), torch.float32)
-    h = torch.empty((L, d), dtype=torch.float32, device=x.device)
-    h_final = torch.empty((n_layers, d), dtype=torch.float32, device=x.device)
-    c_final = torch.empty((n_layers, d), dtype=torch.float32, device=x.device)
+    if h is None:
+        h = torch.empty((L, d), dtype=torch.float32, device=x.device)
+    if h_final is None:
+        h_final = torch.empty((n_layers, d), dtype=torch.float32, device=x.device)
+    if c_final is None:
+        c_final = torch.empty((n_layers, d), dtype=torch.float32, device=x.device)
+    _req(h, "h", (L, d), torch.float32)
+    _req(h_final, "h_final", (n_layers, d), torch.float32)
+    _req(c_final, "c_final", (n_layers, d), torch.float32)
     if workspace is None:
         workspace = Workspace(lib.lstm_workspace_bytes(n_layers, d, int(T)), x.device)
     wt, ut, bt = _ptr_table(W), _ptr_table(U), _ptr_table(bias)

@@ -110,3 +110,69 @@ def test_lstm_rejects_bad_arguments():
     with pytest.raises(ss.SsrnnError):
         ss.lstm_forward(W, W, None, x, T=0)
     torch.cuda.synchronize()
+
+
+def _random_cases(n=24, seed=20241201):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = int(rng.choice([1, 3, 4, 12, 60, 64, 96, 250, 256, 260, 350, 384, 512, 700, 1000, 1024, 1536]))
+        n_layers = int(rng.integers(1, 4))
+        T = int(rng.choice([1, 2, 3, 5, 8, 15, 16, 17, 33]))
+        L = int(rng.integers(1, 3 * min(T, 16) + 4))
+        cases.append((d, n_layers, L, T, bool(rng.integers(0, 2)), int(rng.integers(0, 1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(), ids=lambda c: f"d{c[0]}-n{c[1]}-L{c[2]}-T{c[3]}{'-b' if c[4] else ''}")
+def test_lstm_random_shape_against_oracle(case):
+    d, n_layers, L, T, bias, seed = case
+    print(f"lstm case {case}", flush=True)
+    W, U, b, x, h0, c0 = _inputs(seed, n_layers, d, L, scale=2.0, bias=bias)
+    ref = oracle.lstm_forward(W, U, b, x, h_init=h0, c_init=c0, T=T)
+    got = gpu_lstm(W, U, b, x, h0, c0, T=T)
+    for u, r in zip(got, ref):
+        assert u.shape == r.shape and np.all(np.isfinite(u))
+        assert max_abs(u, r) <= TOL, max_abs(u, r)
+
+
+def test_lstm_forward_can_be_recorded_into_a_graph():
+    """lstm_forward only enqueues kernels on the given stream (no memset, no host synchronisation, no
+    allocation), so a call can be captured into a HIP graph: every replay, with new inputs and with eager
+    work in between, gives the eager result bit for bit."""
+    import torch
+    import paper_1803_11389_amd as ss
+    from gpu_util import to_dev
+    d, n_layers, L, T = 256, 2, 19, 4
+    W, U, b, x0, h0, c0 = _inputs(8500, n_layers, d, L)
+    Wd, Ud, bd = [to_dev(w) for w in W], [to_dev(u) for u in U], [to_dev(v) for v in b]
+    x, h_in, c_in = to_dev(x0), to_dev(h0), to_dev(c0)
+    ws = ss.Workspace(ss.load_library().lstm_workspace_bytes(n_layers, d, T))
+    h = torch.empty((L, d), dtype=torch.float32, device="cuda")
+    hf = torch.empty((n_layers, d), dtype=torch.float32, device="cuda")
+    cf = torch.empty((n_layers, d), dtype=torch.float32, device="cuda")
+
+    def call():
+        ss.lstm_forward(Wd, Ud, bd, x, h_in, c_in, T=T, h=h, h_final=hf, c_final=cf, workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(8501)
+    for rep in range(3):
+        x.copy_(to_dev(rng.standard_normal((L, d)).astype(np.float32)))
+        c_in.copy_(to_dev(rng.standard_normal((n_layers, d)).astype(np.float32)))
+        h.zero_(); hf.zero_(); cf.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (h.clone(), hf.clone(), cf.clone())
+        call()                                   # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], h) and torch.equal(got[1], hf) and torch.equal(got[2], cf), rep
+    ref = oracle.lstm_forward(W, U, b, x.cpu().numpy(), h_init=h0, c_init=c_in.cpu().numpy(), T=T)
+    assert max_abs(h.cpu().numpy(), ref[0]) <= TOL and max_abs(cf.cpu().numpy(), ref[2]) <= TOL
