@@ -244,19 +244,24 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
         }
       }
     }
+    if constexpr (WT == W_F32) {
+      // four K-slices of four columns; the gates innermost, so that consecutive MFMAs write different accumulators
+      const floatx4_t bv = bq[q % BQ];
 #pragma unroll
-    for (int g = 0; g < 3; ++g) {
-      if constexpr (WT == W_FP8) {
-        acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(awide[g], bq[q % BQ], acc[g][n], 0, 0, 0);
-      } else if constexpr (WT == W_BF16) {
-        bf16x8_t a;
-        __builtin_memcpy(&a, &aring[slot][u][g * 2 + h], sizeof a);
-        acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[q % BQ], acc[g][n], 0, 0, 0);
-      } else {
-        const floatx4_t av = aring[slot][u][g * 2 + h];
-        const floatx4_t bv = bq[q % BQ];
+      for (int e = 0; e < 4; ++e)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[e], bv[e], acc[g][n], 0, 0, 0);
+        for (int g = 0; g < 3; ++g)
+          acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(aring[slot][u][g * 2 + h][e], bv[e], acc[g][n], 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int g = 0; g < 3; ++g) {
+        if constexpr (WT == W_FP8) {
+          acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(awide[g], bq[q % BQ], acc[g][n], 0, 0, 0);
+        } else {
+          bf16x8_t a;
+          __builtin_memcpy(&a, &aring[slot][u][g * 2 + h], sizeof a);
+          acc[g][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[q % BQ], acc[g][n], 0, 0, 0);
+        }
       }
     }
   };

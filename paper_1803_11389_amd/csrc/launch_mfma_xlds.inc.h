@@ -16,7 +16,8 @@ static int launch_cell(const Plan& p, const StageBatch& s, int nstage, hipStream
     return SSRNN_OK;                                                                             \
   }
   // fp32 weights: from four time tiles on the stage is bound by the matrix cores, where the 16-feature
-  // kernel (no barrier, no LDS reads) measured faster (d = 4096, T = 64: 57.3 against 60.0 us per stage)
+  // kernel (no barrier, no LDS reads) measured the same or faster (d = 4096, us per stage: T = 64 56.8
+  // against 56.1 here, T = 128 101.4 against 108.9)
   SSRNN_XL_CASE(2)
   if constexpr (WT != W_F32) { SSRNN_XL_CASE(4) SSRNN_XL_CASE(8) SSRNN_XL_CASE(16) }
 #undef SSRNN_XL_CASE
