@@ -6,12 +6,13 @@
 
 namespace ssrnn {
 
+// (blocks of up to 16 steps, which the planner sends here for narrow weight types, run on the two-tile instance)
 template <int CELL>
 static int launch_cell(const Plan& p, const StageBatch& s, int nstage, hipStream_t st) {
   constexpr int WT = SSRNN_XL_WT;
   const dim3 grid(p.d / XLDS_F, launch_rows(s, nstage)), block(XLDS_TILES * 64);
 #define SSRNN_XL_CASE(NT_)                                                                       \
-  if (p.nt_tiles == NT_) {                                                                       \
+  if ((p.nt_tiles == 1 ? 2 : p.nt_tiles) == NT_) {                                               \
     hipLaunchKernelGGL((stage_mfma_xlds_kernel<CELL, WT, NT_>), grid, block, 0, st, s, p.d, p.k); \
     return SSRNN_OK;                                                                             \
   }

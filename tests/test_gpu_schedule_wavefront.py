@@ -125,9 +125,12 @@ def test_two_feature_tiles_per_workgroup_give_the_same_bits(cell, k, T, mode, d,
     ("qrnn", 3, 130, 2048, 8, 9, "bf16"),
     ("sru", 1, 24, 4096, 4, 6, "fp8"), ("qrnn", 2, 70, 2048, 8, 8, "fp8"), ("sru", 1, 256, 4096, 4, 4, "fp8"),
     ("qrnn", 3, 130, 2048, 8, 9, "fp8"), ("qrnn", 2, 50, 4096, 4, 5, "fp8"),
+    # narrow weight types reach this kernel with shorter blocks as well (8-bit from 5 steps, bf16 from 9)
+    ("sru", 1, 12, 4096, 4, 6, "fp8"), ("qrnn", 2, 7, 4096, 4, 7, "fp8"), ("qrnn", 2, 16, 2048, 8, 9, "bf16"),
+    ("sru", 1, 9, 4096, 4, 5, "bf16"),
 ])
 def test_long_blocks_of_packed_bf16_weights_on_the_64_feature_kernel(cell, k, T, d, n_layers, nblocks, mode):
-    """17 <= T <= 256, packed bf16 or 8-bit weights and launches wide enough for d/64 workgroups per stage to
+    """Packed bf16 or 8-bit weights, blocks of up to 256 steps and launches wide enough for d/64 workgroups per stage to
     fill the chip: the kernel whose waves own a feature tile each and share the input block through LDS.
     Against the oracle (bf16 bar), against the oracle that rounds the same operand, and against the 16-feature
     kernel on the same inputs (the two sum a row's products in different orders, so not bit for bit)."""
