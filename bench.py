@@ -18,7 +18,8 @@ one launch per stage in streaming order, block b through all layers before block
 b+1 starts (no look-ahead: the T-step latency of Section 3 of the paper).
 
 Prints ONE JSON line.  `sweep` lists the other block sizes of the headline
-workload, `c5_sweep` the bf16 matrix-core configuration (8-layer QRNN, d = 4096,
+workload (each row in the weight layout that is faster there -- row-major, or
+re-tiled once by ssrnn_pack_weights -- with the other layout beside it), `c5_sweep` the bf16 matrix-core configuration (8-layer QRNN, d = 4096,
 T = 16, 64, 256), `cache_resident_configs` the two configurations whose weights
 fit the Infinity Cache, priced against a read probe on resident data,
 `lstm_comparator` the paper's comparison network (Eq. 1, Section 3.1) on the same
@@ -365,9 +366,18 @@ def main():
             if sched == 0 and nstage != nlaunch:
                 ps = stack.row(T, stack.time_median(T, args.flags | ss.SCHED_STAGES, args.packed))
                 r["per_stage_schedule"] = {key: ps[key] for key in ("steps_per_s", "us_per_stage", "frac_hbm_peak")}
+                r["per_stage_schedule"]["weights"] = head["weights"]
             if stack.W_packed is not None and not args.packed:
+                # the one-time weight pre-pack is part of the path: the row shows the layout that is faster at
+                # this block size, the other one beside it
                 pk = stack.row(T, stack.time_median(T, args.flags, True))
-                r["packed"] = {key: pk[key] for key in ("steps_per_s", "us_per_stage", "algorithmic_GBps", "frac_hbm_peak", "TFLOPps")}
+                keys = ("steps_per_s", "ms_per_pass", "us_per_stage", "algorithmic_GBps", "frac_hbm_peak", "TFLOPps")
+                if pk["steps_per_s"] > r["steps_per_s"]:
+                    r["row_major"] = {key: r[key] for key in keys}
+                    r.update({key: pk[key] for key in keys})
+                    r["weights"] = "packed"
+                else:
+                    r["packed"] = {key: pk[key] for key in keys}
             sweep.append(r)
 
     # ---- what a kernel that only reads reaches, in launches of the stage launches' shape and size: eight
