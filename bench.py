@@ -189,9 +189,13 @@ class Stack:
         nstage = cfg.n_layers * ((cfg.L + T - 1) // T)
         steps_s = cfg.L / (ms * 1e-3)
         gbs = cfg.algorithmic_bytes_per_step(T) * steps_s / 1e9
-        return {"T": T, "steps_per_s": round(steps_s, 1), "ms_per_pass": round(ms, 3),
-                "us_per_stage": round(ms * 1e3 / nstage, 2), "algorithmic_GBps": round(gbs, 1),
-                "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "TFLOPps": round(cfg.flops_per_step() * steps_s / 1e12, 2)}
+        tflops = cfg.flops_per_step() * steps_s / 1e12
+        r = {"T": T, "steps_per_s": round(steps_s, 1), "ms_per_pass": round(ms, 3),
+             "us_per_stage": round(ms * 1e3 / nstage, 2), "algorithmic_GBps": round(gbs, 1),
+             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "TFLOPps": round(tflops, 2)}
+        if cfg.wdtype == "f32" and T >= 32:        # near and past the fp32 ridge (T = 39) the matrix cores are the bound
+            r["frac_fp32_mfma_peak"] = round(tflops / FP32_PEAK_TFLOPS, 4)
+        return r
 
 
 def roofline_block(stack, T, ev_ms, flags, packed, index_rows):
@@ -371,7 +375,8 @@ def main():
                 # the one-time weight pre-pack is part of the path: the row shows the layout that is faster at
                 # this block size, the other one beside it
                 pk = stack.row(T, stack.time_median(T, args.flags, True))
-                keys = ("steps_per_s", "ms_per_pass", "us_per_stage", "algorithmic_GBps", "frac_hbm_peak", "TFLOPps")
+                keys = tuple(k for k in r if k in ("steps_per_s", "ms_per_pass", "us_per_stage", "algorithmic_GBps",
+                                                   "frac_hbm_peak", "TFLOPps", "frac_fp32_mfma_peak"))
                 if pk["steps_per_s"] > r["steps_per_s"]:
                     r["row_major"] = {key: r[key] for key in keys}
                     r.update({key: pk[key] for key in keys})
