@@ -176,3 +176,24 @@ def test_lstm_forward_can_be_recorded_into_a_graph():
         assert torch.equal(got[0], h) and torch.equal(got[1], hf) and torch.equal(got[2], cf), rep
     ref = oracle.lstm_forward(W, U, b, x.cpu().numpy(), h_init=h0, c_init=c_in.cpu().numpy(), T=T)
     assert max_abs(h.cpu().numpy(), ref[0]) <= TOL and max_abs(cf.cpu().numpy(), ref[2]) <= TOL
+
+
+def test_lstm_comparator_workloads_against_oracle():
+    """The two workloads the bench times the comparison network on, with the bench's inputs: the paper's large
+    LSTM (one layer of 700, Section 4) over its 1,024 steps, and the first 40 steps of the 8-layer d = 2560 stack."""
+    import workloads as wl
+    small = wl.LSTM_CONFIGS[1]
+    inp = wl.make_lstm_inputs(small)
+    print(f"{small.name}: L={small.L}", flush=True)
+    ref = oracle.lstm_forward(inp["W"], inp["U"], None, inp["x"], T=16)
+    got = gpu_lstm(inp["W"], inp["U"], None, inp["x"], T=16)
+    for u, r in zip(got, ref):
+        assert max_abs(u, r) <= TOL, max_abs(u, r)
+    big = wl.LSTM_CONFIGS[0]
+    inp = wl.make_lstm_inputs(big, L=40)
+    print(f"{big.name}: first 40 steps", flush=True)
+    ref = oracle.lstm_forward(inp["W"], inp["U"], None, inp["x"], T=16)
+    got = gpu_lstm(inp["W"], inp["U"], None, inp["x"], T=16)
+    for u, r in zip(got, ref):
+        assert np.all(np.isfinite(u))
+        assert max_abs(u, r) <= TOL, max_abs(u, r)
