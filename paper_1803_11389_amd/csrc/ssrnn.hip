@@ -644,7 +644,7 @@ void* static_scratch(int* status) {
 
 extern "C" {
 
-int ssrnn_version(void) { return 410; }   // 0.4.1: 8-bit weights in the 64-feature kernel, input staging inside the stage launches, LSTM comparator
+int ssrnn_version(void) { return 500; }   // 0.5.0: 8-bit weights in the 64-feature kernel, input staging inside the stage launches, LSTM comparator
 
 const char* ssrnn_last_error(void) { return g_last_error.c_str(); }
 
