@@ -420,6 +420,17 @@ def main():
             r["traffic"] = int(_num(prow["traffic bytes per launch"])) if prow and _num(prow.get("traffic bytes per launch")) else None
             r["profile"] = ("profiles/" + prow["file"]) if prow else None
             c5_sweep.append(r)
+        # the longest block again on a stream four times as long: with 16 blocks in the sequence the launches
+        # at its two ends (fewer than eight stages) weigh 38 rounds of workgroups for 32 rounds' worth of work
+        import dataclasses
+        long_cfg = dataclasses.replace(c5, L=4 * c5.L)
+        s5.cfg = long_cfg
+        s5.x = torch.from_numpy(wl.normal(c5.seed, wl.TID_X, (long_cfg.L * c5.d,)).reshape(long_cfg.L, c5.d)).to(dev)
+        s5.h = torch.empty((long_cfg.L, c5.d), dtype=torch.float32, device=dev)
+        T_long = max(c5.Ts)
+        rl_ = s5.row(T_long, s5.time_median(T_long, 0, True, passes=3))
+        c5_sweep[-1]["stream_four_times_as_long"] = {"L": long_cfg.L, **{key: rl_[key] for key in
+                                                    ("steps_per_s", "us_per_stage", "frac_hbm_peak", "TFLOPps")}}
         del s5
         torch.cuda.empty_cache()
         for name in ("C2", "C3"):
