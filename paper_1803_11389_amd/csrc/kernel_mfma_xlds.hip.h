@@ -79,7 +79,7 @@ __device__ __forceinline__ void load_to_lds16(const LdsLoadWindow&, char*, int) 
 template <int WT, int NT>
 struct XldsCfg {
   static constexpr int R = NT * 16;                       // time rows of an X tile
-  static_assert(R >= 32, "at least two time tiles");
+  static_assert(R >= 16, "at least one time tile");
   static constexpr int NSUB = (R >= 256) ? 1 : 2;         // k-steps per B-step
   static constexpr int KCOLS = (WT == W_F32) ? 32 : 64;   // weight columns per k-step (fp32, bf16: 128 bytes of a row; 8-bit: 64)
   static constexpr int VEC = (WT == W_F32) ? 4 : 8;       // X elements per 16-byte chunk of the operand copy
@@ -89,7 +89,7 @@ struct XldsCfg {
   static constexpr int NTHREADS = XLDS_TILES * 64;
   static_assert(BSTEP_BYTES % (NTHREADS * 16) == 0, "every thread moves whole 16-byte pieces");
   static constexpr int NCOPY = BSTEP_BYTES / (NTHREADS * 16);   // X pieces a thread requests per B-step
-  static constexpr int PER_KSTEP = NCOPY / NSUB;                 // of which per k-step
+  static constexpr int PER_KSTEP = NCOPY / NSUB;                 // of which per k-step (0: one piece per thread covers both)
   static constexpr int NA = AFR * NSUB;                          // weight fragments a wave requests per B-step
   static constexpr int NFRAG = NSUB * 2 * NT;                    // B fragments (k-step, half, time tile) per B-step
   static constexpr int KSTEPS_PER_ITER = XLDS_NBUF * NSUB;       // k-steps of one loop body
@@ -204,8 +204,11 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
       if (x_m >= d) { x_m -= d; ++x_j; }
     }
   };
-  auto request_x_piece = [&](int buf, int i) {       // piece i lies in k-step (i*256 + tid) / (8*R) = i / PER_KSTEP of the B-step
-    load_to_lds16(xwin, smem + buf * Cfg::BSTEP_BYTES + wave * 1024 + i * (Cfg::NTHREADS * 16), xbase[i / Cfg::PER_KSTEP] + cp_off[i]);
+  auto request_x_piece = [&](int buf, int i) {       // piece i lies in k-step (i*256 + tid) / (8*R) of the B-step
+    int xb;
+    if constexpr (Cfg::PER_KSTEP > 0) xb = xbase[i / Cfg::PER_KSTEP];
+    else xb = (wave * 64 >= 8 * R) ? xbase[NSUB - 1] : xbase[0];      // one tile: waves 0, 1 move the first k-step, 2, 3 the second
+    load_to_lds16(xwin, smem + buf * Cfg::BSTEP_BYTES + wave * 1024 + i * (Cfg::NTHREADS * 16), xb + cp_off[i]);
   };
 
   // ---- weight side: ring of NBUF B-steps of this wave's fragments
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(XLDS_TILES * 64) void stage_mfma_xlds_kernel(const 
   // ---- B fragments: fragment q of a B-step is (k-step q / 2NT, half (q / NT) % 2, time tile q % NT); lane
   // (li, kg) reads time row li of the tile from chunk column 2*kg + half.  They pass through a ring of BQ
   // register sets, BQ-1 reads ahead of the MFMAs that use them.
-  constexpr int BQ = 4;
+  constexpr int BQ = (NFRAG >= 8) ? 4 : 2;
   static_assert(NFRAG % BQ == 0 && NFRAG >= 2 * BQ, "the fragment ring repeats with the B-step");
   using bfrag_t = std::conditional_t<WT == W_F32, floatx4_t, bf16x8_t>;
   bfrag_t bq[BQ];

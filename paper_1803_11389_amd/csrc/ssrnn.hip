@@ -335,14 +335,14 @@ bool plan_mfma(Plan& p, const void* const* W, const float* x, const float* xhist
   // the chip with larger workgroups, a workgroup owns 64 features and shares the input block through LDS
   // (packed weights of any type); launches that kernel does not take may still put 32 features into a
   // workgroup of the packed kernel itself.
-  // Narrow weight types take it for shorter blocks too, on the two-tile instance: its extra matrix-core work is
-  // small next to the weight stream, while per 16-feature workgroup the input block weighs more the fewer
-  // bytes a weight has (d = 4096, us per stage, 16-feature kernel -> this one: 8-bit weights T = 8 8.10 -> 7.86,
-  // T = 12 8.90 -> 8.06, T = 16 9.61 -> 8.28, with k = 2 T = 16 17.7 -> 16.0; bf16 T = 16 16.2 -> 15.9, with
-  // k = 2 31.1 -> 30.8; below these block sizes it measured 1 to 2 % slower).
-  const bool short_blocks_too = p.nt_tiles == 1 && ((p.wdt == SSRNN_FP8 && p.T > 4) || (p.wdt == SSRNN_BF16 && p.T > 8));
-  const int xlds_tiles = short_blocks_too ? 2 : p.nt_tiles;
-  p.xlds = p.packed && xlds_tiles >= 2 && p.ksplit == 1 && p.d % XLDS_F == 0 && xlds_takes(p.wdt, xlds_tiles, ncol) &&
+  // Blocks of up to 16 steps (one time tile) take it from the size on where it measured faster than the
+  // 16-feature kernel; per 16-feature workgroup the input block weighs the more the fewer bytes a weight has
+  // (d = 4096, us per stage, 16-feature kernel -> this one: 8-bit weights T = 8 8.10 -> 7.89, T = 16 9.61 -> 8.31,
+  // T = 4 7.59 -> 7.78; bf16 T = 16 with k = 2 31.05 -> 30.77, T = 8 15.28 -> 15.43; fp32 T = 16 31.85 -> 31.0,
+  // T = 8 30.19 -> 30.15, T = 4 29.63 -> 29.74).
+  const bool short_blocks_too = p.nt_tiles == 1 && p.T > (p.wdt == SSRNN_FP8 ? 4 : 8);
+  const int xlds_tiles = p.nt_tiles;
+  p.xlds = p.packed && (xlds_tiles >= 2 || short_blocks_too) && p.ksplit == 1 && p.d % XLDS_F == 0 && xlds_takes(p.wdt, xlds_tiles, ncol) &&
            static_cast<long>(p.d) / XLDS_F * conc >= 256 && op_stride < (1ull << 31) && !(p.opts & SSRNN_OPT_ONE_TILE);
   p.ft = 1;
   if (p.packed && (p.nt_tiles == 2 || (p.nt_tiles == 4 && p.wdt != SSRNN_F32)) && p.ksplit == 1 && ntile % 2 == 0 &&
