@@ -435,12 +435,17 @@ def main():
         torch.cuda.empty_cache()
         for name in ("C2", "C3"):
             oc = wl.by_name(name)
-            so = Stack(ss, wl, torch, oc, dev, want_packed=False)
+            so = Stack(ss, wl, torch, oc, dev, want_packed=True)
             # the weights of the whole stack, read again and again: they stay in the Infinity Cache
             cache_probe = read_probe_rate(ss, torch, so.W, len(so.W), reps_bytes=2e9)
             for T_ in oc.Ts:
                 r = so.row(T_, so.time_median(T_))
-                others.append({"workload": oc.name, "T": T_, "steps_per_s": r["steps_per_s"], "us_per_stage": r["us_per_stage"],
+                weights = "row-major"
+                if so.W_packed is not None:          # as in the sweep: the layout that is faster at this block size
+                    pk = so.row(T_, so.time_median(T_, 0, True))
+                    if pk["steps_per_s"] > r["steps_per_s"]:
+                        r, weights = pk, "packed"
+                others.append({"workload": oc.name, "T": T_, "weights": weights, "steps_per_s": r["steps_per_s"], "us_per_stage": r["us_per_stage"],
                                "algorithmic_GBps": r["algorithmic_GBps"],
                                "cache_read_probe_GBps": cache_probe["GBps"],
                                "frac_of_cache_read_probe": round(r["algorithmic_GBps"] / cache_probe["GBps"], 4),
